@@ -1,0 +1,10 @@
+"""CPU oracle for the batched max-flow feasibility path -- test infrastructure only.
+
+Only tests, the smoke check and the bench's `cpu_baseline` leg may import this
+package; it shares no code with the HIP library and never imports it.
+"""
+from .reference import (Disconnected, build_c, maxflow, aux_network, aux_maxflow,
+                        aux_maxflow_batch, feasible, in_bandwidths,
+                        min_compute_in_bandwidth, fraction_in_interval,
+                        optimality_binary_search, smallest_U_k, brute_inv_xstar,
+                        brute_min_cut, brute_cut_condition)

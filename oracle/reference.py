@@ -1,0 +1,291 @@
+"""CPU ORACLE -- TEST INFRASTRUCTURE ONLY (tests, the smoke check and the bench's
+`cpu_baseline` leg may use it; the product path never does).
+
+Plain definitions of everything the batched feasibility path outputs, written from
+the paper (ForestColl, arXiv 2402.06787):
+
+* F(s, v): max-flow value in the auxiliary network of Section 5.2 / Appendix E.1
+  (`aux_network`, `aux_maxflow`), solved by the C routines of `maxflow.c`
+  (Dinic, Edmonds-Karp), or by brute-force cut enumeration (`brute_min_cut`).
+* the feasibility verdict of Theorem 1 / the integer form after Proposition 3
+  (`feasible`).
+* 1/x* by Algorithm 1 taken literally in exact rational arithmetic
+  (`optimality_binary_search`), or by enumerating every cut of the bound (star) of
+  Section 4 (`brute_inv_xstar`).
+* (U, k) by the gcd rule of Section 5.2 "Determine k" / Proposition 3 (`smallest_U_k`).
+
+Readings of the paper taken here (each also listed in the design notes):
+ - Algorithm 1 tests "max-flow is N x"; Theorem 1 says ">= N x".  They are the same
+   because s emits at most N x; `feasible` uses >= and asserts <=.
+ - s is joined to every compute node including the sink itself, so F >= k.
+ - B^-(v) in Algorithm 1 is the in-bandwidth of v in the input graph G (no source
+   arc), taken over compute nodes only.
+ - a rational candidate 1/x = A/D is tested on integers by uniform scaling
+   (Appendix E.1): arc capacities A*b_e, source arcs D, threshold N*D.
+ - the final interval is closed: the fraction with denominator <= B may sit on an
+   end point (the initial lower bound can equal 1/x*).
+ - parallel arcs add up; self-loops and zero-bandwidth arcs carry nothing.
+ - if some cut with compute nodes on both sides has no exiting bandwidth the bound
+   is infinite (the paper assumes B^+(S) >= 1): `Disconnected` is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from fractions import Fraction
+from math import gcd
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libfc_oracle.so")
+_SRC = os.path.join(_HERE, "maxflow.c")
+_lib_handle = None
+
+ALGO = {"dinic": 0, "edmonds_karp": 1}
+_I64_GUARD = 1 << 62
+
+
+class Disconnected(Exception):
+    """Some compute node cannot reach another one: the bound (star) is infinite."""
+
+
+def build_c(force: bool = False) -> str:
+    """Compile maxflow.c into libfc_oracle.so with gcc -O2 (plain C, pthreads)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        tmp = _SO + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-pthread",
+                               "-Wall", "-Wextra", "-o", tmp, _SRC])
+        os.replace(tmp, _SO)
+    return _SO
+
+
+def _lib():
+    global _lib_handle
+    if _lib_handle is None:
+        lib = ctypes.CDLL(build_c())
+        p32 = ctypes.POINTER(ctypes.c_int32); p64 = ctypes.POINTER(ctypes.c_int64)
+        pu8 = ctypes.POINTER(ctypes.c_uint8)
+        lib.fco_maxflow.restype = ctypes.c_int64
+        lib.fco_maxflow.argtypes = [ctypes.c_int32, ctypes.c_int64, p32, p32, p64,
+                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, p64]
+        lib.fco_aux_maxflow_batch.restype = ctypes.c_int32
+        lib.fco_aux_maxflow_batch.argtypes = [ctypes.c_int32, ctypes.c_int64, p32, p32, p32, pu8,
+                                              ctypes.c_int64, p32, p64, p64, p64,
+                                              ctypes.c_int32, ctypes.c_int32]
+        _lib_handle = lib
+    return _lib_handle
+
+
+def _ptr(a, ty):
+    return a.ctypes.data_as(ctypes.POINTER(ty))
+
+
+# ------------------------------------------------------------------ F(x, y; D)
+
+def maxflow(n_vertices, tail, head, cap, src, dst, algo="dinic", return_arc_flow=False):
+    """Value of a maximum src->dst flow in the digraph (tail, head, cap) -- the
+    quantity F(x, y; D) of the Appendix E preamble."""
+    tail = np.ascontiguousarray(tail, dtype=np.int32)
+    head = np.ascontiguousarray(head, dtype=np.int32)
+    cap_py = [int(c) for c in np.asarray(cap).reshape(-1)]
+    if sum(c for t, c in zip(tail.tolist(), cap_py) if t == src) >= _I64_GUARD:
+        raise OverflowError("source out-capacity exceeds the int64 guard")
+    cap = np.asarray([min(c, _I64_GUARD) for c in cap_py], dtype=np.int64)
+    m = tail.shape[0]
+    arc_flow = np.zeros(m, dtype=np.int64) if return_arc_flow else None
+    f = _lib().fco_maxflow(int(n_vertices), m, _ptr(tail, ctypes.c_int32), _ptr(head, ctypes.c_int32),
+                           _ptr(cap, ctypes.c_int64), int(src), int(dst), ALGO[algo],
+                           _ptr(arc_flow, ctypes.c_int64) if return_arc_flow else None)
+    if f < 0:
+        raise ValueError("bad arguments to the oracle max-flow")
+    return (int(f), arc_flow) if return_arc_flow else int(f)
+
+
+def aux_network(topo, U, k):
+    """Auxiliary network of Section 5.2 on integers: vertices V + {s}, s = n_vertices;
+    arc e with capacity U*b_e; arc (s, c) with capacity k for every compute node c."""
+    comp = np.flatnonzero(topo.is_compute).astype(np.int32)
+    s = topo.n_vertices
+    tail = np.concatenate([topo.tail.astype(np.int32), np.full(comp.shape[0], s, dtype=np.int32)])
+    head = np.concatenate([topo.head.astype(np.int32), comp])
+    cap = [int(U) * int(b) for b in topo.bandwidth.tolist()] + [int(k)] * comp.shape[0]
+    return topo.n_vertices + 1, tail, head, cap, s
+
+
+def aux_maxflow(topo, sink, U, k, algo="dinic"):
+    """F(s, sink) in the auxiliary network with edge multiplier U and source arcs k."""
+    n, tail, head, cap, s = aux_network(topo, U, k)
+    return maxflow(n, tail, head, cap, s, int(sink), algo)
+
+
+def aux_maxflow_batch(topo, sink, U, k, algo="dinic", threads=1):
+    """F(s, sink_j) for every problem j = (sink_j, U_j, k_j); int64 values.
+    `threads` > 1 shards the problem list statically over POSIX threads."""
+    sink = np.ascontiguousarray(sink, dtype=np.int32)
+    U = np.ascontiguousarray(U, dtype=np.int64)
+    k = np.ascontiguousarray(k, dtype=np.int64)
+    P = sink.shape[0]
+    assert U.shape[0] == P and k.shape[0] == P
+    if P == 0:
+        return np.zeros(0, dtype=np.int64)
+    if sink.min() < 0 or sink.max() >= topo.n_vertices or U.min() < 0 or k.min() < 0:
+        raise ValueError("bad problem list")
+    max_b = int(topo.bandwidth.max()) if topo.n_arcs else 0
+    if int(U.max()) * max_b >= _I64_GUARD or int(k.max()) * topo.n_compute >= _I64_GUARD:
+        raise OverflowError("capacities exceed the int64 guard")
+    tail = np.ascontiguousarray(topo.tail, dtype=np.int32)
+    head = np.ascontiguousarray(topo.head, dtype=np.int32)
+    bw = np.ascontiguousarray(topo.bandwidth, dtype=np.int32)
+    isc = np.ascontiguousarray(topo.is_compute, dtype=np.uint8)
+    out = np.full(P, -1, dtype=np.int64)
+    rc = _lib().fco_aux_maxflow_batch(topo.n_vertices, topo.n_arcs, _ptr(tail, ctypes.c_int32),
+                                      _ptr(head, ctypes.c_int32), _ptr(bw, ctypes.c_int32),
+                                      _ptr(isc, ctypes.c_uint8), P, _ptr(sink, ctypes.c_int32),
+                                      _ptr(U, ctypes.c_int64), _ptr(k, ctypes.c_int64),
+                                      _ptr(out, ctypes.c_int64), ALGO[algo], int(threads))
+    if rc != 0 or (out < 0).any():
+        raise RuntimeError("oracle batch failed")
+    return out
+
+
+# ------------------------------------------------------------------ verdict (Theorem 1 / Theorem 3)
+
+def feasible(topo, U, k, algo="dinic", threads=1):
+    """Candidate 1/x = U/k is feasible iff min over compute nodes v of F(s, v) >= N*k.
+    Returns (verdict, flows) with flows[i] = F(s, i-th compute node)."""
+    comp = np.flatnonzero(topo.is_compute).astype(np.int32)
+    N = comp.shape[0]
+    flows = aux_maxflow_batch(topo, comp, np.full(N, int(U), dtype=np.int64),
+                              np.full(N, int(k), dtype=np.int64), algo, threads)
+    assert (flows <= N * int(k)).all(), "s cannot emit more than N*k"
+    return bool((flows >= N * int(k)).all()), flows
+
+
+# ------------------------------------------------------------------ Algorithm 1, literally
+
+def in_bandwidths(topo):
+    """B^-_G(v) for every vertex: total bandwidth of arcs entering v from other vertices."""
+    B = [0] * topo.n_vertices
+    for t, h, b in zip(topo.tail.tolist(), topo.head.tolist(), topo.bandwidth.tolist()):
+        if t != h:
+            B[h] += int(b)
+    return B
+
+
+def min_compute_in_bandwidth(topo):
+    B = in_bandwidths(topo)
+    return min(B[v] for v in range(topo.n_vertices) if topo.is_compute[v])
+
+
+def fraction_in_interval(l: Fraction, r: Fraction, max_den: int) -> Fraction:
+    """The fraction p/q in the closed interval [l, r] with q <= max_den (Algorithm 1,
+    last step), by brute force over denominators.  It must be unique."""
+    found = set()
+    for q in range(1, max_den + 1):
+        p_lo = -((-l.numerator * q) // l.denominator)      # ceil(l*q)
+        p_hi = (r.numerator * q) // r.denominator           # floor(r*q)
+        for p in range(p_lo, p_hi + 1):
+            found.add(Fraction(p, q))
+    if len(found) != 1:
+        raise AssertionError(f"expected exactly one fraction in [{l}, {r}] with q <= {max_den}: {sorted(found)}")
+    return found.pop()
+
+
+def optimality_binary_search(topo, algo="dinic", threads=1, log=None):
+    """Algorithm 1 (Optimality Binary Search) in exact rationals.  Returns 1/x* as a
+    Fraction; `log`, if a list, receives (A, D, verdict) for every candidate A/D tested."""
+    N = topo.n_compute
+    if N < 2:
+        raise ValueError("need at least two compute nodes")
+    B = min_compute_in_bandwidth(topo)
+    if B < 1 or not feasible(topo, N - 1, 1, algo, threads)[0]:
+        raise Disconnected()
+    l = Fraction(N - 1, B)
+    r = Fraction(N - 1, 1)
+    width = Fraction(1, B * B)
+    rounds = 0
+    while r - l >= width:
+        mid = (l + r) / 2
+        ok, _ = feasible(topo, mid.numerator, mid.denominator, algo, threads)
+        if log is not None:
+            log.append((mid.numerator, mid.denominator, ok))
+        if ok:
+            r = mid
+        else:
+            l = mid
+        rounds += 1
+    result = fraction_in_interval(l, r, B)
+    if log is not None:
+        log.append(("rounds", rounds, None))
+    return result
+
+
+def smallest_U_k(inv_xstar: Fraction, bandwidths):
+    """Proposition 3: with 1/x* = p/q in lowest terms, g = gcd(q, {b_e}):
+    U = p/g (a rational), k = q/g (an integer)."""
+    p, q = inv_xstar.numerator, inv_xstar.denominator
+    g = q
+    for b in bandwidths:
+        if int(b) > 0:
+            g = gcd(g, int(b))
+    return Fraction(p, g), q // g
+
+
+# ------------------------------------------------------------------ brute force (tiny graphs only)
+
+def brute_inv_xstar(topo):
+    """max over S subset of V, S not containing all compute nodes, of |S n V_c| / B^+(S)
+    (the bound (star) of Section 4) by enumerating all 2^|V| subsets.  Raises
+    Disconnected when a subset holding a compute node has no exiting bandwidth."""
+    n = topo.n_vertices
+    assert n <= 16
+    arcs = [(t, h, int(b)) for t, h, b in zip(topo.tail.tolist(), topo.head.tolist(),
+                                              topo.bandwidth.tolist()) if t != h and b > 0]
+    comp_mask = 0
+    for v in range(n):
+        if topo.is_compute[v]:
+            comp_mask |= 1 << v
+    best = Fraction(0)
+    for S in range(1, 1 << n):
+        if S & comp_mask == comp_mask:
+            continue                                   # S contains every compute node
+        inside = bin(S & comp_mask).count("1")
+        if inside == 0:
+            continue
+        out_bw = sum(b for t, h, b in arcs if (S >> t) & 1 and not (S >> h) & 1)
+        if out_bw == 0:
+            raise Disconnected()
+        best = max(best, Fraction(inside, out_bw))
+    return best
+
+
+def brute_min_cut(n_vertices, tail, head, cap, src, dst):
+    """min over vertex sets A containing src and not dst of the capacity leaving A."""
+    assert n_vertices <= 16
+    arcs = list(zip(np.asarray(tail).tolist(), np.asarray(head).tolist(), [int(c) for c in cap]))
+    others = [v for v in range(n_vertices) if v not in (src, dst)]
+    best = None
+    for bits in range(1 << len(others)):
+        A = 1 << src
+        for i, v in enumerate(others):
+            if (bits >> i) & 1:
+                A |= 1 << v
+        c = sum(cp for t, h, cp in arcs if (A >> t) & 1 and not (A >> h) & 1)
+        best = c if best is None else min(best, c)
+    return best
+
+
+def brute_cut_condition(topo, k):
+    """Theorem 8's cut form on a switch-free integer digraph D:
+    c(S, complement of S; D) >= |S| * k for every proper non-empty subset S of V."""
+    n = topo.n_vertices
+    assert n <= 16 and topo.is_compute.all()
+    arcs = [(t, h, int(b)) for t, h, b in zip(topo.tail.tolist(), topo.head.tolist(),
+                                              topo.bandwidth.tolist()) if t != h]
+    for S in range(1, (1 << n) - 1):
+        c = sum(b for t, h, b in arcs if (S >> t) & 1 and not (S >> h) & 1)
+        if c < bin(S).count("1") * k:
+            return False
+    return True

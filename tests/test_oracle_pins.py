@@ -1,0 +1,268 @@
+"""Pins for the CPU oracle: each test checks it against something other than itself --
+values the paper states for its worked example, closed forms from the min-cut theorem,
+brute-force enumeration on tiny graphs, and invariants the paper's theorems fix."""
+import json
+import os
+from fractions import Fraction
+from math import ceil, log2
+
+import numpy as np
+import pytest
+
+import oracle as o
+import workloads as w
+from workloads.topologies import shrunken_config5
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+ALGOS = ("dinic", "edmonds_karp")
+
+
+def _gold(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return json.load(f)
+
+
+# ---------------------------------------------------------------- the paper's worked example
+
+@pytest.mark.parametrize("b", [1, 2, 3, 7])
+def test_paper_example_bottleneck_and_search(b):
+    g = _gold("paper_worked_example.json")
+    topo = w.paper_example_switch(b)
+    want = Fraction(*g["bottleneck_ratio_times_b"]["value"]) / b       # Section 4: 1/x* = 1/b
+    assert o.brute_inv_xstar(topo) == want
+    assert o.optimality_binary_search(topo) == want
+    # Section 5.2 "Determine k" / Appendix E.1: U = 1/b, k = 1, capacities become {1, 10}
+    U, k = o.smallest_U_k(want, topo.bandwidth)
+    assert (U, k) == (Fraction(g["scaled_capacities"]["U_times_b"], b), g["scaled_capacities"]["k"])
+    assert sorted({int(U * int(x)) for x in topo.bandwidth}) == g["scaled_capacities"]["value"]
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("b", [1, 3])
+def test_paper_example_flows(algo, b):
+    g = _gold("paper_worked_example.json")
+    topo = w.paper_example_switch(b)
+    # x = b: every sink receives all 8x (Section 5.2)
+    for v in range(8):
+        assert o.aux_maxflow(topo, v, 1, b, algo) == g["flow_at_x_equals_b_over_b"]["value"] * b
+    # b < x <= 7b/3: capped at 4x + 4b (Section 5.2); x/b = 2 lies in that range
+    x = 2 * b
+    assert o.aux_maxflow(topo, 5, 1, x, algo) == 4 * x + 4 * b
+    # x/b = 3: the single-node cut x + 11b (B+(S') = 11b, Section 5.2) binds instead
+    x = 3 * b
+    assert o.aux_maxflow(topo, 5, 1, x, algo) == x + g["exit_bandwidth_all_but_one_over_b"]["value"] * b
+    # verdicts around the optimum
+    assert o.feasible(topo, 1, b, algo)[0] is True
+    assert o.feasible(topo, 99, 100 * b, algo)[0] is False   # 1/x slightly below 1/b
+
+
+@pytest.mark.parametrize("b", [1, 2, 5])
+def test_paper_example_variants(b):
+    g = _gold("paper_worked_example.json")
+    ring = w.paper_example_ring_unwound(b)
+    want = Fraction(*g["ring_unwound_ratio_times_b"]["value"]) / b      # 4/b, "4x worse"
+    assert o.brute_inv_xstar(ring) == want
+    assert o.optimality_binary_search(ring) == want
+    split = w.paper_example_split(b)
+    want = Fraction(*g["after_edge_splitting_ratio_times_b"]["value"]) / b
+    assert o.brute_inv_xstar(split) == want
+    assert o.optimality_binary_search(split) == want
+
+
+# ---------------------------------------------------------------- closed forms on the symmetric configs
+
+def _closed_form(cfg, U, k):
+    if cfg == 1:
+        return min(16 * k, k + 12 * U, 8 * k + 8 * U)
+    if cfg == 3:
+        return min(128 * k, k + 26 * U, 8 * k + 16 * U)
+    if cfg == 4:
+        return min(512 * k, k + 36 * U, 8 * k + 32 * U, 32 * k + 256 * U)
+    raise ValueError
+
+
+def test_closed_form_file_matches_test_formulas():
+    g = _gold("config_closed_forms.json")
+    assert g["config1"]["F"] == "min(16k, k+12U, 8k+8U)"
+    assert g["config3"]["F"] == "min(128k, k+26U, 8k+16U)"
+    assert g["config4"]["F"] == "min(512k, k+36U, 8k+32U, 32k+256U)"
+
+
+@pytest.mark.parametrize("cfg,cands", [
+    (1, [(1, 4), (4, 4), (5, 4), (6, 4), (3, 1), (1, 1)]),
+    (3, [(1, 8), (44, 8), (59, 8), (60, 8), (61, 8), (7, 1), (8, 1)]),
+    (4, [(1, 4), (6, 4), (7, 4), (8, 4), (55, 4), (62, 4), (63, 4), (64, 4)]),
+])
+def test_config_closed_form_flows(cfg, cands):
+    topo = w.config_topology(cfg)
+    N = topo.n_compute
+    for U, k in cands:
+        ok, flows = o.feasible(topo, U, k, threads=4)
+        want = _closed_form(cfg, U, k)
+        assert (flows == want).all(), (cfg, U, k, want, flows[:4])
+        assert ok == (want >= N * k)
+    # a few sinks with the second algorithm
+    for U, k in cands[:3]:
+        for v in (0, N // 2, N - 1):
+            assert o.aux_maxflow(topo, v, U, k, "edmonds_karp") == _closed_form(cfg, U, k)
+
+
+@pytest.mark.parametrize("cfg", [1, 3, 4])
+def test_config_closed_form_optimum(cfg):
+    g = _gold("config_closed_forms.json")[f"config{cfg}"]
+    topo = w.config_topology(cfg)
+    log = []
+    x = o.optimality_binary_search(topo, threads=4, log=log)
+    assert x == Fraction(*g["inv_xstar"])
+    U, k = o.smallest_U_k(x, topo.bandwidth)
+    assert (U, k) == (Fraction(*g["U_k"][0]), g["U_k"][1])
+    # iteration ceiling of Appendix F: at most ceil(log2(N * B^2)) rounds
+    B = o.min_compute_in_bandwidth(topo)
+    assert log[-1][1] <= ceil(log2(topo.n_compute * B * B))
+    # every verdict in the log is monotone in A/D (Theorem 1)
+    tested = sorted((Fraction(a, d), ok) for a, d, ok in log[:-1])
+    flags = [ok for _, ok in tested]
+    assert flags == sorted(flags)
+
+
+def test_config1_configured_batch_is_infeasible():
+    topo = w.config_topology(1)
+    ok, flows = o.feasible(topo, 1, 4)
+    assert not ok and (flows == 16).all()          # min(64, 4+12, 32+8) = 16 < 64
+
+
+# ---------------------------------------------------------------- textbook special cases of the bound (star)
+
+@pytest.mark.parametrize("n,c", [(3, 1), (5, 2), (6, 7)])
+def test_textbook_shapes(n, c):
+    assert o.optimality_binary_search(w.complete_digraph(n, c)) == Fraction(1, c)
+    assert o.optimality_binary_search(w.directed_ring(n, c)) == Fraction(n - 1, c)
+    if n >= 3:
+        assert o.optimality_binary_search(w.bidirectional_ring(n, c)) == Fraction(n - 1, 2 * c)
+    assert o.optimality_binary_search(w.star_switch(n, c)) == Fraction(n - 1, c)
+
+
+def test_generic_maxflow_textbook_network():
+    # classic 6-vertex example with max-flow 23 (CLRS figure 26.1 capacities)
+    arcs = [(0, 1, 16), (0, 2, 13), (1, 3, 12), (2, 1, 4), (2, 4, 14), (3, 2, 9), (3, 5, 20), (4, 3, 7), (4, 5, 4)]
+    t, h, c = zip(*arcs)
+    for algo in ALGOS:
+        assert o.maxflow(6, t, h, c, 0, 5, algo) == 23
+    assert o.brute_min_cut(6, t, h, c, 0, 5) == 23
+    # direction matters: nothing flows backwards
+    assert o.maxflow(6, t, h, c, 5, 0) == 0
+
+
+# ---------------------------------------------------------------- brute force on random tiny graphs
+
+@pytest.mark.parametrize("seed", range(60))
+def test_tiny_random_flow_equals_brute_min_cut(seed):
+    topo = w.random_tiny(seed)
+    rng = np.random.default_rng(1000 + seed)
+    U, k = int(rng.integers(1, 5)), int(rng.integers(1, 12))
+    n, tail, head, cap, s = o.aux_network(topo, U, k)
+    for v in topo.compute_nodes:
+        want = o.brute_min_cut(n, tail, head, cap, s, int(v))
+        got_d, flow = o.maxflow(n, tail, head, cap, s, int(v), "dinic", return_arc_flow=True)
+        got_e = o.maxflow(n, tail, head, cap, s, int(v), "edmonds_karp")
+        assert got_d == want == got_e
+        # capacity + conservation + value on the returned arc flows
+        capa = np.asarray(cap, dtype=np.int64)
+        assert (flow >= 0).all() and (flow <= capa).all()
+        net = np.zeros(n, dtype=np.int64)
+        np.add.at(net, head, flow); np.subtract.at(net, tail, flow)
+        assert net[int(v)] == got_d and net[s] == -got_d
+        mask = np.ones(n, bool); mask[[s, int(v)]] = False
+        assert (net[mask] == 0).all()
+        # bounds: k <= F <= min(N k, k + U B^-(v))
+        Bv = o.in_bandwidths(topo)[int(v)]
+        assert k <= got_d <= min(topo.n_compute * k, k + U * Bv)
+
+
+@pytest.mark.parametrize("seed", range(80))
+def test_tiny_random_search_equals_brute_bound(seed):
+    topo = w.random_tiny(seed, strongly_connected=(seed % 4 != 3))
+    try:
+        want = o.brute_inv_xstar(topo)
+    except o.Disconnected:
+        with pytest.raises(o.Disconnected):
+            o.optimality_binary_search(topo)
+        return
+    got = o.optimality_binary_search(topo, algo=ALGOS[seed % 2])
+    assert got == want
+    N, B = topo.n_compute, o.min_compute_in_bandwidth(topo)
+    assert Fraction(N - 1, B) <= got <= N - 1 and got.denominator <= B    # Appendix E.1 range
+    # Theorem 1 at and just below the optimum
+    assert o.feasible(topo, got.numerator, got.denominator)[0]
+    below = got - Fraction(1, 1000 * got.denominator)
+    assert not o.feasible(topo, below.numerator, below.denominator)[0]
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_shrunken_config5_and_config2_like(seed):
+    topo = shrunken_config5(seed)
+    assert o.optimality_binary_search(topo) == o.brute_inv_xstar(topo)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_theorem8_cut_form_switch_free(seed):
+    topo = w.random_tiny(500 + seed, n_vertices=int(3 + seed % 5), switch_free=True, density=0.6)
+    for k in (1, 2, 3, 5):
+        assert o.brute_cut_condition(topo, k) == o.feasible(topo, 1, k)[0]
+
+
+# ---------------------------------------------------------------- invariants (Theorem 1, Appendix E.1)
+
+@pytest.mark.parametrize("cfg", [2, 3])
+def test_monotone_and_scaling(cfg):
+    topo = w.config_topology(cfg)
+    k = 4
+    prev = None
+    for U in range(1, 40, 3):
+        ok, flows = o.feasible(topo, U, k, threads=4)
+        if prev is not None:
+            assert (flows >= prev[1]).all() and ok >= prev[0]
+        prev = (ok, flows)
+        if U % 2:
+            _, f3 = o.feasible(topo, 3 * U, 3 * k, threads=4)     # uniform scaling (Appendix E.1)
+            assert (f3 == 3 * flows).all()
+
+
+def test_proposition3_gcd_rule():
+    assert o.smallest_U_k(Fraction(1, 3), [3, 30]) == (Fraction(1, 3), 1)
+    assert o.smallest_U_k(Fraction(5, 4), [12, 8]) == (Fraction(5, 4), 1)
+    assert o.smallest_U_k(Fraction(5, 6), [4, 10]) == (Fraction(5, 2), 3)
+    assert o.smallest_U_k(Fraction(7, 5), [3, 4]) == (Fraction(7, 1), 5)
+    # U*b_e integral, U/k = p/q, and no smaller k works
+    for p, q, bw in [(5, 6, [4, 10]), (9, 8, [12, 20, 8]), (3, 7, [14, 21])]:
+        U, k = o.smallest_U_k(Fraction(p, q), bw)
+        assert U / k == Fraction(p, q) and all((U * b).denominator == 1 for b in bw)
+        for k2 in range(1, k):
+            U2 = Fraction(p, q) * k2
+            assert not all((U2 * b).denominator == 1 for b in bw)
+
+
+def test_fraction_gap_proposition2():
+    # two different fractions with denominators <= X differ by at least 1/X^2
+    X = 9
+    fr = sorted({Fraction(p, q) for q in range(1, X + 1) for p in range(0, 3 * q + 1)})
+    assert min(b - a for a, b in zip(fr, fr[1:])) >= Fraction(1, X * X)
+    assert o.fraction_in_interval(Fraction(5, 4), Fraction(5, 4) + Fraction(1, 200), 12) == Fraction(5, 4)
+    assert o.fraction_in_interval(Fraction(299, 80), Fraction(301, 80), 8) == Fraction(15, 4)
+
+
+def test_planted_mistakes_are_caught():
+    """Each plausible slip, planted in a copy of the oracle's network builder, changes a pinned value."""
+    topo = w.paper_example_switch(1)
+
+    def flow_with(build):
+        n, t, h, c, s = build()
+        return o.maxflow(n, t, h, c, s, 5)
+
+    n, t, h, c, s = o.aux_network(topo, 1, 2)
+    assert flow_with(lambda: (n, t, h, c, s)) == 12
+    assert flow_with(lambda: (n, h, t, c, s)) != 12                       # transposed arcs
+    c_no_sink = [0 if (tt == s and hh == 5) else cc for tt, hh, cc in zip(t, h, c)]
+    assert flow_with(lambda: (n, t, h, c_no_sink, s)) != 12               # dropped s->sink arc
+    c_unscaled = [cc if tt == s else 2 * cc for tt, cc in zip(t, c)]
+    assert flow_with(lambda: (n, t, h, c_unscaled, s)) != 12              # wrong capacity scaling
