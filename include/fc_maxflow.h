@@ -1,0 +1,204 @@
+/*
+ * fc_maxflow.h -- C ABI of the batched integer max-flow feasibility library for
+ * AMD MI355X (gfx950).
+ *
+ * The library implements the data-parallel hot path of ForestColl's schedule
+ * generator (arXiv 2402.06787): the max-flow tests of the optimality search.
+ * Notation follows the paper's Appendix A: G = (V = V_s u V_c, E) is the topology
+ * digraph with integer link bandwidths b_e, N = |V_c| compute nodes, s the auxiliary
+ * super-source, x the per-node broadcast bandwidth, k the source-arc capacity of the
+ * integer network, U the edge-capacity multiplier (candidate 1/x = U/k), F(a,b;D) a
+ * max-flow value.
+ *
+ * Conventions
+ *  - Every function returns FC_OK (0) or a negative FC_E* code; outputs are not
+ *    written on error unless stated.  Nothing throws or aborts across this boundary.
+ *  - "host" pointers are ordinary CPU memory, borrowed for the duration of the call.
+ *    "device" pointers are HIP device memory on the GPU that was current when the
+ *    graph was uploaded; the caller owns them and keeps them alive until the work
+ *    queued on `hip_stream` has finished.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *  - An fc_graph is immutable after creation and may be shared by concurrent calls on
+ *    different streams as long as each call has its own workspace.
+ */
+#ifndef FC_MAXFLOW_H
+#define FC_MAXFLOW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FC_OK             0
+#define FC_EINVAL        -1   /* null pointer, id out of range, negative bandwidth, N < 2, bad option  */
+#define FC_EOVERFLOW     -2   /* a quantity does not fit the integer type the device path uses         */
+#define FC_EDISCONNECTED -3   /* some compute node cannot reach another: the bound (star) is infinite  */
+#define FC_ENOMEM        -4   /* host allocation failed                                                */
+#define FC_EWORKSPACE    -5   /* workspace pointer null or smaller than *_workspace_bytes reports      */
+#define FC_EDEVICE       -6   /* a HIP call failed, or no usable GPU / the graph is not on the device  */
+#define FC_ENOCONVERGE   -7   /* a safety cap on device iterations was hit (indicates a bug)           */
+#define FC_EUNSUPPORTED  -8   /* graph too large for the on-chip state layout of this build            */
+
+/* value written to flow_out[j] when problem j itself is invalid (sink out of range, U < 1,
+ * k < 1, or N*k >= 2^31); valid flows are always >= 1 */
+#define FC_FLOW_INVALID     ((int32_t)-1)
+/* the safety cap on device iterations was hit for problem j (a bug; never expected) */
+#define FC_FLOW_NOCONVERGE  ((int32_t)-2)
+/* N*k_j > 65535 needs the 32-bit on-chip layout, which does not fit this graph */
+#define FC_FLOW_UNSUPPORTED ((int32_t)-3)
+
+typedef struct fc_graph fc_graph;                  /* opaque; owned by the library            */
+typedef struct { int64_t num, den; } fc_rational;  /* always reduced, den > 0                  */
+
+/* Work counters summed over the problems of one call (all optional). */
+typedef struct {
+    uint64_t pushes;           /* residual-edge updates: one per (arc, push)                          */
+    uint64_t relabels;         /* single-vertex height increases by the discharge step                */
+    uint64_t arc_scans;        /* residual arcs examined by discharge steps                           */
+    uint64_t global_relabels;  /* backward breadth-first relabelings from the sink                    */
+    uint64_t gr_arc_scans;     /* residual arcs examined by those                                     */
+    uint64_t level_steps;      /* discharge steps (one height level of one problem each)              */
+    uint64_t discharges;       /* vertex discharges                                                   */
+    uint64_t not_converged;    /* problems that hit the iteration cap (must be 0)                     */
+    float    device_ms;        /* duration of the call's kernels, HIP events on `hip_stream`          */
+} fc_stats;
+
+/* Tuning knobs; zero-initialise and override what you need (0 = library default). */
+typedef struct {
+    int32_t threads_per_problem;   /* workgroup size, multiple of 64 in [64, 1024]                     */
+    int32_t lanes_per_vertex;      /* power of two in [2, 64]: lanes that scan one vertex's arc list   */
+    int32_t global_relabel_steps;  /* relabel from the sink when this many level steps passed since
+                                      the last one and some vertex was relabeled                       */
+    int32_t global_relabel_permille; /* ... or when relabels since then reach this fraction of |V|     */
+    int32_t use_gap;               /* 1 = on (default), 2 = off: empty-height-level cut detection      */
+    int32_t use_label_table;       /* 1 = on (default), 2 = off: initial exact labels from the
+                                      per-sink distance table built at upload                          */
+    int32_t force_wide;            /* 1 = always use 32-bit on-chip state (default: 16-bit when it fits) */
+    int32_t max_level_steps;       /* safety cap per problem (default max(100000, 200*|V|))            */
+    int32_t src_cap_bound;         /* > 0: the caller promises k_j <= this for every problem of the call.
+                                      If N * bound <= 65535 only the 16-bit-state kernel is launched;
+                                      a problem that breaks the promise gets FC_FLOW_UNSUPPORTED        */
+} fc_options;
+
+/* ------------------------------------------------------------------------------------------
+ * Graph ingest (the paper's problem definition, Section 5: a directed graph with integer link
+ * bandwidths whose vertices are compute nodes V_c and switch nodes V_s).
+ *
+ * tail/head/bandwidth: host arrays of n_arcs directed arcs (tail -> head).  Vertex ids are
+ * 0..n_vertices-1; the super-source s is implicit and never listed.  Parallel arcs are allowed
+ * and their bandwidths add (integer capacity = number of multi-edges, Appendix E.1);
+ * self-loops and zero-bandwidth arcs are ignored; antiparallel arcs are independent.  The
+ * graph need not be Eulerian for the calls below.  is_compute: host array [n_vertices],
+ * non-zero = compute node.
+ *
+ * fc_graph_build   : host-side part only (validation, merging, residual CSR); needs no GPU.
+ * fc_graph_upload  : fc_graph_build + copy to the current HIP device (+ per-sink label table).
+ * Errors: FC_EINVAL (null pointers, ids out of range, negative bandwidth, fewer than two
+ * compute nodes, n_vertices < 2), FC_EOVERFLOW (a merged bandwidth or an in-bandwidth sum
+ * reaches 2^31), FC_ENOMEM, FC_EDEVICE, FC_EUNSUPPORTED (per-problem state exceeds on-chip memory).
+ * On success *out owns host and device memory until fc_graph_free.
+ */
+int fc_graph_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
+                   const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out);
+int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
+                    const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out);
+int fc_graph_free(fc_graph *g);
+
+/* Facts Algorithm 1 and Proposition 3 need: N = |V_c|; number of arcs after merging;
+ * min over compute nodes of the in-bandwidth B^-_G(v); max_e b_e; gcd of all b_e; whether
+ * every vertex has equal in- and out-bandwidth (the paper's Eulerian assumption, needed only
+ * by later stages).  Any output pointer may be null. */
+int fc_graph_info(const fc_graph *g, int32_t *n_compute, int64_t *n_arcs_merged,
+                  int64_t *min_in_bw_compute, int32_t *max_bw, int32_t *gcd_bw, int32_t *is_eulerian);
+
+/* Residual CSR as built on the host (for inspection and tests).  Vertex u owns records
+ * row_ptr[u] .. row_ptr[u+1]-1; record r describes a residual arc u -> other[r] that belongs to
+ * merged topology arc pair[r] of bandwidth bw[r]; forward[r] = 1 if the topology arc leaves u,
+ * 0 if it enters u.  Pass null to skip an array; sizes: row_ptr [n_vertices+1], others
+ * [2 * n_arcs_merged]. */
+int fc_graph_csr(const fc_graph *g, int32_t *row_ptr, int32_t *other, int32_t *pair,
+                 int32_t *bw, uint8_t *forward);
+
+/* ------------------------------------------------------------------------------------------
+ * fc_maxflow_batch -- many independent max-flows on the auxiliary network (Section 5.2,
+ * Appendix E.1): problem j adds s with an arc (s, c) of capacity src_cap[j] = k_j for every
+ * compute node c (the sink included), gives every topology arc e capacity edge_mult[j] * b_e
+ * = U_j * b_e, and asks for F(s, sink[j]).  By the min-cut theorem that value is unique.
+ *
+ * d_sink, d_edge_mult, d_src_cap: device int32 [n_problems].  d_flow_out: device int32
+ * [n_problems]; entry j receives F(s, sink_j) (>= k_j when sink_j is a compute node), or
+ * FC_FLOW_INVALID if problem j is malformed (sink not a vertex, U_j < 1, k_j < 1,
+ * N * k_j >= 2^31).  U_j * b_e may exceed 32 bits: capacities are clamped at N * k_j, which
+ * cannot change the value.  The call is asynchronous on `hip_stream` unless `stats` is
+ * non-null, in which case it synchronises the stream and fills *stats.
+ * d_workspace: device scratch of at least fc_maxflow_batch_workspace_bytes(g, n_problems)
+ * bytes, 256-byte aligned; contents are undefined afterwards; it may be reused by later
+ * calls on the same stream.  n_problems == 0 is valid and does nothing.
+ * Errors: FC_EINVAL, FC_EWORKSPACE, FC_EDEVICE; with stats: FC_ENOCONVERGE.
+ */
+size_t fc_maxflow_batch_workspace_bytes(const fc_graph *g, int64_t n_problems);
+int fc_maxflow_batch(const fc_graph *g, int64_t n_problems, const int32_t *d_sink,
+                     const int32_t *d_edge_mult, const int32_t *d_src_cap, int32_t *d_flow_out,
+                     void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                     const fc_options *options_or_null, fc_stats *stats_or_null);
+
+/* ------------------------------------------------------------------------------------------
+ * fc_feasible -- the verdict of Theorem 1 in its integer form (Theorem 3 / Appendix E.1) for
+ * each candidate j = (U_j, k_j):   feasible_j  <=>  min over v in V_c of F(s, v) >= N * k_j.
+ * Runs N max-flows per candidate (every compute node as sink) in one batch.
+ *
+ * d_edge_mult, d_src_cap: device int32 [n_candidates].  d_feasible_out: device uint8
+ * [n_candidates], 1 / 0 (0 also for malformed candidates).  d_witness_sink_or_null: device
+ * int32 [n_candidates]: the smallest compute-node id v with F(s, v) < N * k_j, or -1.
+ * d_flows_or_null: device int32 [n_candidates * N], candidate-major, compute nodes in
+ * increasing id order: all per-sink flow values.  Workspace as above with
+ * fc_feasible_workspace_bytes.  Asynchronous unless stats is non-null.
+ */
+size_t fc_feasible_workspace_bytes(const fc_graph *g, int32_t n_candidates);
+int fc_feasible(const fc_graph *g, int32_t n_candidates, const int32_t *d_edge_mult,
+                const int32_t *d_src_cap, uint8_t *d_feasible_out, int32_t *d_witness_sink_or_null,
+                int32_t *d_flows_or_null, void *d_workspace, size_t workspace_bytes,
+                void *hip_stream, const fc_options *options_or_null, fc_stats *stats_or_null);
+
+/* ------------------------------------------------------------------------------------------
+ * fc_opt_throughput_search -- the result of Algorithm 1 (Optimality Binary Search) and of
+ * Proposition 3:  1/x* = max over cuts S of |S n V_c| / B^+(S) as the reduced fraction p/q,
+ * then U = p / gcd(q, {b_e}) and k = q / gcd(q, {b_e}).
+ *
+ * The answer is unique, so any exact monotone search over Theorem 1's verdict returns it.
+ * Instead of the paper's bisection (whose dyadic midpoints need ever larger integers) this
+ * driver walks the Stern-Brocot tree between the paper's bounds (N-1)/B and N-1,
+ * B = min over compute nodes of B^-(v), testing up to `candidates_per_round` fractions of
+ * denominator <= B per fc_feasible round, so all device integers stay below 2^31.
+ * Synchronous; allocates its own device scratch; results go to host memory.
+ *
+ * trace_* (optional, host, capacity trace_capacity): every candidate (U, k) evaluated and its
+ * verdict, in evaluation order; *trace_len_or_null receives the total number evaluated (which
+ * may exceed trace_capacity).  Errors: FC_EDISCONNECTED (candidate N-1 is infeasible),
+ * FC_EOVERFLOW, FC_EINVAL, FC_EDEVICE, FC_ENOMEM.
+ */
+int fc_opt_throughput_search(const fc_graph *g, int32_t candidates_per_round,
+                             fc_rational *inv_xstar, fc_rational *U, int64_t *k,
+                             int32_t *rounds_or_null, void *hip_stream,
+                             const fc_options *options_or_null,
+                             int32_t *trace_U, int32_t *trace_k, uint8_t *trace_verdict,
+                             int32_t trace_capacity, int32_t *trace_len_or_null);
+
+/* The search logic alone, with the verdict supplied by the caller (host only, no GPU):
+ * `verdicts(ctx, n, U, k, out)` must set out[i] = 1 iff candidate U[i]/k[i] >= 1/x*, and return
+ * FC_OK or an error code, which is passed through.  n_compute = N, min_in_bw = B, gcd_bw =
+ * gcd{b_e}.  fc_opt_throughput_search is this function with fc_feasible as the callback. */
+typedef int (*fc_verdict_fn)(void *ctx, int32_t n, const int32_t *U, const int32_t *k, uint8_t *out);
+int fc_search_with_verdicts(int32_t n_compute, int64_t min_in_bw, int32_t gcd_bw,
+                            int32_t candidates_per_round, fc_verdict_fn verdicts, void *ctx,
+                            fc_rational *inv_xstar, fc_rational *U, int64_t *k,
+                            int32_t *rounds_or_null);
+
+const char *fc_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FC_MAXFLOW_H */

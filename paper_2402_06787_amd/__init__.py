@@ -1,0 +1,13 @@
+"""MI355X-native batched integer max-flow feasibility checks (the data-parallel hot path of
+ForestColl's schedule generator, arXiv 2402.06787).
+
+The product is the C-ABI library `libfcmaxflow.so` (HIP kernels for gfx950 + host driver);
+this package is its thin Python binding.  Build it with `python -m paper_2402_06787_amd.build`.
+"""
+from .binding import (FcError, Graph, GraphInfo, fc_options, fc_stats, fc_rational, load_library, strerror,
+                      fc_graph_build, fc_graph_upload, fc_graph_info, fc_graph_csr,
+                      fc_maxflow_batch_workspace_bytes, fc_maxflow_batch,
+                      fc_feasible_workspace_bytes, fc_feasible, fc_opt_throughput_search,
+                      fc_search_with_verdicts, LIB_PATH, EXPORTED)
+from .binding import (FC_OK, FC_EINVAL, FC_EOVERFLOW, FC_EDISCONNECTED, FC_ENOMEM, FC_EWORKSPACE, FC_EDEVICE,
+                      FC_ENOCONVERGE, FC_EUNSUPPORTED, FC_FLOW_INVALID, FC_FLOW_NOCONVERGE, FC_FLOW_UNSUPPORTED)

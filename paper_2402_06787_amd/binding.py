@@ -1,0 +1,320 @@
+"""Thin ctypes binding of libfcmaxflow.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see include/fc_maxflow.h).
+Device buffers are torch tensors on the GPU; torch is used for device memory and streams
+only.  There is no CPU fallback: if the shared library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from fractions import Fraction
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libfcmaxflow.so")
+
+FC_OK = 0
+FC_EINVAL, FC_EOVERFLOW, FC_EDISCONNECTED, FC_ENOMEM = -1, -2, -3, -4
+FC_EWORKSPACE, FC_EDEVICE, FC_ENOCONVERGE, FC_EUNSUPPORTED = -5, -6, -7, -8
+FC_FLOW_INVALID, FC_FLOW_NOCONVERGE, FC_FLOW_UNSUPPORTED = -1, -2, -3
+
+EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_free", "fc_graph_info", "fc_graph_csr",
+            "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_feasible_workspace_bytes",
+            "fc_feasible", "fc_opt_throughput_search", "fc_search_with_verdicts", "fc_strerror"]
+
+
+class FcError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+class fc_rational(ctypes.Structure):
+    _fields_ = [("num", ctypes.c_int64), ("den", ctypes.c_int64)]
+
+
+class fc_stats(ctypes.Structure):
+    _fields_ = [("pushes", ctypes.c_uint64), ("relabels", ctypes.c_uint64), ("arc_scans", ctypes.c_uint64),
+                ("global_relabels", ctypes.c_uint64), ("gr_arc_scans", ctypes.c_uint64),
+                ("level_steps", ctypes.c_uint64), ("discharges", ctypes.c_uint64),
+                ("not_converged", ctypes.c_uint64), ("device_ms", ctypes.c_float)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class fc_options(ctypes.Structure):
+    _fields_ = [("threads_per_problem", ctypes.c_int32), ("lanes_per_vertex", ctypes.c_int32),
+                ("global_relabel_steps", ctypes.c_int32), ("global_relabel_permille", ctypes.c_int32),
+                ("use_gap", ctypes.c_int32), ("use_label_table", ctypes.c_int32),
+                ("force_wide", ctypes.c_int32), ("max_level_steps", ctypes.c_int32),
+                ("src_cap_bound", ctypes.c_int32)]
+
+
+VERDICT_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32),
+                              ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_uint8))
+
+_lib = None
+
+
+def load_library():
+    """dlopen the in-tree library and declare the C signatures.  Raises if it is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2402_06787_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i32, i64, sz = c.c_void_p, c.c_int32, c.c_int64, c.c_size_t
+    lib.fc_graph_build.restype = c.c_int
+    lib.fc_graph_build.argtypes = [i32, i64, vp, vp, vp, vp, c.POINTER(vp)]
+    lib.fc_graph_upload.restype = c.c_int
+    lib.fc_graph_upload.argtypes = [i32, i64, vp, vp, vp, vp, c.POINTER(vp)]
+    lib.fc_graph_free.restype = c.c_int
+    lib.fc_graph_free.argtypes = [vp]
+    lib.fc_graph_info.restype = c.c_int
+    lib.fc_graph_info.argtypes = [vp, c.POINTER(i32), c.POINTER(i64), c.POINTER(i64), c.POINTER(i32),
+                                  c.POINTER(i32), c.POINTER(i32)]
+    lib.fc_graph_csr.restype = c.c_int
+    lib.fc_graph_csr.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.fc_maxflow_batch_workspace_bytes.restype = sz
+    lib.fc_maxflow_batch_workspace_bytes.argtypes = [vp, i64]
+    lib.fc_maxflow_batch.restype = c.c_int
+    lib.fc_maxflow_batch.argtypes = [vp, i64, vp, vp, vp, vp, vp, sz, vp, c.POINTER(fc_options), c.POINTER(fc_stats)]
+    lib.fc_feasible_workspace_bytes.restype = sz
+    lib.fc_feasible_workspace_bytes.argtypes = [vp, i32]
+    lib.fc_feasible.restype = c.c_int
+    lib.fc_feasible.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, sz, vp, c.POINTER(fc_options), c.POINTER(fc_stats)]
+    lib.fc_opt_throughput_search.restype = c.c_int
+    lib.fc_opt_throughput_search.argtypes = [vp, i32, c.POINTER(fc_rational), c.POINTER(fc_rational),
+                                             c.POINTER(i64), c.POINTER(i32), vp, c.POINTER(fc_options),
+                                             vp, vp, vp, i32, c.POINTER(i32)]
+    lib.fc_search_with_verdicts.restype = c.c_int
+    lib.fc_search_with_verdicts.argtypes = [i32, i64, i32, i32, VERDICT_FN, vp, c.POINTER(fc_rational),
+                                            c.POINTER(fc_rational), c.POINTER(i64), c.POINTER(i32)]
+    lib.fc_strerror.restype = c.c_char_p
+    lib.fc_strerror.argtypes = [c.c_int]
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().fc_strerror(int(code)).decode()
+
+
+def _check(code: int, where: str):
+    if code != FC_OK:
+        raise FcError(code, where)
+
+
+def _np(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _host_ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p) if a is not None and a.size else None
+
+
+def _opts(options):
+    if options is None:
+        return None
+    if isinstance(options, fc_options):
+        return ctypes.byref(options)
+    o = fc_options()
+    for key, val in dict(options).items():
+        setattr(o, key, int(val))
+    return ctypes.byref(o)
+
+
+@dataclass
+class GraphInfo:
+    n_compute: int
+    n_arcs_merged: int
+    min_in_bw_compute: int
+    max_bw: int
+    gcd_bw: int
+    is_eulerian: bool
+
+
+class Graph:
+    """Owns an fc_graph handle; freed on `close()` or garbage collection."""
+
+    def __init__(self, handle: int, n_vertices: int):
+        self.handle = ctypes.c_void_p(handle)
+        self.n_vertices = n_vertices
+
+    def close(self):
+        if self.handle:
+            load_library().fc_graph_free(self.handle)
+            self.handle = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+
+def _graph_call(fn_name, n_vertices, tail, head, bandwidth, is_compute) -> Graph:
+    lib = load_library()
+    tail = _np(tail, np.int32); head = _np(head, np.int32); bandwidth = _np(bandwidth, np.int32)
+    is_compute = _np(is_compute, np.uint8)
+    if not (tail.shape == head.shape == bandwidth.shape) or tail.ndim != 1:
+        raise ValueError("tail, head, bandwidth must be 1-d arrays of equal length")
+    if is_compute.shape != (int(n_vertices),):
+        raise ValueError("is_compute must have n_vertices entries")
+    out = ctypes.c_void_p(None)
+    rc = getattr(lib, fn_name)(int(n_vertices), int(tail.shape[0]), _host_ptr(tail), _host_ptr(head),
+                               _host_ptr(bandwidth), _host_ptr(is_compute), ctypes.byref(out))
+    _check(rc, fn_name)
+    return Graph(out.value, int(n_vertices))
+
+
+def fc_graph_build(n_vertices, tail, head, bandwidth, is_compute) -> Graph:
+    return _graph_call("fc_graph_build", n_vertices, tail, head, bandwidth, is_compute)
+
+
+def fc_graph_upload(n_vertices, tail, head, bandwidth, is_compute) -> Graph:
+    return _graph_call("fc_graph_upload", n_vertices, tail, head, bandwidth, is_compute)
+
+
+def fc_graph_info(g: Graph) -> GraphInfo:
+    c = ctypes
+    nc, m, mb, mx, gc, eu = c.c_int32(), c.c_int64(), c.c_int64(), c.c_int32(), c.c_int32(), c.c_int32()
+    _check(load_library().fc_graph_info(g.handle, c.byref(nc), c.byref(m), c.byref(mb), c.byref(mx),
+                                        c.byref(gc), c.byref(eu)), "fc_graph_info")
+    return GraphInfo(nc.value, m.value, mb.value, mx.value, gc.value, bool(eu.value))
+
+
+def fc_graph_csr(g: Graph):
+    info = fc_graph_info(g)
+    M = 2 * info.n_arcs_merged
+    row_ptr = np.zeros(g.n_vertices + 1, np.int32)
+    other = np.zeros(M, np.int32); pair = np.zeros(M, np.int32); bw = np.zeros(M, np.int32)
+    fwd = np.zeros(M, np.uint8)
+    _check(load_library().fc_graph_csr(g.handle, _host_ptr(row_ptr), _host_ptr(other), _host_ptr(pair),
+                                       _host_ptr(bw), _host_ptr(fwd)), "fc_graph_csr")
+    return row_ptr, other, pair, bw, fwd
+
+
+# ------------------------------------------------------------------ device calls (torch tensors)
+
+def _dev_ptr(t, dtype, n, name):
+    import torch
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous() or t.numel() < n:
+        raise ValueError(f"{name}: need a contiguous {dtype} device tensor with at least {n} elements")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def fc_maxflow_batch_workspace_bytes(g: Graph, n_problems: int) -> int:
+    return int(load_library().fc_maxflow_batch_workspace_bytes(g.handle, int(n_problems)))
+
+
+def fc_maxflow_batch(g: Graph, d_sink, d_edge_mult, d_src_cap, d_flow_out=None, d_workspace=None,
+                     stream=None, options=None, want_stats=False):
+    """Returns (d_flow_out, stats dict or None).  Allocates outputs/workspace with torch if not given."""
+    import torch
+    P = int(d_sink.numel())
+    if d_flow_out is None:
+        d_flow_out = torch.empty(P, dtype=torch.int32, device=d_sink.device)
+    need = fc_maxflow_batch_workspace_bytes(g, P)
+    if d_workspace is None:
+        d_workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=d_sink.device)
+    st = fc_stats() if want_stats else None
+    rc = load_library().fc_maxflow_batch(
+        g.handle, P, _dev_ptr(d_sink, torch.int32, P, "d_sink"), _dev_ptr(d_edge_mult, torch.int32, P, "d_edge_mult"),
+        _dev_ptr(d_src_cap, torch.int32, P, "d_src_cap"), _dev_ptr(d_flow_out, torch.int32, P, "d_flow_out"),
+        ctypes.c_void_p(d_workspace.data_ptr()), d_workspace.numel(), _stream_ptr(stream), _opts(options),
+        ctypes.byref(st) if st is not None else None)
+    _check(rc, "fc_maxflow_batch")
+    return d_flow_out, (st.as_dict() if st is not None else None)
+
+
+def fc_feasible_workspace_bytes(g: Graph, n_candidates: int) -> int:
+    return int(load_library().fc_feasible_workspace_bytes(g.handle, int(n_candidates)))
+
+
+def fc_feasible(g: Graph, d_edge_mult, d_src_cap, want_flows=False, want_witness=True, d_workspace=None,
+                stream=None, options=None, want_stats=False):
+    """Returns dict(feasible=uint8 tensor, witness=int32 tensor|None, flows=int32 [C, N]|None, stats)."""
+    import torch
+    C = int(d_edge_mult.numel())
+    dev = d_edge_mult.device
+    N = fc_graph_info(g).n_compute
+    feas = torch.empty(C, dtype=torch.uint8, device=dev)
+    wit = torch.empty(C, dtype=torch.int32, device=dev) if want_witness else None
+    flows = torch.empty(C * N, dtype=torch.int32, device=dev) if want_flows else None
+    need = fc_feasible_workspace_bytes(g, C)
+    if d_workspace is None:
+        d_workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    st = fc_stats() if want_stats else None
+    rc = load_library().fc_feasible(
+        g.handle, C, _dev_ptr(d_edge_mult, torch.int32, C, "d_edge_mult"), _dev_ptr(d_src_cap, torch.int32, C, "d_src_cap"),
+        _dev_ptr(feas, torch.uint8, C, "feasible"), _dev_ptr(wit, torch.int32, C, "witness"),
+        _dev_ptr(flows, torch.int32, C * N, "flows"), ctypes.c_void_p(d_workspace.data_ptr()), d_workspace.numel(),
+        _stream_ptr(stream), _opts(options), ctypes.byref(st) if st is not None else None)
+    _check(rc, "fc_feasible")
+    return {"feasible": feas, "witness": wit, "flows": flows.view(C, N) if flows is not None else None,
+            "stats": st.as_dict() if st is not None else None}
+
+
+def fc_opt_throughput_search(g: Graph, candidates_per_round: int = 16, stream=None, options=None,
+                             trace_capacity: int = 4096):
+    """Returns dict(inv_xstar=Fraction, U=Fraction, k=int, rounds=int, trace=[(U, k, verdict), ...])."""
+    c = ctypes
+    r1, r2, kk, rounds, tlen = fc_rational(), fc_rational(), c.c_int64(), c.c_int32(), c.c_int32()
+    tU = np.zeros(trace_capacity, np.int32); tk = np.zeros(trace_capacity, np.int32)
+    tv = np.zeros(trace_capacity, np.uint8)
+    rc = load_library().fc_opt_throughput_search(
+        g.handle, int(candidates_per_round), c.byref(r1), c.byref(r2), c.byref(kk), c.byref(rounds),
+        _stream_ptr(stream), _opts(options), _host_ptr(tU), _host_ptr(tk), _host_ptr(tv), trace_capacity, c.byref(tlen))
+    _check(rc, "fc_opt_throughput_search")
+    nt = min(tlen.value, trace_capacity)
+    return {"inv_xstar": Fraction(r1.num, r1.den), "U": Fraction(r2.num, r2.den), "k": int(kk.value),
+            "rounds": int(rounds.value), "trace": [(int(tU[i]), int(tk[i]), int(tv[i])) for i in range(nt)],
+            "trace_len": int(tlen.value)}
+
+
+def fc_search_with_verdicts(n_compute: int, min_in_bw: int, gcd_bw: int, candidates_per_round: int, verdict_fn):
+    """Host-only search logic.  `verdict_fn(list of (U, k))` returns a list of 0/1 verdicts
+    (or raises); returns dict(inv_xstar, U, k, rounds)."""
+    c = ctypes
+    err = []
+
+    def _cb(_ctx, n, pU, pk, pout):
+        try:
+            res = verdict_fn([(int(pU[i]), int(pk[i])) for i in range(n)])
+            for i in range(n):
+                pout[i] = 1 if res[i] else 0
+            return FC_OK
+        except Exception as exc:            # never let an exception cross the C boundary
+            err.append(exc)
+            return FC_EINVAL
+
+    cb = VERDICT_FN(_cb)
+    r1, r2, kk, rounds = fc_rational(), fc_rational(), c.c_int64(), c.c_int32()
+    rc = load_library().fc_search_with_verdicts(int(n_compute), int(min_in_bw), int(gcd_bw), int(candidates_per_round),
+                                               cb, None, c.byref(r1), c.byref(r2), c.byref(kk), c.byref(rounds))
+    if err:
+        raise err[0]
+    _check(rc, "fc_search_with_verdicts")
+    return {"inv_xstar": Fraction(r1.num, r1.den), "U": Fraction(r2.num, r2.den), "k": int(kk.value),
+            "rounds": int(rounds.value)}

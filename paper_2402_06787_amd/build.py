@@ -1,0 +1,49 @@
+"""Builds libfcmaxflow.so (host C++ + HIP kernels for gfx950) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+CSRC = os.path.join(PKG, "csrc")
+LIB = os.path.join(PKG, "libfcmaxflow.so")
+SOURCES = [os.path.join(CSRC, "fc_host.cpp"), os.path.join(CSRC, "fc_device.hip")]
+HEADERS = [os.path.join(CSRC, "fc_internal.h"), os.path.join(ROOT, "include", "fc_maxflow.h")]
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# packed-fp32 code generation is switched off for all device code of this project
+HIP_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-Wall", "-Wno-unused-function"]
+
+
+def is_stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
+
+
+def build_library(force: bool = False, verbose: bool = False) -> str:
+    """Compile the library.  Without `force` it is rebuilt only when a source is newer."""
+    if not force and not is_stale():
+        return LIB
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    obj_host = os.path.join(CSRC, "fc_host.o")
+    obj_dev = os.path.join(CSRC, "fc_device.o")
+    cmds = [
+        ["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-c", SOURCES[0], "-o", obj_host] + inc,
+        [HIPCC] + HIP_FLAGS + ["-c", SOURCES[1], "-o", obj_dev] + inc,
+        [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", obj_host, obj_dev, "-o", LIB + ".tmp"],
+    ]
+    for c in cmds:
+        if verbose:
+            print(" ".join(c), flush=True)
+        subprocess.check_call(c)
+    os.replace(LIB + ".tmp", LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(force=True, verbose=True))

@@ -1,0 +1,794 @@
+// Device side of the library: HIP kernels for gfx950 (MI355X) and the C-ABI entry points that
+// launch them.
+//
+// One workgroup solves one max-flow problem (sink v_j, edge multiplier U_j, source-arc capacity
+// k_j) of the auxiliary network of the paper's Section 5.2 with a level-synchronous
+// push-relabel (push-relabel is the algorithm family the paper names in Appendix C; the
+// schedule below is this library's own).  All per-problem state -- the flow on every topology
+// arc, the height and excess of every vertex -- lives in LDS; only the shared, read-only
+// topology (residual CSR records) is read from global memory, where it stays cache resident.
+//
+// The super-source is never materialised: its arcs (s, c) are saturated by the initial preflow
+// (excess k_j at every compute node, the sink included) and, because s keeps the largest height,
+// nothing is ever pushed back to it.  F(s, v_j) is the excess collected at the sink when no
+// vertex that can still reach the sink holds excess (min-cut theorem, Appendix E preamble).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "fc_internal.h"
+
+#define FC_NSTAT 8   // per-problem counters: pushes, relabels, arc_scans, grs, gr_arc_scans, level_steps, discharges, not_converged
+
+namespace {
+
+struct KParams {
+    int32_t n, N, m0;
+    const int32_t *row_ptr;
+    const int4 *arc_wide;
+    const uint2 *arc_compact;
+    const uint8_t *is_compute;
+    const uint16_t *labels;      // [n*n] or null
+    const int32_t *sink, *U, *k;
+    int32_t *flow_out;
+    uint32_t *stats;             // [P * FC_NSTAT] or null
+    int32_t gr_steps, gr_relabels, use_gap, max_steps;
+    int32_t wide_available;      // the 32-bit-state kernel is launched too
+};
+
+struct ArcRec { int32_t w, pair, bw, fwd; };
+
+template <bool COMPACT>
+__device__ __forceinline__ ArcRec load_arc(const KParams &p, int32_t a) {
+    ArcRec r;
+    if (COMPACT) {
+        uint2 q = p.arc_compact[a];
+        r.w = int32_t(q.x & 0x7fffu); r.fwd = int32_t((q.x >> 15) & 1u); r.pair = int32_t(q.x >> 16); r.bw = int32_t(q.y);
+    } else {
+        int4 q = p.arc_wide[a];
+        r.w = q.x; r.pair = q.y; r.bw = q.z; r.fwd = q.w;
+    }
+    return r;
+}
+
+__device__ __forceinline__ int32_t arc_cap(int32_t U, int32_t bw, int32_t NK) {
+    // capacity U * b_e clamped at N * k: no flow needs more than s can emit
+    long long c = (long long)U * (long long)bw;
+    return c > (long long)NK ? NK : int32_t(c);
+}
+
+// LDS scalars shared by a workgroup
+struct Shared {
+    int32_t count[2];      // length of the current level list (by step parity)
+    int32_t down[2];       // some push of this step went to a non-sink vertex
+    int32_t nrel[2];       // vertices relabeled in this step
+    int32_t hmax_next;     // largest finite new height assigned during this pass
+    int32_t rel_since;     // relabels since the last global relabel
+    int32_t tmp;           // scratch for rare scans
+    uint32_t st[FC_NSTAT];
+};
+
+template <typename HT>
+struct State {
+    HT *h;          // [n] height; n = "cannot reach the sink"
+    HT *list;       // [n] vertices of the level being processed
+    HT *lnew;       // [n] new height for list[i] (0 = none)
+    int32_t *e;     // [n] excess
+    Shared *sh;
+};
+
+// Compact vertices v with e[v] > 0, v != t, h[v] == d into st.list; returns after a barrier with
+// the list length.  `par` selects the scalar set.
+template <typename HT>
+__device__ __forceinline__ int32_t compact_level(const State<HT> &st, int32_t n, int32_t t, int32_t d, int32_t par) {
+    const int32_t tid = threadIdx.x, T = blockDim.x, lane = tid & 63;
+    for (int32_t base = 0; base < n; base += T) {
+        int32_t v = base + tid;
+        bool isd = false;
+        if (v < n) isd = (st.e[v] > 0) && (v != t) && (int32_t(st.h[v]) == d);
+        unsigned long long b = __ballot(isd);
+        if (b) {
+            int32_t pos = 0;
+            if (lane == 0) pos = atomicAdd(&st.sh->count[par], __popcll(b));
+            pos = __shfl(pos, 0);
+            if (isd) st.list[pos + __popcll(b & ((1ull << lane) - 1ull))] = HT(v);
+        }
+    }
+    __syncthreads();
+    return st.sh->count[par];
+}
+
+// max over v of h[v] subject to e[v] > 0, v != t, h[v] < below; 0 if none.  Two barriers.
+template <typename HT>
+__device__ __forceinline__ int32_t max_active_height_below(const State<HT> &st, int32_t n, int32_t t, int32_t below) {
+    const int32_t tid = threadIdx.x, T = blockDim.x;
+    if (tid == 0) st.sh->tmp = 0;
+    __syncthreads();
+    int32_t best = 0;
+    for (int32_t v = tid; v < n; v += T) {
+        int32_t hv = int32_t(st.h[v]);
+        if (st.e[v] > 0 && v != t && hv < below && hv > best) best = hv;
+    }
+    if (best > 0) atomicMax(&st.sh->tmp, best);
+    __syncthreads();
+    int32_t r = st.sh->tmp;
+    __syncthreads();
+    return r;
+}
+
+// Exact heights by backward breadth-first search from the sink over arcs with positive residual
+// capacity; vertices that cannot reach the sink get height n.  Ends with a barrier.
+template <bool COMPACT, int G, typename FT, typename HT>
+__device__ void global_relabel(const KParams &p, const State<HT> &st, const FT *f, int32_t t, int32_t U, int32_t NK,
+                               uint32_t &gr_scans) {
+    const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n;
+    const int32_t lg = tid & (G - 1), grp = tid / G, ngrp = T / G;
+    for (int32_t v = tid; v < n; v += T) st.h[v] = HT(v == t ? 0 : n);
+    if (tid == 0) st.sh->count[0] = 0;
+    __syncthreads();
+    for (int32_t d = 0;; ++d) {
+        int32_t par = d & 1;
+        // frontier: vertices at distance d (found by a scan; keeps the search free of queues and CAS)
+        for (int32_t base = 0; base < n; base += T) {
+            int32_t v = base + tid;
+            bool isd = v < n && int32_t(st.h[v]) == d;
+            unsigned long long b = __ballot(isd);
+            if (b) {
+                int32_t pos = 0;
+                if ((tid & 63) == 0) pos = atomicAdd(&st.sh->count[par], __popcll(b));
+                pos = __shfl(pos, 0);
+                if (isd) st.list[pos + __popcll(b & ((1ull << (tid & 63)) - 1ull))] = HT(v);
+            }
+        }
+        __syncthreads();
+        int32_t cnt = st.sh->count[par];
+        if (tid == 0) st.sh->count[par ^ 1] = 0;
+        if (cnt == 0) break;
+        for (int32_t i = grp; i < cnt; i += ngrp) {
+            int32_t w = int32_t(st.list[i]);
+            int32_t beg = p.row_ptr[w], end = p.row_ptr[w + 1];
+            for (int32_t a = beg + lg; a < end; a += G) {
+                ArcRec r = load_arc<COMPACT>(p, a);
+                ++gr_scans;
+                int32_t fv = int32_t(f[r.pair]);
+                // residual capacity of the arc r.w -> w
+                int32_t res = r.fwd ? fv : arc_cap(U, r.bw, NK) - fv;
+                if (res > 0 && int32_t(st.h[r.w]) == n) st.h[r.w] = HT(d + 1);   // same value from every writer
+            }
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+}
+
+template <bool COMPACT, int G>
+__global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
+    using FT = typename std::conditional<COMPACT, uint16_t, int32_t>::type;
+    using HT = typename std::conditional<COMPACT, uint16_t, int32_t>::type;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n, m0 = p.m0;
+    const int32_t j = blockIdx.x;
+
+    // ---- problem and its validity (uniform over the workgroup)
+    const int32_t t = p.sink[j], U = p.U[j], k = p.k[j];
+    const long long NKll = (long long)p.N * (long long)k;
+    const bool valid = t >= 0 && t < n && U >= 1 && k >= 1 && NKll < (1ll << 31);
+    if (!valid) {                       // both layouts write the same marker
+        if (tid == 0) p.flow_out[j] = FC_FLOW_INVALID;
+        return;
+    }
+    // the 16-bit layout holds flows up to 65535 = largest N*k it accepts; larger problems are left
+    // to the 32-bit kernel, which in turn skips the ones the 16-bit kernel took
+    const bool small = NKll <= 65535ll;
+    if (COMPACT) {
+        if (!small) { if (!p.wide_available && tid == 0) p.flow_out[j] = FC_FLOW_UNSUPPORTED; return; }
+    } else if (small && p.arc_compact != nullptr) return;
+    const int32_t NK = int32_t(NKll);
+
+    // ---- LDS carve-up
+    size_t off = 0;
+    FT *f = reinterpret_cast<FT *>(smem + off); off += (size_t(m0) * sizeof(FT) + 15) & ~size_t(15);
+    State<HT> st;
+    st.h = reinterpret_cast<HT *>(smem + off); off += (size_t(n) * sizeof(HT) + 15) & ~size_t(15);
+    st.list = reinterpret_cast<HT *>(smem + off); off += (size_t(n) * sizeof(HT) + 15) & ~size_t(15);
+    st.lnew = reinterpret_cast<HT *>(smem + off); off += (size_t(n) * sizeof(HT) + 15) & ~size_t(15);
+    st.e = reinterpret_cast<int32_t *>(smem + off); off += (size_t(n) * sizeof(int32_t) + 15) & ~size_t(15);
+    st.sh = reinterpret_cast<Shared *>(smem + off);
+
+    const int32_t lg = tid & (G - 1), grp = tid / G, ngrp = T / G;
+    const int32_t lane = tid & 63;
+    const unsigned long long gmask = (G == 64 ? ~0ull : ((1ull << G) - 1ull)) << (lane & ~(G - 1));
+
+    uint32_t c_push = 0, c_scan = 0, c_grscan = 0;            // per-thread counters
+    uint32_t c_rel = 0, c_gr = 0, c_step = 0, c_dis = 0;      // counted by one lane per event / thread 0
+
+    // ---- preflow: every arc (s, c) saturated, all topology arcs empty
+    {
+        uint32_t *fz = reinterpret_cast<uint32_t *>(f);
+        int32_t words = int32_t((size_t(m0) * sizeof(FT) + 3) / 4);
+        for (int32_t i = tid; i < words; i += T) fz[i] = 0u;
+        const bool have_labels = p.labels != nullptr;
+        for (int32_t v = tid; v < n; v += T) {
+            st.e[v] = p.is_compute[v] ? k : 0;
+            if (have_labels) st.h[v] = HT(p.labels[size_t(t) * size_t(n) + size_t(v)]);
+        }
+        if (tid == 0) {
+            st.sh->count[0] = st.sh->count[1] = 0; st.sh->down[0] = st.sh->down[1] = 0;
+            st.sh->nrel[0] = st.sh->nrel[1] = 0; st.sh->hmax_next = 0; st.sh->tmp = 0; st.sh->rel_since = 0;
+            for (int i = 0; i < FC_NSTAT; ++i) st.sh->st[i] = 0;
+        }
+        __syncthreads();
+        if (!have_labels) {
+            global_relabel<COMPACT, G>(p, st, f, t, U, NK, c_grscan);
+            if (tid == 0) { ++c_gr; st.sh->count[0] = st.sh->count[1] = 0; }
+            __syncthreads();
+        }
+    }
+
+    int32_t hmax = max_active_height_below(st, n, t, n);      // highest level holding excess
+    int32_t steps_since = 0, total_steps = 0, step = 0;
+    bool failed = false;
+
+    // ---- passes: sweep the height levels from the highest active one down to 1
+    while (hmax >= 1 && st.e[t] != NK) {
+        int32_t d = hmax;
+        bool done = false;
+        while (d >= 1) {
+            const int32_t par = step & 1;
+            const int32_t cnt = compact_level(st, n, t, d, par);          // barrier inside
+            if (tid == 0) { st.sh->count[par ^ 1] = 0; st.sh->down[par ^ 1] = 0; st.sh->nrel[par ^ 1] = 0; }
+
+            // discharge every vertex of the level: G lanes scan one vertex's residual arcs
+            for (int32_t i = grp; i < cnt; i += ngrp) {
+                const int32_t u = int32_t(st.list[i]);
+                int32_t rem = st.e[u];
+                const int32_t beg = p.row_ptr[u], end = p.row_ptr[u + 1];
+                int32_t minh = 0x7fffffff;
+                if (lg == 0) ++c_dis;
+                for (int32_t base = beg; base < end && rem > 0; base += G) {
+                    const int32_t a = base + lg;
+                    int32_t ra = 0, hw = 0, fv = 0;
+                    ArcRec r; r.w = 0; r.pair = 0; r.bw = 0; r.fwd = 0;
+                    if (a < end) {
+                        r = load_arc<COMPACT>(p, a);
+                        ++c_scan;
+                        fv = int32_t(f[r.pair]);
+                        ra = r.fwd ? arc_cap(U, r.bw, NK) - fv : fv;
+                        hw = int32_t(st.h[r.w]);
+                    }
+                    const bool adm = ra > 0 && hw + 1 == d;
+                    if (ra > 0 && !adm && hw < minh) minh = hw;
+                    const unsigned long long bal = __ballot(adm) & gmask;
+                    if (bal) {
+                        int32_t delta = 0, rem_new;
+                        const bool first = adm && ((bal & ((1ull << lane) - 1ull)) == 0ull);
+                        const unsigned long long absorbed = __ballot(first && ra >= rem) & gmask;
+                        if (absorbed) {                       // first admissible arc takes everything
+                            if (first) delta = rem;
+                            rem_new = 0;
+                        } else {                              // split the excess in arc order
+                            const int32_t x = adm ? ra : 0;
+                            int32_t incl = x;
+#pragma unroll
+                            for (int s = 1; s < G; s <<= 1) {
+                                int32_t y = __shfl_up(incl, s, G);
+                                if (lg >= s) incl += y;
+                            }
+                            const int32_t total = __shfl(incl, G - 1, G);
+                            const int32_t excl = incl - x;
+                            delta = rem - excl; if (delta > x) delta = x; if (delta < 0) delta = 0;
+                            rem_new = total >= rem ? 0 : rem - total;
+                        }
+                        if (delta > 0) {
+                            f[r.pair] = FT(r.fwd ? fv + delta : fv - delta);
+                            atomicAdd(&st.e[r.w], delta);
+                            if (r.w != t) st.sh->down[par] = 1;
+                            ++c_push;
+                        }
+                        rem = rem_new;
+                    }
+                }
+                if (rem > 0) {                                // every admissible arc is saturated: relabel
+#pragma unroll
+                    for (int s = G / 2; s > 0; s >>= 1) {
+                        int32_t y = __shfl_xor(minh, s, G);
+                        if (y < minh) minh = y;
+                    }
+                    if (lg == 0) {
+                        st.lnew[i] = HT(minh >= n - 1 ? n : minh + 1);
+                        st.sh->nrel[par] = 1;
+                        ++c_rel;
+                    }
+                } else if (lg == 0) st.lnew[i] = HT(0);
+                if (lg == 0) st.e[u] = rem;
+            }
+            __syncthreads();
+            const int32_t nrel = st.sh->nrel[par], down = st.sh->down[par];
+            ++step; ++steps_since; ++total_steps;
+            if (tid == 0) ++c_step;
+
+            if (nrel) {
+                // apply the new heights (deferred so that the level's scans all saw the same heights)
+                for (int32_t i = tid; i < cnt; i += T) {
+                    int32_t nh = int32_t(st.lnew[i]);
+                    if (nh) {
+                        st.h[int32_t(st.list[i])] = HT(nh);
+                        atomicAdd(&st.sh->rel_since, 1);
+                        if (nh < n) atomicMax(&st.sh->hmax_next, nh);
+                    }
+                }
+                __syncthreads();
+                if (p.use_gap) {
+                    // level d lost vertices; if it is now empty nothing above it can reach the sink
+                    int32_t mine = 0;
+                    for (int32_t v = tid; v < n; v += T) mine |= (int32_t(st.h[v]) == d);
+                    if (!__syncthreads_or(mine)) {
+                        for (int32_t v = tid; v < n; v += T) {
+                            int32_t hv = int32_t(st.h[v]);
+                            if (hv > d && hv < n) st.h[v] = HT(n);
+                        }
+                        if (tid == 0) st.sh->hmax_next = 0;
+                        __syncthreads();
+                    }
+                }
+            }
+            if (st.e[t] == NK) { done = true; break; }
+            if (total_steps >= p.max_steps) { failed = true; done = true; break; }
+            if (down) d = d - 1;
+            else if (d > 1) d = max_active_height_below(st, n, t, d);
+            else d = 0;
+        }
+        if (done) break;
+        const int32_t rel_total = st.sh->rel_since;     // last written before a barrier: uniform
+        if (rel_total > 0 && (rel_total >= p.gr_relabels || steps_since >= p.gr_steps)) {
+            global_relabel<COMPACT, G>(p, st, f, t, U, NK, c_grscan);
+            if (tid == 0) { ++c_gr; st.sh->count[0] = st.sh->count[1] = 0; st.sh->hmax_next = 0; st.sh->rel_since = 0; }
+            steps_since = 0;
+            __syncthreads();
+            hmax = max_active_height_below(st, n, t, n);
+        } else {
+            hmax = st.sh->hmax_next;
+            __syncthreads();
+            if (tid == 0) st.sh->hmax_next = 0;
+        }
+    }
+
+    __syncthreads();
+    if (tid == 0) p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : st.e[t];
+    if (p.stats) {
+        atomicAdd(&st.sh->st[0], c_push); atomicAdd(&st.sh->st[2], c_scan); atomicAdd(&st.sh->st[4], c_grscan);
+        if (c_rel) atomicAdd(&st.sh->st[1], c_rel);
+        if (c_dis) atomicAdd(&st.sh->st[6], c_dis);
+        if (tid == 0) { st.sh->st[3] = c_gr; st.sh->st[5] = c_step; st.sh->st[7] = failed ? 1u : 0u; }
+        __syncthreads();
+        if (tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = st.sh->st[tid];
+    }
+}
+
+// Initial exact labels for every possible sink: breadth-first distances to the sink in the
+// topology (all arcs have positive capacity before any flow is pushed).  One workgroup per sink.
+__global__ void __launch_bounds__(256) fc_label_table_kernel(int32_t n, const int32_t *row_ptr, const int4 *arc,
+                                                             uint16_t *labels) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    int32_t *h = reinterpret_cast<int32_t *>(smem);
+    __shared__ int32_t changed;
+    const int32_t t = blockIdx.x, tid = threadIdx.x, T = blockDim.x;
+    for (int32_t v = tid; v < n; v += T) h[v] = v == t ? 0 : n;
+    __syncthreads();
+    for (int32_t d = 0; d < n; ++d) {
+        if (tid == 0) changed = 0;
+        __syncthreads();
+        for (int32_t w = tid; w < n; w += T) {
+            if (h[w] != d) continue;
+            for (int32_t a = row_ptr[w]; a < row_ptr[w + 1]; ++a) {
+                int4 r = arc[a];
+                if (!r.w && h[r.x] == n) { h[r.x] = d + 1; changed = 1; }   // topology arc r.x -> w
+            }
+        }
+        __syncthreads();
+        int32_t c = changed;
+        __syncthreads();
+        if (!c) break;
+    }
+    for (int32_t v = tid; v < n; v += T) labels[size_t(t) * size_t(n) + size_t(v)] = uint16_t(h[v]);
+}
+
+__global__ void fc_expand_candidates_kernel(int32_t C, int32_t N, const int32_t *compute_ids, const int32_t *cU,
+                                            const int32_t *ck, int32_t *sink, int32_t *U, int32_t *k) {
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)C * N) return;
+    int32_t c = int32_t(idx / N), s = int32_t(idx % N);
+    sink[idx] = compute_ids[s]; U[idx] = cU[c]; k[idx] = ck[c];
+}
+
+// feasible_c = AND over sinks of [F(s, v) >= N * k_c] (Theorem 1 / Theorem 3); one workgroup per candidate
+__global__ void __launch_bounds__(256) fc_verdict_kernel(int32_t N, const int32_t *compute_ids, const int32_t *ck,
+                                                         const int32_t *cU, const int32_t *flows, uint8_t *feasible,
+                                                         int32_t *witness) {
+    __shared__ int32_t s_wit;
+    const int32_t c = blockIdx.x, tid = threadIdx.x;
+    if (tid == 0) s_wit = 0x7fffffff;
+    __syncthreads();
+    const int32_t k = ck[c], U = cU[c];
+    const long long need = (long long)N * (long long)k;
+    const bool ok_cand = U >= 1 && k >= 1 && need < (1ll << 31);
+    int32_t best = 0x7fffffff;
+    for (int32_t s = tid; s < N; s += blockDim.x) {
+        int32_t fl = flows[size_t(c) * size_t(N) + size_t(s)];
+        if (fl < 0 || (long long)fl < need) { int32_t v = compute_ids[s]; if (v < best) best = v; }
+    }
+    if (best != 0x7fffffff) atomicMin(&s_wit, best);
+    __syncthreads();
+    if (tid == 0) {
+        bool feas = ok_cand && s_wit == 0x7fffffff;
+        feasible[c] = feas ? 1 : 0;
+        if (witness) witness[c] = (feas || !ok_cand) ? -1 : s_wit;
+    }
+}
+
+__global__ void __launch_bounds__(256) fc_stats_reduce_kernel(long long P, const uint32_t *per_problem,
+                                                              unsigned long long *totals) {
+    __shared__ unsigned long long acc[FC_NSTAT];
+    if (threadIdx.x < FC_NSTAT) acc[threadIdx.x] = 0ull;
+    __syncthreads();
+    unsigned long long mine[FC_NSTAT];
+    for (int i = 0; i < FC_NSTAT; ++i) mine[i] = 0ull;
+    for (long long j = (long long)blockIdx.x * blockDim.x + threadIdx.x; j < P; j += (long long)gridDim.x * blockDim.x)
+        for (int i = 0; i < FC_NSTAT; ++i) mine[i] += per_problem[size_t(j) * FC_NSTAT + i];
+    for (int i = 0; i < FC_NSTAT; ++i) if (mine[i]) atomicAdd(&acc[i], mine[i]);
+    __syncthreads();
+    if (threadIdx.x < FC_NSTAT && acc[threadIdx.x]) atomicAdd(&totals[threadIdx.x], acc[threadIdx.x]);
+}
+
+// ------------------------------------------------------------------------------------------ host helpers
+
+#define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { return FC_EDEVICE; } } while (0)
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t lds_bytes(const fc_graph *g, bool compact) {
+    size_t ft = compact ? 2 : 4, ht = compact ? 2 : 4;
+    size_t b = align_up(size_t(g->m0) * ft, 16) + 3 * align_up(size_t(g->n) * ht, 16) +
+               align_up(size_t(g->n) * 4, 16) + sizeof(Shared);
+    return align_up(b, 16);
+}
+
+bool compact_ids_fit(const fc_graph *g) { return g->n <= 32767 && g->m0 <= 65535; }
+
+struct Resolved {
+    int32_t T, G, gr_steps, gr_relabels, use_gap, use_labels, force_wide, max_steps, src_cap_bound;
+};
+
+int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
+    fc_options z; std::memset(&z, 0, sizeof z);
+    if (!o) o = &z;
+    int32_t T = o->threads_per_problem;
+    if (T == 0) T = g->n >= 512 ? 256 : (g->n >= 96 ? 128 : 64);
+    if (T < 64 || T > 1024 || (T % 64) != 0) return FC_EINVAL;
+    int32_t G = o->lanes_per_vertex;
+    if (G == 0) {
+        double avg = g->n > 0 ? double(2 * g->m0) / double(g->n) : 1.0;
+        G = 4; while (G < 64 && double(G) < 0.75 * avg) G *= 2;
+    }
+    if (G < 2 || G > 64 || (G & (G - 1)) != 0) return FC_EINVAL;
+    if (G == 2) G = 4;
+    r->T = T; r->G = G;
+    r->gr_steps = o->global_relabel_steps > 0 ? o->global_relabel_steps : 32;
+    int32_t permille = o->global_relabel_permille > 0 ? o->global_relabel_permille : 100;
+    r->gr_relabels = std::max<int32_t>(1, int32_t((long long)g->n * permille / 1000));
+    if (o->use_gap < 0 || o->use_gap > 2 || o->use_label_table < 0 || o->use_label_table > 2) return FC_EINVAL;
+    r->use_gap = o->use_gap != 2;
+    r->use_labels = o->use_label_table != 2;
+    r->force_wide = o->force_wide != 0;
+    r->max_steps = o->max_level_steps > 0 ? o->max_level_steps : std::max<int32_t>(100000, 200 * g->n);
+    if (o->src_cap_bound < 0) return FC_EINVAL;
+    r->src_cap_bound = o->src_cap_bound;
+    return FC_OK;
+}
+
+template <bool COMPACT, int G>
+int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_t stream) {
+    auto kern = fc_push_relabel_kernel<COMPACT, G>;
+    static size_t lds_allowed = 0;                  // per instantiation; raised on demand
+    if (lds > lds_allowed) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
+        lds_allowed = lds;
+    }
+    hipLaunchKernelGGL(kern, dim3(unsigned(P)), dim3(unsigned(T)), lds, stream, kp);
+    HIP_TRY(hipGetLastError());
+    return FC_OK;
+}
+
+template <bool COMPACT>
+int launch_g(const KParams &kp, long long P, int32_t T, int32_t G, size_t lds, hipStream_t stream) {
+    switch (G) {
+        case 4: return launch_one<COMPACT, 4>(kp, P, T, lds, stream);
+        case 8: return launch_one<COMPACT, 8>(kp, P, T, lds, stream);
+        case 16: return launch_one<COMPACT, 16>(kp, P, T, lds, stream);
+        case 32: return launch_one<COMPACT, 32>(kp, P, T, lds, stream);
+        case 64: return launch_one<COMPACT, 64>(kp, P, T, lds, stream);
+    }
+    return FC_EINVAL;
+}
+
+struct StatsScratch { uint32_t *per_problem; unsigned long long *totals; };
+
+// Launch the solver kernels for P problems.  stats_ws: null, or room for P*FC_NSTAT u32 + FC_NSTAT u64.
+int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32_t *d_U, const int32_t *d_k,
+              int32_t *d_flow, const Resolved &opt, hipStream_t stream, uint32_t *d_stats_pp) {
+    KParams kp;
+    kp.n = g->n; kp.N = g->N; kp.m0 = int32_t(g->m0);
+    kp.row_ptr = g->d_row_ptr;
+    kp.arc_wide = reinterpret_cast<const int4 *>(g->d_arc_wide);
+    const bool compact_possible = !opt.force_wide && g->d_arc_compact != nullptr &&
+                                  lds_bytes(g, true) <= size_t(g->lds_limit);
+    bool wide_possible = lds_bytes(g, false) <= size_t(g->lds_limit);
+    if (!compact_possible && !wide_possible) return FC_EUNSUPPORTED;
+    // the caller vouches that every N * k_j fits the 16-bit layout: skip the 32-bit launch
+    if (compact_possible && opt.src_cap_bound > 0 && (long long)g->N * opt.src_cap_bound <= 65535ll) wide_possible = false;
+    kp.arc_compact = compact_possible ? reinterpret_cast<const uint2 *>(g->d_arc_compact) : nullptr;
+    kp.is_compute = g->d_is_compute;
+    kp.labels = opt.use_labels ? g->d_labels : nullptr;
+    kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.flow_out = d_flow; kp.stats = d_stats_pp;
+    kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
+    kp.wide_available = wide_possible ? 1 : 0;
+    const long long CH = 1ll << 30;                     // grid.x limit
+    for (long long first = 0; first < P; first += CH) {
+        long long cnt = std::min(CH, P - first);
+        KParams q = kp;
+        q.sink += first; q.U += first; q.k += first; q.flow_out += first;
+        if (q.stats) q.stats += size_t(first) * FC_NSTAT;
+        if (compact_possible) {
+            int rc = launch_g<true>(q, cnt, opt.T, opt.G, lds_bytes(g, true), stream);
+            if (rc != FC_OK) return rc;
+        }
+        if (wide_possible) {
+            int rc = launch_g<false>(q, cnt, opt.T, opt.G, lds_bytes(g, false), stream);
+            if (rc != FC_OK) return rc;
+        }
+    }
+    return FC_OK;
+}
+
+int fill_stats(long long P, uint32_t *d_pp, unsigned long long *d_tot, hipStream_t stream, hipEvent_t ev0,
+               hipEvent_t ev1, fc_stats *out) {
+    HIP_TRY(hipMemsetAsync(d_tot, 0, sizeof(unsigned long long) * FC_NSTAT, stream));
+    if (P > 0) {
+        unsigned blocks = unsigned(std::min<long long>((P + 255) / 256, 1024));
+        hipLaunchKernelGGL(fc_stats_reduce_kernel, dim3(blocks), dim3(256), 0, stream, P, d_pp, d_tot);
+        HIP_TRY(hipGetLastError());
+    }
+    unsigned long long h[FC_NSTAT];
+    HIP_TRY(hipMemcpyAsync(h, d_tot, sizeof h, hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, ev0, ev1));
+    out->pushes = h[0]; out->relabels = h[1]; out->arc_scans = h[2]; out->global_relabels = h[3];
+    out->gr_arc_scans = h[4]; out->level_steps = h[5]; out->discharges = h[6]; out->not_converged = h[7];
+    out->device_ms = ms;
+    return FC_OK;
+}
+
+size_t stats_bytes(long long P) { return align_up(size_t(P) * FC_NSTAT * 4, 256) + 256; }
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------ C ABI
+
+extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
+                               const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out) {
+    if (!out) return FC_EINVAL;
+    fc_graph *g = nullptr;
+    int rc = fc_host_build(n_vertices, n_arcs, tail, head, bandwidth, is_compute, &g);
+    if (rc != FC_OK) return rc;
+    auto fail = [&](int code) { fc_graph_free(g); return code; };
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(FC_EDEVICE);
+    g->device = dev;
+    int lds = 0, cus = 0;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return fail(FC_EDEVICE);
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return fail(FC_EDEVICE);
+    g->lds_limit = lds; g->n_cu = cus;
+    if (lds_bytes(g, false) > size_t(lds) && !(compact_ids_fit(g) && lds_bytes(g, true) <= size_t(lds)))
+        return fail(FC_EUNSUPPORTED);
+
+    const size_t M = size_t(2 * g->m0), n = size_t(g->n);
+    try {
+        std::vector<int4> wide(M ? M : 1);
+        for (size_t i = 0; i < M; ++i) wide[i] = make_int4(g->other[i], g->pair[i], g->bw[i], g->fwd[i]);
+        g->on_device = true;
+        if (hipMalloc(&g->d_row_ptr, sizeof(int32_t) * (n + 1)) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMalloc(&g->d_arc_wide, sizeof(int4) * (M ? M : 1)) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMalloc(&g->d_is_compute, n) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMalloc(&g->d_compute_ids, sizeof(int32_t) * size_t(g->N)) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMemcpy(g->d_row_ptr, g->row_ptr.data(), sizeof(int32_t) * (n + 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMemcpy(g->d_arc_wide, wide.data(), sizeof(int4) * M, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMemcpy(g->d_is_compute, g->is_compute.data(), n, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMemcpy(g->d_compute_ids, g->compute_ids.data(), sizeof(int32_t) * size_t(g->N), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+        if (compact_ids_fit(g)) {
+            std::vector<uint2> cmp(M ? M : 1);
+            for (size_t i = 0; i < M; ++i)
+                cmp[i] = make_uint2(uint32_t(g->other[i]) | (uint32_t(g->fwd[i]) << 15) | (uint32_t(g->pair[i]) << 16), uint32_t(g->bw[i]));
+            if (hipMalloc(&g->d_arc_compact, sizeof(uint2) * (M ? M : 1)) != hipSuccess) return fail(FC_EDEVICE);
+            if (hipMemcpy(g->d_arc_compact, cmp.data(), sizeof(uint2) * M, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+        }
+        // per-sink exact initial labels, while the table stays small (n^2 16-bit entries)
+        if (n <= 8192 && n * 4 <= size_t(lds)) {
+            if (hipMalloc(&g->d_labels, n * n * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
+            hipLaunchKernelGGL(fc_label_table_kernel, dim3(unsigned(n)), dim3(256), n * 4, 0, g->n, g->d_row_ptr,
+                               reinterpret_cast<const int4 *>(g->d_arc_wide), g->d_labels);
+            if (hipGetLastError() != hipSuccess) return fail(FC_EDEVICE);
+            if (hipDeviceSynchronize() != hipSuccess) return fail(FC_EDEVICE);
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(FC_ENOMEM);
+    }
+    *out = g;
+    return FC_OK;
+}
+
+extern "C" int fc_graph_free(fc_graph *g) {
+    if (!g) return FC_OK;
+    if (g->on_device) {
+        if (g->d_row_ptr) (void)hipFree(g->d_row_ptr);
+        if (g->d_arc_wide) (void)hipFree(g->d_arc_wide);
+        if (g->d_arc_compact) (void)hipFree(g->d_arc_compact);
+        if (g->d_is_compute) (void)hipFree(g->d_is_compute);
+        if (g->d_compute_ids) (void)hipFree(g->d_compute_ids);
+        if (g->d_labels) (void)hipFree(g->d_labels);
+    }
+    delete g;
+    return FC_OK;
+}
+
+extern "C" size_t fc_maxflow_batch_workspace_bytes(const fc_graph *g, int64_t n_problems) {
+    if (!g || n_problems < 0) return 0;
+    return stats_bytes(n_problems);
+}
+
+extern "C" int fc_maxflow_batch(const fc_graph *g, int64_t n_problems, const int32_t *d_sink,
+                                const int32_t *d_edge_mult, const int32_t *d_src_cap, int32_t *d_flow_out,
+                                void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                                const fc_options *options_or_null, fc_stats *stats_or_null) {
+    if (!g || n_problems < 0) return FC_EINVAL;
+    if (!g->on_device) return FC_EDEVICE;
+    Resolved opt;
+    int rc = resolve_options(g, options_or_null, &opt);
+    if (rc != FC_OK) return rc;
+    if (n_problems == 0) { if (stats_or_null) std::memset(stats_or_null, 0, sizeof *stats_or_null); return FC_OK; }
+    if (!d_sink || !d_edge_mult || !d_src_cap || !d_flow_out) return FC_EINVAL;
+    if (!d_workspace || workspace_bytes < stats_bytes(n_problems) || (reinterpret_cast<uintptr_t>(d_workspace) & 255u)) return FC_EWORKSPACE;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    uint32_t *d_pp = reinterpret_cast<uint32_t *>(d_workspace);
+    unsigned long long *d_tot = reinterpret_cast<unsigned long long *>(reinterpret_cast<unsigned char *>(d_workspace) + align_up(size_t(n_problems) * FC_NSTAT * 4, 256));
+    if (!stats_or_null) return run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, nullptr);
+
+    hipEvent_t ev0, ev1;
+    HIP_TRY(hipEventCreate(&ev0));
+    if (hipEventCreate(&ev1) != hipSuccess) { (void)hipEventDestroy(ev0); return FC_EDEVICE; }
+    auto done = [&](int code) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); return code; };
+    if (hipEventRecord(ev0, stream) != hipSuccess) return done(FC_EDEVICE);
+    rc = run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, d_pp);
+    if (rc != FC_OK) return done(rc);
+    if (hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
+    rc = fill_stats(n_problems, d_pp, d_tot, stream, ev0, ev1, stats_or_null);
+    if (rc != FC_OK) return done(rc);
+    return done(stats_or_null->not_converged ? FC_ENOCONVERGE : FC_OK);
+}
+
+extern "C" size_t fc_feasible_workspace_bytes(const fc_graph *g, int32_t n_candidates) {
+    if (!g || n_candidates < 0) return 0;
+    size_t P = size_t(n_candidates) * size_t(g->N);
+    return 4 * align_up(P * 4, 256) + stats_bytes((long long)P);
+}
+
+extern "C" int fc_feasible(const fc_graph *g, int32_t n_candidates, const int32_t *d_edge_mult,
+                           const int32_t *d_src_cap, uint8_t *d_feasible_out, int32_t *d_witness_sink_or_null,
+                           int32_t *d_flows_or_null, void *d_workspace, size_t workspace_bytes,
+                           void *hip_stream, const fc_options *options_or_null, fc_stats *stats_or_null) {
+    if (!g || n_candidates < 0) return FC_EINVAL;
+    if (!g->on_device) return FC_EDEVICE;
+    Resolved opt;
+    int rc = resolve_options(g, options_or_null, &opt);
+    if (rc != FC_OK) return rc;
+    if (n_candidates == 0) { if (stats_or_null) std::memset(stats_or_null, 0, sizeof *stats_or_null); return FC_OK; }
+    if (!d_edge_mult || !d_src_cap || !d_feasible_out) return FC_EINVAL;
+    if (!d_workspace || workspace_bytes < fc_feasible_workspace_bytes(g, n_candidates) || (reinterpret_cast<uintptr_t>(d_workspace) & 255u)) return FC_EWORKSPACE;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    const long long P = (long long)n_candidates * g->N;
+    unsigned char *ws = reinterpret_cast<unsigned char *>(d_workspace);
+    size_t slab = align_up(size_t(P) * 4, 256);
+    int32_t *d_sink = reinterpret_cast<int32_t *>(ws), *d_U = reinterpret_cast<int32_t *>(ws + slab),
+            *d_k = reinterpret_cast<int32_t *>(ws + 2 * slab);
+    int32_t *d_flow = d_flows_or_null ? d_flows_or_null : reinterpret_cast<int32_t *>(ws + 3 * slab);
+    uint32_t *d_pp = reinterpret_cast<uint32_t *>(ws + 4 * slab);
+    unsigned long long *d_tot = reinterpret_cast<unsigned long long *>(ws + 4 * slab + align_up(size_t(P) * FC_NSTAT * 4, 256));
+
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (stats_or_null) {
+        HIP_TRY(hipEventCreate(&ev0));
+        if (hipEventCreate(&ev1) != hipSuccess) { (void)hipEventDestroy(ev0); return FC_EDEVICE; }
+    }
+    auto done = [&](int code) { if (ev0) (void)hipEventDestroy(ev0); if (ev1) (void)hipEventDestroy(ev1); return code; };
+    hipLaunchKernelGGL(fc_expand_candidates_kernel, dim3(unsigned((P + 255) / 256)), dim3(256), 0, stream,
+                       n_candidates, g->N, g->d_compute_ids, d_edge_mult, d_src_cap, d_sink, d_U, d_k);
+    if (hipGetLastError() != hipSuccess) return done(FC_EDEVICE);
+    // device_ms brackets the solver kernel(s) only
+    if (stats_or_null && hipEventRecord(ev0, stream) != hipSuccess) return done(FC_EDEVICE);
+    rc = run_batch(g, P, d_sink, d_U, d_k, d_flow, opt, stream, stats_or_null ? d_pp : nullptr);
+    if (rc != FC_OK) return done(rc);
+    if (stats_or_null && hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
+    hipLaunchKernelGGL(fc_verdict_kernel, dim3(unsigned(n_candidates)), dim3(256), 0, stream, g->N, g->d_compute_ids,
+                       d_src_cap, d_edge_mult, d_flow, d_feasible_out, d_witness_sink_or_null);
+    if (hipGetLastError() != hipSuccess) return done(FC_EDEVICE);
+    if (!stats_or_null) return done(FC_OK);
+    rc = fill_stats(P, d_pp, d_tot, stream, ev0, ev1, stats_or_null);
+    if (rc != FC_OK) return done(rc);
+    return done(stats_or_null->not_converged ? FC_ENOCONVERGE : FC_OK);
+}
+
+namespace {
+struct SearchCtx {
+    const fc_graph *g; hipStream_t stream; const fc_options *opt;
+    int32_t *d_U, *d_k; uint8_t *d_v; void *d_ws; size_t ws_bytes; int32_t cap;
+    int32_t *tU, *tk; uint8_t *tv; int32_t tcap; int32_t tlen;
+};
+int search_verdicts(void *vctx, int32_t n, const int32_t *U, const int32_t *k, uint8_t *out) {
+    SearchCtx *c = static_cast<SearchCtx *>(vctx);
+    if (n > c->cap) return FC_EINVAL;
+    fc_options o; std::memset(&o, 0, sizeof o);
+    if (c->opt) o = *c->opt;
+    o.src_cap_bound = 0;
+    for (int32_t i = 0; i < n; ++i) o.src_cap_bound = std::max(o.src_cap_bound, k[i]);
+    HIP_TRY(hipMemcpyAsync(c->d_U, U, sizeof(int32_t) * size_t(n), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipMemcpyAsync(c->d_k, k, sizeof(int32_t) * size_t(n), hipMemcpyHostToDevice, c->stream));
+    int rc = fc_feasible(c->g, n, c->d_U, c->d_k, c->d_v, nullptr, nullptr, c->d_ws, c->ws_bytes, c->stream, &o, nullptr);
+    if (rc != FC_OK) return rc;
+    HIP_TRY(hipMemcpyAsync(out, c->d_v, size_t(n), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    for (int32_t i = 0; i < n; ++i) {
+        if (c->tlen < c->tcap) {
+            if (c->tU) c->tU[c->tlen] = U[i];
+            if (c->tk) c->tk[c->tlen] = k[i];
+            if (c->tv) c->tv[c->tlen] = out[i];
+        }
+        c->tlen++;
+    }
+    return FC_OK;
+}
+}  // namespace
+
+extern "C" int fc_opt_throughput_search(const fc_graph *g, int32_t candidates_per_round, fc_rational *inv_xstar,
+                                        fc_rational *U, int64_t *k, int32_t *rounds_or_null, void *hip_stream,
+                                        const fc_options *options_or_null, int32_t *trace_U, int32_t *trace_k,
+                                        uint8_t *trace_verdict, int32_t trace_capacity, int32_t *trace_len_or_null) {
+    if (!g || !inv_xstar || !U || !k || candidates_per_round < 1 || candidates_per_round > 4096 || trace_capacity < 0) return FC_EINVAL;
+    if (!g->on_device) return FC_EDEVICE;
+    Resolved opt;
+    int rc = resolve_options(g, options_or_null, &opt);
+    if (rc != FC_OK) return rc;
+    SearchCtx c; std::memset(&c, 0, sizeof c);
+    c.g = g; c.stream = reinterpret_cast<hipStream_t>(hip_stream); c.opt = options_or_null;
+    c.cap = std::max<int32_t>(candidates_per_round, 2);
+    c.tU = trace_U; c.tk = trace_k; c.tv = trace_verdict; c.tcap = trace_capacity; c.tlen = 0;
+    c.ws_bytes = fc_feasible_workspace_bytes(g, c.cap);
+    auto cleanup = [&]() {
+        if (c.d_U) (void)hipFree(c.d_U); if (c.d_k) (void)hipFree(c.d_k);
+        if (c.d_v) (void)hipFree(c.d_v); if (c.d_ws) (void)hipFree(c.d_ws);
+    };
+    if (hipMalloc(&c.d_U, sizeof(int32_t) * size_t(c.cap)) != hipSuccess || hipMalloc(&c.d_k, sizeof(int32_t) * size_t(c.cap)) != hipSuccess ||
+        hipMalloc(&c.d_v, size_t(c.cap)) != hipSuccess || hipMalloc(&c.d_ws, c.ws_bytes) != hipSuccess) { cleanup(); return FC_EDEVICE; }
+    fc_rational r1, r2; int64_t kk = 0; int32_t rounds = 0;
+    rc = fc_search_with_verdicts(g->N, g->min_in_bw, g->gcd_bw, candidates_per_round, search_verdicts, &c, &r1, &r2, &kk, &rounds);
+    cleanup();
+    if (rc != FC_OK) return rc;
+    *inv_xstar = r1; *U = r2; *k = kk;
+    if (rounds_or_null) *rounds_or_null = rounds;
+    if (trace_len_or_null) *trace_len_or_null = c.tlen;
+    return FC_OK;
+}

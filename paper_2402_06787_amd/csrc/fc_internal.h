@@ -1,0 +1,39 @@
+// Internal layout of fc_graph, shared by the host-side ingest (fc_host.cpp) and the
+// device side (fc_device.hip).  Not part of the public ABI.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "fc_maxflow.h"
+
+struct fc_graph {
+    // ---- host side (always valid)
+    int32_t n = 0;                 // |V| (super-source excluded)
+    int32_t N = 0;                 // |V_c|
+    int64_t m0 = 0;                // topology arcs after merging parallels
+    std::vector<int32_t> row_ptr;  // [n+1] residual CSR offsets
+    std::vector<int32_t> other;    // [2*m0] other endpoint of the residual arc
+    std::vector<int32_t> pair;     // [2*m0] merged topology arc the record belongs to
+    std::vector<int32_t> bw;       // [2*m0] bandwidth b_e of that topology arc
+    std::vector<uint8_t> fwd;      // [2*m0] 1: topology arc leaves the row's vertex
+    std::vector<uint8_t> is_compute;   // [n]
+    std::vector<int32_t> compute_ids;  // [N] increasing
+    int64_t min_in_bw = 0;         // min over compute nodes of B^-(v)
+    int32_t max_bw = 0, gcd_bw = 0, eulerian = 0;
+    int32_t max_row = 0;           // longest residual row
+    // ---- device side (valid when on_device)
+    bool on_device = false;
+    int device = -1;
+    int32_t *d_row_ptr = nullptr;      // [n+1]
+    void *d_arc_wide = nullptr;        // int4 [2*m0]: {other, pair, bw, fwd}
+    void *d_arc_compact = nullptr;     // uint2 [2*m0]: {other | fwd<<15 | pair<<16, bw}; null if ids do not fit
+    uint8_t *d_is_compute = nullptr;   // [n]
+    int32_t *d_compute_ids = nullptr;  // [N]
+    uint16_t *d_labels = nullptr;      // [n*n] exact initial labels per sink (row = sink), or null
+    int32_t lds_limit = 0;             // bytes of LDS one workgroup may use
+    int32_t n_cu = 0;
+};
+
+// host-only helpers implemented in fc_host.cpp
+int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
+                  const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out);

@@ -1,0 +1,259 @@
+"""GPU parity tests: the HIP library, called through its C ABI, against the CPU oracle on the
+same seeded inputs.  All quantities are integers, so every comparison is bit-exact."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle as o
+import workloads as w
+from workloads.problems import config_candidates
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+if not torch.cuda.is_available():          # selected explicitly on a machine without a GPU
+    pytest.skip("needs a GPU", allow_module_level=True)
+
+import paper_2402_06787_amd as fc   # noqa: E402
+
+DEV = torch.device("cuda:0")
+_OPTIMA = {}
+
+
+def _upload(topo):
+    return fc.fc_graph_upload(topo.n_vertices, topo.tail, topo.head, topo.bandwidth, topo.is_compute)
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def _gpu_flows(g, sink, U, k, options=None, want_stats=False):
+    flows, stats = fc.fc_maxflow_batch(g, _dev(sink), _dev(U), _dev(k), options=options, want_stats=want_stats)
+    torch.cuda.synchronize()
+    return flows.cpu().numpy().astype(np.int64), stats
+
+
+def _optimum(cfg, topo):
+    if cfg not in _OPTIMA:
+        x = o.optimality_binary_search(topo, threads=16)
+        _OPTIMA[cfg] = (x.numerator, x.denominator)
+    return _OPTIMA[cfg]
+
+
+# ------------------------------------------------------------------ the paper's worked example
+
+def test_paper_example_on_gpu():
+    topo = w.paper_example_switch(1)
+    with _upload(topo) as g:
+        sink = np.array([5, 5, 5, 0, 7], np.int32)
+        U = np.array([1, 1, 1, 1, 1], np.int32)
+        k = np.array([1, 2, 3, 1, 2], np.int32)
+        got, _ = _gpu_flows(g, sink, U, k)
+        assert got.tolist() == [8, 12, 14, 8, 12]          # 8x; 4x+4b; x+11b (Section 5.2)
+        res = fc.fc_opt_throughput_search(g, 4)
+        assert res["inv_xstar"] == 1 and res["U"] == 1 and res["k"] == 1
+
+
+# ------------------------------------------------------------------ the five configs, full problem lists
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_config_flows_match_oracle(cfg):
+    topo = w.config_topology(cfg)
+    inv = _optimum(cfg, topo) if cfg in (2, 5) else None
+    pl = w.config_problems(cfg, topo, inv, extra_parity=True)
+    want = o.aux_maxflow_batch(topo, pl.sink, pl.edge_mult, pl.src_cap, threads=16)
+    with _upload(topo) as g:
+        got, stats = _gpu_flows(g, pl.sink, pl.edge_mult, pl.src_cap, want_stats=True)
+        assert got.shape == want.shape
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, (cfg, bad[:8], got[bad[:8]], want[bad[:8]])
+        assert stats["not_converged"] == 0 and stats["pushes"] > 0 and stats["arc_scans"] >= stats["pushes"]
+        # bounds that hold for any correct value: k <= F <= min(N k, k + U B^-(v))
+        Bin = np.asarray(o.in_bandwidths(topo), dtype=np.int64)
+        k64 = pl.src_cap.astype(np.int64); U64 = pl.edge_mult.astype(np.int64)
+        assert (got >= k64).all() and (got <= np.minimum(topo.n_compute * k64, k64 + U64 * Bin[pl.sink])).all()
+
+
+@pytest.mark.parametrize("cfg", [1, 3, 4])
+def test_config_closed_forms_on_gpu(cfg):
+    topo = w.config_topology(cfg)
+    formula = {1: lambda U, k: min(16 * k, k + 12 * U, 8 * k + 8 * U),
+               3: lambda U, k: min(128 * k, k + 26 * U, 8 * k + 16 * U),
+               4: lambda U, k: min(512 * k, k + 36 * U, 8 * k + 32 * U, 32 * k + 256 * U)}[cfg]
+    cand = [(1, 4), (5, 4), (44, 8), (60, 8), (63, 4), (7, 1), (1000, 3), (3, 700)]
+    pl = w.all_sinks(topo, [c[0] for c in cand], [c[1] for c in cand])
+    with _upload(topo) as g:
+        got, _ = _gpu_flows(g, pl.sink, pl.edge_mult, pl.src_cap)
+    got = got.reshape(len(cand), topo.n_compute)
+    for i, (U, k) in enumerate(cand):
+        assert (got[i] == formula(U, k)).all(), (cfg, U, k)
+
+
+# ------------------------------------------------------------------ random small graphs, every vertex as sink
+
+@pytest.mark.parametrize("block", range(4))
+def test_tiny_random_graphs_match_oracle(block):
+    for seed in range(block * 25, block * 25 + 25):
+        topo = w.random_tiny(seed, n_vertices=None if seed % 3 else 12, strongly_connected=(seed % 4 != 3))
+        rng = np.random.default_rng(77 + seed)
+        P = 64
+        sink = rng.integers(0, topo.n_vertices, P).astype(np.int32)           # switches too
+        U = rng.integers(1, 9, P).astype(np.int32)
+        k = rng.integers(1, 30, P).astype(np.int32)
+        k[::7] = rng.integers(20000, 3000000, k[::7].shape)                    # N*k > 65535: 32-bit state
+        U[::11] = rng.integers(1 << 20, 1 << 30, U[::11].shape)                # U*b beyond 32 bits: clamped
+        want = o.aux_maxflow_batch(topo, sink, U, k, algo="edmonds_karp" if seed % 2 else "dinic")
+        with _upload(topo) as g:
+            got, _ = _gpu_flows(g, sink, U, k)
+            assert (got == want).all(), (seed, np.flatnonzero(got != want)[:5])
+            if seed % 5 == 0:
+                got2, _ = _gpu_flows(g, sink, U, k, options={"force_wide": 1, "use_label_table": 2})
+                assert (got2 == want).all(), seed
+
+
+# ------------------------------------------------------------------ every launch shape gives the same values
+
+def test_option_matrix_same_values():
+    topo = w.config_topology(5)
+    inv = _optimum(5, topo)
+    pl = w.config_problems(5, topo, inv)
+    rng = np.random.default_rng(3)
+    idx = np.sort(rng.choice(pl.n_problems, 96, replace=False))
+    idx[:16] = np.flatnonzero(pl.sink == pl.sink[np.argmin(o.in_bandwidths(topo)[:1024])])[:16]  # the bottleneck sink
+    sink, U, k = pl.sink[idx], pl.edge_mult[idx], pl.src_cap[idx]
+    want = o.aux_maxflow_batch(topo, sink, U, k, threads=16)
+    with _upload(topo) as g:
+        for opts in [dict(threads_per_problem=64, lanes_per_vertex=4), dict(threads_per_problem=128, lanes_per_vertex=8),
+                     dict(threads_per_problem=256, lanes_per_vertex=16), dict(threads_per_problem=512, lanes_per_vertex=32),
+                     dict(threads_per_problem=1024, lanes_per_vertex=64), dict(use_gap=2), dict(use_label_table=2),
+                     dict(force_wide=1), dict(global_relabel_steps=1), dict(global_relabel_steps=100000, global_relabel_permille=1000000),
+                     dict(force_wide=1, use_gap=2, use_label_table=2, threads_per_problem=192, lanes_per_vertex=64)]:
+            got, stats = _gpu_flows(g, sink, U, k, options=opts, want_stats=True)
+            assert (got == want).all(), (opts, np.flatnonzero(got != want)[:5])
+            assert stats["not_converged"] == 0
+
+
+# ------------------------------------------------------------------ edge cases of the boundary
+
+def test_empty_invalid_and_workspace_errors():
+    topo = w.config_topology(1)
+    with _upload(topo) as g:
+        empty = torch.empty(0, dtype=torch.int32, device=DEV)
+        out, stats = fc.fc_maxflow_batch(g, empty, empty, empty, want_stats=True)
+        assert out.numel() == 0 and stats["pushes"] == 0
+        sink = np.array([0, 19, -1, 3, 4, 5, 18], np.int32)       # 19 and -1 are not vertices; 18 is a switch
+        U = np.array([1, 1, 1, 0, 1, 1, 2], np.int32)
+        k = np.array([4, 4, 4, 4, 0, 2 ** 28, 4], np.int32)       # 16 * 2^28 >= 2^31
+        got, _ = _gpu_flows(g, sink, U, k)
+        assert got[0] == 16 and got[1:6].tolist() == [fc.FC_FLOW_INVALID] * 5
+        assert got[6] == o.aux_maxflow(topo, 18, 2, 4)
+        d = _dev(sink)
+        small = torch.empty(8, dtype=torch.uint8, device=DEV)
+        with pytest.raises(fc.FcError) as ei:
+            fc.fc_maxflow_batch(g, d, d, d, d_workspace=small)
+        assert ei.value.code == fc.FC_EWORKSPACE
+        with pytest.raises(fc.FcError) as ei:
+            fc.fc_maxflow_batch(g, d, d, d, options={"threads_per_problem": 100})
+        assert ei.value.code == fc.FC_EINVAL
+
+
+def test_large_graph_limits():
+    # largest shapes the 32-bit on-chip layout takes on a 160 KB LDS, and one beyond every layout
+    rng = np.random.default_rng(11)
+    n, deg = 3000, 6
+    tail = np.repeat(np.arange(n), deg).astype(np.int32)
+    head = ((tail + rng.integers(1, n, tail.shape)) % n).astype(np.int32)
+    head[::deg] = (np.arange(n) + 1) % n                                      # ring keeps it connected
+    bw = rng.integers(1, 50, tail.shape).astype(np.int32)
+    isc = (np.arange(n) % 3 != 0).astype(np.uint8)
+    topo = w.Topology("limit", n, tail, head, bw, isc)
+    P = 48
+    sink = rng.integers(0, n, P).astype(np.int32); U = rng.integers(1, 400, P).astype(np.int32)
+    k = rng.integers(1, 40, P).astype(np.int32); k[::4] = 5000                # both layouts in one batch
+    want = o.aux_maxflow_batch(topo, sink, U, k, threads=16)
+    with _upload(topo) as g:
+        got, stats = _gpu_flows(g, sink, U, k, want_stats=True)
+        assert (got == want).all() and stats["not_converged"] == 0
+    n2 = 40000
+    t2 = np.arange(n2, dtype=np.int32); h2 = ((t2 + 1) % n2).astype(np.int32)
+    with pytest.raises(fc.FcError) as ei:
+        fc.fc_graph_upload(n2, t2, h2, np.ones(n2, np.int32), np.ones(n2, np.uint8))
+    assert ei.value.code == fc.FC_EUNSUPPORTED
+
+
+# ------------------------------------------------------------------ verdicts (Theorem 1) and the search (Algorithm 1)
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_feasible_matches_oracle(cfg):
+    topo = w.config_topology(cfg)
+    inv = _optimum(cfg, topo) if cfg in (2, 5) else None
+    U, k = config_candidates(cfg, inv, extra_parity=True)
+    U = np.concatenate([U, [0, 5]]).astype(np.int32); k = np.concatenate([k, [3, 0]]).astype(np.int32)   # two malformed
+    with _upload(topo) as g:
+        res = fc.fc_feasible(g, _dev(U), _dev(k), want_flows=True, want_stats=True)
+        torch.cuda.synchronize()
+        feas = res["feasible"].cpu().numpy(); wit = res["witness"].cpu().numpy(); flows = res["flows"].cpu().numpy()
+    comp = topo.compute_nodes
+    for c in range(len(U) - 2):
+        ok, want = o.feasible(topo, int(U[c]), int(k[c]), threads=16)
+        assert (flows[c] == want).all(), (cfg, c)
+        assert bool(feas[c]) == ok
+        short = comp[want < topo.n_compute * int(k[c])]
+        assert wit[c] == (-1 if ok else short.min())
+    assert feas[-2:].tolist() == [0, 0] and wit[-2:].tolist() == [-1, -1]
+    assert (flows[-2:] == fc.FC_FLOW_INVALID).all()
+    # Theorem 1: verdicts are monotone in U/k
+    order = np.argsort([Fraction(int(a), int(b)) for a, b in zip(U[:-2], k[:-2])], kind="stable")
+    f = feas[:-2][order].tolist()
+    assert f == sorted(f)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_search_matches_oracle_on_configs(cfg):
+    topo = w.config_topology(cfg)
+    want = Fraction(*_optimum(cfg, topo))
+    wantU, wantk = o.smallest_U_k(want, topo.bandwidth)
+    with _upload(topo) as g:
+        for cpr in (16, 3):
+            res = fc.fc_opt_throughput_search(g, cpr)
+            assert res["inv_xstar"] == want and res["U"] == wantU and res["k"] == wantk
+            assert res["trace_len"] == len(res["trace"]) > 0
+            # every verdict the GPU produced, re-evaluated by the oracle (sampled on the big config)
+            trace = res["trace"] if cfg < 5 else res["trace"][:: max(1, len(res["trace"]) // 6)]
+            for U, k, v in trace:
+                assert bool(v) == o.feasible(topo, U, k, threads=16)[0], (U, k)
+            if cfg >= 4:
+                break
+
+
+def test_search_on_random_and_disconnected_graphs():
+    for seed in range(40):
+        topo = w.random_tiny(seed, strongly_connected=(seed % 4 != 3))
+        with _upload(topo) as g:
+            try:
+                want = o.optimality_binary_search(topo)
+            except o.Disconnected:
+                with pytest.raises(fc.FcError) as ei:
+                    fc.fc_opt_throughput_search(g, 5)
+                assert ei.value.code == fc.FC_EDISCONNECTED
+                continue
+            res = fc.fc_opt_throughput_search(g, 1 + seed % 7)
+            assert res["inv_xstar"] == want
+            assert (res["U"], res["k"]) == o.smallest_U_k(want, topo.bandwidth)
+    for topo, want in [(w.paper_example_ring_unwound(2), Fraction(2)), (w.paper_example_split(3), Fraction(1, 3)),
+                       (w.complete_digraph(6, 7), Fraction(1, 7)), (w.star_switch(9, 4), Fraction(2))]:
+        with _upload(topo) as g:
+            assert fc.fc_opt_throughput_search(g, 8)["inv_xstar"] == want
+
+
+def test_scaling_identity_on_gpu():
+    # multiplying every capacity, source arcs included, by t multiplies F by t (Appendix E.1)
+    topo = w.config_topology(2)
+    pl = w.all_sinks(topo, [3, 9, 14], [2, 5, 4])
+    with _upload(topo) as g:
+        base, _ = _gpu_flows(g, pl.sink, pl.edge_mult, pl.src_cap)
+        for t in (2, 7, 1000):
+            got, _ = _gpu_flows(g, pl.sink, pl.edge_mult * t, pl.src_cap * t)
+            assert (got == t * base).all()

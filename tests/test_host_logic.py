@@ -1,0 +1,174 @@
+"""CPU tests of the library's host side: the shared object loads and exports the declared
+symbols, graph ingest builds the residual CSR it documents, and the search driver (fed with
+the oracle's verdicts) returns the oracle's optimum.  No GPU compute is called here."""
+import ctypes
+import os
+import re
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle as o
+import workloads as w
+import paper_2402_06787_amd as fc
+from paper_2402_06787_amd import build as fcbuild
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    fcbuild.build_library()          # rebuilds only when a source is newer than the library
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "fc_maxflow.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(fc_[a-z_]+)\s*\(", body))
+    declared.discard("fc_verdict_fn")
+    assert declared == set(fc.EXPORTED), declared ^ set(fc.EXPORTED)
+    lib = ctypes.CDLL(fc.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert fc.strerror(fc.FC_OK) == "ok" and "workspace" in fc.strerror(fc.FC_EWORKSPACE)
+
+
+def test_graph_build_merges_and_classifies():
+    # 4 vertices: 0,1 compute, 2 switch, 3 compute; parallel arcs, a self-loop and a zero arc
+    tail = [0, 0, 1, 2, 2, 3, 1, 0]
+    head = [1, 1, 2, 0, 3, 3, 2, 2]
+    bw = [2, 3, 4, 5, 6, 9, 1, 0]
+    g = fc.fc_graph_build(4, tail, head, bw, [1, 1, 0, 1])
+    info = fc.fc_graph_info(g)
+    assert info.n_compute == 3
+    assert info.n_arcs_merged == 4                   # (0,1)=5, (1,2)=5, (2,0)=5, (2,3)=6
+    assert info.min_in_bw_compute == 5               # B^-(0)=5, B^-(1)=5, B^-(3)=6
+    assert info.max_bw == 6 and info.gcd_bw == 1 and not info.is_eulerian
+    row_ptr, other, pair, bwr, fwd = fc.fc_graph_csr(g)
+    assert row_ptr.tolist() == [0, 2, 4, 7, 8]
+    arcs = {}
+    for u in range(4):
+        for r in range(row_ptr[u], row_ptr[u + 1]):
+            key = (u, int(other[r])) if fwd[r] else (int(other[r]), u)
+            arcs.setdefault(int(pair[r]), set()).add((key, int(bwr[r]), int(fwd[r])))
+    # every merged arc appears exactly twice: once forward at its tail, once reversed at its head
+    assert sorted(next(iter(v))[0] for v in arcs.values()) == [(0, 1), (1, 2), (2, 0), (2, 3)]
+    for v in arcs.values():
+        assert len(v) == 2 and {x[2] for x in v} == {0, 1} and len({x[1] for x in v}) == 1
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_graph_info_matches_oracle_side(cfg):
+    topo = w.config_topology(cfg)
+    g = fc.fc_graph_build(topo.n_vertices, topo.tail, topo.head, topo.bandwidth, topo.is_compute)
+    info = fc.fc_graph_info(g)
+    assert info.n_compute == topo.n_compute
+    assert info.min_in_bw_compute == o.min_compute_in_bandwidth(topo)
+    assert info.max_bw == max(np.bincount(topo.tail.astype(np.int64) * topo.n_vertices + topo.head,
+                                          weights=topo.bandwidth).astype(np.int64))
+    assert info.gcd_bw == int(np.gcd.reduce(topo.bandwidth[topo.bandwidth > 0]))
+    row_ptr, other, pair, bwr, fwd = fc.fc_graph_csr(g)
+    assert row_ptr[-1] == 2 * info.n_arcs_merged and (np.diff(row_ptr) >= 0).all()
+    assert other.min() >= 0 and other.max() < topo.n_vertices
+    assert np.bincount(pair, minlength=info.n_arcs_merged).tolist() == [2] * info.n_arcs_merged
+    g.close()
+
+
+def test_graph_build_rejects_bad_input():
+    ok = dict(n_vertices=3, tail=[0, 1], head=[1, 2], bandwidth=[1, 1], is_compute=[1, 1, 0])
+    fc.fc_graph_build(**ok).close()
+    for bad, code in [
+        (dict(ok, head=[1, 3]), fc.FC_EINVAL),                 # id out of range
+        (dict(ok, tail=[-1, 1]), fc.FC_EINVAL),
+        (dict(ok, bandwidth=[1, -2]), fc.FC_EINVAL),           # negative bandwidth
+        (dict(ok, is_compute=[1, 0, 0]), fc.FC_EINVAL),        # fewer than two compute nodes
+        (dict(n_vertices=1, tail=[], head=[], bandwidth=[], is_compute=[1]), fc.FC_EINVAL),
+        (dict(ok, tail=[0, 0, 0], head=[1, 1, 1], bandwidth=[2 ** 30, 2 ** 30, 5]), fc.FC_EOVERFLOW),
+    ]:
+        with pytest.raises(fc.FcError) as ei:
+            fc.fc_graph_build(**bad)
+        assert ei.value.code == code
+
+
+def test_device_calls_fail_loudly_without_device_graph():
+    g = fc.fc_graph_build(3, [0, 1], [1, 2], [1, 1], [1, 1, 0])   # host-only graph
+    lib = fc.load_library()
+    rc = lib.fc_maxflow_batch(g.handle, 1, None, None, None, None, None, 0, None, None, None)
+    assert rc == fc.FC_EDEVICE
+    rc = lib.fc_feasible(g.handle, 1, None, None, None, None, None, None, 0, None, None, None)
+    assert rc == fc.FC_EDEVICE
+    assert lib.fc_maxflow_batch(None, 1, None, None, None, None, None, 0, None, None, None) == fc.FC_EINVAL
+
+
+def _search_with_oracle(topo, cpr):
+    g = fc.fc_graph_build(topo.n_vertices, topo.tail, topo.head, topo.bandwidth, topo.is_compute)
+    info = fc.fc_graph_info(g)
+    seen = []
+
+    def verdicts(cands):
+        out = []
+        for U, k in cands:
+            assert 1 <= k <= info.min_in_bw_compute and U >= 1
+            ok = o.feasible(topo, U, k)[0]
+            seen.append((Fraction(U, k), ok))
+            out.append(ok)
+        return out
+
+    res = fc.fc_search_with_verdicts(info.n_compute, info.min_in_bw_compute, info.gcd_bw, cpr, verdicts)
+    return res, seen
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_search_driver_matches_oracle_on_tiny_graphs(seed):
+    topo = w.random_tiny(seed, strongly_connected=(seed % 5 != 4))
+    cpr = [1, 2, 3, 5, 16][seed % 5]
+    try:
+        want = o.optimality_binary_search(topo)
+    except o.Disconnected:
+        with pytest.raises(fc.FcError) as ei:
+            _search_with_oracle(topo, cpr)
+        assert ei.value.code == fc.FC_EDISCONNECTED
+        return
+    res, seen = _search_with_oracle(topo, cpr)
+    assert res["inv_xstar"] == want
+    U, k = o.smallest_U_k(want, topo.bandwidth)
+    assert (res["U"], res["k"]) == (U, k)
+    # everything the driver tested is consistent with Theorem 1's monotone verdict
+    for frac, ok in seen:
+        assert ok == (frac >= want)
+
+
+@pytest.mark.parametrize("cfg,want", [(1, Fraction(5, 4)), (3, Fraction(15, 2)), (4, Fraction(63, 4))])
+def test_search_driver_on_closed_form_configs(cfg, want):
+    topo = w.config_topology(cfg)
+    calls = []
+    info = fc.fc_graph_info(fc.fc_graph_build(topo.n_vertices, topo.tail, topo.head, topo.bandwidth, topo.is_compute))
+
+    def verdicts(cands):                       # closed-form verdict: U/k >= 1/x*
+        calls.append(len(cands))
+        return [Fraction(U, k) >= want for U, k in cands]
+
+    for cpr in (1, 4, 16, 64):
+        res = fc.fc_search_with_verdicts(info.n_compute, info.min_in_bw_compute, info.gcd_bw, cpr, verdicts)
+        assert res["inv_xstar"] == want and res["k"] == 1 and res["U"] == want
+
+
+def test_search_driver_synthetic_optima():
+    # any fraction p/q in [(N-1)/B, N-1] with q <= B must be found exactly, for any batch width
+    N, B = 40, 23
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        q = int(rng.integers(1, B + 1))
+        lo = -(-(N - 1) * q // B)
+        p = int(rng.integers(lo, (N - 1) * q + 1))
+        want = Fraction(p, q)
+        cpr = int(rng.integers(1, 20))
+        res = fc.fc_search_with_verdicts(N, B, 1, cpr, lambda c: [Fraction(U, k) >= want for U, k in c])
+        assert res["inv_xstar"] == want
+    with pytest.raises(fc.FcError) as ei:        # candidate N-1 infeasible => disconnected
+        fc.fc_search_with_verdicts(N, B, 1, 8, lambda c: [False] * len(c))
+    assert ei.value.code == fc.FC_EDISCONNECTED
+    with pytest.raises(fc.FcError) as ei:        # (N-1)*B must fit 31 bits
+        fc.fc_search_with_verdicts(70000, 70000, 1, 8, lambda c: [True] * len(c))
+    assert ei.value.code == fc.FC_EOVERFLOW
