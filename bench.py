@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched max-flow feasibility path on one MI355X.
+
+One "step" is one pass of the hot path over one batch: `fc_feasible` on the 16 candidate
+throughputs of the largest benchmark configuration (1024 compute + 128 switch nodes, random
+out-degree-8 fabric) = 16 384 independent max-flows F(s, v) on the auxiliary network of the
+paper's Section 5.2 (preflow initialisation, discharge sweeps, relabeling, termination) plus
+the per-candidate verdict reduction of Theorem 1.  The topology is uploaded once, outside the
+timed region; candidate arrays are resident in HBM when the clock starts.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(stats, n_problems, n_with_source, m_with_source):
+    """Bytes the method itself must move for the work one launch did, in the plain 32-bit
+    layout: per arc scan a residual (4) and a height (4); per push two residuals and two
+    excesses (16); per relabel a height (4); per global relabel all residuals read and all
+    heights written; per problem the private state (2m residuals, n heights + excesses)
+    written once."""
+    n, m = n_with_source, m_with_source
+    init = n_problems * (2 * m * 4 + n * 8)
+    return (8 * stats["arc_scans"] + 16 * stats["pushes"] + 4 * stats["relabels"] +
+            8 * stats["gr_arc_scans"] + stats["global_relabels"] * 4 * n + init)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--threads-per-problem", type=int, default=0)
+    ap.add_argument("--lanes-per-vertex", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on ONE GPU (independent problems, no collectives); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as w
+    from workloads.problems import config_candidates
+    import paper_2402_06787_amd as fc
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    if not os.path.exists(fc.LIB_PATH):
+        from paper_2402_06787_amd import build as fcbuild
+        fcbuild.build_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = args.config
+    topo = w.config_topology(cfg)
+    g = fc.fc_graph_upload(topo.n_vertices, topo.tail, topo.head, topo.bandwidth, topo.is_compute)
+    info = fc.fc_graph_info(g)
+    N = info.n_compute
+
+    # candidates: configs 2 and 5 centre them on the optimum, found here by the library's own search
+    t0 = time.perf_counter()
+    search = fc.fc_opt_throughput_search(g, 16)
+    search_ms = (time.perf_counter() - t0) * 1e3
+    inv = (search["inv_xstar"].numerator, search["inv_xstar"].denominator)
+    cU, ck = config_candidates(cfg, inv)
+    C = len(cU)
+    P = C * N
+    d_U = torch.from_numpy(cU).to(dev); d_k = torch.from_numpy(ck).to(dev)
+    opts = {"src_cap_bound": int(ck.max())}
+    if args.threads_per_problem:
+        opts["threads_per_problem"] = args.threads_per_problem
+    if args.lanes_per_vertex:
+        opts["lanes_per_vertex"] = args.lanes_per_vertex
+    ws = torch.empty(fc.fc_feasible_workspace_bytes(g, C), dtype=torch.uint8, device=dev)
+
+    def step(want_stats=False, want_flows=False):
+        return fc.fc_feasible(g, d_U, d_k, want_flows=want_flows, want_witness=True, d_workspace=ws,
+                              options=opts, want_stats=want_stats)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    solves_per_s = P * args.steps / elapsed
+
+    # the dominant kernel alone: HIP events recorded by the library on the launch stream around
+    # the solver kernel, same inputs, same launch configuration
+    kms, last = [], None
+    for _ in range(min(args.steps, 50)):
+        last = step(want_stats=True)
+        kms.append(last["stats"]["device_ms"])
+    st = last["stats"]
+    kernel_ms = float(np.mean(kms))
+    n_src, m_src = topo.n_vertices + 1, info.n_arcs_merged + N
+    bytes_alg = algorithmic_bytes(st, P, n_src, m_src)
+    achieved = bytes_alg / (kernel_ms * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"cfg{cfg}", {}).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "max-flow solves/sec", "value": solves_per_s, "unit": "solves/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.CONFIG_NAMES[cfg]}: {N} sinks x {C} candidates = {P} max-flows per step "
+                               f"(|V|={topo.n_vertices}, merged arcs={info.n_arcs_merged}, k={int(ck[0])}, "
+                               f"U={int(cU[0])}..{int(cU[-1])}, 1/x*={inv[0]}/{inv[1]})",
+                   "entry_point": "fc_feasible", "problems_per_step": P},
+        "residual_edge_updates_per_sec": st["pushes"] / (kernel_ms * 1e-3),
+        "arc_scans_per_sec": st["arc_scans"] / (kernel_ms * 1e-3),
+        "kernel_ms": kernel_ms,
+        "per_launch": {k: int(v) for k, v in st.items() if k != "device_ms"},
+        "search": {"inv_xstar": f"{inv[0]}/{inv[1]}", "U": str(search["U"]), "k": search["k"],
+                   "rounds": search["rounds"], "candidates_tested": search["trace_len"], "wall_ms": search_ms},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "fc_push_relabel_kernel", "algorithmic_bytes_per_launch": int(bytes_alg)},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        flows = step(want_flows=True)["flows"]
+        torch.cuda.synchronize()
+        gpu_flows = flows.cpu().numpy().astype(np.int64).reshape(-1)
+        pl = w.all_sinks(topo, cU, ck)
+        cores = max(1, min(16, os.cpu_count() or 1))
+        # bounded sample: about 20 s of single-core work at ~1.2 ms per solve on the largest config
+        stride = max(1, P // 16384)
+        idx = np.arange(0, P, stride)
+        t0 = time.perf_counter()
+        ref = oracle.aux_maxflow_batch(topo, pl.sink[idx], pl.edge_mult[idx], pl.src_cap[idx], threads=cores)
+        t_all = time.perf_counter() - t0
+        idx1 = idx[:: max(1, len(idx) // 1024)]
+        t0 = time.perf_counter()
+        oracle.aux_maxflow_batch(topo, pl.sink[idx1], pl.edge_mult[idx1], pl.src_cap[idx1], threads=1)
+        t_one = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": len(idx) / t_all, "unit": "solves/s", "cores": cores, "kind": "oracle",
+                               "sample": f"{len(idx)} of the step's {P} problems (Dinic, gcc -O2, problems split "
+                                         f"statically over {cores} threads)",
+                               "single_thread_value": len(idx1) / t_one, "single_thread_sample": len(idx1)}
+        out["parity_vs_oracle"] = {"checked": int(len(idx)), "mismatches": int((gpu_flows[idx] != ref).sum())}
+    g.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -180,13 +180,20 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     const bool valid = t >= 0 && t < n && U >= 1 && k >= 1 && NKll < (1ll << 31);
     if (!valid) {                       // both layouts write the same marker
         if (tid == 0) p.flow_out[j] = FC_FLOW_INVALID;
+        if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
         return;
     }
     // the 16-bit layout holds flows up to 65535 = largest N*k it accepts; larger problems are left
     // to the 32-bit kernel, which in turn skips the ones the 16-bit kernel took
     const bool small = NKll <= 65535ll;
     if (COMPACT) {
-        if (!small) { if (!p.wide_available && tid == 0) p.flow_out[j] = FC_FLOW_UNSUPPORTED; return; }
+        if (!small) {
+            if (!p.wide_available) {
+                if (tid == 0) p.flow_out[j] = FC_FLOW_UNSUPPORTED;
+                if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
+            }
+            return;
+        }
     } else if (small && p.arc_compact != nullptr) return;
     const int32_t NK = int32_t(NKll);
 
