@@ -25,15 +25,26 @@
 
 #define FC_NSTAT 8   // per-problem counters: pushes, relabels, arc_scans, grs, gr_arc_scans, level_steps, discharges, not_converged
 
+// Optional per-phase cycle accounting for tuning builds (-DFC_PHASE_TIMING): the per-problem
+// counters relabels/global_relabels/gr_arc_scans/discharges are then replaced by the cycles
+// thread 0 spent in level compaction / discharge / initialisation / everything else.
+#ifdef FC_PHASE_TIMING
+#define FC_TICK(var) do { long long now_ = clock64(); var += uint32_t(now_ - tick_); tick_ = now_; } while (0)
+#else
+#define FC_TICK(var) do { } while (0)
+#endif
+
 namespace {
 
 struct KParams {
     int32_t n, N, m0;
+    int32_t n_rec;               // residual arc records (at least 1: a zeroed dummy when the graph has no arcs)
     const int32_t *row_ptr;
     const int4 *arc_wide;
     const uint2 *arc_compact;
     const uint8_t *is_compute;
-    const uint16_t *labels;      // [n*n] or null
+    const uint16_t *labels;      // [n*n] exact initial heights per sink (row = sink), or null
+    const uint16_t *label_hmax;  // [n] highest finite label of a compute node per sink
     const int32_t *sink, *U, *k;
     int32_t *flow_out;
     uint32_t *stats;             // [P * FC_NSTAT] or null
@@ -43,17 +54,33 @@ struct KParams {
 
 struct ArcRec { int32_t w, pair, bw, fwd; };
 
+// Raw residual-arc record as stored in global memory, and its decoded form.  Loading and decoding
+// are separate so that several loads can be in flight before the first one is consumed.
+template <bool COMPACT> struct ArcRaw;
+template <> struct ArcRaw<true> { uint2 q; };
+template <> struct ArcRaw<false> { int4 q; };
+
 template <bool COMPACT>
-__device__ __forceinline__ ArcRec load_arc(const KParams &p, int32_t a) {
+__device__ __forceinline__ ArcRaw<COMPACT> load_arc_raw(const KParams &p, int32_t a) {
+    ArcRaw<COMPACT> r;
+    if constexpr (COMPACT) r.q = p.arc_compact[a]; else r.q = p.arc_wide[a];
+    return r;
+}
+
+template <bool COMPACT>
+__device__ __forceinline__ ArcRec decode_arc(const ArcRaw<COMPACT> &raw) {
     ArcRec r;
-    if (COMPACT) {
-        uint2 q = p.arc_compact[a];
-        r.w = int32_t(q.x & 0x7fffu); r.fwd = int32_t((q.x >> 15) & 1u); r.pair = int32_t(q.x >> 16); r.bw = int32_t(q.y);
+    if constexpr (COMPACT) {
+        r.w = int32_t(raw.q.x & 0x7fffu); r.fwd = int32_t((raw.q.x >> 15) & 1u); r.pair = int32_t(raw.q.x >> 16); r.bw = int32_t(raw.q.y);
     } else {
-        int4 q = p.arc_wide[a];
-        r.w = q.x; r.pair = q.y; r.bw = q.z; r.fwd = q.w;
+        r.w = raw.q.x; r.pair = raw.q.y; r.bw = raw.q.z; r.fwd = raw.q.w;
     }
     return r;
+}
+
+template <bool COMPACT>
+__device__ __forceinline__ ArcRec load_arc(const KParams &p, int32_t a) {
+    return decode_arc<COMPACT>(load_arc_raw<COMPACT>(p, a));
 }
 
 __device__ __forceinline__ int32_t arc_cap(int32_t U, int32_t bw, int32_t NK) {
@@ -65,54 +92,102 @@ __device__ __forceinline__ int32_t arc_cap(int32_t U, int32_t bw, int32_t NK) {
 // LDS scalars shared by a workgroup
 struct Shared {
     int32_t count[2];      // length of the current level list (by step parity)
+    int32_t lvl[2];        // number of vertices (active or not) at the level being processed
     int32_t down[2];       // some push of this step went to a non-sink vertex
     int32_t nrel[2];       // vertices relabeled in this step
     int32_t hmax_next;     // largest finite new height assigned during this pass
     int32_t rel_since;     // relabels since the last global relabel
     int32_t tmp;           // scratch for rare scans
+    int32_t pad;
     uint32_t st[FC_NSTAT];
 };
 
-template <typename HT>
+// Byte offsets of the per-problem LDS arrays.  COMPACT: every array 16-bit; else 32-bit.
+struct Carve { uint32_t f, h, list, lnew, e, rp, sh, total; };
+
+__host__ __device__ inline Carve carve_lds(int32_t n, int32_t m0, bool compact) {
+    const uint32_t w = compact ? 2u : 4u;
+    auto up = [](uint32_t x) { return (x + 15u) & ~15u; };
+    Carve c; uint32_t off = 0;
+    c.f = off; off += up(uint32_t(m0) * w);          // flow on every merged topology arc
+    c.h = off; off += up(uint32_t(n) * w);           // height; n = cannot reach the sink
+    c.list = off; off += up(uint32_t(n) * w);        // vertices of the level being processed
+    c.lnew = off; off += up(uint32_t(n) * w);        // new height for list[i] (0 = none)
+    c.e = off; off += up(uint32_t(n) * w);           // excess
+    c.rp = off; off += up(uint32_t(n + 1) * w);      // residual CSR row offsets (copy of the shared ones)
+    c.sh = off; off += up(uint32_t(sizeof(Shared)));
+    c.total = off;
+    return c;
+}
+
+// Per-problem state in LDS.  In the 16-bit layout two excess values share a dword and are
+// updated with 32-bit atomics on that dword: a half never exceeds N*k <= 65535, so no carry
+// crosses into its neighbour.
+template <bool COMPACT>
 struct State {
-    HT *h;          // [n] height; n = "cannot reach the sink"
-    HT *list;       // [n] vertices of the level being processed
-    HT *lnew;       // [n] new height for list[i] (0 = none)
-    int32_t *e;     // [n] excess
+    using W = typename std::conditional<COMPACT, uint16_t, int32_t>::type;
+    W *f, *h, *list, *lnew, *e, *rp;
     Shared *sh;
+    __device__ __forceinline__ int32_t excess(int32_t v) const { return int32_t(e[v]); }
+    __device__ __forceinline__ void excess_add(int32_t v, int32_t d) const {
+        if (COMPACT) atomicAdd(reinterpret_cast<uint32_t *>(e) + (v >> 1), uint32_t(d) << ((v & 1) * 16));
+        else atomicAdd(reinterpret_cast<int32_t *>(e) + v, d);
+    }
+    __device__ __forceinline__ void excess_sub(int32_t v, int32_t d) const {
+        if (COMPACT) atomicSub(reinterpret_cast<uint32_t *>(e) + (v >> 1), uint32_t(d) << ((v & 1) * 16));
+        else atomicSub(reinterpret_cast<int32_t *>(e) + v, d);
+    }
 };
 
-// Compact vertices v with e[v] > 0, v != t, h[v] == d into st.list; returns after a barrier with
-// the list length.  `par` selects the scalar set.
-template <typename HT>
-__device__ __forceinline__ int32_t compact_level(const State<HT> &st, int32_t n, int32_t t, int32_t d, int32_t par) {
+// Compact vertices v with e[v] > 0, v != t, h[v] == d into st.list and count all vertices at height
+// d; returns after a barrier with the list length.  `par` selects the scalar set.  Four strided
+// vertices per thread are examined per round so that their LDS reads overlap and each wave needs
+// one counter update per round.
+template <bool COMPACT>
+__device__ __forceinline__ int32_t compact_level(const State<COMPACT> &st, int32_t n, int32_t t, int32_t d, int32_t par) {
+    using W = typename State<COMPACT>::W;
     const int32_t tid = threadIdx.x, T = blockDim.x, lane = tid & 63;
-    for (int32_t base = 0; base < n; base += T) {
-        int32_t v = base + tid;
-        bool isd = false;
-        if (v < n) isd = (st.e[v] > 0) && (v != t) && (int32_t(st.h[v]) == d);
-        unsigned long long b = __ballot(isd);
-        if (b) {
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int32_t base = 0; base < n; base += 4 * T) {
+        bool act[4]; unsigned long long ba[4]; int32_t tot = 0, lv = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int32_t v = base + q * T + tid;
+            const int32_t vc = v < n ? v : n - 1;                 // clamped: reads stay unconditional
+            const bool at = v < n && int32_t(st.h[vc]) == d;
+            act[q] = at && st.excess(vc) > 0 && v != t;
+            ba[q] = __ballot(act[q]);
+            tot += __popcll(ba[q]);
+            lv += __popcll(__ballot(at));
+        }
+        if (tot | lv) {
             int32_t pos = 0;
-            if (lane == 0) pos = atomicAdd(&st.sh->count[par], __popcll(b));
+            if (lane == 0) {
+                if (tot) pos = atomicAdd(&st.sh->count[par], tot);
+                if (lv) atomicAdd(&st.sh->lvl[par], lv);
+            }
             pos = __shfl(pos, 0);
-            if (isd) st.list[pos + __popcll(b & ((1ull << lane) - 1ull))] = HT(v);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (act[q]) st.list[pos + __popcll(ba[q] & below)] = W(base + q * T + tid);
+                pos += __popcll(ba[q]);
+            }
         }
     }
     __syncthreads();
     return st.sh->count[par];
 }
 
-// max over v of h[v] subject to e[v] > 0, v != t, h[v] < below; 0 if none.  Two barriers.
-template <typename HT>
-__device__ __forceinline__ int32_t max_active_height_below(const State<HT> &st, int32_t n, int32_t t, int32_t below) {
+// max over v of h[v] subject to e[v] > 0, v != t, h[v] < below; 0 if none.  Three barriers.
+template <bool COMPACT>
+__device__ __forceinline__ int32_t max_active_height_below(const State<COMPACT> &st, int32_t n, int32_t t, int32_t below) {
     const int32_t tid = threadIdx.x, T = blockDim.x;
     if (tid == 0) st.sh->tmp = 0;
     __syncthreads();
     int32_t best = 0;
     for (int32_t v = tid; v < n; v += T) {
         int32_t hv = int32_t(st.h[v]);
-        if (st.e[v] > 0 && v != t && hv < below && hv > best) best = hv;
+        if (st.excess(v) > 0 && v != t && hv < below && hv > best) best = hv;
     }
     if (best > 0) atomicMax(&st.sh->tmp, best);
     __syncthreads();
@@ -123,42 +198,42 @@ __device__ __forceinline__ int32_t max_active_height_below(const State<HT> &st, 
 
 // Exact heights by backward breadth-first search from the sink over arcs with positive residual
 // capacity; vertices that cannot reach the sink get height n.  Ends with a barrier.
-template <bool COMPACT, int G, typename FT, typename HT>
-__device__ void global_relabel(const KParams &p, const State<HT> &st, const FT *f, int32_t t, int32_t U, int32_t NK,
+template <bool COMPACT, int G>
+__device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32_t t, int32_t U, int32_t NK,
                                uint32_t &gr_scans) {
+    using W = typename State<COMPACT>::W;
     const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n;
     const int32_t lg = tid & (G - 1), grp = tid / G, ngrp = T / G;
-    for (int32_t v = tid; v < n; v += T) st.h[v] = HT(v == t ? 0 : n);
+    for (int32_t v = tid; v < n; v += T) st.h[v] = W(v == t ? 0 : n);
     if (tid == 0) st.sh->count[0] = 0;
     __syncthreads();
     for (int32_t d = 0;; ++d) {
-        int32_t par = d & 1;
+        const int32_t par = d & 1;
         // frontier: vertices at distance d (found by a scan; keeps the search free of queues and CAS)
         for (int32_t base = 0; base < n; base += T) {
-            int32_t v = base + tid;
-            bool isd = v < n && int32_t(st.h[v]) == d;
-            unsigned long long b = __ballot(isd);
+            const int32_t v = base + tid;
+            const bool isd = v < n && int32_t(st.h[v]) == d;
+            const unsigned long long b = __ballot(isd);
             if (b) {
                 int32_t pos = 0;
                 if ((tid & 63) == 0) pos = atomicAdd(&st.sh->count[par], __popcll(b));
                 pos = __shfl(pos, 0);
-                if (isd) st.list[pos + __popcll(b & ((1ull << (tid & 63)) - 1ull))] = HT(v);
+                if (isd) st.list[pos + __popcll(b & ((1ull << (tid & 63)) - 1ull))] = W(v);
             }
         }
         __syncthreads();
-        int32_t cnt = st.sh->count[par];
+        const int32_t cnt = st.sh->count[par];
         if (tid == 0) st.sh->count[par ^ 1] = 0;
         if (cnt == 0) break;
         for (int32_t i = grp; i < cnt; i += ngrp) {
-            int32_t w = int32_t(st.list[i]);
-            int32_t beg = p.row_ptr[w], end = p.row_ptr[w + 1];
+            const int32_t w = int32_t(st.list[i]);
+            const int32_t beg = int32_t(st.rp[w]), end = int32_t(st.rp[w + 1]);
             for (int32_t a = beg + lg; a < end; a += G) {
-                ArcRec r = load_arc<COMPACT>(p, a);
+                const ArcRec r = load_arc<COMPACT>(p, a);
                 ++gr_scans;
-                int32_t fv = int32_t(f[r.pair]);
-                // residual capacity of the arc r.w -> w
-                int32_t res = r.fwd ? fv : arc_cap(U, r.bw, NK) - fv;
-                if (res > 0 && int32_t(st.h[r.w]) == n) st.h[r.w] = HT(d + 1);   // same value from every writer
+                const int32_t fv = int32_t(st.f[r.pair]);
+                const int32_t res = r.fwd ? fv : arc_cap(U, r.bw, NK) - fv;     // residual of r.w -> w
+                if (res > 0 && int32_t(st.h[r.w]) == n) st.h[r.w] = W(d + 1);    // same value from every writer
             }
         }
         __syncthreads();
@@ -166,10 +241,14 @@ __device__ void global_relabel(const KParams &p, const State<HT> &st, const FT *
     __syncthreads();
 }
 
+#ifndef FC_PREFETCH_DEPTH
+#define FC_PREFETCH_DEPTH 4
+#endif
+constexpr int FC_PREFETCH = FC_PREFETCH_DEPTH;   // vertices whose first arc chunk a lane group fetches before discharging them
+
 template <bool COMPACT, int G>
 __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
-    using FT = typename std::conditional<COMPACT, uint16_t, int32_t>::type;
-    using HT = typename std::conditional<COMPACT, uint16_t, int32_t>::type;
+    using W = typename State<COMPACT>::W;
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n, m0 = p.m0;
     const int32_t j = blockIdx.x;
@@ -197,124 +276,175 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     } else if (small && p.arc_compact != nullptr) return;
     const int32_t NK = int32_t(NKll);
 
-    // ---- LDS carve-up
-    size_t off = 0;
-    FT *f = reinterpret_cast<FT *>(smem + off); off += (size_t(m0) * sizeof(FT) + 15) & ~size_t(15);
-    State<HT> st;
-    st.h = reinterpret_cast<HT *>(smem + off); off += (size_t(n) * sizeof(HT) + 15) & ~size_t(15);
-    st.list = reinterpret_cast<HT *>(smem + off); off += (size_t(n) * sizeof(HT) + 15) & ~size_t(15);
-    st.lnew = reinterpret_cast<HT *>(smem + off); off += (size_t(n) * sizeof(HT) + 15) & ~size_t(15);
-    st.e = reinterpret_cast<int32_t *>(smem + off); off += (size_t(n) * sizeof(int32_t) + 15) & ~size_t(15);
-    st.sh = reinterpret_cast<Shared *>(smem + off);
+    const Carve cv = carve_lds(n, m0, COMPACT);
+    State<COMPACT> st;
+    st.f = reinterpret_cast<W *>(smem + cv.f); st.h = reinterpret_cast<W *>(smem + cv.h);
+    st.list = reinterpret_cast<W *>(smem + cv.list); st.lnew = reinterpret_cast<W *>(smem + cv.lnew);
+    st.e = reinterpret_cast<W *>(smem + cv.e); st.rp = reinterpret_cast<W *>(smem + cv.rp);
+    st.sh = reinterpret_cast<Shared *>(smem + cv.sh);
 
     const int32_t lg = tid & (G - 1), grp = tid / G, ngrp = T / G;
     const int32_t lane = tid & 63;
     const unsigned long long gmask = (G == 64 ? ~0ull : ((1ull << G) - 1ull)) << (lane & ~(G - 1));
 
+#ifdef FC_PHASE_TIMING
+    long long tick_ = clock64();
+    uint32_t t_init = 0, t_compact = 0, t_discharge = 0, t_other = 0;
+#endif
     uint32_t c_push = 0, c_scan = 0, c_grscan = 0;            // per-thread counters
     uint32_t c_rel = 0, c_gr = 0, c_step = 0, c_dis = 0;      // counted by one lane per event / thread 0
 
-    // ---- preflow: every arc (s, c) saturated, all topology arcs empty
+    // ---- preflow: every arc (s, c) saturated (excess k at every compute node), topology arcs empty
+    int32_t hmax;
     {
-        uint32_t *fz = reinterpret_cast<uint32_t *>(f);
-        int32_t words = int32_t((size_t(m0) * sizeof(FT) + 3) / 4);
-        for (int32_t i = tid; i < words; i += T) fz[i] = 0u;
+        uint4 *fz = reinterpret_cast<uint4 *>(smem + cv.f);
+        const int32_t quads = int32_t((cv.h - cv.f) / 16);
+        for (int32_t i = tid; i < quads; i += T) fz[i] = make_uint4(0u, 0u, 0u, 0u);
         const bool have_labels = p.labels != nullptr;
         for (int32_t v = tid; v < n; v += T) {
-            st.e[v] = p.is_compute[v] ? k : 0;
-            if (have_labels) st.h[v] = HT(p.labels[size_t(t) * size_t(n) + size_t(v)]);
+            st.e[v] = W(p.is_compute[v] ? k : 0);
+            st.rp[v] = W(p.row_ptr[v]);
+            if (have_labels) st.h[v] = W(p.labels[size_t(t) * size_t(n) + size_t(v)]);
         }
         if (tid == 0) {
-            st.sh->count[0] = st.sh->count[1] = 0; st.sh->down[0] = st.sh->down[1] = 0;
-            st.sh->nrel[0] = st.sh->nrel[1] = 0; st.sh->hmax_next = 0; st.sh->tmp = 0; st.sh->rel_since = 0;
+            st.rp[n] = W(p.row_ptr[n]);
+            st.sh->count[0] = st.sh->count[1] = 0; st.sh->lvl[0] = st.sh->lvl[1] = 0;
+            st.sh->down[0] = st.sh->down[1] = 0; st.sh->nrel[0] = st.sh->nrel[1] = 0;
+            st.sh->hmax_next = 0; st.sh->tmp = 0; st.sh->rel_since = 0;
             for (int i = 0; i < FC_NSTAT; ++i) st.sh->st[i] = 0;
         }
         __syncthreads();
-        if (!have_labels) {
-            global_relabel<COMPACT, G>(p, st, f, t, U, NK, c_grscan);
+        if (have_labels) {
+            hmax = int32_t(p.label_hmax[t]);                 // highest level that holds a compute node
+        } else {
+            global_relabel<COMPACT, G>(p, st, t, U, NK, c_grscan);
             if (tid == 0) { ++c_gr; st.sh->count[0] = st.sh->count[1] = 0; }
             __syncthreads();
+            hmax = max_active_height_below(st, n, t, n);
         }
     }
-
-    int32_t hmax = max_active_height_below(st, n, t, n);      // highest level holding excess
+    FC_TICK(t_init);
     int32_t steps_since = 0, total_steps = 0, step = 0;
     bool failed = false;
 
     // ---- passes: sweep the height levels from the highest active one down to 1
-    while (hmax >= 1 && st.e[t] != NK) {
+    while (hmax >= 1 && st.excess(t) != NK) {
         int32_t d = hmax;
         bool done = false;
         while (d >= 1) {
             const int32_t par = step & 1;
+            FC_TICK(t_other);
             const int32_t cnt = compact_level(st, n, t, d, par);          // barrier inside
-            if (tid == 0) { st.sh->count[par ^ 1] = 0; st.sh->down[par ^ 1] = 0; st.sh->nrel[par ^ 1] = 0; }
+            FC_TICK(t_compact);
+            const int32_t lvltot = st.sh->lvl[par];
+            if (tid == 0) { st.sh->count[par ^ 1] = 0; st.sh->lvl[par ^ 1] = 0; st.sh->down[par ^ 1] = 0; st.sh->nrel[par ^ 1] = 0; }
 
-            // discharge every vertex of the level: G lanes scan one vertex's residual arcs
-            for (int32_t i = grp; i < cnt; i += ngrp) {
-                const int32_t u = int32_t(st.list[i]);
-                int32_t rem = st.e[u];
-                const int32_t beg = p.row_ptr[u], end = p.row_ptr[u + 1];
-                int32_t minh = 0x7fffffff;
-                if (lg == 0) ++c_dis;
-                for (int32_t base = beg; base < end && rem > 0; base += G) {
-                    const int32_t a = base + lg;
-                    int32_t ra = 0, hw = 0, fv = 0;
-                    ArcRec r; r.w = 0; r.pair = 0; r.bw = 0; r.fwd = 0;
-                    if (a < end) {
-                        r = load_arc<COMPACT>(p, a);
-                        ++c_scan;
-                        fv = int32_t(f[r.pair]);
-                        ra = r.fwd ? arc_cap(U, r.bw, NK) - fv : fv;
-                        hw = int32_t(st.h[r.w]);
-                    }
-                    const bool adm = ra > 0 && hw + 1 == d;
-                    if (ra > 0 && !adm && hw < minh) minh = hw;
-                    const unsigned long long bal = __ballot(adm) & gmask;
-                    if (bal) {
-                        int32_t delta = 0, rem_new;
-                        const bool first = adm && ((bal & ((1ull << lane) - 1ull)) == 0ull);
-                        const unsigned long long absorbed = __ballot(first && ra >= rem) & gmask;
-                        if (absorbed) {                       // first admissible arc takes everything
-                            if (first) delta = rem;
-                            rem_new = 0;
-                        } else {                              // split the excess in arc order
-                            const int32_t x = adm ? ra : 0;
-                            int32_t incl = x;
+            // Discharge every vertex of the level: G lanes scan one vertex's residual arcs.  Heights are
+            // frozen during the step and every listed vertex sits at height d, so pushes only go to
+            // height d-1: no arc is updated from both ends and no listed vertex receives excess.
+            for (int32_t i0 = grp; i0 < cnt; i0 += ngrp * FC_PREFETCH) {
+                // stage 1: fetch the first arc chunk (and what it points at) of up to FC_PREFETCH vertices
+                // (all loads are unconditional on clamped indices so that they can be issued back to back)
+                int32_t pu[FC_PREFETCH], pbeg[FC_PREFETCH], pend[FC_PREFETCH], pav[FC_PREFETCH];
+                int32_t pfv[FC_PREFETCH], phw[FC_PREFETCH];
+                ArcRaw<COMPACT> praw[FC_PREFETCH];
+                ArcRec prec[FC_PREFETCH];
+                bool pok[FC_PREFETCH];
 #pragma unroll
-                            for (int s = 1; s < G; s <<= 1) {
-                                int32_t y = __shfl_up(incl, s, G);
-                                if (lg >= s) incl += y;
-                            }
-                            const int32_t total = __shfl(incl, G - 1, G);
-                            const int32_t excl = incl - x;
-                            delta = rem - excl; if (delta > x) delta = x; if (delta < 0) delta = 0;
-                            rem_new = total >= rem ? 0 : rem - total;
-                        }
-                        if (delta > 0) {
-                            f[r.pair] = FT(r.fwd ? fv + delta : fv - delta);
-                            atomicAdd(&st.e[r.w], delta);
-                            if (r.w != t) st.sh->down[par] = 1;
-                            ++c_push;
-                        }
-                        rem = rem_new;
-                    }
+                for (int q = 0; q < FC_PREFETCH; ++q) {
+                    const int32_t i = i0 + q * ngrp;
+                    pok[q] = i < cnt;
+                    pu[q] = int32_t(st.list[pok[q] ? i : cnt - 1]);
                 }
-                if (rem > 0) {                                // every admissible arc is saturated: relabel
 #pragma unroll
-                    for (int s = G / 2; s > 0; s >>= 1) {
-                        int32_t y = __shfl_xor(minh, s, G);
-                        if (y < minh) minh = y;
+                for (int q = 0; q < FC_PREFETCH; ++q) {
+                    pbeg[q] = int32_t(st.rp[pu[q]]);
+                    pend[q] = int32_t(st.rp[pu[q] + 1]);
+                    pav[q] = st.excess(pu[q]);
+                }
+#pragma unroll
+                for (int q = 0; q < FC_PREFETCH; ++q) {
+                    const int32_t a = pbeg[q] + lg;
+                    praw[q] = load_arc_raw<COMPACT>(p, a < p.n_rec ? a : p.n_rec - 1);
+                }
+#pragma unroll
+                for (int q = 0; q < FC_PREFETCH; ++q) {
+                    prec[q] = decode_arc<COMPACT>(praw[q]);
+                    pfv[q] = int32_t(st.f[prec[q].pair]);
+                    phw[q] = int32_t(st.h[prec[q].w]);
+                }
+                // stage 2: discharge them one after the other
+#pragma unroll
+                for (int q = 0; q < FC_PREFETCH; ++q) {
+                    if (!pok[q]) continue;                                // uniform over the lane group
+                    const int32_t u = pu[q], beg = pbeg[q], end = pend[q], i = i0 + q * ngrp;
+                    int32_t rem = pav[q];
+                    int32_t minh = 0x7fffffff;
+                    if (lg == 0) ++c_dis;
+                    ArcRec r = prec[q];
+                    int32_t fv = pfv[q], hw = phw[q];
+                    bool have = beg + lg < end;
+                    for (int32_t base = beg; base < end && rem > 0;) {
+                        if (have) ++c_scan;
+                        const int32_t ra = have ? (r.fwd ? arc_cap(U, r.bw, NK) - fv : fv) : 0;
+                        const bool adm = ra > 0 && hw + 1 == d;
+                        if (ra > 0 && !adm && hw < minh) minh = hw;
+                        const unsigned long long bal = __ballot(adm) & gmask;
+                        if (bal) {
+                            int32_t delta = 0, rem_new;
+                            const bool first = adm && ((bal & ((1ull << lane) - 1ull)) == 0ull);
+                            const unsigned long long absorbed = __ballot(first && ra >= rem) & gmask;
+                            if (absorbed) {                       // first admissible arc takes everything
+                                if (first) delta = rem;
+                                rem_new = 0;
+                            } else {                              // split the excess in arc order
+                                const int32_t x = adm ? ra : 0;
+                                int32_t incl = x;
+#pragma unroll
+                                for (int s = 1; s < G; s <<= 1) {
+                                    const int32_t y = __shfl_up(incl, s, G);
+                                    if (lg >= s) incl += y;
+                                }
+                                const int32_t total = __shfl(incl, G - 1, G);
+                                const int32_t excl = incl - x;
+                                delta = rem - excl; if (delta > x) delta = x; if (delta < 0) delta = 0;
+                                rem_new = total >= rem ? 0 : rem - total;
+                            }
+                            if (delta > 0) {
+                                st.f[r.pair] = W(r.fwd ? fv + delta : fv - delta);
+                                st.excess_add(r.w, delta);
+                                if (r.w != t) st.sh->down[par] = 1;
+                                ++c_push;
+                            }
+                            rem = rem_new;
+                        }
+                        base += G;
+                        if (base < end && rem > 0) {                  // next chunk of a long row
+                            have = base + lg < end;
+                            if (have) {
+                                r = load_arc<COMPACT>(p, base + lg);
+                                fv = int32_t(st.f[r.pair]);
+                                hw = int32_t(st.h[r.w]);
+                            }
+                        }
                     }
-                    if (lg == 0) {
-                        st.lnew[i] = HT(minh >= n - 1 ? n : minh + 1);
-                        st.sh->nrel[par] = 1;
-                        ++c_rel;
-                    }
-                } else if (lg == 0) st.lnew[i] = HT(0);
-                if (lg == 0) st.e[u] = rem;
+                    if (rem > 0) {                                // every admissible arc is saturated: relabel
+#pragma unroll
+                        for (int s = G / 2; s > 0; s >>= 1) {
+                            const int32_t y = __shfl_xor(minh, s, G);
+                            if (y < minh) minh = y;
+                        }
+                        if (lg == 0) {
+                            st.lnew[i] = W(minh >= n - 1 ? n : minh + 1);
+                            atomicAdd(&st.sh->nrel[par], 1);
+                            ++c_rel;
+                        }
+                    } else if (lg == 0) st.lnew[i] = W(0);
+                    if (lg == 0 && rem != pav[q]) st.excess_sub(u, pav[q] - rem);
+                }
             }
             __syncthreads();
+            FC_TICK(t_discharge);
             const int32_t nrel = st.sh->nrel[par], down = st.sh->down[par];
             ++step; ++steps_since; ++total_steps;
             if (tid == 0) ++c_step;
@@ -322,29 +452,26 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
             if (nrel) {
                 // apply the new heights (deferred so that the level's scans all saw the same heights)
                 for (int32_t i = tid; i < cnt; i += T) {
-                    int32_t nh = int32_t(st.lnew[i]);
+                    const int32_t nh = int32_t(st.lnew[i]);
                     if (nh) {
-                        st.h[int32_t(st.list[i])] = HT(nh);
-                        atomicAdd(&st.sh->rel_since, 1);
+                        st.h[int32_t(st.list[i])] = W(nh);
                         if (nh < n) atomicMax(&st.sh->hmax_next, nh);
                     }
                 }
-                __syncthreads();
-                if (p.use_gap) {
-                    // level d lost vertices; if it is now empty nothing above it can reach the sink
-                    int32_t mine = 0;
-                    for (int32_t v = tid; v < n; v += T) mine |= (int32_t(st.h[v]) == d);
-                    if (!__syncthreads_or(mine)) {
-                        for (int32_t v = tid; v < n; v += T) {
-                            int32_t hv = int32_t(st.h[v]);
-                            if (hv > d && hv < n) st.h[v] = HT(n);
-                        }
-                        if (tid == 0) st.sh->hmax_next = 0;
-                        __syncthreads();
+                if (tid == 0) st.sh->rel_since += nrel;
+                if (p.use_gap && nrel == lvltot) {
+                    // every vertex of level d left it: the level is empty, so nothing above it can
+                    // reach the sink any more
+                    __syncthreads();
+                    for (int32_t v = tid; v < n; v += T) {
+                        const int32_t hv = int32_t(st.h[v]);
+                        if (hv > d && hv < n) st.h[v] = W(n);
                     }
+                    if (tid == 0) st.sh->hmax_next = 0;
                 }
+                __syncthreads();
             }
-            if (st.e[t] == NK) { done = true; break; }
+            if (st.excess(t) == NK) { done = true; break; }
             if (total_steps >= p.max_steps) { failed = true; done = true; break; }
             if (down) d = d - 1;
             else if (d > 1) d = max_active_height_below(st, n, t, d);
@@ -353,8 +480,11 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
         if (done) break;
         const int32_t rel_total = st.sh->rel_since;     // last written before a barrier: uniform
         if (rel_total > 0 && (rel_total >= p.gr_relabels || steps_since >= p.gr_steps)) {
-            global_relabel<COMPACT, G>(p, st, f, t, U, NK, c_grscan);
-            if (tid == 0) { ++c_gr; st.sh->count[0] = st.sh->count[1] = 0; st.sh->hmax_next = 0; st.sh->rel_since = 0; }
+            global_relabel<COMPACT, G>(p, st, t, U, NK, c_grscan);
+            if (tid == 0) {
+                ++c_gr; st.sh->count[0] = st.sh->count[1] = 0; st.sh->lvl[0] = st.sh->lvl[1] = 0;
+                st.sh->hmax_next = 0; st.sh->rel_since = 0;
+            }
             steps_since = 0;
             __syncthreads();
             hmax = max_active_height_below(st, n, t, n);
@@ -366,26 +496,34 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     }
 
     __syncthreads();
-    if (tid == 0) p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : st.e[t];
+    if (tid == 0) p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : st.excess(t);
     if (p.stats) {
         atomicAdd(&st.sh->st[0], c_push); atomicAdd(&st.sh->st[2], c_scan); atomicAdd(&st.sh->st[4], c_grscan);
         if (c_rel) atomicAdd(&st.sh->st[1], c_rel);
         if (c_dis) atomicAdd(&st.sh->st[6], c_dis);
         if (tid == 0) { st.sh->st[3] = c_gr; st.sh->st[5] = c_step; st.sh->st[7] = failed ? 1u : 0u; }
+#ifdef FC_PHASE_TIMING
+        __syncthreads();
+        FC_TICK(t_other);
+        if (tid == 0) { st.sh->st[1] = t_compact; st.sh->st[3] = t_discharge; st.sh->st[4] = t_init; st.sh->st[6] = t_other; }
+#endif
         __syncthreads();
         if (tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = st.sh->st[tid];
     }
 }
 
 // Initial exact labels for every possible sink: breadth-first distances to the sink in the
-// topology (all arcs have positive capacity before any flow is pushed).  One workgroup per sink.
+// topology (all arcs have positive capacity before any flow is pushed), and the largest finite
+// distance of a compute node (the first level to discharge).  One workgroup per sink.
 __global__ void __launch_bounds__(256) fc_label_table_kernel(int32_t n, const int32_t *row_ptr, const int4 *arc,
-                                                             uint16_t *labels) {
+                                                             const uint8_t *is_compute, uint16_t *labels,
+                                                             uint16_t *label_hmax) {
     extern __shared__ __align__(16) unsigned char smem[];
     int32_t *h = reinterpret_cast<int32_t *>(smem);
-    __shared__ int32_t changed;
+    __shared__ int32_t changed, hm;
     const int32_t t = blockIdx.x, tid = threadIdx.x, T = blockDim.x;
     for (int32_t v = tid; v < n; v += T) h[v] = v == t ? 0 : n;
+    if (tid == 0) hm = 0;
     __syncthreads();
     for (int32_t d = 0; d < n; ++d) {
         if (tid == 0) changed = 0;
@@ -402,7 +540,12 @@ __global__ void __launch_bounds__(256) fc_label_table_kernel(int32_t n, const in
         __syncthreads();
         if (!c) break;
     }
-    for (int32_t v = tid; v < n; v += T) labels[size_t(t) * size_t(n) + size_t(v)] = uint16_t(h[v]);
+    for (int32_t v = tid; v < n; v += T) {
+        labels[size_t(t) * size_t(n) + size_t(v)] = uint16_t(h[v]);
+        if (v != t && is_compute[v] && h[v] < n) atomicMax(&hm, h[v]);
+    }
+    __syncthreads();
+    if (tid == 0) label_hmax[t] = uint16_t(hm);
 }
 
 __global__ void fc_expand_candidates_kernel(int32_t C, int32_t N, const int32_t *compute_ids, const int32_t *cU,
@@ -458,14 +601,10 @@ __global__ void __launch_bounds__(256) fc_stats_reduce_kernel(long long P, const
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-size_t lds_bytes(const fc_graph *g, bool compact) {
-    size_t ft = compact ? 2 : 4, ht = compact ? 2 : 4;
-    size_t b = align_up(size_t(g->m0) * ft, 16) + 3 * align_up(size_t(g->n) * ht, 16) +
-               align_up(size_t(g->n) * 4, 16) + sizeof(Shared);
-    return align_up(b, 16);
-}
+size_t lds_bytes(const fc_graph *g, bool compact) { return carve_lds(g->n, int32_t(g->m0), compact).total; }
 
-bool compact_ids_fit(const fc_graph *g) { return g->n <= 32767 && g->m0 <= 65535; }
+// 15-bit vertex ids and arc ids, 16-bit row offsets
+bool compact_ids_fit(const fc_graph *g) { return g->n <= 32767 && 2 * g->m0 <= 65535; }
 
 struct Resolved {
     int32_t T, G, gr_steps, gr_relabels, use_gap, use_labels, force_wide, max_steps, src_cap_bound;
@@ -530,6 +669,7 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
               int32_t *d_flow, const Resolved &opt, hipStream_t stream, uint32_t *d_stats_pp) {
     KParams kp;
     kp.n = g->n; kp.N = g->N; kp.m0 = int32_t(g->m0);
+    kp.n_rec = std::max<int32_t>(1, int32_t(2 * g->m0));
     kp.row_ptr = g->d_row_ptr;
     kp.arc_wide = reinterpret_cast<const int4 *>(g->d_arc_wide);
     const bool compact_possible = !opt.force_wide && g->d_arc_compact != nullptr &&
@@ -541,6 +681,7 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     kp.arc_compact = compact_possible ? reinterpret_cast<const uint2 *>(g->d_arc_compact) : nullptr;
     kp.is_compute = g->d_is_compute;
     kp.labels = opt.use_labels ? g->d_labels : nullptr;
+    kp.label_hmax = g->d_label_hmax;
     kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.flow_out = d_flow; kp.stats = d_stats_pp;
     kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
     kp.wide_available = wide_possible ? 1 : 0;
@@ -606,7 +747,7 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
 
     const size_t M = size_t(2 * g->m0), n = size_t(g->n);
     try {
-        std::vector<int4> wide(M ? M : 1);
+        std::vector<int4> wide(M ? M : 1, make_int4(0, 0, 0, 0));
         for (size_t i = 0; i < M; ++i) wide[i] = make_int4(g->other[i], g->pair[i], g->bw[i], g->fwd[i]);
         g->on_device = true;
         if (hipMalloc(&g->d_row_ptr, sizeof(int32_t) * (n + 1)) != hipSuccess) return fail(FC_EDEVICE);
@@ -614,21 +755,22 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
         if (hipMalloc(&g->d_is_compute, n) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMalloc(&g->d_compute_ids, sizeof(int32_t) * size_t(g->N)) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMemcpy(g->d_row_ptr, g->row_ptr.data(), sizeof(int32_t) * (n + 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
-        if (hipMemcpy(g->d_arc_wide, wide.data(), sizeof(int4) * M, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMemcpy(g->d_arc_wide, wide.data(), sizeof(int4) * (M ? M : 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMemcpy(g->d_is_compute, g->is_compute.data(), n, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMemcpy(g->d_compute_ids, g->compute_ids.data(), sizeof(int32_t) * size_t(g->N), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         if (compact_ids_fit(g)) {
-            std::vector<uint2> cmp(M ? M : 1);
+            std::vector<uint2> cmp(M ? M : 1, make_uint2(0u, 0u));
             for (size_t i = 0; i < M; ++i)
                 cmp[i] = make_uint2(uint32_t(g->other[i]) | (uint32_t(g->fwd[i]) << 15) | (uint32_t(g->pair[i]) << 16), uint32_t(g->bw[i]));
             if (hipMalloc(&g->d_arc_compact, sizeof(uint2) * (M ? M : 1)) != hipSuccess) return fail(FC_EDEVICE);
-            if (hipMemcpy(g->d_arc_compact, cmp.data(), sizeof(uint2) * M, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+            if (hipMemcpy(g->d_arc_compact, cmp.data(), sizeof(uint2) * (M ? M : 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         }
         // per-sink exact initial labels, while the table stays small (n^2 16-bit entries)
         if (n <= 8192 && n * 4 <= size_t(lds)) {
             if (hipMalloc(&g->d_labels, n * n * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
+            if (hipMalloc(&g->d_label_hmax, n * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
             hipLaunchKernelGGL(fc_label_table_kernel, dim3(unsigned(n)), dim3(256), n * 4, 0, g->n, g->d_row_ptr,
-                               reinterpret_cast<const int4 *>(g->d_arc_wide), g->d_labels);
+                               reinterpret_cast<const int4 *>(g->d_arc_wide), g->d_is_compute, g->d_labels, g->d_label_hmax);
             if (hipGetLastError() != hipSuccess) return fail(FC_EDEVICE);
             if (hipDeviceSynchronize() != hipSuccess) return fail(FC_EDEVICE);
         }
@@ -648,6 +790,7 @@ extern "C" int fc_graph_free(fc_graph *g) {
         if (g->d_is_compute) (void)hipFree(g->d_is_compute);
         if (g->d_compute_ids) (void)hipFree(g->d_compute_ids);
         if (g->d_labels) (void)hipFree(g->d_labels);
+        if (g->d_label_hmax) (void)hipFree(g->d_label_hmax);
     }
     delete g;
     return FC_OK;

@@ -26,10 +26,11 @@ struct fc_graph {
     int device = -1;
     int32_t *d_row_ptr = nullptr;      // [n+1]
     void *d_arc_wide = nullptr;        // int4 [2*m0]: {other, pair, bw, fwd}
-    void *d_arc_compact = nullptr;     // uint2 [2*m0]: {other | fwd<<15 | pair<<16, bw}; null if ids do not fit
+    void *d_arc_compact = nullptr;     // uint2 [2*m0]: {other | fwd<<15 | pair<<16, bw}; null if ids do not fit 15 bits
     uint8_t *d_is_compute = nullptr;   // [n]
     int32_t *d_compute_ids = nullptr;  // [N]
     uint16_t *d_labels = nullptr;      // [n*n] exact initial labels per sink (row = sink), or null
+    uint16_t *d_label_hmax = nullptr;  // [n] highest finite label of a compute node, per sink
     int32_t lds_limit = 0;             // bytes of LDS one workgroup may use
     int32_t n_cu = 0;
 };
