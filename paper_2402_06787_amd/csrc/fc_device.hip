@@ -43,8 +43,10 @@ struct KParams {
     const int4 *arc_wide;
     const uint2 *arc_compact;
     const uint8_t *is_compute;
-    const uint16_t *labels;      // [n*n] exact initial heights per sink (row = sink), or null
+    const uint16_t *labels;      // [n*n] exact initial heights per sink (row = sink), bit 15 = compute node; or null
     const uint16_t *label_hmax;  // [n] highest finite label of a compute node per sink
+    const uint4 *p1;             // [n*n] first-pass entries per sink in level order, or null
+    const uint16_t *level_off;   // [n*64] level boundaries in `order` per sink
     const int32_t *sink, *U, *k;
     int32_t *flow_out;
     uint32_t *stats;             // [P * FC_NSTAT] or null
@@ -89,21 +91,25 @@ __device__ __forceinline__ int32_t arc_cap(int32_t U, int32_t bw, int32_t NK) {
     return c > (long long)NK ? NK : int32_t(c);
 }
 
+constexpr int FC_MAX_LEVELS = 62;    // deepest breadth-first level the per-sink level table can describe
+
 // LDS scalars shared by a workgroup
 struct Shared {
-    int32_t count[2];      // length of the current level list (by step parity)
-    int32_t lvl[2];        // number of vertices (active or not) at the level being processed
-    int32_t down[2];       // some push of this step went to a non-sink vertex
-    int32_t nrel[2];       // vertices relabeled in this step
+    int32_t count[3];      // length of the current level list (indexed by step mod 3: a set is
+                           // cleared one step ahead, when nobody can still be reading it)
+    int32_t lvl[3];        // number of vertices (active or not) at the level being processed
+    int32_t down[3];       // some push of this step went to a non-sink vertex
+    int32_t nrel[3];       // vertices relabeled in this step
     int32_t hmax_next;     // largest finite new height assigned during this pass
     int32_t rel_since;     // relabels since the last global relabel
     int32_t tmp;           // scratch for rare scans
     int32_t pad;
     uint32_t st[FC_NSTAT];
+    uint16_t off[64];      // level table of this sink: off[0] = deepest level L, off[1 + j] = start of level L - j
 };
 
 // Byte offsets of the per-problem LDS arrays.  COMPACT: every array 16-bit; else 32-bit.
-struct Carve { uint32_t f, h, list, lnew, e, rp, sh, total; };
+struct Carve { uint32_t f, h, e, hnew, list, rp, sh, total; };
 
 __host__ __device__ inline Carve carve_lds(int32_t n, int32_t m0, bool compact) {
     const uint32_t w = compact ? 2u : 4u;
@@ -111,9 +117,9 @@ __host__ __device__ inline Carve carve_lds(int32_t n, int32_t m0, bool compact) 
     Carve c; uint32_t off = 0;
     c.f = off; off += up(uint32_t(m0) * w);          // flow on every merged topology arc
     c.h = off; off += up(uint32_t(n) * w);           // height; n = cannot reach the sink
-    c.list = off; off += up(uint32_t(n) * w);        // vertices of the level being processed
-    c.lnew = off; off += up(uint32_t(n) * w);        // new height for list[i] (0 = none)
     c.e = off; off += up(uint32_t(n) * w);           // excess
+    c.hnew = off; off += up(uint32_t(n) * w);        // height a stuck vertex gets after the step (0 = none)
+    c.list = off; off += up(uint32_t(n) * w);        // vertices of the level being processed
     c.rp = off; off += up(uint32_t(n + 1) * w);      // residual CSR row offsets (copy of the shared ones)
     c.sh = off; off += up(uint32_t(sizeof(Shared)));
     c.total = off;
@@ -126,7 +132,7 @@ __host__ __device__ inline Carve carve_lds(int32_t n, int32_t m0, bool compact) 
 template <bool COMPACT>
 struct State {
     using W = typename std::conditional<COMPACT, uint16_t, int32_t>::type;
-    W *f, *h, *list, *lnew, *e, *rp;
+    W *f, *h, *e, *hnew, *list, *rp;
     Shared *sh;
     __device__ __forceinline__ int32_t excess(int32_t v) const { return int32_t(e[v]); }
     __device__ __forceinline__ void excess_add(int32_t v, int32_t d) const {
@@ -212,7 +218,7 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
         // frontier: vertices at distance d (found by a scan; keeps the search free of queues and CAS)
         for (int32_t base = 0; base < n; base += T) {
             const int32_t v = base + tid;
-            const bool isd = v < n && int32_t(st.h[v]) == d;
+            const bool isd = v < n && int32_t(st.h[v < n ? v : 0]) == d;
             const unsigned long long b = __ballot(isd);
             if (b) {
                 int32_t pos = 0;
@@ -241,11 +247,18 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
     __syncthreads();
 }
 
-#ifndef FC_PREFETCH_DEPTH
-#define FC_PREFETCH_DEPTH 4
-#endif
-constexpr int FC_PREFETCH = FC_PREFETCH_DEPTH;   // vertices whose first arc chunk a lane group fetches before discharging them
-
+// One workgroup = one max-flow problem.  Level-synchronous push-relabel: a pass walks the height
+// levels from the highest one holding excess down to 1; in a step every vertex of one level is
+// discharged with all heights frozen, so pushes only go one level down, no arc is touched from
+// both ends and no vertex of the level receives excess.  New heights are applied after the step.
+//
+// A step has up to two parts.  Fast part (first pass only, when the per-sink tables exist): heights
+// still equal the breadth-first labels, so level d is a slice of the sink's precomputed order and
+// one lane per vertex pushes along the vertex's precomputed first admissible arc, read with
+// coalesced loads; a vertex whose excess that arc cannot take goes to the level list.  Group part:
+// G lanes scan the residual row of each listed vertex in chunks, split the excess over the
+// admissible arcs in row order and collect the smallest neighbouring height for a relabel.  After
+// the first pass the list is compacted from the height and excess arrays.
 template <bool COMPACT, int G>
 __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     using W = typename State<COMPACT>::W;
@@ -279,46 +292,51 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     const Carve cv = carve_lds(n, m0, COMPACT);
     State<COMPACT> st;
     st.f = reinterpret_cast<W *>(smem + cv.f); st.h = reinterpret_cast<W *>(smem + cv.h);
-    st.list = reinterpret_cast<W *>(smem + cv.list); st.lnew = reinterpret_cast<W *>(smem + cv.lnew);
-    st.e = reinterpret_cast<W *>(smem + cv.e); st.rp = reinterpret_cast<W *>(smem + cv.rp);
+    st.e = reinterpret_cast<W *>(smem + cv.e); st.hnew = reinterpret_cast<W *>(smem + cv.hnew);
+    st.list = reinterpret_cast<W *>(smem + cv.list); st.rp = reinterpret_cast<W *>(smem + cv.rp);
     st.sh = reinterpret_cast<Shared *>(smem + cv.sh);
-
-    const int32_t lg = tid & (G - 1), grp = tid / G, ngrp = T / G;
     const int32_t lane = tid & 63;
+    const int32_t lg = tid & (G - 1), grp = tid / G, ngrp = T / G;
     const unsigned long long gmask = (G == 64 ? ~0ull : ((1ull << G) - 1ull)) << (lane & ~(G - 1));
 
 #ifdef FC_PHASE_TIMING
     long long tick_ = clock64();
-    uint32_t t_init = 0, t_compact = 0, t_discharge = 0, t_other = 0;
+    uint32_t t_init = 0, t_compact = 0, t_discharge = 0, t_other = 0, t_post = 0, t_next = 0;
 #endif
-    uint32_t c_push = 0, c_scan = 0, c_grscan = 0;            // per-thread counters
-    uint32_t c_rel = 0, c_gr = 0, c_step = 0, c_dis = 0;      // counted by one lane per event / thread 0
+    uint32_t c_push = 0, c_scan = 0, c_grscan = 0, c_rel = 0, c_dis = 0;   // per-thread counters
+    uint32_t c_gr = 0, c_step = 0;                                         // thread 0 only
 
     // ---- preflow: every arc (s, c) saturated (excess k at every compute node), topology arcs empty
+    const bool have_labels = p.labels != nullptr;
+    const bool have_p1 = have_labels && p.p1 != nullptr;
+    const uint4 *p1_row = have_p1 ? p.p1 + size_t(t) * size_t(n) : nullptr;
     int32_t hmax;
     {
         uint4 *fz = reinterpret_cast<uint4 *>(smem + cv.f);
         const int32_t quads = int32_t((cv.h - cv.f) / 16);
         for (int32_t i = tid; i < quads; i += T) fz[i] = make_uint4(0u, 0u, 0u, 0u);
-        const bool have_labels = p.labels != nullptr;
         for (int32_t v = tid; v < n; v += T) {
-            st.e[v] = W(p.is_compute[v] ? k : 0);
             st.rp[v] = W(p.row_ptr[v]);
-            if (have_labels) st.h[v] = W(p.labels[size_t(t) * size_t(n) + size_t(v)]);
+            st.hnew[v] = W(0);
+            if (have_labels) {
+                const uint32_t lc = p.labels[size_t(t) * size_t(n) + size_t(v)];
+                st.h[v] = W(lc & 0x7fffu);
+                st.e[v] = W((lc & 0x8000u) ? k : 0);
+            } else st.e[v] = W(p.is_compute[v] ? k : 0);
         }
         if (tid == 0) {
             st.rp[n] = W(p.row_ptr[n]);
-            st.sh->count[0] = st.sh->count[1] = 0; st.sh->lvl[0] = st.sh->lvl[1] = 0;
-            st.sh->down[0] = st.sh->down[1] = 0; st.sh->nrel[0] = st.sh->nrel[1] = 0;
+            for (int i = 0; i < 3; ++i) { st.sh->count[i] = 0; st.sh->lvl[i] = 0; st.sh->down[i] = 0; st.sh->nrel[i] = 0; }
             st.sh->hmax_next = 0; st.sh->tmp = 0; st.sh->rel_since = 0;
             for (int i = 0; i < FC_NSTAT; ++i) st.sh->st[i] = 0;
         }
+        if (have_p1 && tid < 64) st.sh->off[tid] = p.level_off[size_t(t) * 64 + tid];
         __syncthreads();
         if (have_labels) {
             hmax = int32_t(p.label_hmax[t]);                 // highest level that holds a compute node
         } else {
             global_relabel<COMPACT, G>(p, st, t, U, NK, c_grscan);
-            if (tid == 0) { ++c_gr; st.sh->count[0] = st.sh->count[1] = 0; }
+            if (tid == 0) { ++c_gr; st.sh->count[0] = st.sh->count[1] = 0; }   // the search used these two
             __syncthreads();
             hmax = max_active_height_below(st, n, t, n);
         }
@@ -326,122 +344,115 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     FC_TICK(t_init);
     int32_t steps_since = 0, total_steps = 0, step = 0;
     bool failed = false;
+    bool first_pass = true;
 
     // ---- passes: sweep the height levels from the highest active one down to 1
     while (hmax >= 1 && st.excess(t) != NK) {
         int32_t d = hmax;
         bool done = false;
         while (d >= 1) {
-            const int32_t par = step & 1;
+            const int32_t par = step % 3, nxt = (step + 1) % 3;
             FC_TICK(t_other);
-            const int32_t cnt = compact_level(st, n, t, d, par);          // barrier inside
-            FC_TICK(t_compact);
-            const int32_t lvltot = st.sh->lvl[par];
-            if (tid == 0) { st.sh->count[par ^ 1] = 0; st.sh->lvl[par ^ 1] = 0; st.sh->down[par ^ 1] = 0; st.sh->nrel[par ^ 1] = 0; }
-
-            // Discharge every vertex of the level: G lanes scan one vertex's residual arcs.  Heights are
-            // frozen during the step and every listed vertex sits at height d, so pushes only go to
-            // height d-1: no arc is updated from both ends and no listed vertex receives excess.
-            for (int32_t i0 = grp; i0 < cnt; i0 += ngrp * FC_PREFETCH) {
-                // stage 1: fetch the first arc chunk (and what it points at) of up to FC_PREFETCH vertices
-                // (all loads are unconditional on clamped indices so that they can be issued back to back)
-                int32_t pu[FC_PREFETCH], pbeg[FC_PREFETCH], pend[FC_PREFETCH], pav[FC_PREFETCH];
-                int32_t pfv[FC_PREFETCH], phw[FC_PREFETCH];
-                ArcRaw<COMPACT> praw[FC_PREFETCH];
-                ArcRec prec[FC_PREFETCH];
-                bool pok[FC_PREFETCH];
-#pragma unroll
-                for (int q = 0; q < FC_PREFETCH; ++q) {
-                    const int32_t i = i0 + q * ngrp;
-                    pok[q] = i < cnt;
-                    pu[q] = int32_t(st.list[pok[q] ? i : cnt - 1]);
-                }
-#pragma unroll
-                for (int q = 0; q < FC_PREFETCH; ++q) {
-                    pbeg[q] = int32_t(st.rp[pu[q]]);
-                    pend[q] = int32_t(st.rp[pu[q] + 1]);
-                    pav[q] = st.excess(pu[q]);
-                }
-#pragma unroll
-                for (int q = 0; q < FC_PREFETCH; ++q) {
-                    const int32_t a = pbeg[q] + lg;
-                    praw[q] = load_arc_raw<COMPACT>(p, a < p.n_rec ? a : p.n_rec - 1);
-                }
-#pragma unroll
-                for (int q = 0; q < FC_PREFETCH; ++q) {
-                    prec[q] = decode_arc<COMPACT>(praw[q]);
-                    pfv[q] = int32_t(st.f[prec[q].pair]);
-                    phw[q] = int32_t(st.h[prec[q].w]);
-                }
-                // stage 2: discharge them one after the other
-#pragma unroll
-                for (int q = 0; q < FC_PREFETCH; ++q) {
-                    if (!pok[q]) continue;                                // uniform over the lane group
-                    const int32_t u = pu[q], beg = pbeg[q], end = pend[q], i = i0 + q * ngrp;
-                    int32_t rem = pav[q];
-                    int32_t minh = 0x7fffffff;
-                    if (lg == 0) ++c_dis;
-                    ArcRec r = prec[q];
-                    int32_t fv = pfv[q], hw = phw[q];
-                    bool have = beg + lg < end;
-                    for (int32_t base = beg; base < end && rem > 0;) {
-                        if (have) ++c_scan;
-                        const int32_t ra = have ? (r.fwd ? arc_cap(U, r.bw, NK) - fv : fv) : 0;
-                        const bool adm = ra > 0 && hw + 1 == d;
-                        if (ra > 0 && !adm && hw < minh) minh = hw;
-                        const unsigned long long bal = __ballot(adm) & gmask;
-                        if (bal) {
-                            int32_t delta = 0, rem_new;
-                            const bool first = adm && ((bal & ((1ull << lane) - 1ull)) == 0ull);
-                            const unsigned long long absorbed = __ballot(first && ra >= rem) & gmask;
-                            if (absorbed) {                       // first admissible arc takes everything
-                                if (first) delta = rem;
-                                rem_new = 0;
-                            } else {                              // split the excess in arc order
-                                const int32_t x = adm ? ra : 0;
-                                int32_t incl = x;
-#pragma unroll
-                                for (int s = 1; s < G; s <<= 1) {
-                                    const int32_t y = __shfl_up(incl, s, G);
-                                    if (lg >= s) incl += y;
-                                }
-                                const int32_t total = __shfl(incl, G - 1, G);
-                                const int32_t excl = incl - x;
-                                delta = rem - excl; if (delta > x) delta = x; if (delta < 0) delta = 0;
-                                rem_new = total >= rem ? 0 : rem - total;
-                            }
-                            if (delta > 0) {
-                                st.f[r.pair] = W(r.fwd ? fv + delta : fv - delta);
-                                st.excess_add(r.w, delta);
-                                if (r.w != t) st.sh->down[par] = 1;
-                                ++c_push;
-                            }
-                            rem = rem_new;
-                        }
-                        base += G;
-                        if (base < end && rem > 0) {                  // next chunk of a long row
-                            have = base + lg < end;
-                            if (have) {
-                                r = load_arc<COMPACT>(p, base + lg);
-                                fv = int32_t(st.f[r.pair]);
-                                hw = int32_t(st.h[r.w]);
-                            }
-                        }
+            if (tid == 0) { st.sh->count[nxt] = 0; st.sh->lvl[nxt] = 0; st.sh->down[nxt] = 0; st.sh->nrel[nxt] = 0; }
+            const bool fast = first_pass && have_p1;
+            int32_t cnt, lvltot;
+            if (fast) {
+                // ---- fast part: one lane per vertex of the level, along its precomputed first arc.  That
+                // arc carries no flow yet and its head still has its initial height d-1, because in the
+                // first pass a vertex is touched for the first time in the step of its own level.
+                const int32_t L = int32_t(st.sh->off[0]);
+                const int32_t lo = int32_t(st.sh->off[1 + L - d]);
+                lvltot = int32_t(st.sh->off[2 + L - d]) - lo;
+                for (int32_t base = 0; base < lvltot; base += T) {
+                    const int32_t pos = base + tid;
+                    const bool ok = pos < lvltot;
+                    const uint4 en = p1_row[lo + (ok ? pos : 0)];
+                    const int32_t u = int32_t(en.z & 0xffffu);
+                    const int32_t ex = ok ? st.excess(u) : 0;
+                    if (ex > 0) {
+                        const int32_t w = int32_t(en.x & 0x7fffu), pair = int32_t(en.x >> 16);
+                        const int32_t cap = arc_cap(U, int32_t(en.y), NK);
+                        const int32_t delta = ex < cap ? ex : cap;
+                        ++c_dis; ++c_scan; ++c_push;
+                        st.f[pair] = W(delta);
+                        st.excess_add(w, delta);
+                        st.excess_sub(u, delta);
+                        if (w != t) st.sh->down[par] = 1;
+                        if (delta < ex) st.list[atomicAdd(&st.sh->count[par], 1)] = W(u);   // the arc is full
                     }
-                    if (rem > 0) {                                // every admissible arc is saturated: relabel
-#pragma unroll
-                        for (int s = G / 2; s > 0; s >>= 1) {
-                            const int32_t y = __shfl_xor(minh, s, G);
-                            if (y < minh) minh = y;
-                        }
-                        if (lg == 0) {
-                            st.lnew[i] = W(minh >= n - 1 ? n : minh + 1);
-                            atomicAdd(&st.sh->nrel[par], 1);
-                            ++c_rel;
-                        }
-                    } else if (lg == 0) st.lnew[i] = W(0);
-                    if (lg == 0 && rem != pav[q]) st.excess_sub(u, pav[q] - rem);
                 }
+                __syncthreads();
+                cnt = st.sh->count[par];
+            } else {
+                cnt = compact_level(st, n, t, d, par);                    // barrier inside
+                lvltot = st.sh->lvl[par];
+            }
+            FC_TICK(t_compact);
+
+            // ---- group part: G lanes scan one listed vertex's residual row, a chunk at a time
+            for (int32_t i = grp; i < cnt; i += ngrp) {
+                const int32_t u = int32_t(st.list[i]);
+                const int32_t beg = int32_t(st.rp[u]), end = int32_t(st.rp[u + 1]);
+                const int32_t ex = st.excess(u);
+                int32_t rem = ex;
+                int32_t minh = 0x7fffffff;
+                if (lg == 0) ++c_dis;
+                for (int32_t base = beg; base < end && rem > 0; base += G) {
+                    const int32_t a = base + lg;
+                    int32_t ra = 0, hw = 0, fv = 0;
+                    ArcRec r; r.w = 0; r.pair = 0; r.bw = 0; r.fwd = 0;
+                    if (a < end) {
+                        r = load_arc<COMPACT>(p, a);
+                        ++c_scan;
+                        fv = int32_t(st.f[r.pair]);
+                        ra = r.fwd ? arc_cap(U, r.bw, NK) - fv : fv;
+                        hw = int32_t(st.h[r.w]);
+                    }
+                    const bool adm = ra > 0 && hw + 1 == d;
+                    if (ra > 0 && !adm && hw < minh) minh = hw;
+                    const unsigned long long bal = __ballot(adm) & gmask;
+                    if (bal) {
+                        int32_t delta = 0, rem_new;
+                        const bool first = adm && ((bal & ((1ull << lane) - 1ull)) == 0ull);
+                        const unsigned long long absorbed = __ballot(first && ra >= rem) & gmask;
+                        if (absorbed) {                       // first admissible arc takes everything
+                            if (first) delta = rem;
+                            rem_new = 0;
+                        } else {                              // split the excess in arc order
+                            const int32_t x = adm ? ra : 0;
+                            int32_t incl = x;
+#pragma unroll
+                            for (int s = 1; s < G; s <<= 1) {
+                                const int32_t y = __shfl_up(incl, s, G);
+                                if (lg >= s) incl += y;
+                            }
+                            const int32_t total = __shfl(incl, G - 1, G);
+                            const int32_t excl = incl - x;
+                            delta = rem - excl; if (delta > x) delta = x; if (delta < 0) delta = 0;
+                            rem_new = total >= rem ? 0 : rem - total;
+                        }
+                        if (delta > 0) {
+                            st.f[r.pair] = W(r.fwd ? fv + delta : fv - delta);
+                            st.excess_add(r.w, delta);
+                            if (r.w != t) st.sh->down[par] = 1;
+                            ++c_push;
+                        }
+                        rem = rem_new;
+                    }
+                }
+                if (rem > 0) {                                // every admissible arc is saturated: relabel
+#pragma unroll
+                    for (int s = G / 2; s > 0; s >>= 1) {
+                        const int32_t y = __shfl_xor(minh, s, G);
+                        if (y < minh) minh = y;
+                    }
+                    if (lg == 0) {
+                        st.hnew[u] = W(minh >= n - 1 ? n : minh + 1);
+                        atomicAdd(&st.sh->nrel[par], 1);
+                        ++c_rel;
+                    }
+                }
+                if (lg == 0 && rem != ex) st.excess_sub(u, ex - rem);
             }
             __syncthreads();
             FC_TICK(t_discharge);
@@ -452,9 +463,11 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
             if (nrel) {
                 // apply the new heights (deferred so that the level's scans all saw the same heights)
                 for (int32_t i = tid; i < cnt; i += T) {
-                    const int32_t nh = int32_t(st.lnew[i]);
+                    const int32_t u = int32_t(st.list[i]);
+                    const int32_t nh = int32_t(st.hnew[u]);
                     if (nh) {
-                        st.h[int32_t(st.list[i])] = W(nh);
+                        st.h[u] = W(nh);
+                        st.hnew[u] = W(0);
                         if (nh < n) atomicMax(&st.sh->hmax_next, nh);
                     }
                 }
@@ -471,18 +484,22 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                 }
                 __syncthreads();
             }
+            FC_TICK(t_post);
             if (st.excess(t) == NK) { done = true; break; }
             if (total_steps >= p.max_steps) { failed = true; done = true; break; }
-            if (down) d = d - 1;
+            if (fast) d = d - 1;                                  // lower levels still hold their compute nodes
+            else if (down) d = d - 1;
             else if (d > 1) d = max_active_height_below(st, n, t, d);
             else d = 0;
+            FC_TICK(t_next);
         }
         if (done) break;
+        first_pass = false;
         const int32_t rel_total = st.sh->rel_since;     // last written before a barrier: uniform
         if (rel_total > 0 && (rel_total >= p.gr_relabels || steps_since >= p.gr_steps)) {
             global_relabel<COMPACT, G>(p, st, t, U, NK, c_grscan);
             if (tid == 0) {
-                ++c_gr; st.sh->count[0] = st.sh->count[1] = 0; st.sh->lvl[0] = st.sh->lvl[1] = 0;
+                ++c_gr; st.sh->count[0] = st.sh->count[1] = 0;             // the search used these two
                 st.sh->hmax_next = 0; st.sh->rel_since = 0;
             }
             steps_since = 0;
@@ -498,32 +515,49 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     __syncthreads();
     if (tid == 0) p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : st.excess(t);
     if (p.stats) {
-        atomicAdd(&st.sh->st[0], c_push); atomicAdd(&st.sh->st[2], c_scan); atomicAdd(&st.sh->st[4], c_grscan);
-        if (c_rel) atomicAdd(&st.sh->st[1], c_rel);
-        if (c_dis) atomicAdd(&st.sh->st[6], c_dis);
+#ifndef FC_PHASE_TIMING
+        // one LDS update per wavefront and counter: sum over the lanes first
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) {
+            c_push += __shfl_xor(c_push, s); c_scan += __shfl_xor(c_scan, s); c_grscan += __shfl_xor(c_grscan, s);
+            c_rel += __shfl_xor(c_rel, s); c_dis += __shfl_xor(c_dis, s);
+        }
+        if (lane == 0) {
+            atomicAdd(&st.sh->st[0], c_push); atomicAdd(&st.sh->st[2], c_scan); atomicAdd(&st.sh->st[4], c_grscan);
+            atomicAdd(&st.sh->st[1], c_rel); atomicAdd(&st.sh->st[6], c_dis);
+        }
+#endif
         if (tid == 0) { st.sh->st[3] = c_gr; st.sh->st[5] = c_step; st.sh->st[7] = failed ? 1u : 0u; }
 #ifdef FC_PHASE_TIMING
         __syncthreads();
         FC_TICK(t_other);
-        if (tid == 0) { st.sh->st[1] = t_compact; st.sh->st[3] = t_discharge; st.sh->st[4] = t_init; st.sh->st[6] = t_other; }
+        if (tid == 0) { st.sh->st[0] = t_init; st.sh->st[1] = t_compact; st.sh->st[2] = t_discharge; st.sh->st[3] = t_post; st.sh->st[4] = t_next; st.sh->st[6] = t_other; }
 #endif
         __syncthreads();
         if (tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = st.sh->st[tid];
     }
 }
 
-// Initial exact labels for every possible sink: breadth-first distances to the sink in the
-// topology (all arcs have positive capacity before any flow is pushed), and the largest finite
-// distance of a compute node (the first level to discharge).  One workgroup per sink.
-__global__ void __launch_bounds__(256) fc_label_table_kernel(int32_t n, const int32_t *row_ptr, const int4 *arc,
+// Per-sink tables built once per graph (one workgroup per sink t; every arc has positive capacity
+// before any flow is pushed, so they depend on the topology alone):
+//   labels[t][v]     breadth-first distance from v to t (n = cannot reach t): the exact initial
+//                    heights; bit 15 marks compute nodes (which start with excess k)
+//   label_hmax[t]    largest finite label of a compute node: the first level to discharge
+//   level_off[t][*]  [0] = deepest level L, [1 + j] = start of level L - j in p1[t], [1 + L] = end
+//   p1[t][i]         the i-th vertex in order of decreasing label (ties by id) together with the
+//                    first arc of its residual row that is admissible under these labels:
+//                    {x, y} = that arc's 16-bit-layout record, z = vertex
+// *deep_flag is set when some sink has a level deeper than FC_MAX_LEVELS (then p1/level_off are unusable).
+__global__ void __launch_bounds__(256) fc_sink_tables_kernel(int32_t n, const int32_t *row_ptr, const int4 *arc,
                                                              const uint8_t *is_compute, uint16_t *labels,
-                                                             uint16_t *label_hmax) {
+                                                             uint16_t *label_hmax, uint4 *p1, uint16_t *level_off,
+                                                             int32_t *deep_flag) {
     extern __shared__ __align__(16) unsigned char smem[];
     int32_t *h = reinterpret_cast<int32_t *>(smem);
-    __shared__ int32_t changed, hm;
-    const int32_t t = blockIdx.x, tid = threadIdx.x, T = blockDim.x;
+    __shared__ int32_t changed, hm, deepest, fill, wave_base[4];
+    const int32_t t = blockIdx.x, tid = threadIdx.x, T = blockDim.x, lane = tid & 63;
     for (int32_t v = tid; v < n; v += T) h[v] = v == t ? 0 : n;
-    if (tid == 0) hm = 0;
+    if (tid == 0) { hm = 0; deepest = 0; fill = 0; }
     __syncthreads();
     for (int32_t d = 0; d < n; ++d) {
         if (tid == 0) changed = 0;
@@ -541,11 +575,48 @@ __global__ void __launch_bounds__(256) fc_label_table_kernel(int32_t n, const in
         if (!c) break;
     }
     for (int32_t v = tid; v < n; v += T) {
-        labels[size_t(t) * size_t(n) + size_t(v)] = uint16_t(h[v]);
-        if (v != t && is_compute[v] && h[v] < n) atomicMax(&hm, h[v]);
+        const int32_t hv = h[v];
+        labels[size_t(t) * size_t(n) + size_t(v)] = uint16_t(hv | (is_compute[v] ? 0x8000 : 0));
+        if (v != t && hv < n) {
+            atomicMax(&deepest, hv);
+            if (is_compute[v]) atomicMax(&hm, hv);
+        }
     }
     __syncthreads();
-    if (tid == 0) label_hmax[t] = uint16_t(hm);
+    const int32_t L = deepest;
+    if (tid == 0) { label_hmax[t] = uint16_t(hm); if (L > FC_MAX_LEVELS) atomicOr(deep_flag, 1); }
+    if (L > FC_MAX_LEVELS || p1 == nullptr) return;
+    if (tid == 0) level_off[size_t(t) * 64] = uint16_t(L);
+    // stable counting sort by decreasing label: one scan of all vertices per level
+    for (int32_t d = L; d >= 1; --d) {
+        if (tid == 0) level_off[size_t(t) * 64 + 1 + (L - d)] = uint16_t(fill);
+        for (int32_t base = 0; base < n; base += T) {
+            const int32_t v = base + tid;
+            const bool isd = v < n && h[v < n ? v : 0] == d;
+            const unsigned long long b = __ballot(isd);
+            __syncthreads();
+            if (lane == 0) wave_base[tid >> 6] = __popcll(b);
+            __syncthreads();
+            int32_t before = 0, tot = 0;
+            for (int w = 0; w < int(T >> 6); ++w) { if (w < (tid >> 6)) before += wave_base[w]; tot += wave_base[w]; }
+            if (isd) {
+                uint4 en = make_uint4(0u, 0u, uint32_t(v), 0u);
+                for (int32_t a = row_ptr[v]; a < row_ptr[v + 1]; ++a) {
+                    const int4 r = arc[a];
+                    if (r.w && h[r.x] + 1 == d) {          // first admissible arc: leaves v, ends one level down
+                        en.x = uint32_t(r.x) | (1u << 15) | (uint32_t(r.y) << 16);
+                        en.y = uint32_t(r.z);
+                        break;
+                    }
+                }
+                p1[size_t(t) * size_t(n) + size_t(fill + before + __popcll(b & ((1ull << lane) - 1ull)))] = en;
+            }
+            __syncthreads();
+            if (tid == 0) fill += tot;
+            __syncthreads();
+        }
+    }
+    if (tid == 0) level_off[size_t(t) * 64 + 1 + L] = uint16_t(fill);
 }
 
 __global__ void fc_expand_candidates_kernel(int32_t C, int32_t N, const int32_t *compute_ids, const int32_t *cU,
@@ -682,6 +753,8 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     kp.is_compute = g->d_is_compute;
     kp.labels = opt.use_labels ? g->d_labels : nullptr;
     kp.label_hmax = g->d_label_hmax;
+    kp.p1 = opt.use_labels ? reinterpret_cast<const uint4 *>(g->d_p1) : nullptr;
+    kp.level_off = g->d_level_off;
     kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.flow_out = d_flow; kp.stats = d_stats_pp;
     kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
     kp.wide_available = wide_possible ? 1 : 0;
@@ -765,14 +838,33 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
             if (hipMalloc(&g->d_arc_compact, sizeof(uint2) * (M ? M : 1)) != hipSuccess) return fail(FC_EDEVICE);
             if (hipMemcpy(g->d_arc_compact, cmp.data(), sizeof(uint2) * (M ? M : 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         }
-        // per-sink exact initial labels, while the table stays small (n^2 16-bit entries)
+        // per-sink tables, while they stay small: exact initial labels (n^2 x 2 bytes) and, for graphs
+        // that fit the 16-bit record layout, first-pass entries in level order (n^2 x 16 bytes)
         if (n <= 8192 && n * 4 <= size_t(lds)) {
+            const bool with_p1 = compact_ids_fit(g) && n <= 4096;
+            int32_t *d_flag = nullptr;
             if (hipMalloc(&g->d_labels, n * n * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
             if (hipMalloc(&g->d_label_hmax, n * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
-            hipLaunchKernelGGL(fc_label_table_kernel, dim3(unsigned(n)), dim3(256), n * 4, 0, g->n, g->d_row_ptr,
-                               reinterpret_cast<const int4 *>(g->d_arc_wide), g->d_is_compute, g->d_labels, g->d_label_hmax);
-            if (hipGetLastError() != hipSuccess) return fail(FC_EDEVICE);
-            if (hipDeviceSynchronize() != hipSuccess) return fail(FC_EDEVICE);
+            if (with_p1) {
+                if (hipMalloc(&g->d_p1, n * n * sizeof(uint4)) != hipSuccess) return fail(FC_EDEVICE);
+                if (hipMalloc(&g->d_level_off, n * 64 * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
+            }
+            if (hipMalloc(&d_flag, sizeof(int32_t)) != hipSuccess) return fail(FC_EDEVICE);
+            int32_t flag = 0;
+            bool ok = hipMemset(d_flag, 0, sizeof(int32_t)) == hipSuccess;
+            if (ok) {
+                hipLaunchKernelGGL(fc_sink_tables_kernel, dim3(unsigned(n)), dim3(256), n * 4, 0, g->n, g->d_row_ptr,
+                                   reinterpret_cast<const int4 *>(g->d_arc_wide), g->d_is_compute, g->d_labels,
+                                   g->d_label_hmax, reinterpret_cast<uint4 *>(g->d_p1), g->d_level_off, d_flag);
+                ok = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess &&
+                     hipMemcpy(&flag, d_flag, sizeof(int32_t), hipMemcpyDeviceToHost) == hipSuccess;
+            }
+            (void)hipFree(d_flag);
+            if (!ok) return fail(FC_EDEVICE);
+            if (flag && g->d_p1) {                        // some sink is deeper than the level table: no level order
+                (void)hipFree(g->d_p1); g->d_p1 = nullptr;
+                (void)hipFree(g->d_level_off); g->d_level_off = nullptr;
+            }
         }
     } catch (const std::bad_alloc &) {
         return fail(FC_ENOMEM);
@@ -791,6 +883,8 @@ extern "C" int fc_graph_free(fc_graph *g) {
         if (g->d_compute_ids) (void)hipFree(g->d_compute_ids);
         if (g->d_labels) (void)hipFree(g->d_labels);
         if (g->d_label_hmax) (void)hipFree(g->d_label_hmax);
+        if (g->d_p1) (void)hipFree(g->d_p1);
+        if (g->d_level_off) (void)hipFree(g->d_level_off);
     }
     delete g;
     return FC_OK;

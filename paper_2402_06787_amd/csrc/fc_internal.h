@@ -29,8 +29,10 @@ struct fc_graph {
     void *d_arc_compact = nullptr;     // uint2 [2*m0]: {other | fwd<<15 | pair<<16, bw}; null if ids do not fit 15 bits
     uint8_t *d_is_compute = nullptr;   // [n]
     int32_t *d_compute_ids = nullptr;  // [N]
-    uint16_t *d_labels = nullptr;      // [n*n] exact initial labels per sink (row = sink), or null
+    uint16_t *d_labels = nullptr;      // [n*n] exact initial labels per sink (row = sink), bit 15 = compute; or null
     uint16_t *d_label_hmax = nullptr;  // [n] highest finite label of a compute node, per sink
+    void *d_p1 = nullptr;              // uint4 [n*n] first-pass entries in level order, per sink (null: not built)
+    uint16_t *d_level_off = nullptr;   // [n*64] level boundaries in d_p1, per sink
     int32_t lds_limit = 0;             // bytes of LDS one workgroup may use
     int32_t n_cu = 0;
 };
