@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--threads-per-problem", type=int, default=0)
     ap.add_argument("--lanes-per-vertex", type=int, default=0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run a plain device copy of known size instead (calibrates the rocprofv3 HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (independent problems, no collectives); "
@@ -64,6 +66,18 @@ def main():
         fcbuild.build_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.copy_probe:
+        nbytes = 1 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe": True, "bytes_read_per_copy": nbytes, "bytes_written_per_copy": nbytes,
+                          "copies": 5}), flush=True)
+        return
 
     cfg = args.config
     topo = w.config_topology(cfg)

@@ -16,6 +16,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -91,6 +92,14 @@ __device__ __forceinline__ int32_t arc_cap(int32_t U, int32_t bw, int32_t NK) {
     return c > (long long)NK ? NK : int32_t(c);
 }
 
+// Workgroup barrier for code whose lanes communicate through LDS only: it waits for this wave's LDS
+// operations and leaves global loads in flight, so table reads issued before it overlap the wait.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 constexpr int FC_MAX_LEVELS = 62;    // deepest breadth-first level the per-sink level table can describe
 
 // LDS scalars shared by a workgroup
@@ -146,25 +155,29 @@ struct State {
 };
 
 // Compact vertices v with e[v] > 0, v != t, h[v] == d into st.list and count all vertices at height
-// d; returns after a barrier with the list length.  `par` selects the scalar set.  Four strided
-// vertices per thread are examined per round so that their LDS reads overlap and each wave needs
-// one counter update per round.
+// d; returns after a barrier with the list length.  `par` selects the scalar set.  Up to eight
+// strided vertices per thread are examined per round so that their LDS reads overlap and each
+// wave needs one counter update per round.
 template <bool COMPACT>
 __device__ __forceinline__ int32_t compact_level(const State<COMPACT> &st, int32_t n, int32_t t, int32_t d, int32_t par) {
     using W = typename State<COMPACT>::W;
+    constexpr int Q = 8;
     const int32_t tid = threadIdx.x, T = blockDim.x, lane = tid & 63;
     const unsigned long long below = (1ull << lane) - 1ull;
-    for (int32_t base = 0; base < n; base += 4 * T) {
-        bool act[4]; unsigned long long ba[4]; int32_t tot = 0, lv = 0;
+    for (int32_t base = 0; base < n; base += Q * T) {
+        bool act[Q]; unsigned long long ba[Q]; int32_t tot = 0, lv = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int32_t v = base + q * T + tid;
-            const int32_t vc = v < n ? v : n - 1;                 // clamped: reads stay unconditional
-            const bool at = v < n && int32_t(st.h[vc]) == d;
-            act[q] = at && st.excess(vc) > 0 && v != t;
-            ba[q] = __ballot(act[q]);
-            tot += __popcll(ba[q]);
-            lv += __popcll(__ballot(at));
+        for (int q = 0; q < Q; ++q) {
+            act[q] = false; ba[q] = 0ull;
+            if (base + q * T < n) {                               // uniform over the workgroup
+                const int32_t v = base + q * T + tid;
+                const int32_t vc = v < n ? v : n - 1;             // clamped: reads stay unconditional
+                const bool at = v < n && int32_t(st.h[vc]) == d;
+                act[q] = at && st.excess(vc) > 0 && v != t;
+                ba[q] = __ballot(act[q]);
+                tot += __popcll(ba[q]);
+                lv += __popcll(__ballot(at));
+            }
         }
         if (tot | lv) {
             int32_t pos = 0;
@@ -174,13 +187,13 @@ __device__ __forceinline__ int32_t compact_level(const State<COMPACT> &st, int32
             }
             pos = __shfl(pos, 0);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < Q; ++q) {
                 if (act[q]) st.list[pos + __popcll(ba[q] & below)] = W(base + q * T + tid);
                 pos += __popcll(ba[q]);
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
     return st.sh->count[par];
 }
 
@@ -189,16 +202,16 @@ template <bool COMPACT>
 __device__ __forceinline__ int32_t max_active_height_below(const State<COMPACT> &st, int32_t n, int32_t t, int32_t below) {
     const int32_t tid = threadIdx.x, T = blockDim.x;
     if (tid == 0) st.sh->tmp = 0;
-    __syncthreads();
+    lds_barrier();
     int32_t best = 0;
     for (int32_t v = tid; v < n; v += T) {
         int32_t hv = int32_t(st.h[v]);
         if (st.excess(v) > 0 && v != t && hv < below && hv > best) best = hv;
     }
     if (best > 0) atomicMax(&st.sh->tmp, best);
-    __syncthreads();
+    lds_barrier();
     int32_t r = st.sh->tmp;
-    __syncthreads();
+    lds_barrier();
     return r;
 }
 
@@ -212,7 +225,7 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
     const int32_t lg = tid & (G - 1), grp = tid / G, ngrp = T / G;
     for (int32_t v = tid; v < n; v += T) st.h[v] = W(v == t ? 0 : n);
     if (tid == 0) st.sh->count[0] = 0;
-    __syncthreads();
+    lds_barrier();
     for (int32_t d = 0;; ++d) {
         const int32_t par = d & 1;
         // frontier: vertices at distance d (found by a scan; keeps the search free of queues and CAS)
@@ -227,7 +240,7 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
                 if (isd) st.list[pos + __popcll(b & ((1ull << (tid & 63)) - 1ull))] = W(v);
             }
         }
-        __syncthreads();
+        lds_barrier();
         const int32_t cnt = st.sh->count[par];
         if (tid == 0) st.sh->count[par ^ 1] = 0;
         if (cnt == 0) break;
@@ -242,9 +255,9 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
                 if (res > 0 && int32_t(st.h[r.w]) == n) st.h[r.w] = W(d + 1);    // same value from every writer
             }
         }
-        __syncthreads();
+        lds_barrier();
     }
-    __syncthreads();
+    lds_barrier();
 }
 
 // One workgroup = one max-flow problem.  Level-synchronous push-relabel: a pass walks the height
@@ -310,7 +323,7 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     const bool have_labels = p.labels != nullptr;
     const bool have_p1 = have_labels && p.p1 != nullptr;
     const uint4 *p1_row = have_p1 ? p.p1 + size_t(t) * size_t(n) : nullptr;
-    int32_t hmax;
+    int32_t hmax = have_labels ? int32_t(p.label_hmax[t]) : 0;   // highest level that holds a compute node
     {
         uint4 *fz = reinterpret_cast<uint4 *>(smem + cv.f);
         const int32_t quads = int32_t((cv.h - cv.f) / 16);
@@ -331,15 +344,21 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
             for (int i = 0; i < FC_NSTAT; ++i) st.sh->st[i] = 0;
         }
         if (have_p1 && tid < 64) st.sh->off[tid] = p.level_off[size_t(t) * 64 + tid];
-        __syncthreads();
-        if (have_labels) {
-            hmax = int32_t(p.label_hmax[t]);                 // highest level that holds a compute node
-        } else {
+        lds_barrier();
+        if (!have_labels) {
             global_relabel<COMPACT, G>(p, st, t, U, NK, c_grscan);
             if (tid == 0) { ++c_gr; st.sh->count[0] = st.sh->count[1] = 0; }   // the search used these two
-            __syncthreads();
+            lds_barrier();
             hmax = max_active_height_below(st, n, t, n);
         }
+    }
+    // first-pass entries are read one round ahead: the sink's levels lie back to back in p1_row, so
+    // the entry a lane needs next is known before the current round (and its barrier) is done
+    uint4 en_next = make_uint4(0u, 0u, 0u, 0u);
+    if (have_p1 && hmax >= 1) {
+        const int32_t L = int32_t(st.sh->off[0]);
+        const int32_t i0 = int32_t(st.sh->off[1 + L - hmax]) + tid;
+        en_next = p1_row[i0 < n ? i0 : n - 1];
     }
     FC_TICK(t_init);
     int32_t steps_since = 0, total_steps = 0, step = 0;
@@ -361,12 +380,16 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                 // arc carries no flow yet and its head still has its initial height d-1, because in the
                 // first pass a vertex is touched for the first time in the step of its own level.
                 const int32_t L = int32_t(st.sh->off[0]);
-                const int32_t lo = int32_t(st.sh->off[1 + L - d]);
-                lvltot = int32_t(st.sh->off[2 + L - d]) - lo;
+                const int32_t lo = int32_t(st.sh->off[1 + L - d]), hi = int32_t(st.sh->off[2 + L - d]);
+                lvltot = hi - lo;
                 for (int32_t base = 0; base < lvltot; base += T) {
                     const int32_t pos = base + tid;
                     const bool ok = pos < lvltot;
-                    const uint4 en = p1_row[lo + (ok ? pos : 0)];
+                    const uint4 en = en_next;
+                    {   // next round of this level, else first round of the level below
+                        const int32_t inext = (base + T < lvltot ? lo + base + T : hi) + tid;
+                        en_next = p1_row[inext < n ? inext : n - 1];
+                    }
                     const int32_t u = int32_t(en.z & 0xffffu);
                     const int32_t ex = ok ? st.excess(u) : 0;
                     if (ex > 0) {
@@ -381,7 +404,7 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                         if (delta < ex) st.list[atomicAdd(&st.sh->count[par], 1)] = W(u);   // the arc is full
                     }
                 }
-                __syncthreads();
+                lds_barrier();
                 cnt = st.sh->count[par];
             } else {
                 cnt = compact_level(st, n, t, d, par);                    // barrier inside
@@ -454,7 +477,7 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                 }
                 if (lg == 0 && rem != ex) st.excess_sub(u, ex - rem);
             }
-            __syncthreads();
+            lds_barrier();
             FC_TICK(t_discharge);
             const int32_t nrel = st.sh->nrel[par], down = st.sh->down[par];
             ++step; ++steps_since; ++total_steps;
@@ -475,14 +498,14 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                 if (p.use_gap && nrel == lvltot) {
                     // every vertex of level d left it: the level is empty, so nothing above it can
                     // reach the sink any more
-                    __syncthreads();
+                    lds_barrier();
                     for (int32_t v = tid; v < n; v += T) {
                         const int32_t hv = int32_t(st.h[v]);
                         if (hv > d && hv < n) st.h[v] = W(n);
                     }
                     if (tid == 0) st.sh->hmax_next = 0;
                 }
-                __syncthreads();
+                lds_barrier();
             }
             FC_TICK(t_post);
             if (st.excess(t) == NK) { done = true; break; }
@@ -503,16 +526,16 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                 st.sh->hmax_next = 0; st.sh->rel_since = 0;
             }
             steps_since = 0;
-            __syncthreads();
+            lds_barrier();
             hmax = max_active_height_below(st, n, t, n);
         } else {
             hmax = st.sh->hmax_next;
-            __syncthreads();
+            lds_barrier();
             if (tid == 0) st.sh->hmax_next = 0;
         }
     }
 
-    __syncthreads();
+    lds_barrier();
     if (tid == 0) p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : st.excess(t);
     if (p.stats) {
 #ifndef FC_PHASE_TIMING
@@ -529,11 +552,11 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
 #endif
         if (tid == 0) { st.sh->st[3] = c_gr; st.sh->st[5] = c_step; st.sh->st[7] = failed ? 1u : 0u; }
 #ifdef FC_PHASE_TIMING
-        __syncthreads();
+        lds_barrier();
         FC_TICK(t_other);
         if (tid == 0) { st.sh->st[0] = t_init; st.sh->st[1] = t_compact; st.sh->st[2] = t_discharge; st.sh->st[3] = t_post; st.sh->st[4] = t_next; st.sh->st[6] = t_other; }
 #endif
-        __syncthreads();
+        lds_barrier();
         if (tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = st.sh->st[tid];
     }
 }
@@ -711,6 +734,7 @@ int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
 template <bool COMPACT, int G>
 int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_t stream) {
     auto kern = fc_push_relabel_kernel<COMPACT, G>;
+    if (const char *pad = getenv("FC_LDS_PAD")) lds += size_t(atol(pad));     // tuning aid: occupancy experiments
     static size_t lds_allowed = 0;                  // per instantiation; raised on demand
     if (lds > lds_allowed) {
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
