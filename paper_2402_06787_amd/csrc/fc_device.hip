@@ -100,7 +100,6 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-constexpr int FC_MAX_LEVELS = 62;    // deepest breadth-first level the per-sink level table can describe
 
 // LDS scalars shared by a workgroup
 struct Shared {
@@ -561,87 +560,6 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     }
 }
 
-// Per-sink tables built once per graph (one workgroup per sink t; every arc has positive capacity
-// before any flow is pushed, so they depend on the topology alone):
-//   labels[t][v]     breadth-first distance from v to t (n = cannot reach t): the exact initial
-//                    heights; bit 15 marks compute nodes (which start with excess k)
-//   label_hmax[t]    largest finite label of a compute node: the first level to discharge
-//   level_off[t][*]  [0] = deepest level L, [1 + j] = start of level L - j in p1[t], [1 + L] = end
-//   p1[t][i]         the i-th vertex in order of decreasing label (ties by id) together with the
-//                    first arc of its residual row that is admissible under these labels:
-//                    {x, y} = that arc's 16-bit-layout record, z = vertex
-// *deep_flag is set when some sink has a level deeper than FC_MAX_LEVELS (then p1/level_off are unusable).
-__global__ void __launch_bounds__(256) fc_sink_tables_kernel(int32_t n, const int32_t *row_ptr, const int4 *arc,
-                                                             const uint8_t *is_compute, uint16_t *labels,
-                                                             uint16_t *label_hmax, uint4 *p1, uint16_t *level_off,
-                                                             int32_t *deep_flag) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    int32_t *h = reinterpret_cast<int32_t *>(smem);
-    __shared__ int32_t changed, hm, deepest, fill, wave_base[4];
-    const int32_t t = blockIdx.x, tid = threadIdx.x, T = blockDim.x, lane = tid & 63;
-    for (int32_t v = tid; v < n; v += T) h[v] = v == t ? 0 : n;
-    if (tid == 0) { hm = 0; deepest = 0; fill = 0; }
-    __syncthreads();
-    for (int32_t d = 0; d < n; ++d) {
-        if (tid == 0) changed = 0;
-        __syncthreads();
-        for (int32_t w = tid; w < n; w += T) {
-            if (h[w] != d) continue;
-            for (int32_t a = row_ptr[w]; a < row_ptr[w + 1]; ++a) {
-                int4 r = arc[a];
-                if (!r.w && h[r.x] == n) { h[r.x] = d + 1; changed = 1; }   // topology arc r.x -> w
-            }
-        }
-        __syncthreads();
-        int32_t c = changed;
-        __syncthreads();
-        if (!c) break;
-    }
-    for (int32_t v = tid; v < n; v += T) {
-        const int32_t hv = h[v];
-        labels[size_t(t) * size_t(n) + size_t(v)] = uint16_t(hv | (is_compute[v] ? 0x8000 : 0));
-        if (v != t && hv < n) {
-            atomicMax(&deepest, hv);
-            if (is_compute[v]) atomicMax(&hm, hv);
-        }
-    }
-    __syncthreads();
-    const int32_t L = deepest;
-    if (tid == 0) { label_hmax[t] = uint16_t(hm); if (L > FC_MAX_LEVELS) atomicOr(deep_flag, 1); }
-    if (L > FC_MAX_LEVELS || p1 == nullptr) return;
-    if (tid == 0) level_off[size_t(t) * 64] = uint16_t(L);
-    // stable counting sort by decreasing label: one scan of all vertices per level
-    for (int32_t d = L; d >= 1; --d) {
-        if (tid == 0) level_off[size_t(t) * 64 + 1 + (L - d)] = uint16_t(fill);
-        for (int32_t base = 0; base < n; base += T) {
-            const int32_t v = base + tid;
-            const bool isd = v < n && h[v < n ? v : 0] == d;
-            const unsigned long long b = __ballot(isd);
-            __syncthreads();
-            if (lane == 0) wave_base[tid >> 6] = __popcll(b);
-            __syncthreads();
-            int32_t before = 0, tot = 0;
-            for (int w = 0; w < int(T >> 6); ++w) { if (w < (tid >> 6)) before += wave_base[w]; tot += wave_base[w]; }
-            if (isd) {
-                uint4 en = make_uint4(0u, 0u, uint32_t(v), 0u);
-                for (int32_t a = row_ptr[v]; a < row_ptr[v + 1]; ++a) {
-                    const int4 r = arc[a];
-                    if (r.w && h[r.x] + 1 == d) {          // first admissible arc: leaves v, ends one level down
-                        en.x = uint32_t(r.x) | (1u << 15) | (uint32_t(r.y) << 16);
-                        en.y = uint32_t(r.z);
-                        break;
-                    }
-                }
-                p1[size_t(t) * size_t(n) + size_t(fill + before + __popcll(b & ((1ull << lane) - 1ull)))] = en;
-            }
-            __syncthreads();
-            if (tid == 0) fill += tot;
-            __syncthreads();
-        }
-    }
-    if (tid == 0) level_off[size_t(t) * 64 + 1 + L] = uint16_t(fill);
-}
-
 __global__ void fc_expand_candidates_kernel(int32_t C, int32_t N, const int32_t *compute_ids, const int32_t *cU,
                                             const int32_t *ck, int32_t *sink, int32_t *U, int32_t *k) {
     long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -862,32 +780,24 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
             if (hipMalloc(&g->d_arc_compact, sizeof(uint2) * (M ? M : 1)) != hipSuccess) return fail(FC_EDEVICE);
             if (hipMemcpy(g->d_arc_compact, cmp.data(), sizeof(uint2) * (M ? M : 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         }
-        // per-sink tables, while they stay small: exact initial labels (n^2 x 2 bytes) and, for graphs
-        // that fit the 16-bit record layout, first-pass entries in level order (n^2 x 16 bytes)
-        if (n <= 8192 && n * 4 <= size_t(lds)) {
+        // per-sink tables (built on the host from the topology alone), while they stay small: exact
+        // initial labels (n^2 x 2 bytes) and, for graphs that fit the 16-bit record layout, first-pass
+        // entries in level order (n^2 x 16 bytes)
+        if (n <= 8192) {
             const bool with_p1 = compact_ids_fit(g) && n <= 4096;
-            int32_t *d_flag = nullptr;
+            std::vector<uint16_t> labels, hmax, level_off; std::vector<uint32_t> p1;
+            bool too_deep = false;
+            int rc2 = fc_host_sink_tables(g, with_p1, labels, hmax, p1, level_off, &too_deep);
+            if (rc2 != FC_OK) return fail(rc2);
             if (hipMalloc(&g->d_labels, n * n * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
             if (hipMalloc(&g->d_label_hmax, n * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
-            if (with_p1) {
-                if (hipMalloc(&g->d_p1, n * n * sizeof(uint4)) != hipSuccess) return fail(FC_EDEVICE);
+            if (hipMemcpy(g->d_labels, labels.data(), n * n * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+            if (hipMemcpy(g->d_label_hmax, hmax.data(), n * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+            if (with_p1 && !too_deep) {                   // a sink deeper than the level table: no level order
+                if (hipMalloc(&g->d_p1, n * n * 16) != hipSuccess) return fail(FC_EDEVICE);
                 if (hipMalloc(&g->d_level_off, n * 64 * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
-            }
-            if (hipMalloc(&d_flag, sizeof(int32_t)) != hipSuccess) return fail(FC_EDEVICE);
-            int32_t flag = 0;
-            bool ok = hipMemset(d_flag, 0, sizeof(int32_t)) == hipSuccess;
-            if (ok) {
-                hipLaunchKernelGGL(fc_sink_tables_kernel, dim3(unsigned(n)), dim3(256), n * 4, 0, g->n, g->d_row_ptr,
-                                   reinterpret_cast<const int4 *>(g->d_arc_wide), g->d_is_compute, g->d_labels,
-                                   g->d_label_hmax, reinterpret_cast<uint4 *>(g->d_p1), g->d_level_off, d_flag);
-                ok = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess &&
-                     hipMemcpy(&flag, d_flag, sizeof(int32_t), hipMemcpyDeviceToHost) == hipSuccess;
-            }
-            (void)hipFree(d_flag);
-            if (!ok) return fail(FC_EDEVICE);
-            if (flag && g->d_p1) {                        // some sink is deeper than the level table: no level order
-                (void)hipFree(g->d_p1); g->d_p1 = nullptr;
-                (void)hipFree(g->d_level_off); g->d_level_off = nullptr;
+                if (hipMemcpy(g->d_p1, p1.data(), n * n * 16, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+                if (hipMemcpy(g->d_level_off, level_off.data(), n * 64 * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
             }
         }
     } catch (const std::bad_alloc &) {

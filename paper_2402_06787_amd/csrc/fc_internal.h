@@ -38,5 +38,8 @@ struct fc_graph {
 };
 
 // host-only helpers implemented in fc_host.cpp
+int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &labels,
+                        std::vector<uint16_t> &label_hmax, std::vector<uint32_t> &p1,
+                        std::vector<uint16_t> &level_off, bool *too_deep);
 int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
                   const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out);
