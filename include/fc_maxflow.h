@@ -80,6 +80,8 @@ typedef struct {
     int32_t src_cap_bound;         /* > 0: the caller promises k_j <= this for every problem of the call.
                                       If N * bound <= 65535 only the 16-bit-state kernel is launched;
                                       a problem that breaks the promise gets FC_FLOW_UNSUPPORTED        */
+    int32_t schedule;              /* 1 = on (default), 2 = off: start the problems that look hardest (least
+                                      slack in the sink's own cut) first, so the launch has no long tail */
 } fc_options;
 
 /* ------------------------------------------------------------------------------------------

@@ -53,6 +53,7 @@ struct KParams {
     uint32_t *stats;             // [P * FC_NSTAT] or null
     int32_t gr_steps, gr_relabels, use_gap, max_steps;
     int32_t wide_available;      // the 32-bit-state kernel is launched too
+    const int32_t *order;        // workgroup -> problem (hardest first), or null for the identity
 };
 
 struct ArcRec { int32_t w, pair, bw, fwd; };
@@ -101,15 +102,14 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 
-// LDS scalars shared by a workgroup
+// LDS scalars shared by a workgroup.  Per-step scalars come in two sets indexed by step parity:
+// thread 0 clears the other set after the first barrier of a step, when nobody can still read it.
 struct Shared {
-    int32_t count[3];      // length of the current level list (indexed by step mod 3: a set is
-                           // cleared one step ahead, when nobody can still be reading it)
-    int32_t lvl[3];        // number of vertices (active or not) at the level being processed
-    int32_t down[3];       // some push of this step went to a non-sink vertex
-    int32_t nrel[3];       // vertices relabeled in this step
-    int32_t hmax_next;     // largest finite new height assigned during this pass
-    int32_t rel_since;     // relabels since the last global relabel
+    int32_t cnt[2];        // length of the list being discharged
+    int32_t down[2];       // some push of this step went to a non-sink vertex
+    int32_t nrel[2];       // vertices relabeled in this step
+    int32_t dnext[2];      // largest height among the vertices put on the pending list in this step
+    int32_t back[2];       // per list array: pending entries occupy [back, n)
     int32_t tmp;           // scratch for rare scans
     int32_t pad;
     uint32_t st[FC_NSTAT];
@@ -117,7 +117,7 @@ struct Shared {
 };
 
 // Byte offsets of the per-problem LDS arrays.  COMPACT: every array 16-bit; else 32-bit.
-struct Carve { uint32_t f, h, e, hnew, list, rp, sh, total; };
+struct Carve { uint32_t f, h, e, list0, list1, rp, sh, total; };
 
 __host__ __device__ inline Carve carve_lds(int32_t n, int32_t m0, bool compact) {
     const uint32_t w = compact ? 2u : 4u;
@@ -126,8 +126,8 @@ __host__ __device__ inline Carve carve_lds(int32_t n, int32_t m0, bool compact) 
     c.f = off; off += up(uint32_t(m0) * w);          // flow on every merged topology arc
     c.h = off; off += up(uint32_t(n) * w);           // height; n = cannot reach the sink
     c.e = off; off += up(uint32_t(n) * w);           // excess
-    c.hnew = off; off += up(uint32_t(n) * w);        // height a stuck vertex gets after the step (0 = none)
-    c.list = off; off += up(uint32_t(n) * w);        // vertices of the level being processed
+    c.list0 = off; off += up(uint32_t(n) * w);       // two list arrays: the front holds the vertices being
+    c.list1 = off; off += up(uint32_t(n) * w);       //   discharged, the back collects pending ones
     c.rp = off; off += up(uint32_t(n + 1) * w);      // residual CSR row offsets (copy of the shared ones)
     c.sh = off; off += up(uint32_t(sizeof(Shared)));
     c.total = off;
@@ -140,10 +140,21 @@ __host__ __device__ inline Carve carve_lds(int32_t n, int32_t m0, bool compact) 
 template <bool COMPACT>
 struct State {
     using W = typename std::conditional<COMPACT, uint16_t, int32_t>::type;
-    W *f, *h, *e, *hnew, *list, *rp;
+    // a stuck vertex keeps its new height in h[] behind this flag until the step is over; during the
+    // step every flagged vertex still counts as being at the step's level
+    static constexpr int32_t NEWH = COMPACT ? 0x8000 : 0x40000000;
+    W *f, *h, *e, *list0, *list1, *rp;
     Shared *sh;
     __device__ __forceinline__ int32_t excess(int32_t v) const { return int32_t(e[v]); }
-    __device__ __forceinline__ void excess_add(int32_t v, int32_t d) const {
+    // returns the excess v had before
+    __device__ __forceinline__ int32_t excess_add(int32_t v, int32_t d) const {
+        if (COMPACT) {
+            const uint32_t old = atomicAdd(reinterpret_cast<uint32_t *>(e) + (v >> 1), uint32_t(d) << ((v & 1) * 16));
+            return int32_t((old >> ((v & 1) * 16)) & 0xffffu);
+        }
+        return atomicAdd(reinterpret_cast<int32_t *>(e) + v, d);
+    }
+    __device__ __forceinline__ void excess_add_noret(int32_t v, int32_t d) const {
         if (COMPACT) atomicAdd(reinterpret_cast<uint32_t *>(e) + (v >> 1), uint32_t(d) << ((v & 1) * 16));
         else atomicAdd(reinterpret_cast<int32_t *>(e) + v, d);
     }
@@ -151,71 +162,64 @@ struct State {
         if (COMPACT) atomicSub(reinterpret_cast<uint32_t *>(e) + (v >> 1), uint32_t(d) << ((v & 1) * 16));
         else atomicSub(reinterpret_cast<int32_t *>(e) + v, d);
     }
+    __device__ __forceinline__ int32_t height_during_step(int32_t v, int32_t d) const {
+        const int32_t raw = int32_t(h[v]);
+        return (raw & NEWH) ? d : raw;
+    }
+    // the two list arrays (selected by value: no indexed pointer table, which would live in scratch memory)
+    __device__ __forceinline__ W *list(int32_t a) const { return a ? list1 : list0; }
+    // put v on the pending part of list array `a`
+    __device__ __forceinline__ void pend(int32_t a, int32_t v) const { list(a)[atomicSub(&sh->back[a], 1) - 1] = W(v); }
 };
 
-// Compact vertices v with e[v] > 0, v != t, h[v] == d into st.list and count all vertices at height
-// d; returns after a barrier with the list length.  `par` selects the scalar set.  Up to eight
-// strided vertices per thread are examined per round so that their LDS reads overlap and each
-// wave needs one counter update per round.
+// Collect every vertex that holds excess, is not the sink and can still reach it on the pending
+// part of list array `a` (emptied first).  Used at the start when there is no per-sink order and
+// after a global relabel.  Returns after a barrier with the largest height among them (0 if none).
 template <bool COMPACT>
-__device__ __forceinline__ int32_t compact_level(const State<COMPACT> &st, int32_t n, int32_t t, int32_t d, int32_t par) {
+__device__ __forceinline__ int32_t rebuild_pending(const State<COMPACT> &st, int32_t n, int32_t t, int32_t a) {
     using W = typename State<COMPACT>::W;
     constexpr int Q = 8;
     const int32_t tid = threadIdx.x, T = blockDim.x, lane = tid & 63;
     const unsigned long long below = (1ull << lane) - 1ull;
+    if (tid == 0) { st.sh->back[a] = n; st.sh->tmp = 0; }
+    lds_barrier();
+    int32_t best = 0;
     for (int32_t base = 0; base < n; base += Q * T) {
-        bool act[Q]; unsigned long long ba[Q]; int32_t tot = 0, lv = 0;
+        bool act[Q]; unsigned long long ba[Q]; int32_t tot = 0;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             act[q] = false; ba[q] = 0ull;
             if (base + q * T < n) {                               // uniform over the workgroup
                 const int32_t v = base + q * T + tid;
                 const int32_t vc = v < n ? v : n - 1;             // clamped: reads stay unconditional
-                const bool at = v < n && int32_t(st.h[vc]) == d;
-                act[q] = at && st.excess(vc) > 0 && v != t;
+                const int32_t hv = int32_t(st.h[vc]);
+                act[q] = v < n && v != t && hv < n && st.excess(vc) > 0;
+                if (act[q] && hv > best) best = hv;
                 ba[q] = __ballot(act[q]);
                 tot += __popcll(ba[q]);
-                lv += __popcll(__ballot(at));
             }
         }
-        if (tot | lv) {
+        if (tot) {
             int32_t pos = 0;
-            if (lane == 0) {
-                if (tot) pos = atomicAdd(&st.sh->count[par], tot);
-                if (lv) atomicAdd(&st.sh->lvl[par], lv);
-            }
+            if (lane == 0) pos = atomicSub(&st.sh->back[a], tot) - tot;
             pos = __shfl(pos, 0);
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
-                if (act[q]) st.list[pos + __popcll(ba[q] & below)] = W(base + q * T + tid);
+                if (act[q]) st.list(a)[pos + __popcll(ba[q] & below)] = W(base + q * T + tid);
                 pos += __popcll(ba[q]);
             }
         }
     }
-    lds_barrier();
-    return st.sh->count[par];
-}
-
-// max over v of h[v] subject to e[v] > 0, v != t, h[v] < below; 0 if none.  Three barriers.
-template <bool COMPACT>
-__device__ __forceinline__ int32_t max_active_height_below(const State<COMPACT> &st, int32_t n, int32_t t, int32_t below) {
-    const int32_t tid = threadIdx.x, T = blockDim.x;
-    if (tid == 0) st.sh->tmp = 0;
-    lds_barrier();
-    int32_t best = 0;
-    for (int32_t v = tid; v < n; v += T) {
-        int32_t hv = int32_t(st.h[v]);
-        if (st.excess(v) > 0 && v != t && hv < below && hv > best) best = hv;
-    }
     if (best > 0) atomicMax(&st.sh->tmp, best);
     lds_barrier();
-    int32_t r = st.sh->tmp;
+    const int32_t r = st.sh->tmp;
     lds_barrier();
     return r;
 }
 
 // Exact heights by backward breadth-first search from the sink over arcs with positive residual
-// capacity; vertices that cannot reach the sink get height n.  Ends with a barrier.
+// capacity; vertices that cannot reach the sink get height n.  Uses list array 0 and both cnt
+// scalars as scratch.  Ends with a barrier.
 template <bool COMPACT, int G>
 __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32_t t, int32_t U, int32_t NK,
                                uint32_t &gr_scans) {
@@ -223,7 +227,7 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
     const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n;
     const int32_t lg = tid & (G - 1), grp = tid / G, ngrp = T / G;
     for (int32_t v = tid; v < n; v += T) st.h[v] = W(v == t ? 0 : n);
-    if (tid == 0) st.sh->count[0] = 0;
+    if (tid == 0) st.sh->cnt[0] = 0;
     lds_barrier();
     for (int32_t d = 0;; ++d) {
         const int32_t par = d & 1;
@@ -234,17 +238,17 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
             const unsigned long long b = __ballot(isd);
             if (b) {
                 int32_t pos = 0;
-                if ((tid & 63) == 0) pos = atomicAdd(&st.sh->count[par], __popcll(b));
+                if ((tid & 63) == 0) pos = atomicAdd(&st.sh->cnt[par], __popcll(b));
                 pos = __shfl(pos, 0);
-                if (isd) st.list[pos + __popcll(b & ((1ull << (tid & 63)) - 1ull))] = W(v);
+                if (isd) st.list0[pos + __popcll(b & ((1ull << (tid & 63)) - 1ull))] = W(v);
             }
         }
         lds_barrier();
-        const int32_t cnt = st.sh->count[par];
-        if (tid == 0) st.sh->count[par ^ 1] = 0;
+        const int32_t cnt = st.sh->cnt[par];
+        if (tid == 0) st.sh->cnt[par ^ 1] = 0;
         if (cnt == 0) break;
         for (int32_t i = grp; i < cnt; i += ngrp) {
-            const int32_t w = int32_t(st.list[i]);
+            const int32_t w = int32_t(st.list0[i]);
             const int32_t beg = int32_t(st.rp[w]), end = int32_t(st.rp[w + 1]);
             for (int32_t a = beg + lg; a < end; a += G) {
                 const ArcRec r = load_arc<COMPACT>(p, a);
@@ -257,26 +261,38 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
         lds_barrier();
     }
     lds_barrier();
+    if (tid == 0) st.sh->cnt[0] = st.sh->cnt[1] = 0;
+    lds_barrier();
 }
 
-// One workgroup = one max-flow problem.  Level-synchronous push-relabel: a pass walks the height
-// levels from the highest one holding excess down to 1; in a step every vertex of one level is
-// discharged with all heights frozen, so pushes only go one level down, no arc is touched from
-// both ends and no vertex of the level receives excess.  New heights are applied after the step.
+// One workgroup = one max-flow problem: a level-synchronous push-relabel.  In a step every listed
+// vertex of ONE height level d is discharged with all heights frozen, so pushes only go to level
+// d-1, no arc is touched from both ends and no listed vertex receives excess.  A vertex left with
+// excess (all its admissible arcs saturated) gets its new height when the step is over.  The only
+// concurrent updates are commutative integer atomics: the run is deterministic.
 //
-// A step has up to two parts.  Fast part (first pass only, when the per-sink tables exist): heights
-// still equal the breadth-first labels, so level d is a slice of the sink's precomputed order and
-// one lane per vertex pushes along the vertex's precomputed first admissible arc, read with
-// coalesced loads; a vertex whose excess that arc cannot take goes to the level list.  Group part:
-// G lanes scan the residual row of each listed vertex in chunks, split the excess over the
-// admissible arcs in row order and collect the smallest neighbouring height for a relabel.  After
-// the first pass the list is compacted from the height and excess arrays.
+// First pass (when the per-sink tables exist).  Heights still equal the breadth-first labels, so
+// level d is a slice of the sink's precomputed order and no list is needed: one lane per vertex
+// pushes along the vertex's precomputed first arc, read with coalesced loads (fast part); a
+// vertex whose excess that arc cannot take goes to the list and is finished by the group part.
+// Levels are walked from the highest one holding a compute node down to 1.
+//
+// Afterwards (and from the start without tables) the kernel keeps a pending list: vertices that
+// hold excess and are not being discharged.  Each step takes the highest pending level (highest-
+// label-first), moves its vertices to the front of the other list array, carries the rest over,
+// and discharges them with the group part; vertices that receive excess for the first time and
+// vertices that were relabeled join the pending list.  No step scans all vertices.
+//
+// Group part: G lanes scan the residual row of one listed vertex in chunks, give all excess to the
+// first admissible arc when it suffices, else split it by a segmented prefix sum in row order, and
+// collect the smallest residual-neighbour height for the relabel in the same scan.
 template <bool COMPACT, int G>
 __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     using W = typename State<COMPACT>::W;
+    constexpr int32_t NEWH = State<COMPACT>::NEWH;
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n, m0 = p.m0;
-    const int32_t j = blockIdx.x;
+    const int32_t j = p.order ? p.order[blockIdx.x] : int32_t(blockIdx.x);
 
     // ---- problem and its validity (uniform over the workgroup)
     const int32_t t = p.sink[j], U = p.U[j], k = p.k[j];
@@ -304,8 +320,9 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     const Carve cv = carve_lds(n, m0, COMPACT);
     State<COMPACT> st;
     st.f = reinterpret_cast<W *>(smem + cv.f); st.h = reinterpret_cast<W *>(smem + cv.h);
-    st.e = reinterpret_cast<W *>(smem + cv.e); st.hnew = reinterpret_cast<W *>(smem + cv.hnew);
-    st.list = reinterpret_cast<W *>(smem + cv.list); st.rp = reinterpret_cast<W *>(smem + cv.rp);
+    st.e = reinterpret_cast<W *>(smem + cv.e);
+    st.list0 = reinterpret_cast<W *>(smem + cv.list0); st.list1 = reinterpret_cast<W *>(smem + cv.list1);
+    st.rp = reinterpret_cast<W *>(smem + cv.rp);
     st.sh = reinterpret_cast<Shared *>(smem + cv.sh);
     const int32_t lane = tid & 63;
     const int32_t lg = tid & (G - 1), grp = tid / G, ngrp = T / G;
@@ -313,6 +330,9 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
 
 #ifdef FC_PHASE_TIMING
     long long tick_ = clock64();
+#ifdef FC_WALLCLOCK
+    const uint32_t wc_start_ = uint32_t(wall_clock64());
+#endif
     uint32_t t_init = 0, t_compact = 0, t_discharge = 0, t_other = 0, t_post = 0, t_next = 0;
 #endif
     uint32_t c_push = 0, c_scan = 0, c_grscan = 0, c_rel = 0, c_dis = 0;   // per-thread counters
@@ -322,14 +342,13 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     const bool have_labels = p.labels != nullptr;
     const bool have_p1 = have_labels && p.p1 != nullptr;
     const uint4 *p1_row = have_p1 ? p.p1 + size_t(t) * size_t(n) : nullptr;
-    int32_t hmax = have_labels ? int32_t(p.label_hmax[t]) : 0;   // highest level that holds a compute node
+    int32_t d = have_labels ? int32_t(p.label_hmax[t]) : 0;   // first level: the highest one holding a compute node
     {
         uint4 *fz = reinterpret_cast<uint4 *>(smem + cv.f);
         const int32_t quads = int32_t((cv.h - cv.f) / 16);
         for (int32_t i = tid; i < quads; i += T) fz[i] = make_uint4(0u, 0u, 0u, 0u);
         for (int32_t v = tid; v < n; v += T) {
             st.rp[v] = W(p.row_ptr[v]);
-            st.hnew[v] = W(0);
             if (have_labels) {
                 const uint32_t lc = p.labels[size_t(t) * size_t(n) + size_t(v)];
                 st.h[v] = W(lc & 0x7fffu);
@@ -338,200 +357,250 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
         }
         if (tid == 0) {
             st.rp[n] = W(p.row_ptr[n]);
-            for (int i = 0; i < 3; ++i) { st.sh->count[i] = 0; st.sh->lvl[i] = 0; st.sh->down[i] = 0; st.sh->nrel[i] = 0; }
-            st.sh->hmax_next = 0; st.sh->tmp = 0; st.sh->rel_since = 0;
+            for (int i = 0; i < 2; ++i) { st.sh->cnt[i] = 0; st.sh->down[i] = 0; st.sh->nrel[i] = 0; st.sh->dnext[i] = 0; st.sh->back[i] = n; }
+            st.sh->tmp = 0;
             for (int i = 0; i < FC_NSTAT; ++i) st.sh->st[i] = 0;
         }
         if (have_p1 && tid < 64) st.sh->off[tid] = p.level_off[size_t(t) * 64 + tid];
         lds_barrier();
         if (!have_labels) {
             global_relabel<COMPACT, G>(p, st, t, U, NK, c_grscan);
-            if (tid == 0) { ++c_gr; st.sh->count[0] = st.sh->count[1] = 0; }   // the search used these two
-            lds_barrier();
-            hmax = max_active_height_below(st, n, t, n);
+            if (tid == 0) ++c_gr;
         }
     }
     // first-pass entries are read one round ahead: the sink's levels lie back to back in p1_row, so
     // the entry a lane needs next is known before the current round (and its barrier) is done
     uint4 en_next = make_uint4(0u, 0u, 0u, 0u);
-    if (have_p1 && hmax >= 1) {
-        const int32_t L = int32_t(st.sh->off[0]);
-        const int32_t i0 = int32_t(st.sh->off[1 + L - hmax]) + tid;
-        en_next = p1_row[i0 < n ? i0 : n - 1];
+    bool fast = have_p1;                   // still in the table-driven first pass
+    int32_t cur = 0;                       // list array whose front is discharged in this step
+    int32_t pend_hmax = 0;                 // first pass: largest height put on the pending list so far
+    int32_t prev_cnt = 0;                  // vertices discharged in the previous step (front of the other array)
+    if (fast) {
+        if (d >= 1) {
+            const int32_t L = int32_t(st.sh->off[0]);
+            const int32_t i0 = int32_t(st.sh->off[1 + L - d]) + tid;
+            en_next = p1_row[i0 < n ? i0 : n - 1];
+        }
+    } else {
+        d = rebuild_pending(st, n, t, 1);  // everything that holds excess, on array 1
+        cur = 0;
     }
     FC_TICK(t_init);
-    int32_t steps_since = 0, total_steps = 0, step = 0;
+    int32_t steps_since = 0, total_steps = 0, rel_since = 0;
     bool failed = false;
-    bool first_pass = true;
 
-    // ---- passes: sweep the height levels from the highest active one down to 1
-    while (hmax >= 1 && st.excess(t) != NK) {
-        int32_t d = hmax;
-        bool done = false;
-        while (d >= 1) {
-            const int32_t par = step % 3, nxt = (step + 1) % 3;
-            FC_TICK(t_other);
-            if (tid == 0) { st.sh->count[nxt] = 0; st.sh->lvl[nxt] = 0; st.sh->down[nxt] = 0; st.sh->nrel[nxt] = 0; }
-            const bool fast = first_pass && have_p1;
-            int32_t cnt, lvltot;
-            if (fast) {
-                // ---- fast part: one lane per vertex of the level, along its precomputed first arc.  That
-                // arc carries no flow yet and its head still has its initial height d-1, because in the
-                // first pass a vertex is touched for the first time in the step of its own level.
-                const int32_t L = int32_t(st.sh->off[0]);
-                const int32_t lo = int32_t(st.sh->off[1 + L - d]), hi = int32_t(st.sh->off[2 + L - d]);
-                lvltot = hi - lo;
-                for (int32_t base = 0; base < lvltot; base += T) {
-                    const int32_t pos = base + tid;
-                    const bool ok = pos < lvltot;
-                    const uint4 en = en_next;
-                    {   // next round of this level, else first round of the level below
-                        const int32_t inext = (base + T < lvltot ? lo + base + T : hi) + tid;
-                        en_next = p1_row[inext < n ? inext : n - 1];
-                    }
-                    const int32_t u = int32_t(en.z & 0xffffu);
-                    const int32_t ex = ok ? st.excess(u) : 0;
-                    if (ex > 0) {
-                        const int32_t w = int32_t(en.x & 0x7fffu), pair = int32_t(en.x >> 16);
-                        const int32_t cap = arc_cap(U, int32_t(en.y), NK);
-                        const int32_t delta = ex < cap ? ex : cap;
-                        ++c_dis; ++c_scan; ++c_push;
-                        st.f[pair] = W(delta);
-                        st.excess_add(w, delta);
-                        st.excess_sub(u, delta);
-                        if (w != t) st.sh->down[par] = 1;
-                        if (delta < ex) st.list[atomicAdd(&st.sh->count[par], 1)] = W(u);   // the arc is full
-                    }
+    // ---- steps: one height level each
+    while (d >= 1 && st.excess(t) != NK) {
+        const int32_t sp = total_steps & 1;
+        FC_TICK(t_other);
+        int32_t cnt, lvltot = 0;
+        if (fast) {
+            // ---- fast part: one lane per vertex of the level, along its precomputed first arc.  That
+            // arc carries no flow yet and its head still has its initial height d-1, because in the
+            // first pass a vertex is touched for the first time in the step of its own level.
+            const int32_t L = int32_t(st.sh->off[0]);
+            const int32_t lo = int32_t(st.sh->off[1 + L - d]), hi = int32_t(st.sh->off[2 + L - d]);
+            lvltot = hi - lo;
+            for (int32_t base = 0; base < lvltot; base += T) {
+                const int32_t pos = base + tid;
+                const bool ok = pos < lvltot;
+                const uint4 en = en_next;
+                {   // next round of this level, else first round of the level below
+                    const int32_t inext = (base + T < lvltot ? lo + base + T : hi) + tid;
+                    en_next = p1_row[inext < n ? inext : n - 1];
                 }
-                lds_barrier();
-                cnt = st.sh->count[par];
-            } else {
-                cnt = compact_level(st, n, t, d, par);                    // barrier inside
-                lvltot = st.sh->lvl[par];
+                const int32_t u = int32_t(en.z & 0xffffu);
+                const int32_t ex = ok ? st.excess(u) : 0;
+                if (ex > 0) {
+                    const int32_t w = int32_t(en.x & 0x7fffu), pair = int32_t(en.x >> 16);
+                    const int32_t cap = arc_cap(U, int32_t(en.y), NK);
+                    const int32_t delta = ex < cap ? ex : cap;
+                    ++c_dis; ++c_scan; ++c_push;
+                    st.f[pair] = W(delta);
+                    st.excess_add_noret(w, delta);
+                    st.excess_sub(u, delta);
+                    if (w != t) st.sh->down[sp] = 1;
+                    if (delta < ex) st.list(cur)[atomicAdd(&st.sh->cnt[sp], 1)] = W(u);   // the arc is full
+                }
             }
-            FC_TICK(t_compact);
-
-            // ---- group part: G lanes scan one listed vertex's residual row, a chunk at a time
-            for (int32_t i = grp; i < cnt; i += ngrp) {
-                const int32_t u = int32_t(st.list[i]);
-                const int32_t beg = int32_t(st.rp[u]), end = int32_t(st.rp[u + 1]);
-                const int32_t ex = st.excess(u);
-                int32_t rem = ex;
-                int32_t minh = 0x7fffffff;
-                if (lg == 0) ++c_dis;
-                for (int32_t base = beg; base < end && rem > 0; base += G) {
-                    const int32_t a = base + lg;
-                    int32_t ra = 0, hw = 0, fv = 0;
-                    ArcRec r; r.w = 0; r.pair = 0; r.bw = 0; r.fwd = 0;
-                    if (a < end) {
-                        r = load_arc<COMPACT>(p, a);
-                        ++c_scan;
-                        fv = int32_t(st.f[r.pair]);
-                        ra = r.fwd ? arc_cap(U, r.bw, NK) - fv : fv;
-                        hw = int32_t(st.h[r.w]);
-                    }
-                    const bool adm = ra > 0 && hw + 1 == d;
-                    if (ra > 0 && !adm && hw < minh) minh = hw;
-                    const unsigned long long bal = __ballot(adm) & gmask;
-                    if (bal) {
-                        int32_t delta = 0, rem_new;
-                        const bool first = adm && ((bal & ((1ull << lane) - 1ull)) == 0ull);
-                        const unsigned long long absorbed = __ballot(first && ra >= rem) & gmask;
-                        if (absorbed) {                       // first admissible arc takes everything
-                            if (first) delta = rem;
-                            rem_new = 0;
-                        } else {                              // split the excess in arc order
-                            const int32_t x = adm ? ra : 0;
-                            int32_t incl = x;
-#pragma unroll
-                            for (int s = 1; s < G; s <<= 1) {
-                                const int32_t y = __shfl_up(incl, s, G);
-                                if (lg >= s) incl += y;
-                            }
-                            const int32_t total = __shfl(incl, G - 1, G);
-                            const int32_t excl = incl - x;
-                            delta = rem - excl; if (delta > x) delta = x; if (delta < 0) delta = 0;
-                            rem_new = total >= rem ? 0 : rem - total;
-                        }
-                        if (delta > 0) {
-                            st.f[r.pair] = W(r.fwd ? fv + delta : fv - delta);
-                            st.excess_add(r.w, delta);
-                            if (r.w != t) st.sh->down[par] = 1;
-                            ++c_push;
-                        }
-                        rem = rem_new;
-                    }
-                }
-                if (rem > 0) {                                // every admissible arc is saturated: relabel
-#pragma unroll
-                    for (int s = G / 2; s > 0; s >>= 1) {
-                        const int32_t y = __shfl_xor(minh, s, G);
-                        if (y < minh) minh = y;
-                    }
-                    if (lg == 0) {
-                        st.hnew[u] = W(minh >= n - 1 ? n : minh + 1);
-                        atomicAdd(&st.sh->nrel[par], 1);
-                        ++c_rel;
-                    }
-                }
-                if (lg == 0 && rem != ex) st.excess_sub(u, ex - rem);
-            }
-            lds_barrier();
-            FC_TICK(t_discharge);
-            const int32_t nrel = st.sh->nrel[par], down = st.sh->down[par];
-            ++step; ++steps_since; ++total_steps;
-            if (tid == 0) ++c_step;
-
-            if (nrel) {
-                // apply the new heights (deferred so that the level's scans all saw the same heights)
-                for (int32_t i = tid; i < cnt; i += T) {
-                    const int32_t u = int32_t(st.list[i]);
-                    const int32_t nh = int32_t(st.hnew[u]);
-                    if (nh) {
-                        st.h[u] = W(nh);
-                        st.hnew[u] = W(0);
-                        if (nh < n) atomicMax(&st.sh->hmax_next, nh);
-                    }
-                }
-                if (tid == 0) st.sh->rel_since += nrel;
-                if (p.use_gap && nrel == lvltot) {
-                    // every vertex of level d left it: the level is empty, so nothing above it can
-                    // reach the sink any more
-                    lds_barrier();
-                    for (int32_t v = tid; v < n; v += T) {
-                        const int32_t hv = int32_t(st.h[v]);
-                        if (hv > d && hv < n) st.h[v] = W(n);
-                    }
-                    if (tid == 0) st.sh->hmax_next = 0;
-                }
-                lds_barrier();
-            }
-            FC_TICK(t_post);
-            if (st.excess(t) == NK) { done = true; break; }
-            if (total_steps >= p.max_steps) { failed = true; done = true; break; }
-            if (fast) d = d - 1;                                  // lower levels still hold their compute nodes
-            else if (down) d = d - 1;
-            else if (d > 1) d = max_active_height_below(st, n, t, d);
-            else d = 0;
-            FC_TICK(t_next);
-        }
-        if (done) break;
-        first_pass = false;
-        const int32_t rel_total = st.sh->rel_since;     // last written before a barrier: uniform
-        if (rel_total > 0 && (rel_total >= p.gr_relabels || steps_since >= p.gr_steps)) {
-            global_relabel<COMPACT, G>(p, st, t, U, NK, c_grscan);
-            if (tid == 0) {
-                ++c_gr; st.sh->count[0] = st.sh->count[1] = 0;             // the search used these two
-                st.sh->hmax_next = 0; st.sh->rel_since = 0;
-            }
-            steps_since = 0;
-            lds_barrier();
-            hmax = max_active_height_below(st, n, t, n);
         } else {
-            hmax = st.sh->hmax_next;
-            lds_barrier();
-            if (tid == 0) st.sh->hmax_next = 0;
+            // ---- take level d off the pending list (on the other array): its vertices go to the front
+            // of this array, the rest is carried over to this array's pending part
+            // The source has two parts: its pending part [b0, n), and its old front [0, prev_cnt) -- the
+            // vertices discharged in the last step, of which the ones still holding excess were stuck
+            // (they have their new heights by now).  One counter update per wavefront and destination.
+            const int32_t src = cur ^ 1;
+            const int32_t b0 = st.sh->back[src];
+            const int32_t total = prev_cnt + (n - b0);
+            const unsigned long long below = (1ull << lane) - 1ull;
+            for (int32_t base = 0; base < total; base += T) {
+                const int32_t i = base + tid;
+                bool isd = false, carry = false;
+                int32_t v = 0, hv = 0;
+                if (i < total) {
+                    v = int32_t(st.list(src)[i < prev_cnt ? i : b0 + (i - prev_cnt)]);
+                    hv = int32_t(st.h[v]);
+                    const bool alive = hv < n && (i >= prev_cnt || st.excess(v) > 0);
+                    isd = alive && hv == d; carry = alive && hv != d;
+                }
+                const unsigned long long bd = __ballot(isd), bc = __ballot(carry);
+                if (bd) {
+                    int32_t pos = 0;
+                    if (lane == 0) pos = atomicAdd(&st.sh->cnt[sp], __popcll(bd));
+                    pos = __shfl(pos, 0);
+                    if (isd) st.list(cur)[pos + __popcll(bd & below)] = W(v);
+                }
+                if (bc) {
+                    int32_t pos = 0, m = carry ? hv : 0;
+#pragma unroll
+                    for (int s = 32; s > 0; s >>= 1) { const int32_t y = __shfl_xor(m, s); if (y > m) m = y; }
+                    if (lane == 0) { pos = atomicSub(&st.sh->back[cur], __popcll(bc)) - __popcll(bc); atomicMax(&st.sh->dnext[sp], m); }
+                    pos = __shfl(pos, 0);
+                    if (carry) st.list(cur)[pos + __popcll(bc & below)] = W(v);
+                }
+            }
         }
+        lds_barrier();
+        cnt = st.sh->cnt[sp];
+        if (tid == 0) {                    // nobody reads these any more; they are written again after the next barrier at the earliest
+            st.sh->cnt[sp ^ 1] = 0; st.sh->down[sp ^ 1] = 0; st.sh->nrel[sp ^ 1] = 0; st.sh->dnext[sp ^ 1] = 0;
+            if (!fast) st.sh->back[cur ^ 1] = n;
+        }
+        FC_TICK(t_compact);
+
+        // ---- group part: G lanes scan one listed vertex's residual row, a chunk at a time
+        for (int32_t i = grp; i < cnt; i += ngrp) {
+            const int32_t u = int32_t(st.list(cur)[i]);
+            const int32_t beg = int32_t(st.rp[u]), end = int32_t(st.rp[u + 1]);
+            const int32_t ex = st.excess(u);
+            int32_t rem = ex;
+            int32_t minh = 0x7fffffff;
+            if (lg == 0) ++c_dis;
+            for (int32_t base = beg; base < end && rem > 0; base += G) {
+                const int32_t a = base + lg;
+                int32_t ra = 0, hw = 0, fv = 0;
+                ArcRec r; r.w = 0; r.pair = 0; r.bw = 0; r.fwd = 0;
+                if (a < end) {
+                    r = load_arc<COMPACT>(p, a);
+                    ++c_scan;
+                    fv = int32_t(st.f[r.pair]);
+                    ra = r.fwd ? arc_cap(U, r.bw, NK) - fv : fv;
+                    hw = st.height_during_step(r.w, d);
+                }
+                const bool adm = ra > 0 && hw + 1 == d;
+                if (ra > 0 && !adm && hw < minh) minh = hw;
+                const unsigned long long bal = __ballot(adm) & gmask;
+                if (bal) {
+                    int32_t delta = 0, rem_new;
+                    const bool first = adm && ((bal & ((1ull << lane) - 1ull)) == 0ull);
+                    const unsigned long long absorbed = __ballot(first && ra >= rem) & gmask;
+                    if (absorbed) {                       // first admissible arc takes everything
+                        if (first) delta = rem;
+                        rem_new = 0;
+                    } else {                              // split the excess in arc order
+                        const int32_t x = adm ? ra : 0;
+                        int32_t incl = x;
+#pragma unroll
+                        for (int s = 1; s < G; s <<= 1) {
+                            const int32_t y = __shfl_up(incl, s, G);
+                            if (lg >= s) incl += y;
+                        }
+                        const int32_t total = __shfl(incl, G - 1, G);
+                        const int32_t excl = incl - x;
+                        delta = rem - excl; if (delta > x) delta = x; if (delta < 0) delta = 0;
+                        rem_new = total >= rem ? 0 : rem - total;
+                    }
+                    if (delta > 0) {
+                        st.f[r.pair] = W(r.fwd ? fv + delta : fv - delta);
+                        ++c_push;
+                        if (fast) {                       // the level below is walked in table order anyway
+                            st.excess_add_noret(r.w, delta);
+                            if (r.w != t) st.sh->down[sp] = 1;
+                        } else if (r.w == t) {
+                            st.excess_add_noret(r.w, delta);
+                        } else if (st.excess_add(r.w, delta) == 0) {
+                            st.pend(cur, r.w);            // first excess this vertex gets: it becomes pending
+                            st.sh->down[sp] = 1;
+                        }
+                    }
+                    rem = rem_new;
+                }
+            }
+            if (rem > 0) {                                // every admissible arc is saturated: relabel
+#pragma unroll
+                for (int s = G / 2; s > 0; s >>= 1) {
+                    const int32_t y = __shfl_xor(minh, s, G);
+                    if (y < minh) minh = y;
+                }
+                if (lg == 0) {
+                    const int32_t nh = minh >= n - 1 ? n : minh + 1;
+                    st.h[u] = W(NEWH | nh);
+                    atomicAdd(&st.sh->nrel[sp], 1);
+                    if (nh < n) atomicMax(&st.sh->dnext[sp], nh);
+                    ++c_rel;
+                }
+            }
+            if (lg == 0 && rem != ex) st.excess_sub(u, ex - rem);
+        }
+        lds_barrier();
+        FC_TICK(t_discharge);
+        const int32_t nrel = st.sh->nrel[sp], down = st.sh->down[sp];
+        int32_t dn = st.sh->dnext[sp];
+        ++steps_since; ++total_steps;
+        if (tid == 0) ++c_step;
+
+        if (nrel) {
+            // the new heights take effect (deferred so that the level's scans all saw the same heights)
+            // (first pass: the list is rebuilt for every level, so the relabeled vertices move to the
+            // pending list, kept on array 1; afterwards they are found again in this array's front)
+            for (int32_t i = tid; i < cnt; i += T) {
+                const int32_t u = int32_t(st.list(cur)[i]);
+                const int32_t raw = int32_t(st.h[u]);
+                if (raw & NEWH) {
+                    st.h[u] = W(raw & ~NEWH);
+                    if (fast && (raw & ~NEWH) < n) st.pend(1, u);
+                }
+            }
+            rel_since += nrel;
+            if (fast && p.use_gap && nrel == lvltot) {
+                // every vertex of level d left it: the level is empty, so nothing above it can reach
+                // the sink any more (pending entries that die here are dropped when their turn comes)
+                lds_barrier();
+                for (int32_t v = tid; v < n; v += T) {
+                    const int32_t hv = int32_t(st.h[v]);
+                    if (hv > d && hv < n) st.h[v] = W(n);
+                }
+                pend_hmax = 0; dn = 0;
+            }
+            lds_barrier();
+        }
+        FC_TICK(t_post);
+        if (st.excess(t) == NK) break;
+        if (total_steps >= p.max_steps) { failed = true; break; }
+
+        // ---- next level
+        if (fast) {
+            if (dn > pend_hmax) pend_hmax = dn;
+            if (d > 1) d = d - 1;                         // lower levels still hold their compute nodes
+            else {                                        // first pass over: continue with the pending list (on array 0)
+                fast = false; cur = 0; prev_cnt = 0; d = pend_hmax;
+            }
+        } else {
+            if (down && d - 1 > dn) dn = d - 1;
+            d = dn;
+            prev_cnt = cnt;
+            cur ^= 1;
+        }
+        if (!fast && rel_since > 0 && (rel_since >= p.gr_relabels || steps_since >= p.gr_steps) && d >= 1) {
+            global_relabel<COMPACT, G>(p, st, t, U, NK, c_grscan);
+            if (tid == 0) ++c_gr;
+            rel_since = 0; steps_since = 0;
+            d = rebuild_pending(st, n, t, cur ^ 1);
+            prev_cnt = 0;
+            if (tid == 0) { st.sh->back[cur] = n; st.sh->dnext[0] = st.sh->dnext[1] = 0; }
+            lds_barrier();
+        }
+        FC_TICK(t_next);
     }
 
     lds_barrier();
@@ -554,10 +623,48 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
         lds_barrier();
         FC_TICK(t_other);
         if (tid == 0) { st.sh->st[0] = t_init; st.sh->st[1] = t_compact; st.sh->st[2] = t_discharge; st.sh->st[3] = t_post; st.sh->st[4] = t_next; st.sh->st[6] = t_other; }
+#ifdef FC_WALLCLOCK
+        if (tid == 0) { st.sh->st[4] = uint32_t(wall_clock64()); st.sh->st[6] = wc_start_; }
+#endif
 #endif
         lds_barrier();
         if (tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = st.sh->st[tid];
     }
+}
+
+// Launch order: workgroups are dispatched in index order and a hard problem can run twenty times
+// longer than a typical one, so the hard ones must start first or the launch ends with a long
+// tail of idle CUs.  Hardness is guessed from the slack of the sink's single-vertex cut, the same
+// cut the paper's initial range uses (Appendix E.1): in-capacity U * B^-(sink) (+ k) over the
+// demand N * k.  One workgroup buckets all problems by that ratio and writes the permutation.
+__global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, int32_t N, const int32_t *sink,
+                                                        const int32_t *U, const int32_t *k, const int32_t *in_bw,
+                                                        const uint8_t *is_compute, int32_t *order) {
+    constexpr int NB = 8;
+    __shared__ int32_t hist[NB], base[NB];
+    const int32_t tid = threadIdx.x, T = blockDim.x;
+    if (tid < NB) hist[tid] = 0;
+    __syncthreads();
+    auto bucket = [&](long long jj) -> int {
+        const int32_t t = sink[jj], u = U[jj], kk = k[jj];
+        if (t < 0 || t >= n || u < 1 || kk < 1) return NB - 1;              // nothing to solve
+        const long long need = (long long)N * kk;
+        const long long have = (long long)u * in_bw[t] + (is_compute[t] ? kk : 0);
+        // ratio have / need against 1, 1.25, 1.5, 2, 3, 4, 6
+        if (have * 1 < need * 1) return 0;
+        if (have * 4 < need * 5) return 1;
+        if (have * 2 < need * 3) return 2;
+        if (have < need * 2) return 3;
+        if (have < need * 3) return 4;
+        if (have < need * 4) return 5;
+        if (have < need * 6) return 6;
+        return 7;
+    };
+    for (long long jj = tid; jj < P; jj += T) atomicAdd(&hist[bucket(jj)], 1);
+    __syncthreads();
+    if (tid == 0) { int32_t acc = 0; for (int b = 0; b < NB; ++b) { base[b] = acc; acc += hist[b]; } }
+    __syncthreads();
+    for (long long jj = tid; jj < P; jj += T) order[atomicAdd(&base[bucket(jj)], 1)] = int32_t(jj);
 }
 
 __global__ void fc_expand_candidates_kernel(int32_t C, int32_t N, const int32_t *compute_ids, const int32_t *cU,
@@ -619,7 +726,7 @@ size_t lds_bytes(const fc_graph *g, bool compact) { return carve_lds(g->n, int32
 bool compact_ids_fit(const fc_graph *g) { return g->n <= 32767 && 2 * g->m0 <= 65535; }
 
 struct Resolved {
-    int32_t T, G, gr_steps, gr_relabels, use_gap, use_labels, force_wide, max_steps, src_cap_bound;
+    int32_t T, G, gr_steps, gr_relabels, use_gap, use_labels, force_wide, max_steps, src_cap_bound, schedule;
 };
 
 int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
@@ -646,6 +753,8 @@ int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
     r->max_steps = o->max_level_steps > 0 ? o->max_level_steps : std::max<int32_t>(100000, 200 * g->n);
     if (o->src_cap_bound < 0) return FC_EINVAL;
     r->src_cap_bound = o->src_cap_bound;
+    if (o->schedule < 0 || o->schedule > 2) return FC_EINVAL;
+    r->schedule = o->schedule != 2;
     return FC_OK;
 }
 
@@ -679,7 +788,8 @@ struct StatsScratch { uint32_t *per_problem; unsigned long long *totals; };
 
 // Launch the solver kernels for P problems.  stats_ws: null, or room for P*FC_NSTAT u32 + FC_NSTAT u64.
 int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32_t *d_U, const int32_t *d_k,
-              int32_t *d_flow, const Resolved &opt, hipStream_t stream, uint32_t *d_stats_pp) {
+              int32_t *d_flow, const Resolved &opt, hipStream_t stream, uint32_t *d_stats_pp, int32_t *d_order) {
+    if (P > (1ll << 30)) return FC_EINVAL;
     KParams kp;
     kp.n = g->n; kp.N = g->N; kp.m0 = int32_t(g->m0);
     kp.n_rec = std::max<int32_t>(1, int32_t(2 * g->m0));
@@ -700,20 +810,20 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.flow_out = d_flow; kp.stats = d_stats_pp;
     kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
     kp.wide_available = wide_possible ? 1 : 0;
-    const long long CH = 1ll << 30;                     // grid.x limit
-    for (long long first = 0; first < P; first += CH) {
-        long long cnt = std::min(CH, P - first);
-        KParams q = kp;
-        q.sink += first; q.U += first; q.k += first; q.flow_out += first;
-        if (q.stats) q.stats += size_t(first) * FC_NSTAT;
-        if (compact_possible) {
-            int rc = launch_g<true>(q, cnt, opt.T, opt.G, lds_bytes(g, true), stream);
-            if (rc != FC_OK) return rc;
-        }
-        if (wide_possible) {
-            int rc = launch_g<false>(q, cnt, opt.T, opt.G, lds_bytes(g, false), stream);
-            if (rc != FC_OK) return rc;
-        }
+    kp.order = nullptr;
+    if (opt.schedule && P > 2ll * g->n_cu) {            // small launches fit the machine at once: order is moot
+        hipLaunchKernelGGL(fc_order_kernel, dim3(1), dim3(1024), 0, stream, P, g->n, g->N, d_sink, d_U, d_k,
+                           g->d_in_bw, g->d_is_compute, d_order);
+        HIP_TRY(hipGetLastError());
+        kp.order = d_order;
+    }
+    if (compact_possible) {
+        int rc = launch_g<true>(kp, P, opt.T, opt.G, lds_bytes(g, true), stream);
+        if (rc != FC_OK) return rc;
+    }
+    if (wide_possible) {
+        int rc = launch_g<false>(kp, P, opt.T, opt.G, lds_bytes(g, false), stream);
+        if (rc != FC_OK) return rc;
     }
     return FC_OK;
 }
@@ -737,7 +847,10 @@ int fill_stats(long long P, uint32_t *d_pp, unsigned long long *d_tot, hipStream
     return FC_OK;
 }
 
-size_t stats_bytes(long long P) { return align_up(size_t(P) * FC_NSTAT * 4, 256) + 256; }
+// caller-provided scratch of a batch call: [per-problem counters][totals, 256 B][launch order]
+size_t ws_totals_off(long long P) { return align_up(size_t(P) * FC_NSTAT * 4, 256); }
+size_t ws_order_off(long long P) { return ws_totals_off(P) + 256; }
+size_t stats_bytes(long long P) { return ws_order_off(P) + align_up(size_t(P) * 4, 256); }
 
 }  // namespace
 
@@ -769,6 +882,8 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
         if (hipMalloc(&g->d_arc_wide, sizeof(int4) * (M ? M : 1)) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMalloc(&g->d_is_compute, n) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMalloc(&g->d_compute_ids, sizeof(int32_t) * size_t(g->N)) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMalloc(&g->d_in_bw, sizeof(int32_t) * n) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMemcpy(g->d_in_bw, g->in_bw.data(), sizeof(int32_t) * n, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMemcpy(g->d_row_ptr, g->row_ptr.data(), sizeof(int32_t) * (n + 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMemcpy(g->d_arc_wide, wide.data(), sizeof(int4) * (M ? M : 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMemcpy(g->d_is_compute, g->is_compute.data(), n, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
@@ -815,6 +930,7 @@ extern "C" int fc_graph_free(fc_graph *g) {
         if (g->d_arc_compact) (void)hipFree(g->d_arc_compact);
         if (g->d_is_compute) (void)hipFree(g->d_is_compute);
         if (g->d_compute_ids) (void)hipFree(g->d_compute_ids);
+        if (g->d_in_bw) (void)hipFree(g->d_in_bw);
         if (g->d_labels) (void)hipFree(g->d_labels);
         if (g->d_label_hmax) (void)hipFree(g->d_label_hmax);
         if (g->d_p1) (void)hipFree(g->d_p1);
@@ -844,14 +960,15 @@ extern "C" int fc_maxflow_batch(const fc_graph *g, int64_t n_problems, const int
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     uint32_t *d_pp = reinterpret_cast<uint32_t *>(d_workspace);
     unsigned long long *d_tot = reinterpret_cast<unsigned long long *>(reinterpret_cast<unsigned char *>(d_workspace) + align_up(size_t(n_problems) * FC_NSTAT * 4, 256));
-    if (!stats_or_null) return run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, nullptr);
+    int32_t *d_order = reinterpret_cast<int32_t *>(reinterpret_cast<unsigned char *>(d_workspace) + ws_order_off(n_problems));
+    if (!stats_or_null) return run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, nullptr, d_order);
 
     hipEvent_t ev0, ev1;
     HIP_TRY(hipEventCreate(&ev0));
     if (hipEventCreate(&ev1) != hipSuccess) { (void)hipEventDestroy(ev0); return FC_EDEVICE; }
     auto done = [&](int code) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); return code; };
     if (hipEventRecord(ev0, stream) != hipSuccess) return done(FC_EDEVICE);
-    rc = run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, d_pp);
+    rc = run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, d_pp, d_order);
     if (rc != FC_OK) return done(rc);
     if (hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
     rc = fill_stats(n_problems, d_pp, d_tot, stream, ev0, ev1, stats_or_null);
@@ -898,7 +1015,8 @@ extern "C" int fc_feasible(const fc_graph *g, int32_t n_candidates, const int32_
     if (hipGetLastError() != hipSuccess) return done(FC_EDEVICE);
     // device_ms brackets the solver kernel(s) only
     if (stats_or_null && hipEventRecord(ev0, stream) != hipSuccess) return done(FC_EDEVICE);
-    rc = run_batch(g, P, d_sink, d_U, d_k, d_flow, opt, stream, stats_or_null ? d_pp : nullptr);
+    rc = run_batch(g, P, d_sink, d_U, d_k, d_flow, opt, stream, stats_or_null ? d_pp : nullptr,
+                   reinterpret_cast<int32_t *>(ws + 4 * slab + ws_order_off(P)));
     if (rc != FC_OK) return done(rc);
     if (stats_or_null && hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
     hipLaunchKernelGGL(fc_verdict_kernel, dim3(unsigned(n_candidates)), dim3(256), 0, stream, g->N, g->d_compute_ids,

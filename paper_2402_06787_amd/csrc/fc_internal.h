@@ -18,6 +18,7 @@ struct fc_graph {
     std::vector<uint8_t> fwd;      // [2*m0] 1: topology arc leaves the row's vertex
     std::vector<uint8_t> is_compute;   // [n]
     std::vector<int32_t> compute_ids;  // [N] increasing
+    std::vector<int32_t> in_bw;        // [n] in-bandwidth B^-(v) of every vertex
     int64_t min_in_bw = 0;         // min over compute nodes of B^-(v)
     int32_t max_bw = 0, gcd_bw = 0, eulerian = 0;
     int32_t max_row = 0;           // longest residual row
@@ -29,6 +30,7 @@ struct fc_graph {
     void *d_arc_compact = nullptr;     // uint2 [2*m0]: {other | fwd<<15 | pair<<16, bw}; null if ids do not fit 15 bits
     uint8_t *d_is_compute = nullptr;   // [n]
     int32_t *d_compute_ids = nullptr;  // [N]
+    int32_t *d_in_bw = nullptr;        // [n]
     uint16_t *d_labels = nullptr;      // [n*n] exact initial labels per sink (row = sink), bit 15 = compute; or null
     uint16_t *d_label_hmax = nullptr;  // [n] highest finite label of a compute node, per sink
     void *d_p1 = nullptr;              // uint4 [n*n] first-pass entries in level order, per sink (null: not built)
