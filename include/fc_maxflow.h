@@ -72,6 +72,11 @@ typedef struct {
     int32_t global_relabel_steps;  /* relabel from the sink when this many level steps passed since
                                       the last one and some vertex was relabeled                       */
     int32_t global_relabel_permille; /* ... or when relabels since then reach this fraction of |V|     */
+    int32_t global_relabel_rises;  /* ... or when the working height level moved up this many times since
+                                      then (default and -1: off)                                        */
+    int32_t tight_sink_percent;    /* a problem whose sink cut U*B^-(t) (+k) is below this percentage of the
+                                      demand N*k relabels from the sink the first time the working level
+                                      moves up (default 150, -1: off)                                  */
     int32_t use_gap;               /* 1 = on (default), 2 = off: empty-height-level cut detection      */
     int32_t use_label_table;       /* 1 = on (default), 2 = off: initial exact labels from the
                                       per-sink distance table built at upload                          */

@@ -49,6 +49,7 @@ class fc_stats(ctypes.Structure):
 class fc_options(ctypes.Structure):
     _fields_ = [("threads_per_problem", ctypes.c_int32), ("lanes_per_vertex", ctypes.c_int32),
                 ("global_relabel_steps", ctypes.c_int32), ("global_relabel_permille", ctypes.c_int32),
+                ("global_relabel_rises", ctypes.c_int32), ("tight_sink_percent", ctypes.c_int32),
                 ("use_gap", ctypes.c_int32), ("use_label_table", ctypes.c_int32),
                 ("force_wide", ctypes.c_int32), ("max_level_steps", ctypes.c_int32),
                 ("src_cap_bound", ctypes.c_int32), ("schedule", ctypes.c_int32)]

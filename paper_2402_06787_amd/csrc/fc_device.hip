@@ -24,6 +24,7 @@
 
 #include "fc_internal.h"
 
+#define FC_LVLS 128  // heights below this have a population count (gap detection)
 #define FC_NSTAT 8   // per-problem counters: pushes, relabels, arc_scans, grs, gr_arc_scans, level_steps, discharges, not_converged
 
 // Optional per-phase cycle accounting for tuning builds (-DFC_PHASE_TIMING): the per-problem
@@ -40,6 +41,7 @@ namespace {
 struct KParams {
     int32_t n, N, m0;
     int32_t n_rec;               // residual arc records (at least 1: a zeroed dummy when the graph has no arcs)
+    int32_t gr_lanes, gr_shift, gr_sub;   // global relabel: lanes per work-list entry (2^gr_shift), sub-chunks per entry
     const int32_t *row_ptr;
     const int4 *arc_wide;
     const uint2 *arc_compact;
@@ -51,12 +53,13 @@ struct KParams {
     const int32_t *sink, *U, *k;
     int32_t *flow_out;
     uint32_t *stats;             // [P * FC_NSTAT] or null
-    int32_t gr_steps, gr_relabels, use_gap, max_steps;
+    int32_t gr_steps, gr_relabels, gr_rises, tight_pct, use_gap, max_steps;
+    const int32_t *in_bw;        // [n] in-bandwidth of every vertex
     int32_t wide_available;      // the 32-bit-state kernel is launched too
     const int32_t *order;        // workgroup -> problem (hardest first), or null for the identity
 };
 
-struct ArcRec { int32_t w, pair, bw, fwd; };
+struct ArcRec { int32_t w, pair, bw, fwd, last; };   // last: final record of its vertex's row
 
 // Raw residual-arc record as stored in global memory, and its decoded form.  Loading and decoding
 // are separate so that several loads can be in flight before the first one is consumed.
@@ -75,9 +78,10 @@ template <bool COMPACT>
 __device__ __forceinline__ ArcRec decode_arc(const ArcRaw<COMPACT> &raw) {
     ArcRec r;
     if constexpr (COMPACT) {
-        r.w = int32_t(raw.q.x & 0x7fffu); r.fwd = int32_t((raw.q.x >> 15) & 1u); r.pair = int32_t(raw.q.x >> 16); r.bw = int32_t(raw.q.y);
+        r.w = int32_t(raw.q.x & 0x7fffu); r.fwd = int32_t((raw.q.x >> 15) & 1u); r.pair = int32_t(raw.q.x >> 16);
+        r.bw = int32_t(raw.q.y & 0x7fffffffu); r.last = int32_t(raw.q.y >> 31);
     } else {
-        r.w = raw.q.x; r.pair = raw.q.y; r.bw = raw.q.z; r.fwd = raw.q.w;
+        r.w = raw.q.x; r.pair = raw.q.y; r.bw = raw.q.z; r.fwd = raw.q.w & 1; r.last = (raw.q.w >> 1) & 1;
     }
     return r;
 }
@@ -87,11 +91,13 @@ __device__ __forceinline__ ArcRec load_arc(const KParams &p, int32_t a) {
     return decode_arc<COMPACT>(load_arc_raw<COMPACT>(p, a));
 }
 
-__device__ __forceinline__ int32_t arc_cap(int32_t U, int32_t bw, int32_t NK) {
-    // capacity U * b_e clamped at N * k: no flow needs more than s can emit
-    long long c = (long long)U * (long long)bw;
-    return c > (long long)NK ? NK : int32_t(c);
-}
+// Capacity of a topology arc in one problem: U * b_e clamped at N * k (no flow needs more than s
+// can emit).  b_e > floor(N*k / U) is exactly the case U * b_e > N*k, so 32-bit arithmetic suffices.
+struct ArcCap {
+    int32_t U, NK, sat;
+    __device__ __forceinline__ ArcCap(int32_t U_, int32_t NK_) : U(U_), NK(NK_), sat(NK_ / U_) {}
+    __device__ __forceinline__ int32_t operator()(int32_t bw) const { return bw > sat ? NK : U * bw; }
+};
 
 // Workgroup barrier for code whose lanes communicate through LDS only: it waits for this wave's LDS
 // operations and leaves global loads in flight, so table reads issued before it overlap the wait.
@@ -101,6 +107,68 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Cross-lane helpers.  Within a row of 16 lanes data moves through the VALU's data-parallel
+// primitives (a few cycles) instead of the LDS crossbar that a general shuffle uses (an LDS round
+// trip each); only groups wider than a row fall back to shuffles.
+template <int CTRL>
+__device__ __forceinline__ int32_t dpp_mov(int32_t fill, int32_t v) {
+    // lanes whose source lane does not exist or is inactive get `fill`
+    return __builtin_amdgcn_update_dpp(fill, v, CTRL, 0xf, 0xf, false);
+}
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E;            // quad_perm [1,0,3,2] and [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140; // lane i <-> 7-i within 8, i <-> 15-i within 16
+constexpr int DPP_ROW_SHR = 0x110;                         // + s: lane i reads lane i-s of its row
+
+// op-reduction over every aligned group of G lanes; every lane gets its group's result
+template <int G, class Op>
+__device__ __forceinline__ int32_t group_allreduce(int32_t v, Op op) {
+    if (G >= 2) v = op(v, dpp_mov<DPP_XOR1>(v, v));
+    if (G >= 4) v = op(v, dpp_mov<DPP_XOR2>(v, v));
+    if (G >= 8) v = op(v, dpp_mov<DPP_HALF_MIRROR>(v, v));
+    if (G >= 16) v = op(v, dpp_mov<DPP_MIRROR>(v, v));
+    if (G >= 32) v = op(v, __shfl_xor(v, 16));
+    if (G >= 64) v = op(v, __shfl_xor(v, 32));
+    return v;
+}
+
+// inclusive prefix sum over every aligned group of G lanes (lg = lane index within the group)
+template <int G>
+__device__ __forceinline__ int32_t group_prefix_sum(int32_t x, int32_t lg) {
+    int32_t incl = x;
+    if (G <= 16) {
+        if (G > 1) { const int32_t y = dpp_mov<DPP_ROW_SHR + 1>(0, incl); if (lg >= 1) incl += y; }
+        if (G > 2) { const int32_t y = dpp_mov<DPP_ROW_SHR + 2>(0, incl); if (lg >= 2) incl += y; }
+        if (G > 4) { const int32_t y = dpp_mov<DPP_ROW_SHR + 4>(0, incl); if (lg >= 4) incl += y; }
+        if (G > 8) { const int32_t y = dpp_mov<DPP_ROW_SHR + 8>(0, incl); if (lg >= 8) incl += y; }
+    } else {
+#pragma unroll
+        for (int s = 1; s < G; s <<= 1) {
+            const int32_t y = __shfl_up(incl, s, G);
+            if (lg >= s) incl += y;
+        }
+    }
+    return incl;
+}
+
+// inclusive prefix sum over the wavefront (all 64 lanes must be active)
+__device__ __forceinline__ int32_t wave_prefix_sum(int32_t x) {
+    x += dpp_mov<DPP_ROW_SHR + 1>(0, x);
+    x += dpp_mov<DPP_ROW_SHR + 2>(0, x);
+    x += dpp_mov<DPP_ROW_SHR + 4>(0, x);
+    x += dpp_mov<DPP_ROW_SHR + 8>(0, x);                            // inclusive within each row of 16
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false); // rows 1 and 3 add lane 15 of the row before
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false); // rows 2 and 3 add lane 31
+    return x;
+}
+
+// maximum over the wavefront as a uniform value (all 64 lanes must be active)
+__device__ __forceinline__ int32_t wave_max(int32_t v) {
+    v = group_allreduce<16>(v, [](int32_t a, int32_t b) { return a > b ? a : b; });
+    const int32_t a = __builtin_amdgcn_readlane(v, 0), b = __builtin_amdgcn_readlane(v, 16);
+    const int32_t c = __builtin_amdgcn_readlane(v, 32), d = __builtin_amdgcn_readlane(v, 48);
+    const int32_t ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
+}
 
 // LDS scalars shared by a workgroup.  Per-step scalars come in two sets indexed by step parity:
 // thread 0 clears the other set after the first barrier of a step, when nobody can still read it.
@@ -108,12 +176,14 @@ struct Shared {
     int32_t cnt[2];        // length of the list being discharged
     int32_t down[2];       // some push of this step went to a non-sink vertex
     int32_t nrel[2];       // vertices relabeled in this step
-    int32_t dnext[2];      // largest height among the vertices put on the pending list in this step
+    int32_t dnext[2];      // largest new height given in this step
+    int32_t dcarry[2];     // largest height among the pending vertices carried over in this step
     int32_t back[2];       // per list array: pending entries occupy [back, n)
     int32_t tmp;           // scratch for rare scans
     int32_t pad;
     uint32_t st[FC_NSTAT];
     uint16_t off[64];      // level table of this sink: off[0] = deepest level L, off[1 + j] = start of level L - j
+    int32_t lvl[FC_LVLS];  // number of vertices at height d, for 1 <= d < FC_LVLS
 };
 
 // Byte offsets of the per-problem LDS arrays.  COMPACT: every array 16-bit; else 32-bit.
@@ -202,7 +272,7 @@ __device__ __forceinline__ int32_t rebuild_pending(const State<COMPACT> &st, int
         if (tot) {
             int32_t pos = 0;
             if (lane == 0) pos = atomicSub(&st.sh->back[a], tot) - tot;
-            pos = __shfl(pos, 0);
+            pos = __builtin_amdgcn_readfirstlane(pos);
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 if (act[q]) st.list(a)[pos + __popcll(ba[q] & below)] = W(base + q * T + tid);
@@ -217,51 +287,126 @@ __device__ __forceinline__ int32_t rebuild_pending(const State<COMPACT> &st, int
     return r;
 }
 
+#ifdef FC_GRDETAIL   // tuning builds: cycles in the frontier scans / expansions and the level count
+#define FC_GRDBG_PARAM , uint32_t *g_grdbg
+#define FC_GRDBG_ARG , grdbg
+#else
+#define FC_GRDBG_PARAM
+#define FC_GRDBG_ARG
+#endif
 // Exact heights by backward breadth-first search from the sink over arcs with positive residual
-// capacity; vertices that cannot reach the sink get height n.  Uses list array 0 and both cnt
-// scalars as scratch.  Ends with a barrier.
-template <bool COMPACT, int G>
-__device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32_t t, int32_t U, int32_t NK,
-                               uint32_t &gr_scans) {
+// capacity; vertices that cannot reach the sink get height n.  Also recounts the level populations.
+// Uses both list arrays (as one array of 2n entries) and the cnt and down scalars as scratch.  Ends
+// with a barrier.
+//
+// The search reads every residual arc record once, so it is organised by records, not vertices: a
+// frontier vertex puts one entry per span of its row on the work list (span = p.gr_lanes *
+// p.gr_sub records, sized on the host so that at most 2n entries exist at a time), a group of
+// p.gr_lanes lanes takes K entries at a time and has the K record loads in flight before it looks
+// at the first.  A record carries a flag when it is the last of its row, so no row bounds are needed.
+template <bool COMPACT>
+__device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32_t t, const ArcCap &arc_cap,
+                               uint32_t &gr_scans FC_GRDBG_PARAM) {
     using W = typename State<COMPACT>::W;
-    const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n;
-    const int32_t lg = tid & (G - 1), grp = tid / G, ngrp = T / G;
+#ifdef FC_GRDETAIL
+    long long gtick_ = clock64();
+#define FC_GTICK(i) do { long long now_ = clock64(); g_grdbg[i] += uint32_t(now_ - gtick_); gtick_ = now_; } while (0)
+#else
+#define FC_GTICK(i) do { } while (0)
+#endif
+    constexpr int K = 4, Q = 5;
+    const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n, lane = tid & 63;
+    const int32_t gg = p.gr_lanes, S = p.gr_sub, span = gg * S;
+    const int32_t lg = tid & (gg - 1), grp = tid >> p.gr_shift, ngrp = T >> p.gr_shift;
+    const unsigned long long gmask = (gg == 64 ? ~0ull : ((1ull << gg) - 1ull)) << (lane & ~(gg - 1));
+    const unsigned long long before_me = gmask & ((1ull << lane) - 1ull);      // lower lanes of my group
+    const int32_t last_rec = p.n_rec - 1;
+    W *const work = st.list0;              // list0 and list1 are adjacent
+    lds_barrier();                         // slower wavefronts may still be reading what is overwritten here
     for (int32_t v = tid; v < n; v += T) st.h[v] = W(v == t ? 0 : n);
-    if (tid == 0) st.sh->cnt[0] = 0;
+    for (int32_t i = tid; i < FC_LVLS; i += T) st.sh->lvl[i] = 0;
+    if (tid == 0) { st.sh->cnt[0] = 0; st.sh->down[0] = 0; }
     lds_barrier();
     for (int32_t d = 0;; ++d) {
         const int32_t par = d & 1;
-        // frontier: vertices at distance d (found by a scan; keeps the search free of queues and CAS)
-        for (int32_t base = 0; base < n; base += T) {
-            const int32_t v = base + tid;
-            const bool isd = v < n && int32_t(st.h[v < n ? v : 0]) == d;
-            const unsigned long long b = __ballot(isd);
-            if (b) {
+        // frontier scan: every vertex at distance d appends the starts of the spans of its row
+        for (int32_t base = 0; base < n; base += Q * T) {
+            int32_t row[Q], c[Q], mine = 0, verts = 0;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int32_t v = base + q * T + tid;
+                const int32_t vc = v < n ? v : n - 1;             // clamped: reads stay unconditional
+                const bool isd = int32_t(st.h[vc]) == d && v < n;
+                row[q] = int32_t(st.rp[vc]);
+                const int32_t len = int32_t(st.rp[vc + 1]) - row[q];
+                c[q] = !isd ? 0 : (S == 1 ? (len + gg - 1) >> p.gr_shift : (len + span - 1) / span);
+                mine += c[q];
+                verts += isd ? 1 : 0;
+            }
+            const int32_t incl = wave_prefix_sum(mine | (verts << 20));   // two sums at once: entries <= 2n < 2^20, vertices <= 64 Q
+            const int32_t tot = __builtin_amdgcn_readlane(incl, 63);
+            if (tot) {
                 int32_t pos = 0;
-                if ((tid & 63) == 0) pos = atomicAdd(&st.sh->cnt[par], __popcll(b));
-                pos = __shfl(pos, 0);
-                if (isd) st.list0[pos + __popcll(b & ((1ull << (tid & 63)) - 1ull))] = W(v);
+                if (lane == 0) { pos = atomicAdd(&st.sh->cnt[par], tot & 0xfffff); atomicAdd(&st.sh->down[par], tot >> 20); }
+                pos = __builtin_amdgcn_readfirstlane(pos) + (incl & 0xfffff) - mine;
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+                    for (int32_t j = 0; j < c[q]; ++j) work[pos++] = W(row[q] + j * span);
             }
         }
         lds_barrier();
+        FC_GTICK(0);
         const int32_t cnt = st.sh->cnt[par];
-        if (tid == 0) st.sh->cnt[par ^ 1] = 0;
-        if (cnt == 0) break;
-        for (int32_t i = grp; i < cnt; i += ngrp) {
-            const int32_t w = int32_t(st.list0[i]);
-            const int32_t beg = int32_t(st.rp[w]), end = int32_t(st.rp[w + 1]);
-            for (int32_t a = beg + lg; a < end; a += G) {
-                const ArcRec r = load_arc<COMPACT>(p, a);
-                ++gr_scans;
-                const int32_t fv = int32_t(st.f[r.pair]);
-                const int32_t res = r.fwd ? fv : arc_cap(U, r.bw, NK) - fv;     // residual of r.w -> w
-                if (res > 0 && int32_t(st.h[r.w]) == n) st.h[r.w] = W(d + 1);    // same value from every writer
+        if (tid == 0) {
+            st.sh->cnt[par ^ 1] = 0;
+            if (d >= 1 && d < FC_LVLS) st.sh->lvl[d] = st.sh->down[par];
+            st.sh->down[par ^ 1] = 0;
+        }
+#ifdef FC_GRDETAIL
+        g_grdbg[2] += 1;
+#endif
+        if (st.sh->down[par] == 0) break;                        // empty frontier (a vertex without arcs adds no entry)
+        for (int32_t i0 = grp; i0 < cnt; i0 += ngrp * K) {
+            int32_t a0[K]; bool live[K];
+#pragma unroll
+            for (int q = 0; q < K; ++q) {
+                const int32_t i = i0 + q * ngrp;
+                live[q] = i < cnt;
+                a0[q] = int32_t(work[live[q] ? i : cnt - 1]) + lg;
+            }
+            for (int32_t sub = 0; sub < S; ++sub) {               // S = 1 unless the graph is dense
+                ArcRaw<COMPACT> raw[K];
+#pragma unroll
+                for (int q = 0; q < K; ++q) {
+                    const int32_t a = a0[q] + sub * gg;
+                    raw[q] = load_arc_raw<COMPACT>(p, a < last_rec ? a : last_rec);      // unconditional, in bounds
+                }
+                // all flow reads, then all height reads, then the writes: three LDS round trips
+                int32_t x[K];                                     // tail of a residual arc into the frontier, else the sink
+#pragma unroll
+                for (int q = 0; q < K; ++q) {
+                    const ArcRec r = decode_arc<COMPACT>(raw[q]);
+                    const unsigned long long ends = __ballot(live[q] && r.last) & gmask;
+                    const bool valid = live[q] && (ends & before_me) == 0ull;            // up to the row's last record
+                    live[q] = live[q] && ends == 0ull;
+                    const int32_t fv = int32_t(st.f[r.pair]);
+                    const int32_t res = r.fwd ? fv : arc_cap(r.bw) - fv;                 // residual of r.w -> frontier vertex
+                    x[q] = valid && res > 0 ? r.w : t;
+                    if (valid) ++gr_scans;
+                }
+                int32_t hx[K];
+#pragma unroll
+                for (int q = 0; q < K; ++q) hx[q] = int32_t(st.h[x[q]]);
+#pragma unroll
+                for (int q = 0; q < K; ++q)
+                    if (hx[q] == n) st.h[x[q]] = W(d + 1);        // same value from every writer; h[t] = 0
             }
         }
         lds_barrier();
+        FC_GTICK(1);
     }
     lds_barrier();
-    if (tid == 0) st.sh->cnt[0] = st.sh->cnt[1] = 0;
+    if (tid == 0) { st.sh->cnt[0] = st.sh->cnt[1] = 0; st.sh->down[0] = st.sh->down[1] = 0; }
     lds_barrier();
 }
 
@@ -287,7 +432,7 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
 // first admissible arc when it suffices, else split it by a segmented prefix sum in row order, and
 // collect the smallest residual-neighbour height for the relabel in the same scan.
 template <bool COMPACT, int G>
-__global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
+__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) fc_push_relabel_kernel(KParams p) {
     using W = typename State<COMPACT>::W;
     constexpr int32_t NEWH = State<COMPACT>::NEWH;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -316,6 +461,7 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
         }
     } else if (small && p.arc_compact != nullptr) return;
     const int32_t NK = int32_t(NKll);
+    const ArcCap arc_cap(U, NK);
 
     const Carve cv = carve_lds(n, m0, COMPACT);
     State<COMPACT> st;
@@ -334,6 +480,9 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
     const uint32_t wc_start_ = uint32_t(wall_clock64());
 #endif
     uint32_t t_init = 0, t_compact = 0, t_discharge = 0, t_other = 0, t_post = 0, t_next = 0;
+#endif
+#ifdef FC_GRDETAIL
+    uint32_t grdbg[3] = {0u, 0u, 0u};
 #endif
     uint32_t c_push = 0, c_scan = 0, c_grscan = 0, c_rel = 0, c_dis = 0;   // per-thread counters
     uint32_t c_gr = 0, c_step = 0;                                         // thread 0 only
@@ -357,14 +506,24 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
         }
         if (tid == 0) {
             st.rp[n] = W(p.row_ptr[n]);
-            for (int i = 0; i < 2; ++i) { st.sh->cnt[i] = 0; st.sh->down[i] = 0; st.sh->nrel[i] = 0; st.sh->dnext[i] = 0; st.sh->back[i] = n; }
+            for (int i = 0; i < 2; ++i) { st.sh->cnt[i] = 0; st.sh->down[i] = 0; st.sh->nrel[i] = 0; st.sh->dnext[i] = 0; st.sh->dcarry[i] = 0; st.sh->back[i] = n; }
             st.sh->tmp = 0;
             for (int i = 0; i < FC_NSTAT; ++i) st.sh->st[i] = 0;
         }
         if (have_p1 && tid < 64) st.sh->off[tid] = p.level_off[size_t(t) * 64 + tid];
+        for (int32_t i = tid; i < FC_LVLS; i += T) st.sh->lvl[i] = 0;
         lds_barrier();
+        if (have_p1) {                     // level populations from the sink's level table
+            const int32_t L = int32_t(st.sh->off[0]);
+            if (tid >= 1 && tid <= L && tid < FC_LVLS) st.sh->lvl[tid] = int32_t(st.sh->off[2 + L - tid]) - int32_t(st.sh->off[1 + L - tid]);
+        } else if (have_labels) {          // deep or large graphs: count (one atomic per wavefront and level run would be
+            for (int32_t v = tid; v < n; v += T) {   // nicer; this path runs once per problem)
+                const int32_t hv = int32_t(st.h[v]);
+                if (hv >= 1 && hv < FC_LVLS) atomicAdd(&st.sh->lvl[hv], 1);
+            }
+        }
         if (!have_labels) {
-            global_relabel<COMPACT, G>(p, st, t, U, NK, c_grscan);
+            global_relabel<COMPACT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG);
             if (tid == 0) ++c_gr;
         }
     }
@@ -386,7 +545,14 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
         cur = 0;
     }
     FC_TICK(t_init);
-    int32_t steps_since = 0, total_steps = 0, rel_since = 0;
+    int32_t steps_since = 0, total_steps = 0, rel_since = 0, rises = 0;
+    // a sink whose own cut has little slack tends to leave much excess stranded next to it after the
+    // first pass: such problems get exact heights as soon as the working level first moves up
+    int32_t rise_limit = p.gr_rises;
+    if (p.tight_pct > 0) {
+        const long long have = (long long)U * (long long)p.in_bw[t] + (p.is_compute[t] ? k : 0);
+        if (have * 100ll < NKll * (long long)p.tight_pct) rise_limit = 1;
+    }
     bool failed = false;
 
     // ---- steps: one height level each
@@ -413,7 +579,7 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                 const int32_t ex = ok ? st.excess(u) : 0;
                 if (ex > 0) {
                     const int32_t w = int32_t(en.x & 0x7fffu), pair = int32_t(en.x >> 16);
-                    const int32_t cap = arc_cap(U, int32_t(en.y), NK);
+                    const int32_t cap = arc_cap(int32_t(en.y));
                     const int32_t delta = ex < cap ? ex : cap;
                     ++c_dis; ++c_scan; ++c_push;
                     st.f[pair] = W(delta);
@@ -440,6 +606,7 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                 if (i < total) {
                     v = int32_t(st.list(src)[i < prev_cnt ? i : b0 + (i - prev_cnt)]);
                     hv = int32_t(st.h[v]);
+                    if (hv & NEWH) { hv &= ~NEWH; st.h[v] = W(hv); }      // relabeled in the last step: the new height takes effect
                     const bool alive = hv < n && (i >= prev_cnt || st.excess(v) > 0);
                     isd = alive && hv == d; carry = alive && hv != d;
                 }
@@ -447,15 +614,14 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                 if (bd) {
                     int32_t pos = 0;
                     if (lane == 0) pos = atomicAdd(&st.sh->cnt[sp], __popcll(bd));
-                    pos = __shfl(pos, 0);
+                    pos = __builtin_amdgcn_readfirstlane(pos);
                     if (isd) st.list(cur)[pos + __popcll(bd & below)] = W(v);
                 }
                 if (bc) {
-                    int32_t pos = 0, m = carry ? hv : 0;
-#pragma unroll
-                    for (int s = 32; s > 0; s >>= 1) { const int32_t y = __shfl_xor(m, s); if (y > m) m = y; }
-                    if (lane == 0) { pos = atomicSub(&st.sh->back[cur], __popcll(bc)) - __popcll(bc); atomicMax(&st.sh->dnext[sp], m); }
-                    pos = __shfl(pos, 0);
+                    int32_t pos = 0;
+                    const int32_t m = wave_max(carry ? hv : 0);
+                    if (lane == 0) { pos = atomicSub(&st.sh->back[cur], __popcll(bc)) - __popcll(bc); atomicMax(&st.sh->dcarry[sp], m); }
+                    pos = __builtin_amdgcn_readfirstlane(pos);
                     if (carry) st.list(cur)[pos + __popcll(bc & below)] = W(v);
                 }
             }
@@ -463,7 +629,7 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
         lds_barrier();
         cnt = st.sh->cnt[sp];
         if (tid == 0) {                    // nobody reads these any more; they are written again after the next barrier at the earliest
-            st.sh->cnt[sp ^ 1] = 0; st.sh->down[sp ^ 1] = 0; st.sh->nrel[sp ^ 1] = 0; st.sh->dnext[sp ^ 1] = 0;
+            st.sh->cnt[sp ^ 1] = 0; st.sh->down[sp ^ 1] = 0; st.sh->nrel[sp ^ 1] = 0; st.sh->dnext[sp ^ 1] = 0; st.sh->dcarry[sp ^ 1] = 0;
             if (!fast) st.sh->back[cur ^ 1] = n;
         }
         FC_TICK(t_compact);
@@ -479,12 +645,12 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
             for (int32_t base = beg; base < end && rem > 0; base += G) {
                 const int32_t a = base + lg;
                 int32_t ra = 0, hw = 0, fv = 0;
-                ArcRec r; r.w = 0; r.pair = 0; r.bw = 0; r.fwd = 0;
+                ArcRec r; r.w = 0; r.pair = 0; r.bw = 0; r.fwd = 0; r.last = 0;
                 if (a < end) {
                     r = load_arc<COMPACT>(p, a);
                     ++c_scan;
                     fv = int32_t(st.f[r.pair]);
-                    ra = r.fwd ? arc_cap(U, r.bw, NK) - fv : fv;
+                    ra = r.fwd ? arc_cap(r.bw) - fv : fv;
                     hw = st.height_during_step(r.w, d);
                 }
                 const bool adm = ra > 0 && hw + 1 == d;
@@ -499,13 +665,8 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                         rem_new = 0;
                     } else {                              // split the excess in arc order
                         const int32_t x = adm ? ra : 0;
-                        int32_t incl = x;
-#pragma unroll
-                        for (int s = 1; s < G; s <<= 1) {
-                            const int32_t y = __shfl_up(incl, s, G);
-                            if (lg >= s) incl += y;
-                        }
-                        const int32_t total = __shfl(incl, G - 1, G);
+                        const int32_t incl = group_prefix_sum<G>(x, lg);
+                        const int32_t total = group_allreduce<G>(x, [](int32_t a, int32_t b) { return a + b; });
                         const int32_t excl = incl - x;
                         delta = rem - excl; if (delta > x) delta = x; if (delta < 0) delta = 0;
                         rem_new = total >= rem ? 0 : rem - total;
@@ -527,15 +688,13 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
                 }
             }
             if (rem > 0) {                                // every admissible arc is saturated: relabel
-#pragma unroll
-                for (int s = G / 2; s > 0; s >>= 1) {
-                    const int32_t y = __shfl_xor(minh, s, G);
-                    if (y < minh) minh = y;
-                }
+                minh = group_allreduce<G>(minh, [](int32_t a, int32_t b) { return a < b ? a : b; });
                 if (lg == 0) {
                     const int32_t nh = minh >= n - 1 ? n : minh + 1;
                     st.h[u] = W(NEWH | nh);
                     atomicAdd(&st.sh->nrel[sp], 1);
+                    if (d < FC_LVLS) atomicSub(&st.sh->lvl[d], 1);
+                    if (nh < FC_LVLS) atomicAdd(&st.sh->lvl[nh], 1);
                     if (nh < n) atomicMax(&st.sh->dnext[sp], nh);
                     ++c_rel;
                 }
@@ -546,33 +705,39 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
         FC_TICK(t_discharge);
         const int32_t nrel = st.sh->nrel[sp], down = st.sh->down[sp];
         int32_t dn = st.sh->dnext[sp];
+        const int32_t dcarry = st.sh->dcarry[sp];
+        // level d lost its last vertex: nothing above it can reach the sink any more
+        const bool gap = p.use_gap && nrel > 0 && d < FC_LVLS && st.sh->lvl[d] == 0;
         ++steps_since; ++total_steps;
         if (tid == 0) ++c_step;
 
         if (nrel) {
-            // the new heights take effect (deferred so that the level's scans all saw the same heights)
-            // (first pass: the list is rebuilt for every level, so the relabeled vertices move to the
-            // pending list, kept on array 1; afterwards they are found again in this array's front)
-            for (int32_t i = tid; i < cnt; i += T) {
-                const int32_t u = int32_t(st.list(cur)[i]);
-                const int32_t raw = int32_t(st.h[u]);
-                if (raw & NEWH) {
-                    st.h[u] = W(raw & ~NEWH);
-                    if (fast && (raw & ~NEWH) < n) st.pend(1, u);
-                }
-            }
             rel_since += nrel;
-            if (fast && p.use_gap && nrel == lvltot) {
-                // every vertex of level d left it: the level is empty, so nothing above it can reach
-                // the sink any more (pending entries that die here are dropped when their turn comes)
-                lds_barrier();
+            if (gap) {
+                // (pending entries that die here are dropped when their turn comes)
                 for (int32_t v = tid; v < n; v += T) {
-                    const int32_t hv = int32_t(st.h[v]);
-                    if (hv > d && hv < n) st.h[v] = W(n);
+                    const int32_t raw = int32_t(st.h[v]), hv = raw & ~NEWH;
+                    if ((raw & NEWH) || (hv > d && hv < n)) st.h[v] = W(n);   // flagged = relabeled in this step = above d
                 }
+                lds_barrier();                 // everybody has read lvl[d]
+                for (int32_t i = d + 1 + tid; i < FC_LVLS; i += T) st.sh->lvl[i] = 0;
                 pend_hmax = 0; dn = 0;
+                lds_barrier();
+            } else if (fast) {
+                // the new heights take effect (deferred so that the level's scans all saw the same
+                // heights).  In the first pass the list is rebuilt for every level, so the relabeled
+                // vertices move to the pending list, kept on array 1; afterwards they are found again
+                // in this array's front, and their flags are cleared then.
+                for (int32_t i = tid; i < cnt; i += T) {
+                    const int32_t u = int32_t(st.list(cur)[i]);
+                    const int32_t raw = int32_t(st.h[u]);
+                    if (raw & NEWH) {
+                        st.h[u] = W(raw & ~NEWH);
+                        if ((raw & ~NEWH) < n) st.pend(1, u);
+                    }
+                }
+                lds_barrier();
             }
-            lds_barrier();
         }
         FC_TICK(t_post);
         if (st.excess(t) == NK) break;
@@ -581,20 +746,27 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
         // ---- next level
         if (fast) {
             if (dn > pend_hmax) pend_hmax = dn;
-            if (d > 1) d = d - 1;                         // lower levels still hold their compute nodes
+            if (d > 1) {
+                d = d - 1;                                // lower levels still hold their compute nodes
+                // level 1's lanes push into the sink before the step's first barrier: wait until every
+                // wavefront has taken this step's "sink is full" decision
+                if (d == 1) lds_barrier();
+            }
             else {                                        // first pass over: continue with the pending list (on array 0)
-                fast = false; cur = 0; prev_cnt = 0; d = pend_hmax;
+                fast = false; cur = 0; prev_cnt = 0; d = pend_hmax; rises = 1;
             }
         } else {
+            if (dcarry > dn) dn = dcarry;
             if (down && d - 1 > dn) dn = d - 1;
+            if (dn > d) ++rises;
             d = dn;
             prev_cnt = cnt;
             cur ^= 1;
         }
-        if (!fast && rel_since > 0 && (rel_since >= p.gr_relabels || steps_since >= p.gr_steps) && d >= 1) {
-            global_relabel<COMPACT, G>(p, st, t, U, NK, c_grscan);
+        if (!fast && rel_since > 0 && (rel_since >= p.gr_relabels || steps_since >= p.gr_steps || rises >= rise_limit) && d >= 1) {
+            global_relabel<COMPACT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG);
             if (tid == 0) ++c_gr;
-            rel_since = 0; steps_since = 0;
+            rel_since = 0; steps_since = 0; rises = 0;
             d = rebuild_pending(st, n, t, cur ^ 1);
             prev_cnt = 0;
             if (tid == 0) { st.sh->back[cur] = n; st.sh->dnext[0] = st.sh->dnext[1] = 0; }
@@ -625,6 +797,9 @@ __global__ void __launch_bounds__(1024) fc_push_relabel_kernel(KParams p) {
         if (tid == 0) { st.sh->st[0] = t_init; st.sh->st[1] = t_compact; st.sh->st[2] = t_discharge; st.sh->st[3] = t_post; st.sh->st[4] = t_next; st.sh->st[6] = t_other; }
 #ifdef FC_WALLCLOCK
         if (tid == 0) { st.sh->st[4] = uint32_t(wall_clock64()); st.sh->st[6] = wc_start_; }
+#endif
+#ifdef FC_GRDETAIL
+        if (tid == 0) { st.sh->st[3] = grdbg[0]; st.sh->st[6] = grdbg[1]; st.sh->st[5] = grdbg[2]; }
 #endif
 #endif
         lds_barrier();
@@ -726,7 +901,7 @@ size_t lds_bytes(const fc_graph *g, bool compact) { return carve_lds(g->n, int32
 bool compact_ids_fit(const fc_graph *g) { return g->n <= 32767 && 2 * g->m0 <= 65535; }
 
 struct Resolved {
-    int32_t T, G, gr_steps, gr_relabels, use_gap, use_labels, force_wide, max_steps, src_cap_bound, schedule;
+    int32_t T, G, gr_steps, gr_relabels, gr_rises, tight_pct, use_gap, use_labels, force_wide, max_steps, src_cap_bound, schedule;
 };
 
 int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
@@ -746,6 +921,9 @@ int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
     r->gr_steps = o->global_relabel_steps > 0 ? o->global_relabel_steps : 32;
     int32_t permille = o->global_relabel_permille > 0 ? o->global_relabel_permille : 100;
     r->gr_relabels = std::max<int32_t>(1, int32_t((long long)g->n * permille / 1000));
+    if (o->global_relabel_rises < -1 || o->tight_sink_percent < -1) return FC_EINVAL;
+    r->gr_rises = o->global_relabel_rises > 0 ? o->global_relabel_rises : 0x7fffffff;   // default: off
+    r->tight_pct = o->tight_sink_percent > 0 ? o->tight_sink_percent : (o->tight_sink_percent < 0 ? 0 : 150);
     if (o->use_gap < 0 || o->use_gap > 2 || o->use_label_table < 0 || o->use_label_table > 2) return FC_EINVAL;
     r->use_gap = o->use_gap != 2;
     r->use_labels = o->use_label_table != 2;
@@ -793,6 +971,13 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     KParams kp;
     kp.n = g->n; kp.N = g->N; kp.m0 = int32_t(g->m0);
     kp.n_rec = std::max<int32_t>(1, int32_t(2 * g->m0));
+    {   // work-list entries of a global relabel: at most n (one per frontier vertex) + records / span <= 2n
+        const long long rec = 2 * g->m0, nn = std::max<int32_t>(1, g->n);
+        int32_t lanes = 4, shift = 2;
+        while (lanes < 64 && (long long)lanes * nn < rec) { lanes *= 2; ++shift; }
+        kp.gr_lanes = lanes; kp.gr_shift = shift;
+        kp.gr_sub = int32_t(std::max<long long>(1, (rec + (long long)lanes * nn - 1) / ((long long)lanes * nn)));
+    }
     kp.row_ptr = g->d_row_ptr;
     kp.arc_wide = reinterpret_cast<const int4 *>(g->d_arc_wide);
     const bool compact_possible = !opt.force_wide && g->d_arc_compact != nullptr &&
@@ -808,7 +993,7 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     kp.p1 = opt.use_labels ? reinterpret_cast<const uint4 *>(g->d_p1) : nullptr;
     kp.level_off = g->d_level_off;
     kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.flow_out = d_flow; kp.stats = d_stats_pp;
-    kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
+    kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.gr_rises = opt.gr_rises; kp.tight_pct = opt.tight_pct; kp.in_bw = g->d_in_bw; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
     kp.wide_available = wide_possible ? 1 : 0;
     kp.order = nullptr;
     if (opt.schedule && P > 2ll * g->n_cu) {            // small launches fit the machine at once: order is moot
@@ -876,7 +1061,9 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
     const size_t M = size_t(2 * g->m0), n = size_t(g->n);
     try {
         std::vector<int4> wide(M ? M : 1, make_int4(0, 0, 0, 0));
-        for (size_t i = 0; i < M; ++i) wide[i] = make_int4(g->other[i], g->pair[i], g->bw[i], g->fwd[i]);
+        std::vector<uint8_t> last(M ? M : 1, 0);                     // final record of a vertex's row
+        for (size_t v = 0; v < n; ++v) if (g->row_ptr[v + 1] > g->row_ptr[v]) last[size_t(g->row_ptr[v + 1]) - 1] = 1;
+        for (size_t i = 0; i < M; ++i) wide[i] = make_int4(g->other[i], g->pair[i], g->bw[i], g->fwd[i] | (last[i] << 1));
         g->on_device = true;
         if (hipMalloc(&g->d_row_ptr, sizeof(int32_t) * (n + 1)) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMalloc(&g->d_arc_wide, sizeof(int4) * (M ? M : 1)) != hipSuccess) return fail(FC_EDEVICE);
@@ -891,7 +1078,7 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
         if (compact_ids_fit(g)) {
             std::vector<uint2> cmp(M ? M : 1, make_uint2(0u, 0u));
             for (size_t i = 0; i < M; ++i)
-                cmp[i] = make_uint2(uint32_t(g->other[i]) | (uint32_t(g->fwd[i]) << 15) | (uint32_t(g->pair[i]) << 16), uint32_t(g->bw[i]));
+                cmp[i] = make_uint2(uint32_t(g->other[i]) | (uint32_t(g->fwd[i]) << 15) | (uint32_t(g->pair[i]) << 16), uint32_t(g->bw[i]) | (uint32_t(last[i]) << 31));
             if (hipMalloc(&g->d_arc_compact, sizeof(uint2) * (M ? M : 1)) != hipSuccess) return fail(FC_EDEVICE);
             if (hipMemcpy(g->d_arc_compact, cmp.data(), sizeof(uint2) * (M ? M : 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         }
