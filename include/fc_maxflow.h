@@ -76,7 +76,7 @@ typedef struct {
                                       then (default and -1: off)                                        */
     int32_t tight_sink_percent;    /* a problem whose sink cut U*B^-(t) (+k) is below this percentage of the
                                       demand N*k relabels from the sink the first time the working level
-                                      moves up (default 150, -1: off)                                  */
+                                      moves up (default 200, -1: off)                                  */
     int32_t use_gap;               /* 1 = on (default), 2 = off: empty-height-level cut detection      */
     int32_t use_label_table;       /* 1 = on (default), 2 = off: initial exact labels from the
                                       per-sink distance table built at upload                          */

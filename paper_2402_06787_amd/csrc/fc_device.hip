@@ -57,6 +57,7 @@ struct KParams {
     const int32_t *in_bw;        // [n] in-bandwidth of every vertex
     int32_t wide_available;      // the 32-bit-state kernel is launched too
     const int32_t *order;        // workgroup -> problem (hardest first), or null for the identity
+    uint32_t *sink_cost;         // [n] what the last problem of each sink cost (feeds the next launch's order)
 };
 
 struct ArcRec { int32_t w, pair, bw, fwd, last; };   // last: final record of its vertex's row
@@ -776,7 +777,10 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     }
 
     lds_barrier();
-    if (tid == 0) p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : st.excess(t);
+    if (tid == 0) {
+        p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : st.excess(t);
+        p.sink_cost[t] = uint32_t(total_steps) + 6u * c_gr + 1u;
+    }
     if (p.stats) {
 #ifndef FC_PHASE_TIMING
         // one LDS update per wavefront and counter: sum over the lanes first
@@ -809,31 +813,32 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
 
 // Launch order: workgroups are dispatched in index order and a hard problem can run twenty times
 // longer than a typical one, so the hard ones must start first or the launch ends with a long
-// tail of idle CUs.  Hardness is guessed from the slack of the sink's single-vertex cut, the same
-// cut the paper's initial range uses (Appendix E.1): in-capacity U * B^-(sink) (+ k) over the
-// demand N * k.  One workgroup buckets all problems by that ratio and writes the permutation.
+// tail of idle CUs.  Every solved problem leaves its cost (level steps, plus a charge per global
+// relabel) in a per-sink array that lives with the graph; problems of one sink with nearby
+// candidates cost about the same, so the next launch sorts by it.  A sink not seen yet is guessed
+// from the slack of its own cut, the cut the paper's initial range uses (Appendix E.1): in-capacity
+// U * B^-(sink) (+ k) over the demand N * k.  One workgroup counting-sorts all problems.
 __global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, int32_t N, const int32_t *sink,
                                                         const int32_t *U, const int32_t *k, const int32_t *in_bw,
-                                                        const uint8_t *is_compute, int32_t *order) {
-    constexpr int NB = 8;
+                                                        const uint8_t *is_compute, const uint32_t *sink_cost,
+                                                        int32_t *order) {
+    constexpr int NB = 256;
     __shared__ int32_t hist[NB], base[NB];
     const int32_t tid = threadIdx.x, T = blockDim.x;
-    if (tid < NB) hist[tid] = 0;
+    for (int32_t b = tid; b < NB; b += T) hist[b] = 0;
     __syncthreads();
-    auto bucket = [&](long long jj) -> int {
+    auto bucket = [&](long long jj) -> int {              // 0 = most expensive
         const int32_t t = sink[jj], u = U[jj], kk = k[jj];
         if (t < 0 || t >= n || u < 1 || kk < 1) return NB - 1;              // nothing to solve
-        const long long need = (long long)N * kk;
-        const long long have = (long long)u * in_bw[t] + (is_compute[t] ? kk : 0);
-        // ratio have / need against 1, 1.25, 1.5, 2, 3, 4, 6
-        if (have * 1 < need * 1) return 0;
-        if (have * 4 < need * 5) return 1;
-        if (have * 2 < need * 3) return 2;
-        if (have < need * 2) return 3;
-        if (have < need * 3) return 4;
-        if (have < need * 4) return 5;
-        if (have < need * 6) return 6;
-        return 7;
+        int32_t cost = int32_t(sink_cost[t]);
+        if (cost == 0) {
+            const long long need = (long long)N * kk;
+            const long long have = (long long)u * in_bw[t] + (is_compute[t] ? kk : 0);
+            // ratio have / need against 1, 1.25, 1.5, 2, 3, 4, 6
+            cost = have < need ? 80 : have * 4 < need * 5 ? 60 : have * 2 < need * 3 ? 45 : have < need * 2 ? 35
+                 : have < need * 3 ? 28 : have < need * 4 ? 22 : have < need * 6 ? 16 : 10;
+        }
+        return NB - 1 - (cost < NB - 1 ? cost : NB - 1);
     };
     for (long long jj = tid; jj < P; jj += T) atomicAdd(&hist[bucket(jj)], 1);
     __syncthreads();
@@ -923,7 +928,7 @@ int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
     r->gr_relabels = std::max<int32_t>(1, int32_t((long long)g->n * permille / 1000));
     if (o->global_relabel_rises < -1 || o->tight_sink_percent < -1) return FC_EINVAL;
     r->gr_rises = o->global_relabel_rises > 0 ? o->global_relabel_rises : 0x7fffffff;   // default: off
-    r->tight_pct = o->tight_sink_percent > 0 ? o->tight_sink_percent : (o->tight_sink_percent < 0 ? 0 : 150);
+    r->tight_pct = o->tight_sink_percent > 0 ? o->tight_sink_percent : (o->tight_sink_percent < 0 ? 0 : 200);
     if (o->use_gap < 0 || o->use_gap > 2 || o->use_label_table < 0 || o->use_label_table > 2) return FC_EINVAL;
     r->use_gap = o->use_gap != 2;
     r->use_labels = o->use_label_table != 2;
@@ -993,12 +998,12 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     kp.p1 = opt.use_labels ? reinterpret_cast<const uint4 *>(g->d_p1) : nullptr;
     kp.level_off = g->d_level_off;
     kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.flow_out = d_flow; kp.stats = d_stats_pp;
-    kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.gr_rises = opt.gr_rises; kp.tight_pct = opt.tight_pct; kp.in_bw = g->d_in_bw; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
+    kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.gr_rises = opt.gr_rises; kp.tight_pct = opt.tight_pct; kp.in_bw = g->d_in_bw; kp.sink_cost = g->d_sink_cost; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
     kp.wide_available = wide_possible ? 1 : 0;
     kp.order = nullptr;
     if (opt.schedule && P > 2ll * g->n_cu) {            // small launches fit the machine at once: order is moot
         hipLaunchKernelGGL(fc_order_kernel, dim3(1), dim3(1024), 0, stream, P, g->n, g->N, d_sink, d_U, d_k,
-                           g->d_in_bw, g->d_is_compute, d_order);
+                           g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order);
         HIP_TRY(hipGetLastError());
         kp.order = d_order;
     }
@@ -1070,6 +1075,8 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
         if (hipMalloc(&g->d_is_compute, n) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMalloc(&g->d_compute_ids, sizeof(int32_t) * size_t(g->N)) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMalloc(&g->d_in_bw, sizeof(int32_t) * n) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMalloc(&g->d_sink_cost, sizeof(uint32_t) * n) != hipSuccess) return fail(FC_EDEVICE);
+        if (hipMemset(g->d_sink_cost, 0, sizeof(uint32_t) * n) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMemcpy(g->d_in_bw, g->in_bw.data(), sizeof(int32_t) * n, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMemcpy(g->d_row_ptr, g->row_ptr.data(), sizeof(int32_t) * (n + 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMemcpy(g->d_arc_wide, wide.data(), sizeof(int4) * (M ? M : 1), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
@@ -1118,6 +1125,7 @@ extern "C" int fc_graph_free(fc_graph *g) {
         if (g->d_is_compute) (void)hipFree(g->d_is_compute);
         if (g->d_compute_ids) (void)hipFree(g->d_compute_ids);
         if (g->d_in_bw) (void)hipFree(g->d_in_bw);
+        if (g->d_sink_cost) (void)hipFree(g->d_sink_cost);
         if (g->d_labels) (void)hipFree(g->d_labels);
         if (g->d_label_hmax) (void)hipFree(g->d_label_hmax);
         if (g->d_p1) (void)hipFree(g->d_p1);

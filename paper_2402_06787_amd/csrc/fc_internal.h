@@ -31,6 +31,7 @@ struct fc_graph {
     uint8_t *d_is_compute = nullptr;   // [n]
     int32_t *d_compute_ids = nullptr;  // [N]
     int32_t *d_in_bw = nullptr;        // [n]
+    uint32_t *d_sink_cost = nullptr;   // [n] cost of the last problem solved per sink (scheduling hint, updated by the solver)
     uint16_t *d_labels = nullptr;      // [n*n] exact initial labels per sink (row = sink), bit 15 = compute; or null
     uint16_t *d_label_hmax = nullptr;  // [n] highest finite label of a compute node, per sink
     void *d_p1 = nullptr;              // uint4 [n*n] first-pass entries in level order, per sink (null: not built)
