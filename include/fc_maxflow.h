@@ -18,8 +18,12 @@
  *    graph was uploaded; the caller owns them and keeps them alive until the work
  *    queued on `hip_stream` has finished.
  *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
- *  - An fc_graph is immutable after creation and may be shared by concurrent calls on
- *    different streams as long as each call has its own workspace.
+ *  - An fc_graph's topology is immutable after creation and it may be shared by concurrent
+ *    calls on different streams as long as each call has its own workspace.  An uploaded graph
+ *    also carries one scheduling hint per vertex (what the last max-flow into that sink cost),
+ *    which the solver updates and the next call uses to start the expensive problems first; it
+ *    affects the order problems run in, never a result, and concurrent calls may overwrite each
+ *    other's hints freely.
  */
 #ifndef FC_MAXFLOW_H
 #define FC_MAXFLOW_H

@@ -57,6 +57,10 @@ struct KParams {
     const int32_t *in_bw;        // [n] in-bandwidth of every vertex
     int32_t wide_available;      // the 32-bit-state kernel is launched too
     const int32_t *order;        // workgroup -> problem (hardest first), or null for the identity
+    // candidate x sink launches (fc_feasible): workgroup b solves candidate b % cand_C for the sink that
+    // has place b / cand_C in the order; the problem list is never written out
+    int32_t cand_C;              // 0: plain problem list
+    const int32_t *cand_U, *cand_k, *compute_ids;
     uint32_t *sink_cost;         // [n] what the last problem of each sink cost (feeds the next launch's order)
 };
 
@@ -438,10 +442,17 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     constexpr int32_t NEWH = State<COMPACT>::NEWH;
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n, m0 = p.m0;
-    const int32_t j = p.order ? p.order[blockIdx.x] : int32_t(blockIdx.x);
+    int32_t j, t, U, k;
+    if (p.cand_C) {
+        const int32_t place = int32_t(blockIdx.x) / p.cand_C, c = int32_t(blockIdx.x) - place * p.cand_C;
+        const int32_t i = p.order ? p.order[place] : place;
+        j = c * p.N + i; t = p.compute_ids[i]; U = p.cand_U[c]; k = p.cand_k[c];
+    } else {
+        j = p.order ? p.order[blockIdx.x] : int32_t(blockIdx.x);
+        t = p.sink[j]; U = p.U[j]; k = p.k[j];
+    }
 
     // ---- problem and its validity (uniform over the workgroup)
-    const int32_t t = p.sink[j], U = p.U[j], k = p.k[j];
     const long long NKll = (long long)p.N * (long long)k;
     const bool valid = t >= 0 && t < n && U >= 1 && k >= 1 && NKll < (1ll << 31);
     if (!valid) {                       // both layouts write the same marker
@@ -818,41 +829,135 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
 // candidates cost about the same, so the next launch sorts by it.  A sink not seen yet is guessed
 // from the slack of its own cut, the cut the paper's initial range uses (Appendix E.1): in-capacity
 // U * B^-(sink) (+ k) over the demand N * k.  One workgroup counting-sorts all problems.
+constexpr int FC_ORDER_BUCKETS = 256;
+
+// sort key of a problem: bucket 0 holds the most expensive ones
+__device__ __forceinline__ int32_t order_bucket(int32_t t, int32_t u, int32_t kk, int32_t n, int32_t N, const int32_t *in_bw,
+                                                const uint8_t *is_compute, const uint32_t *sink_cost) {
+    constexpr int NB = FC_ORDER_BUCKETS;
+    if (t < 0 || t >= n || u < 1 || kk < 1) return NB - 1;                  // nothing to solve
+    int32_t cost = int32_t(sink_cost[t]);
+    if (cost == 0) {
+        const long long need = (long long)N * kk;
+        const long long have = (long long)u * in_bw[t] + (is_compute[t] ? kk : 0);
+        // ratio have / need against 1, 1.25, 1.5, 2, 3, 4, 6
+        cost = have < need ? 80 : have * 4 < need * 5 ? 60 : have * 2 < need * 3 ? 45 : have < need * 2 ? 35
+             : have < need * 3 ? 28 : have < need * 4 ? 22 : have < need * 6 ? 16 : 10;
+    }
+    return NB - 1 - (cost < NB - 1 ? cost : NB - 1);
+}
+
+// counter[b] += 1 for every active lane, one LDS atomic per distinct b in the wavefront; returns the
+// value each lane's own increment would have returned (all 64 lanes must call)
+__device__ __forceinline__ int32_t wave_bucket_add(int32_t *counter, int32_t b, bool active) {
+    const int32_t lane = threadIdx.x & 63;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    unsigned long long todo = __ballot(active);
+    int32_t pos = 0;
+    while (todo) {
+        const int32_t leader = __ffsll((long long)todo) - 1;
+        const int32_t bb = __builtin_amdgcn_readlane(b, leader);
+        const unsigned long long same = __ballot(active && b == bb);
+        int32_t start = 0;
+        if (lane == leader) start = atomicAdd(&counter[bb], __popcll(same));
+        start = __builtin_amdgcn_readlane(start, leader);
+        if (active && b == bb) pos = start + __popcll(same & below);
+        todo &= ~same;
+    }
+    return pos;
+}
+
+// exclusive prefix sum of hist[] into base[] by one wavefront (threads 0..63 of the workgroup)
+__device__ __forceinline__ void order_bucket_bases(const int32_t *hist, int32_t *base, int32_t tid) {
+    int32_t acc = 0;
+    for (int c0 = 0; c0 < FC_ORDER_BUCKETS; c0 += 64) {
+        const int32_t x = hist[c0 + tid];
+        const int32_t incl = wave_prefix_sum(x);
+        base[c0 + tid] = acc + incl - x;
+        acc += __builtin_amdgcn_readlane(incl, 63);
+    }
+}
+
 __global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, int32_t N, const int32_t *sink,
                                                         const int32_t *U, const int32_t *k, const int32_t *in_bw,
                                                         const uint8_t *is_compute, const uint32_t *sink_cost,
                                                         int32_t *order) {
-    constexpr int NB = 256;
+    constexpr int NB = FC_ORDER_BUCKETS, R = 8;
     __shared__ int32_t hist[NB], base[NB];
     const int32_t tid = threadIdx.x, T = blockDim.x;
     for (int32_t b = tid; b < NB; b += T) hist[b] = 0;
     __syncthreads();
-    auto bucket = [&](long long jj) -> int {              // 0 = most expensive
-        const int32_t t = sink[jj], u = U[jj], kk = k[jj];
-        if (t < 0 || t >= n || u < 1 || kk < 1) return NB - 1;              // nothing to solve
-        int32_t cost = int32_t(sink_cost[t]);
-        if (cost == 0) {
-            const long long need = (long long)N * kk;
-            const long long have = (long long)u * in_bw[t] + (is_compute[t] ? kk : 0);
-            // ratio have / need against 1, 1.25, 1.5, 2, 3, 4, 6
-            cost = have < need ? 80 : have * 4 < need * 5 ? 60 : have * 2 < need * 3 ? 45 : have < need * 2 ? 35
-                 : have < need * 3 ? 28 : have < need * 4 ? 22 : have < need * 6 ? 16 : 10;
+    // both passes take R problems per thread at a time so that the R load chains (sink -> cost) overlap
+    for (long long j0 = 0; j0 < P; j0 += (long long)R * T) {
+        int32_t b[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const long long jj = j0 + (long long)r * T + tid;
+            b[r] = jj < P ? order_bucket(sink[jj], U[jj], k[jj], n, N, in_bw, is_compute, sink_cost) : -1;
         }
-        return NB - 1 - (cost < NB - 1 ? cost : NB - 1);
-    };
-    for (long long jj = tid; jj < P; jj += T) atomicAdd(&hist[bucket(jj)], 1);
+#pragma unroll
+        for (int r = 0; r < R; ++r) (void)wave_bucket_add(hist, b[r], b[r] >= 0);
+    }
     __syncthreads();
-    if (tid == 0) { int32_t acc = 0; for (int b = 0; b < NB; ++b) { base[b] = acc; acc += hist[b]; } }
+    if (tid < 64) order_bucket_bases(hist, base, tid);
     __syncthreads();
-    for (long long jj = tid; jj < P; jj += T) order[atomicAdd(&base[bucket(jj)], 1)] = int32_t(jj);
+    for (long long j0 = 0; j0 < P; j0 += (long long)R * T) {
+        int32_t b[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const long long jj = j0 + (long long)r * T + tid;
+            b[r] = jj < P ? order_bucket(sink[jj], U[jj], k[jj], n, N, in_bw, is_compute, sink_cost) : -1;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int32_t pos = wave_bucket_add(base, b[r], b[r] >= 0);
+            if (b[r] >= 0) order[pos] = int32_t(j0 + (long long)r * T + tid);
+        }
+    }
 }
 
-__global__ void fc_expand_candidates_kernel(int32_t C, int32_t N, const int32_t *compute_ids, const int32_t *cU,
-                                            const int32_t *ck, int32_t *sink, int32_t *U, int32_t *k) {
-    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long long)C * N) return;
-    int32_t c = int32_t(idx / N), s = int32_t(idx % N);
-    sink[idx] = compute_ids[s]; U[idx] = cU[c]; k[idx] = ck[c];
+// fc_feasible's problems are C candidates x N sinks (problem c * N + i).  Only the N sinks are
+// sorted (by the cost of candidate 0): order[place] = i.  The solver derives each workgroup's
+// (candidate, sink) from its index, so the C problems of a sink sit next to each other in the
+// launch, which also keeps that sink's tables in cache while they run.
+__global__ void __launch_bounds__(1024) fc_order_sinks_kernel(int32_t N, int32_t n, const int32_t *__restrict__ compute_ids,
+                                                              const int32_t *__restrict__ cU, const int32_t *__restrict__ ck,
+                                                              const int32_t *__restrict__ in_bw,
+                                                              const uint8_t *__restrict__ is_compute,
+                                                              const uint32_t *__restrict__ sink_cost,
+                                                              int32_t *__restrict__ order) {
+    constexpr int NB = FC_ORDER_BUCKETS, R = 4;
+    __shared__ int32_t hist[NB], base[NB];
+    const int32_t tid = threadIdx.x, T = blockDim.x;
+    for (int32_t b = tid; b < NB; b += T) hist[b] = 0;
+    __syncthreads();
+    const int32_t u0 = cU[0], k0 = ck[0];
+    for (int32_t i0 = 0; i0 < N; i0 += R * T) {
+        int32_t b[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int32_t i = i0 + r * T + tid;
+            b[r] = i < N ? order_bucket(compute_ids[i], u0, k0, n, N, in_bw, is_compute, sink_cost) : -1;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) (void)wave_bucket_add(hist, b[r], b[r] >= 0);
+    }
+    __syncthreads();
+    if (tid < 64) order_bucket_bases(hist, base, tid);
+    __syncthreads();
+    for (int32_t i0 = 0; i0 < N; i0 += R * T) {
+        int32_t b[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int32_t i = i0 + r * T + tid;
+            b[r] = i < N ? order_bucket(compute_ids[i], u0, k0, n, N, in_bw, is_compute, sink_cost) : -1;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int32_t pos = wave_bucket_add(base, b[r], b[r] >= 0);
+            if (b[r] >= 0) order[pos] = i0 + r * T + tid;
+        }
+    }
 }
 
 // feasible_c = AND over sinks of [F(s, v) >= N * k_c] (Theorem 1 / Theorem 3); one workgroup per candidate
@@ -969,9 +1074,16 @@ int launch_g(const KParams &kp, long long P, int32_t T, int32_t G, size_t lds, h
 
 struct StatsScratch { uint32_t *per_problem; unsigned long long *totals; };
 
+// small launches fit the machine at once: order is moot
+// problems given as candidates x compute nodes (problem c * N + i) instead of a list
+struct CandidateGrid { int32_t C; const int32_t *d_U, *d_k; };
+
+bool wants_order(const fc_graph *g, const Resolved &opt, long long P) { return opt.schedule && P > 2ll * g->n_cu; }
+
 // Launch the solver kernels for P problems.  stats_ws: null, or room for P*FC_NSTAT u32 + FC_NSTAT u64.
 int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32_t *d_U, const int32_t *d_k,
-              int32_t *d_flow, const Resolved &opt, hipStream_t stream, uint32_t *d_stats_pp, int32_t *d_order) {
+              int32_t *d_flow, const Resolved &opt, hipStream_t stream, uint32_t *d_stats_pp, int32_t *d_order,
+              const CandidateGrid *grid = nullptr, hipEvent_t ev_solver_start = nullptr) {
     if (P > (1ll << 30)) return FC_EINVAL;
     KParams kp;
     kp.n = g->n; kp.N = g->N; kp.m0 = int32_t(g->m0);
@@ -1001,12 +1113,22 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.gr_rises = opt.gr_rises; kp.tight_pct = opt.tight_pct; kp.in_bw = g->d_in_bw; kp.sink_cost = g->d_sink_cost; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
     kp.wide_available = wide_possible ? 1 : 0;
     kp.order = nullptr;
-    if (opt.schedule && P > 2ll * g->n_cu) {            // small launches fit the machine at once: order is moot
+    kp.cand_C = 0; kp.cand_U = kp.cand_k = nullptr; kp.compute_ids = g->d_compute_ids;
+    if (grid) {
+        kp.cand_C = grid->C; kp.cand_U = grid->d_U; kp.cand_k = grid->d_k;
+        if (wants_order(g, opt, P)) {
+            hipLaunchKernelGGL(fc_order_sinks_kernel, dim3(1), dim3(1024), 0, stream, g->N, g->n, g->d_compute_ids,
+                               grid->d_U, grid->d_k, g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order);
+            HIP_TRY(hipGetLastError());
+            kp.order = d_order;
+        }
+    } else if (wants_order(g, opt, P)) {
         hipLaunchKernelGGL(fc_order_kernel, dim3(1), dim3(1024), 0, stream, P, g->n, g->N, d_sink, d_U, d_k,
                            g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order);
         HIP_TRY(hipGetLastError());
         kp.order = d_order;
     }
+    if (ev_solver_start) HIP_TRY(hipEventRecord(ev_solver_start, stream));    // after the ordering kernel
     if (compact_possible) {
         int rc = launch_g<true>(kp, P, opt.T, opt.G, lds_bytes(g, true), stream);
         if (rc != FC_OK) return rc;
@@ -1162,8 +1284,7 @@ extern "C" int fc_maxflow_batch(const fc_graph *g, int64_t n_problems, const int
     HIP_TRY(hipEventCreate(&ev0));
     if (hipEventCreate(&ev1) != hipSuccess) { (void)hipEventDestroy(ev0); return FC_EDEVICE; }
     auto done = [&](int code) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); return code; };
-    if (hipEventRecord(ev0, stream) != hipSuccess) return done(FC_EDEVICE);
-    rc = run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, d_pp, d_order);
+    rc = run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, d_pp, d_order, nullptr, ev0);
     if (rc != FC_OK) return done(rc);
     if (hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
     rc = fill_stats(n_problems, d_pp, d_tot, stream, ev0, ev1, stats_or_null);
@@ -1174,7 +1295,7 @@ extern "C" int fc_maxflow_batch(const fc_graph *g, int64_t n_problems, const int
 extern "C" size_t fc_feasible_workspace_bytes(const fc_graph *g, int32_t n_candidates) {
     if (!g || n_candidates < 0) return 0;
     size_t P = size_t(n_candidates) * size_t(g->N);
-    return 4 * align_up(P * 4, 256) + stats_bytes((long long)P);
+    return align_up(P * 4, 256) + stats_bytes((long long)P);
 }
 
 extern "C" int fc_feasible(const fc_graph *g, int32_t n_candidates, const int32_t *d_edge_mult,
@@ -1193,11 +1314,10 @@ extern "C" int fc_feasible(const fc_graph *g, int32_t n_candidates, const int32_
     const long long P = (long long)n_candidates * g->N;
     unsigned char *ws = reinterpret_cast<unsigned char *>(d_workspace);
     size_t slab = align_up(size_t(P) * 4, 256);
-    int32_t *d_sink = reinterpret_cast<int32_t *>(ws), *d_U = reinterpret_cast<int32_t *>(ws + slab),
-            *d_k = reinterpret_cast<int32_t *>(ws + 2 * slab);
-    int32_t *d_flow = d_flows_or_null ? d_flows_or_null : reinterpret_cast<int32_t *>(ws + 3 * slab);
-    uint32_t *d_pp = reinterpret_cast<uint32_t *>(ws + 4 * slab);
-    unsigned long long *d_tot = reinterpret_cast<unsigned long long *>(ws + 4 * slab + align_up(size_t(P) * FC_NSTAT * 4, 256));
+    // workspace: [flows, one int per problem][the batch scratch]
+    int32_t *d_flow = d_flows_or_null ? d_flows_or_null : reinterpret_cast<int32_t *>(ws);
+    uint32_t *d_pp = reinterpret_cast<uint32_t *>(ws + slab);
+    unsigned long long *d_tot = reinterpret_cast<unsigned long long *>(ws + slab + ws_totals_off(P));
 
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     if (stats_or_null) {
@@ -1205,13 +1325,11 @@ extern "C" int fc_feasible(const fc_graph *g, int32_t n_candidates, const int32_
         if (hipEventCreate(&ev1) != hipSuccess) { (void)hipEventDestroy(ev0); return FC_EDEVICE; }
     }
     auto done = [&](int code) { if (ev0) (void)hipEventDestroy(ev0); if (ev1) (void)hipEventDestroy(ev1); return code; };
-    hipLaunchKernelGGL(fc_expand_candidates_kernel, dim3(unsigned((P + 255) / 256)), dim3(256), 0, stream,
-                       n_candidates, g->N, g->d_compute_ids, d_edge_mult, d_src_cap, d_sink, d_U, d_k);
-    if (hipGetLastError() != hipSuccess) return done(FC_EDEVICE);
-    // device_ms brackets the solver kernel(s) only
-    if (stats_or_null && hipEventRecord(ev0, stream) != hipSuccess) return done(FC_EDEVICE);
-    rc = run_batch(g, P, d_sink, d_U, d_k, d_flow, opt, stream, stats_or_null ? d_pp : nullptr,
-                   reinterpret_cast<int32_t *>(ws + 4 * slab + ws_order_off(P)));
+    int32_t *d_order = reinterpret_cast<int32_t *>(ws + slab + ws_order_off(P));
+    // the problem list (candidate c, compute node i) -> c * N + i is never written out: the solver
+    // derives each workgroup's problem from its index.  device_ms brackets the solver kernel(s) only.
+    const CandidateGrid grid{n_candidates, d_edge_mult, d_src_cap};
+    rc = run_batch(g, P, nullptr, nullptr, nullptr, d_flow, opt, stream, stats_or_null ? d_pp : nullptr, d_order, &grid, ev0);
     if (rc != FC_OK) return done(rc);
     if (stats_or_null && hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
     hipLaunchKernelGGL(fc_verdict_kernel, dim3(unsigned(n_candidates)), dim3(256), 0, stream, g->N, g->d_compute_ids,
