@@ -89,6 +89,12 @@ typedef struct {
     int32_t src_cap_bound;         /* > 0: the caller promises k_j <= this for every problem of the call.
                                       If N * bound <= 65535 only the 16-bit-state kernel is launched;
                                       a problem that breaks the promise gets FC_FLOW_UNSUPPORTED        */
+    int32_t tree_certificate;      /* 1 = on, 2 = off (default off; fc_opt_throughput_search: default on).  At
+                                      upload every sink gets a spanning in-tree of first arcs; a problem in
+                                      which that tree alone can carry k units from every compute node within
+                                      the capacities U * b_e has F = N * k, the most s can emit, and is
+                                      answered from a per-sink ratio without running the solver (its
+                                      counters stay 0).  Exact; it only skips work.                      */
     int32_t schedule;              /* 1 = on (default), 2 = off: start the problems that look hardest (least
                                       slack in the sink's own cut) first, so the launch has no long tail */
 } fc_options;

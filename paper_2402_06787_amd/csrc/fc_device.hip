@@ -50,6 +50,7 @@ struct KParams {
     const uint16_t *label_hmax;  // [n] highest finite label of a compute node per sink
     const uint4 *p1;             // [n*n] first-pass entries per sink in level order, or null
     const uint16_t *level_off;   // [n*64] level boundaries in `order` per sink
+    const int32_t *tree_ratio;   // [n*2] per sink {num, den}: first-arc tree certificate, or null (off)
     const int32_t *sink, *U, *k;
     int32_t *flow_out;
     uint32_t *stats;             // [P * FC_NSTAT] or null
@@ -474,6 +475,19 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     } else if (small && p.arc_compact != nullptr) return;
     const int32_t NK = int32_t(NKll);
     const ArcCap arc_cap(U, NK);
+
+    // The first pass sends every compute node's k units down the sink's first-arc tree; the arc below
+    // vertex v then carries k * (compute nodes above it).  If even the most loaded arc, relative to
+    // its bandwidth, has room (k * num <= U * den), no arc saturates, all N * k units arrive, and
+    // that is the maximum the source can emit: the value is known without running the pass.
+    if (p.tree_ratio) {
+        const long long num = p.tree_ratio[2 * t], den = p.tree_ratio[2 * t + 1];
+        if ((long long)k * num <= (long long)U * den) {
+            if (tid == 0) { p.flow_out[j] = NK; p.sink_cost[t] = 1u; }
+            if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
+            return;
+        }
+    }
 
     const Carve cv = carve_lds(n, m0, COMPACT);
     State<COMPACT> st;
@@ -1011,7 +1025,7 @@ size_t lds_bytes(const fc_graph *g, bool compact) { return carve_lds(g->n, int32
 bool compact_ids_fit(const fc_graph *g) { return g->n <= 32767 && 2 * g->m0 <= 65535; }
 
 struct Resolved {
-    int32_t T, G, gr_steps, gr_relabels, gr_rises, tight_pct, use_gap, use_labels, force_wide, max_steps, src_cap_bound, schedule;
+    int32_t tree_certificate, T, G, gr_steps, gr_relabels, gr_rises, tight_pct, use_gap, use_labels, force_wide, max_steps, src_cap_bound, schedule;
 };
 
 int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
@@ -1041,6 +1055,8 @@ int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
     r->max_steps = o->max_level_steps > 0 ? o->max_level_steps : std::max<int32_t>(100000, 200 * g->n);
     if (o->src_cap_bound < 0) return FC_EINVAL;
     r->src_cap_bound = o->src_cap_bound;
+    if (o->tree_certificate < 0 || o->tree_certificate > 2) return FC_EINVAL;
+    r->tree_certificate = o->tree_certificate == 1;
     if (o->schedule < 0 || o->schedule > 2) return FC_EINVAL;
     r->schedule = o->schedule != 2;
     return FC_OK;
@@ -1109,6 +1125,7 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     kp.label_hmax = g->d_label_hmax;
     kp.p1 = opt.use_labels ? reinterpret_cast<const uint4 *>(g->d_p1) : nullptr;
     kp.level_off = g->d_level_off;
+    kp.tree_ratio = opt.tree_certificate && opt.use_labels ? g->d_tree_ratio : nullptr;
     kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.flow_out = d_flow; kp.stats = d_stats_pp;
     kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.gr_rises = opt.gr_rises; kp.tight_pct = opt.tight_pct; kp.in_bw = g->d_in_bw; kp.sink_cost = g->d_sink_cost; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
     kp.wide_available = wide_possible ? 1 : 0;
@@ -1216,9 +1233,9 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
         // entries in level order (n^2 x 16 bytes)
         if (n <= 8192) {
             const bool with_p1 = compact_ids_fit(g) && n <= 4096;
-            std::vector<uint16_t> labels, hmax, level_off; std::vector<uint32_t> p1;
+            std::vector<uint16_t> labels, hmax, level_off; std::vector<uint32_t> p1; std::vector<int32_t> tree_ratio;
             bool too_deep = false;
-            int rc2 = fc_host_sink_tables(g, with_p1, labels, hmax, p1, level_off, &too_deep);
+            int rc2 = fc_host_sink_tables(g, with_p1, labels, hmax, p1, level_off, tree_ratio, &too_deep);
             if (rc2 != FC_OK) return fail(rc2);
             if (hipMalloc(&g->d_labels, n * n * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
             if (hipMalloc(&g->d_label_hmax, n * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
@@ -1229,6 +1246,8 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
                 if (hipMalloc(&g->d_level_off, n * 64 * sizeof(uint16_t)) != hipSuccess) return fail(FC_EDEVICE);
                 if (hipMemcpy(g->d_p1, p1.data(), n * n * 16, hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
                 if (hipMemcpy(g->d_level_off, level_off.data(), n * 64 * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
+                if (hipMalloc(&g->d_tree_ratio, n * 2 * sizeof(int32_t)) != hipSuccess) return fail(FC_EDEVICE);
+                if (hipMemcpy(g->d_tree_ratio, tree_ratio.data(), n * 2 * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) return fail(FC_EDEVICE);
             }
         }
     } catch (const std::bad_alloc &) {
@@ -1248,6 +1267,7 @@ extern "C" int fc_graph_free(fc_graph *g) {
         if (g->d_compute_ids) (void)hipFree(g->d_compute_ids);
         if (g->d_in_bw) (void)hipFree(g->d_in_bw);
         if (g->d_sink_cost) (void)hipFree(g->d_sink_cost);
+        if (g->d_tree_ratio) (void)hipFree(g->d_tree_ratio);
         if (g->d_labels) (void)hipFree(g->d_labels);
         if (g->d_label_hmax) (void)hipFree(g->d_label_hmax);
         if (g->d_p1) (void)hipFree(g->d_p1);
@@ -1353,6 +1373,7 @@ int search_verdicts(void *vctx, int32_t n, const int32_t *U, const int32_t *k, u
     fc_options o; std::memset(&o, 0, sizeof o);
     if (c->opt) o = *c->opt;
     o.src_cap_bound = 0;
+    if (o.tree_certificate == 0) o.tree_certificate = 1;       // the search needs verdicts, not counters
     for (int32_t i = 0; i < n; ++i) o.src_cap_bound = std::max(o.src_cap_bound, k[i]);
     HIP_TRY(hipMemcpyAsync(c->d_U, U, sizeof(int32_t) * size_t(n), hipMemcpyHostToDevice, c->stream));
     HIP_TRY(hipMemcpyAsync(c->d_k, k, sizeof(int32_t) * size_t(n), hipMemcpyHostToDevice, c->stream));

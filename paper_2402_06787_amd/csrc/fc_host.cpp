@@ -109,6 +109,8 @@ int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const
 //                    the exact initial heights of push-relabel, when no flow has been pushed yet
 //   label_hmax[t]    largest finite label of a compute node (the first level to discharge)
 //   level_off[t][*]  [0] = deepest level L, [1 + j] = start of level L - j in p1[t], [1 + L] = end
+//   tree_ratio[t]    {num, den}: the largest ratio (compute nodes whose first-arc path runs through v) /
+//                    (bandwidth of v's first arc) over all v; den = 0 if a compute node cannot reach t
 //   p1[t][i]         4 words: the i-th vertex by decreasing label (ties by id) and the arc its excess is
 //                    sent along first -- {x, y} = that arc's 16-bit-layout record, z = vertex, w = 0
 // Any arc that leaves v and ends one level down is admissible for that first push.  Which one is
@@ -117,12 +119,12 @@ int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const
 // load(q) / downhill bandwidth of q) smallest, where weight = compute nodes in the subtree.
 int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &labels,
                         std::vector<uint16_t> &label_hmax, std::vector<uint32_t> &p1,
-                        std::vector<uint16_t> &level_off, bool *too_deep) {
+                        std::vector<uint16_t> &level_off, std::vector<int32_t> &tree_ratio, bool *too_deep) {
     const int32_t n = g->n;
     const int32_t MAXL = 62;
     try {
         labels.assign(size_t(n) * n, 0); label_hmax.assign(size_t(n), 0);
-        if (want_p1) { p1.assign(size_t(n) * n * 4, 0u); level_off.assign(size_t(n) * 64, 0); }
+        if (want_p1) { p1.assign(size_t(n) * n * 4, 0u); level_off.assign(size_t(n) * 64, 0); tree_ratio.assign(size_t(n) * 2, 0); }
         std::vector<int> deep(64, 0);
         unsigned hw = std::thread::hardware_concurrency();
         const int n_threads = int(std::max(1u, std::min(16u, hw ? hw : 1u)));
@@ -170,6 +172,10 @@ int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &
                     for (int32_t r = g->row_ptr[v]; r < g->row_ptr[v + 1]; ++r)
                         if (g->fwd[r] && dist[g->other[r]] + 1 == dist[v]) cap_down[v] += g->bw[r];
                 }
+                // largest (compute nodes below v) / (bandwidth of v's first arc) over the tree, as a fraction;
+                // 1/0 when some compute node cannot reach t at all
+                int64_t worst_num = 0, worst_den = 1;
+                for (int32_t v = 0; v < n; ++v) if (g->is_compute[v] && dist[v] >= n) { worst_num = 1; worst_den = 0; }
                 for (int32_t i = 0; i < lvl_start[0]; ++i) {             // order[] is by decreasing level
                     const int32_t v = order[i];
                     double best = 0; int32_t best_r = -1;
@@ -185,12 +191,14 @@ int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &
                     parent_rec[v] = best_r;                               // exists: v has a finite label >= 1
                     const int32_t q = g->other[best_r];
                     load[q] += wt[v]; wt[q] += wt[v];
+                    if (worst_den != 0 && wt[v] * worst_den > worst_num * int64_t(g->bw[best_r])) { worst_num = wt[v]; worst_den = g->bw[best_r]; }
                     uint32_t *en = &p1[(size_t(t) * n + size_t(i)) * 4];
                     en[0] = uint32_t(q) | (1u << 15) | (uint32_t(g->pair[best_r]) << 16);
                     en[1] = uint32_t(g->bw[best_r]);
                     en[2] = uint32_t(v);
                     en[3] = 0u;
                 }
+                tree_ratio[size_t(t) * 2] = int32_t(worst_num); tree_ratio[size_t(t) * 2 + 1] = int32_t(worst_den);
             }
         };
         std::vector<std::thread> pool;

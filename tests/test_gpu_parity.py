@@ -129,10 +129,53 @@ def test_option_matrix_same_values():
                      dict(threads_per_problem=256, lanes_per_vertex=16), dict(threads_per_problem=512, lanes_per_vertex=32),
                      dict(threads_per_problem=1024, lanes_per_vertex=64), dict(use_gap=2), dict(use_label_table=2),
                      dict(force_wide=1), dict(global_relabel_steps=1), dict(global_relabel_steps=100000, global_relabel_permille=1000000),
-                     dict(force_wide=1, use_gap=2, use_label_table=2, threads_per_problem=192, lanes_per_vertex=64)]:
+                     dict(force_wide=1, use_gap=2, use_label_table=2, threads_per_problem=192, lanes_per_vertex=64),
+                     dict(schedule=2), dict(tight_sink_percent=-1), dict(tight_sink_percent=100000),
+                     dict(global_relabel_rises=1), dict(global_relabel_rises=3, use_gap=2), dict(tree_certificate=1),
+                     dict(tree_certificate=1, force_wide=1)]:
             got, stats = _gpu_flows(g, sink, U, k, options=opts, want_stats=True)
             assert (got == want).all(), (opts, np.flatnonzero(got != want)[:5])
             assert stats["not_converged"] == 0
+
+
+# ------------------------------------------------------------------ the first-arc tree certificate and the launch order
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_tree_certificate_gives_the_same_flows(cfg):
+    topo = w.config_topology(cfg)
+    inv = _optimum(cfg, topo) if cfg in (2, 5) else None
+    pl = w.config_problems(cfg, topo, inv, extra_parity=True)
+    want = o.aux_maxflow_batch(topo, pl.sink, pl.edge_mult, pl.src_cap, threads=16)
+    with _upload(topo) as g:
+        got, stats = _gpu_flows(g, pl.sink, pl.edge_mult, pl.src_cap, options={"tree_certificate": 1}, want_stats=True)
+        plain, stats0 = _gpu_flows(g, pl.sink, pl.edge_mult, pl.src_cap, want_stats=True)
+        assert (got == want).all(), (cfg, np.flatnonzero(got != want)[:8])
+        assert (plain == want).all()
+        # a certified problem is not solved, so the counters can only shrink; every certified value is N * k
+        assert stats["pushes"] <= stats0["pushes"] and stats["level_steps"] <= stats0["level_steps"]
+        # very generous capacities: the tree carries everything for every sink
+        big = np.full(pl.n_problems, 1 << 20, dtype=np.int32)
+        got2, stats2 = _gpu_flows(g, pl.sink, big, pl.src_cap, options={"tree_certificate": 1}, want_stats=True)
+        assert (got2 == topo.n_compute * pl.src_cap.astype(np.int64)).all()
+        assert stats2["pushes"] == 0 and stats2["level_steps"] == 0
+
+
+def test_repeated_calls_reorder_but_do_not_change_values():
+    # every call leaves per-sink cost hints with the graph and the next call starts the expensive sinks first
+    topo = w.config_topology(5)
+    inv = _optimum(5, topo)
+    pl = w.config_problems(5, topo, inv)
+    want = o.aux_maxflow_batch(topo, pl.sink, pl.edge_mult, pl.src_cap, threads=16)
+    rng = np.random.default_rng(11)
+    with _upload(topo) as g:
+        for rep in range(3):
+            perm = rng.permutation(pl.n_problems)
+            got, _ = _gpu_flows(g, pl.sink[perm], pl.edge_mult[perm], pl.src_cap[perm])
+            assert (got == want[perm]).all(), rep
+        U, k = config_candidates(5, inv)
+        first = fc.fc_feasible(g, _dev(U), _dev(k), want_flows=True)["flows"].cpu().numpy()
+        again = fc.fc_feasible(g, _dev(U), _dev(k), want_flows=True, options={"schedule": 2})["flows"].cpu().numpy()
+        assert (first == again).all() and (first.reshape(-1) == want).all()
 
 
 # ------------------------------------------------------------------ edge cases of the boundary
