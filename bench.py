@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-certificate-leg", action="store_true",
+                    help="skip the side measurement with tree_certificate=1 (keeps profiler traces to one kind of launch)")
     ap.add_argument("--threads-per-problem", type=int, default=0)
     ap.add_argument("--lanes-per-vertex", type=int, default=0)
     ap.add_argument("--copy-probe", action="store_true",
@@ -116,6 +118,23 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     solves_per_s = P * args.steps / elapsed
 
+    # the same step with the optional first-arc tree certificate (problems whose sink tree carries
+    # all N*k units are answered without running the solver); reported beside the headline, never as it
+    elapsed_cert = None
+    if not args.no_certificate_leg:
+        opts_cert = dict(opts, tree_certificate=1)
+        for _ in range(args.warmup):
+            fc.fc_feasible(g, d_U, d_k, want_witness=True, d_workspace=ws, options=opts_cert)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fc.fc_feasible(g, d_U, d_k, want_witness=True, d_workspace=ws, options=opts_cert)
+        torch.cuda.synchronize()
+        elapsed_cert = time.perf_counter() - t0
+        for _ in range(3):                               # restore the cost hints the plain path leaves
+            step()
+        torch.cuda.synchronize()
+
     # the dominant kernel alone: HIP events recorded by the library on the launch stream around
     # the solver kernel, same inputs, same launch configuration
     kms, last = [], None
@@ -149,6 +168,9 @@ def main():
         "arc_scans_per_sec": st["arc_scans"] / (kernel_ms * 1e-3),
         "kernel_ms": kernel_ms,
         "per_launch": {k: int(v) for k, v in st.items() if k != "device_ms"},
+        "with_tree_certificate": None if elapsed_cert is None else
+            {"value": P * args.steps / elapsed_cert, "unit": "solves/s", "ms_per_step": elapsed_cert / args.steps * 1e3,
+             "note": "option tree_certificate=1; not the headline"},
         "search": {"inv_xstar": f"{inv[0]}/{inv[1]}", "U": str(search["U"]), "k": search["k"],
                    "rounds": search["rounds"], "candidates_tested": search["trace_len"], "wall_ms": search_ms},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

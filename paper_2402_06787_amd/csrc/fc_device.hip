@@ -445,7 +445,13 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n, m0 = p.m0;
     int32_t j, t, U, k;
     if (p.cand_C) {
-        const int32_t place = int32_t(blockIdx.x) / p.cand_C, c = int32_t(blockIdx.x) - place * p.cand_C;
+        // Workgroups go to the 8 XCDs (each with an L2 of its own) round-robin by index.  All candidates
+        // of one sink read that sink's tables, so they are given indices that are equal modulo 8:
+        // eight sinks are in flight side by side, one per XCD, each with its candidates one after another.
+        const int32_t xcd = int32_t(blockIdx.x) & 7, q = int32_t(blockIdx.x) >> 3;
+        const int32_t oct = q / p.cand_C, c = q - oct * p.cand_C;
+        const int32_t place = oct * 8 + xcd;
+        if (place >= p.N) return;                         // the last group of eight may be short
         const int32_t i = p.order ? p.order[place] : place;
         j = c * p.N + i; t = p.compute_ids[i]; U = p.cand_U[c]; k = p.cand_k[c];
     } else {
@@ -1146,12 +1152,14 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
         kp.order = d_order;
     }
     if (ev_solver_start) HIP_TRY(hipEventRecord(ev_solver_start, stream));    // after the ordering kernel
+    // grid: one workgroup per problem; the candidate grid is padded to whole groups of eight sinks
+    const long long grid_wgs = grid ? (long long)((g->N + 7) / 8) * 8 * grid->C : P;
     if (compact_possible) {
-        int rc = launch_g<true>(kp, P, opt.T, opt.G, lds_bytes(g, true), stream);
+        int rc = launch_g<true>(kp, grid_wgs, opt.T, opt.G, lds_bytes(g, true), stream);
         if (rc != FC_OK) return rc;
     }
     if (wide_possible) {
-        int rc = launch_g<false>(kp, P, opt.T, opt.G, lds_bytes(g, false), stream);
+        int rc = launch_g<false>(kp, grid_wgs, opt.T, opt.G, lds_bytes(g, false), stream);
         if (rc != FC_OK) return rc;
     }
     return FC_OK;
