@@ -7,4 +7,5 @@ from .reference import (Disconnected, build_c, maxflow, aux_network, aux_maxflow
                         aux_maxflow_batch, feasible, in_bandwidths,
                         min_compute_in_bandwidth, fraction_in_interval,
                         optimality_binary_search, smallest_U_k, brute_inv_xstar,
-                        brute_min_cut, brute_cut_condition)
+                        brute_min_cut, brute_cut_condition, aux_maxflow_batch_floor,
+                        fixed_k_feasible, fixed_k_binary_search, brute_fixed_k, links)

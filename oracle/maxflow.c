@@ -196,6 +196,7 @@ typedef struct {
     int32_t n_vertices; int64_t n_arcs;
     const int32_t *tail, *head, *bandwidth; const uint8_t *is_compute;
     const int32_t *sink; const int64_t *U, *k; int64_t *flow_out;
+    const int64_t *U_den;              /* null: U_j is an integer; else the multiplier is U_j / U_den_j, floored per arc */
     int64_t first, last; int32_t algo; int32_t n_compute;
 } batch_job_t;
 
@@ -211,6 +212,7 @@ static void *batch_worker(void *arg)
         int64_t p = 0;
         for (int64_t i = 0; i < job->n_arcs; ++i, ++p) {
             t2[p] = job->tail[i]; h2[p] = job->head[i]; c2[p] = job->U[j] * (int64_t)job->bandwidth[i];
+            if (job->U_den) c2[p] /= job->U_den[j];       /* nonnegative operands: C division is the floor */
         }
         for (int32_t v = 0; v < job->n_vertices; ++v)
             if (job->is_compute[v]) { t2[p] = s; h2[p] = v; c2[p] = job->k[j]; ++p; }
@@ -220,11 +222,11 @@ static void *batch_worker(void *arg)
     return NULL;
 }
 
-int32_t fco_aux_maxflow_batch(int32_t n_vertices, int64_t n_arcs, const int32_t *tail,
-                              const int32_t *head, const int32_t *bandwidth,
-                              const uint8_t *is_compute, int64_t n_problems, const int32_t *sink,
-                              const int64_t *U, const int64_t *k, int64_t *flow_out,
-                              int32_t algo, int32_t n_threads)
+static int32_t batch_run(int32_t n_vertices, int64_t n_arcs, const int32_t *tail,
+                         const int32_t *head, const int32_t *bandwidth,
+                         const uint8_t *is_compute, int64_t n_problems, const int32_t *sink,
+                         const int64_t *U, const int64_t *U_den, const int64_t *k, int64_t *flow_out,
+                         int32_t algo, int32_t n_threads)
 {
     if (n_threads < 1) n_threads = 1;
     if (n_threads > 256) n_threads = 256;
@@ -236,6 +238,7 @@ int32_t fco_aux_maxflow_batch(int32_t n_vertices, int64_t n_arcs, const int32_t 
         batch_job_t *jb = &jobs[t];
         jb->n_vertices = n_vertices; jb->n_arcs = n_arcs; jb->tail = tail; jb->head = head;
         jb->bandwidth = bandwidth; jb->is_compute = is_compute; jb->sink = sink; jb->U = U; jb->k = k;
+        jb->U_den = U_den;
         jb->flow_out = flow_out; jb->algo = algo; jb->n_compute = n_compute;
         jb->first = t * per < n_problems ? t * per : n_problems;
         jb->last = (t + 1) * per < n_problems ? (t + 1) * per : n_problems;
@@ -245,4 +248,28 @@ int32_t fco_aux_maxflow_batch(int32_t n_vertices, int64_t n_arcs, const int32_t 
         if (pthread_create(&th[t], NULL, batch_worker, &jobs[t]) != 0) return -1;
     for (int32_t t = 0; t < n_threads; ++t) pthread_join(th[t], NULL);
     return 0;
+}
+
+int32_t fco_aux_maxflow_batch(int32_t n_vertices, int64_t n_arcs, const int32_t *tail,
+                              const int32_t *head, const int32_t *bandwidth,
+                              const uint8_t *is_compute, int64_t n_problems, const int32_t *sink,
+                              const int64_t *U, const int64_t *k, int64_t *flow_out,
+                              int32_t algo, int32_t n_threads)
+{
+    return batch_run(n_vertices, n_arcs, tail, head, bandwidth, is_compute, n_problems, sink, U, NULL, k,
+                     flow_out, algo, n_threads);
+}
+
+/* The same batch on the network of the fixed-k test (Algorithm 3, Appendix E.4): a rational
+ * multiplier U_j = U_num_j / U_den_j and every topology arc e with capacity floor(U_j * b_e);
+ * source arcs k_j as before.  U_num_j * b_e must fit int64 (the caller checks). */
+int32_t fco_aux_maxflow_batch_floor(int32_t n_vertices, int64_t n_arcs, const int32_t *tail,
+                                    const int32_t *head, const int32_t *bandwidth,
+                                    const uint8_t *is_compute, int64_t n_problems, const int32_t *sink,
+                                    const int64_t *U_num, const int64_t *U_den, const int64_t *k,
+                                    int64_t *flow_out, int32_t algo, int32_t n_threads)
+{
+    for (int64_t j = 0; j < n_problems; ++j) if (U_den[j] < 1) return -1;
+    return batch_run(n_vertices, n_arcs, tail, head, bandwidth, is_compute, n_problems, sink, U_num, U_den, k,
+                     flow_out, algo, n_threads);
 }

@@ -13,6 +13,10 @@ the paper (ForestColl, arXiv 2402.06787):
   (`optimality_binary_search`), or by enumerating every cut of the bound (star) of
   Section 4 (`brute_inv_xstar`).
 * (U, k) by the gcd rule of Section 5.2 "Determine k" / Proposition 3 (`smallest_U_k`).
+* the fixed-k variant (Section 5.5, Appendix E.4): the verdict on the network with capacities
+  floor(U b_e) for a rational U (`fixed_k_feasible`), U* by Algorithm 3 taken literally in
+  exact rationals (`fixed_k_binary_search`), or by trying every fraction j / b_e
+  (`brute_fixed_k`).
 
 Readings of the paper taken here (each also listed in the design notes):
  - Algorithm 1 tests "max-flow is N x"; Theorem 1 says ">= N x".  They are the same
@@ -27,6 +31,9 @@ Readings of the paper taken here (each also listed in the design notes):
  - parallel arcs add up; self-loops and zero-bandwidth arcs carry nothing.
  - if some cut with compute nodes on both sides has no exiting bandwidth the bound
    is infinite (the paper assumes B^+(S) >= 1): `Disconnected` is raised.
+ - fixed k: "link e with bandwidth b_e" is one ordered vertex pair with the summed bandwidth of
+   its parallel arcs (`links`); floor(U b_e) is taken per link; max_e b_e (termination width and
+   denominator bound of Algorithm 3) is over links; the verdict is F >= N k as in Algorithm 1.
 """
 from __future__ import annotations
 
@@ -74,6 +81,10 @@ def _lib():
         lib.fco_aux_maxflow_batch.argtypes = [ctypes.c_int32, ctypes.c_int64, p32, p32, p32, pu8,
                                               ctypes.c_int64, p32, p64, p64, p64,
                                               ctypes.c_int32, ctypes.c_int32]
+        lib.fco_aux_maxflow_batch_floor.restype = ctypes.c_int32
+        lib.fco_aux_maxflow_batch_floor.argtypes = [ctypes.c_int32, ctypes.c_int64, p32, p32, p32, pu8,
+                                                    ctypes.c_int64, p32, p64, p64, p64, p64,
+                                                    ctypes.c_int32, ctypes.c_int32]
         _lib_handle = lib
     return _lib_handle
 
@@ -231,6 +242,113 @@ def smallest_U_k(inv_xstar: Fraction, bandwidths):
         if int(b) > 0:
             g = gcd(g, int(b))
     return Fraction(p, g), q // g
+
+
+# ------------------------------------------------------------------ fixed k (Section 5.5, Appendix E.4, Algorithm 3)
+
+def links(topo):
+    """The links of the topology: one per ordered vertex pair, its bandwidth the sum over the
+    listed arcs of that pair (an integer bandwidth stands for that many unit multi-edges,
+    Appendix E.1, so parallel arcs are one link); self-loops and zero bandwidths dropped.
+    Flooring is per link, so this has to happen before it."""
+    acc = {}
+    for t, h, b in zip(topo.tail.tolist(), topo.head.tolist(), topo.bandwidth.tolist()):
+        if t != h and b > 0:
+            acc[(t, h)] = acc.get((t, h), 0) + int(b)
+    keys = sorted(acc)
+    tail = np.array([t for t, _ in keys], dtype=np.int32)
+    head = np.array([h for _, h in keys], dtype=np.int32)
+    bw = np.array([acc[key] for key in keys], dtype=np.int32)
+    return tail, head, bw
+
+
+def aux_maxflow_batch_floor(topo, sink, U_num, U_den, k, algo="dinic", threads=1):
+    """F(s, sink_j) in the network of the fixed-k test: problem j has the rational
+    multiplier U_j = U_num_j / U_den_j, every link e gets capacity floor(U_j * b_e)
+    and every arc (s, c) capacity k_j.  int64 values."""
+    sink = np.ascontiguousarray(sink, dtype=np.int32)
+    U_num = np.ascontiguousarray(U_num, dtype=np.int64)
+    U_den = np.ascontiguousarray(U_den, dtype=np.int64)
+    k = np.ascontiguousarray(k, dtype=np.int64)
+    P = sink.shape[0]
+    assert U_num.shape[0] == P and U_den.shape[0] == P and k.shape[0] == P
+    if P == 0:
+        return np.zeros(0, dtype=np.int64)
+    if sink.min() < 0 or sink.max() >= topo.n_vertices or U_num.min() < 0 or U_den.min() < 1 or k.min() < 0:
+        raise ValueError("bad problem list")
+    max_b = int(topo.bandwidth.max()) if topo.n_arcs else 0
+    if int(U_num.max()) * max_b >= _I64_GUARD or int(k.max()) * topo.n_compute >= _I64_GUARD:
+        raise OverflowError("capacities exceed the int64 guard")
+    tail, head, bw = links(topo)
+    isc = np.ascontiguousarray(topo.is_compute, dtype=np.uint8)
+    out = np.full(P, -1, dtype=np.int64)
+    rc = _lib().fco_aux_maxflow_batch_floor(topo.n_vertices, tail.shape[0], _ptr(tail, ctypes.c_int32),
+                                            _ptr(head, ctypes.c_int32), _ptr(bw, ctypes.c_int32),
+                                            _ptr(isc, ctypes.c_uint8), P, _ptr(sink, ctypes.c_int32),
+                                            _ptr(U_num, ctypes.c_int64), _ptr(U_den, ctypes.c_int64),
+                                            _ptr(k, ctypes.c_int64), _ptr(out, ctypes.c_int64),
+                                            ALGO[algo], int(threads))
+    if rc != 0 or (out < 0).any():
+        raise RuntimeError("oracle batch failed")
+    return out
+
+
+def fixed_k_feasible(topo, U: Fraction, k, algo="dinic", threads=1):
+    """The test of Algorithm 3 (Theorems 11, 12 of Appendix E.4): with capacities floor(U b_e) and
+    source arcs k, is min over compute nodes v of F(s, v) >= N k?  Returns (verdict, flows)."""
+    U = Fraction(U)
+    comp = np.flatnonzero(topo.is_compute).astype(np.int32)
+    N = comp.shape[0]
+    flows = aux_maxflow_batch_floor(topo, comp, np.full(N, U.numerator, dtype=np.int64),
+                                    np.full(N, U.denominator, dtype=np.int64),
+                                    np.full(N, int(k), dtype=np.int64), algo, threads)
+    assert (flows <= N * int(k)).all(), "s cannot emit more than N*k"
+    return bool((flows >= N * int(k)).all()), flows
+
+
+def fixed_k_binary_search(topo, k, algo="dinic", threads=1, log=None):
+    """Algorithm 3 (Fixed-k Binary Search) in exact rationals.  Returns U* = 1/y*, the smallest U
+    for which k edge-disjoint out-trees per compute node exist in G({floor(U b_e)}); the
+    communication time is M/(N k) * U*.  `log`, if a list, receives (U, verdict) per test."""
+    N = topo.n_compute
+    k = int(k)
+    if N < 2 or k < 1:
+        raise ValueError("need at least two compute nodes and k >= 1")
+    B = min_compute_in_bandwidth(topo)
+    if B < 1 or not fixed_k_feasible(topo, Fraction((N - 1) * k), k, algo, threads)[0]:
+        raise Disconnected()
+    bmax = int(links(topo)[2].max())
+    l = Fraction((N - 1) * k, B)
+    r = Fraction((N - 1) * k, 1)
+    width = Fraction(1, bmax * bmax)
+    while r - l >= width:
+        mid = (l + r) / 2
+        ok, _ = fixed_k_feasible(topo, mid, k, algo, threads)
+        if log is not None:
+            log.append((mid, ok))
+        if ok:
+            r = mid
+        else:
+            l = mid
+    return fraction_in_interval(l, r, bmax)
+
+
+def brute_fixed_k(topo, k, algo="dinic"):
+    """U* for a fixed k without any search: at U* some U* b_e is an integer (else U* could be
+    lowered, Appendix E.4), so U* is the smallest feasible member of { j / b : b a link bandwidth,
+    j >= 1 } up to the upper end (N - 1) k of the paper's range.  Small graphs only."""
+    N = topo.n_compute
+    k = int(k)
+    top = (N - 1) * k
+    if not fixed_k_feasible(topo, Fraction(top), k, algo)[0]:
+        raise Disconnected()
+    bws = sorted(set(links(topo)[2].tolist()))
+    cands = sorted({Fraction(j, b) for b in bws for j in range(1, top * b + 1)})
+    assert len(cands) <= 200000
+    for U in cands:                                     # increasing: the first feasible one is U*
+        if fixed_k_feasible(topo, U, k, algo)[0]:
+            return U
+    raise AssertionError("the upper end of the range was feasible")
 
 
 # ------------------------------------------------------------------ brute force (tiny graphs only)

@@ -266,3 +266,81 @@ def test_planted_mistakes_are_caught():
     assert flow_with(lambda: (n, t, h, c_no_sink, s)) != 12               # dropped s->sink arc
     c_unscaled = [cc if tt == s else 2 * cc for tt, cc in zip(t, c)]
     assert flow_with(lambda: (n, t, h, c_unscaled, s)) != 12              # wrong capacity scaling
+
+
+# ---------------------------------------------------------------- fixed k (Section 5.5, Appendix E.4, Algorithm 3)
+
+@pytest.mark.parametrize("b", [1, 2, 3, 7])
+def test_fixed_k_on_the_paper_example(b):
+    # the worked example needs k = 1 trees per node at U = 1/b (Section 5.2 "Determine k"), so fixing
+    # k = 1 must give exactly that, and k = j must give j / b: U*/k cannot beat 1/x* = 1/b (Theorem 13's
+    # left side is the optimum) and j/b is feasible because every floor(j/b * b_e) = j * b_e / b is exact
+    topo = w.paper_example_switch(b)
+    for k in (1, 2, 5):
+        assert o.fixed_k_binary_search(topo, k) == Fraction(k, b)
+    assert o.fixed_k_feasible(topo, Fraction(1, b), 1)[0]
+    # just below 1/b the thin links floor to 0 and the boxes fall apart
+    assert not o.fixed_k_feasible(topo, Fraction(1, b) - Fraction(1, 1000), 1)[0]
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_fixed_k_search_equals_enumeration(seed):
+    # Algorithm 3 (bisection + the unique fraction with denominator <= max b) against trying every j / b_e
+    topo = w.random_tiny(seed, max_cap=5)
+    for k in (1, 2, 3):
+        try:
+            want = o.brute_fixed_k(topo, k, algo=ALGOS[seed % 2])
+        except o.Disconnected:
+            with pytest.raises(o.Disconnected):
+                o.fixed_k_binary_search(topo, k)
+            continue
+        got = o.fixed_k_binary_search(topo, k, algo=ALGOS[(seed + 1) % 2])
+        assert got == want, (seed, k)
+        assert got.denominator <= int(o.links(topo)[2].max())
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_fixed_k_bounds_and_multiples_of_the_optimal_k(seed):
+    topo = w.random_tiny(100 + seed, max_cap=6)
+    try:
+        inv = o.optimality_binary_search(topo)
+    except o.Disconnected:
+        return
+    bw = o.links(topo)[2]
+    U_opt, k_opt = o.smallest_U_k(inv, bw)
+    for k in (1, 2, 3, 4):
+        Us = o.fixed_k_binary_search(topo, k)
+        # optimality bound (star) from below, Theorem 13 from above
+        assert inv <= Us / k <= inv + Fraction(1, k * int(bw.min())), (seed, k)
+    # with k a multiple of Proposition 3's k the optimum is reached exactly: U = j U_opt makes every
+    # floor exact (U_opt b_e is an integer) and is feasible by Theorem 3
+    for j in (1, 2):
+        assert o.fixed_k_binary_search(topo, j * k_opt) == j * U_opt, seed
+
+
+def test_fixed_k_verdict_is_monotone_and_floors_per_link():
+    topo = w.config_topology(2)                          # has parallel arcs (links of capacity 2 emitted twice or more)
+    N = topo.n_compute
+    B = o.min_compute_in_bandwidth(topo)
+    Us = [Fraction((N - 1) * 2, B) + Fraction(j, 7) for j in range(0, 60, 3)]
+    verdicts = [o.fixed_k_feasible(topo, U, 2, threads=8)[0] for U in Us]
+    assert verdicts == sorted(verdicts)                  # Theorem 12: feasible iff U >= U*
+    # an integer multiplier floors nothing: same flows as the integer path
+    comp = topo.compute_nodes
+    a = o.aux_maxflow_batch(topo, comp, np.full(N, 3), np.full(N, 2))
+    b = o.aux_maxflow_batch_floor(topo, comp, np.full(N, 9), np.full(N, 3), np.full(N, 2))
+    assert (a == b).all()
+    # two parallel arcs of bandwidth 1 are one link of bandwidth 2: at U = 1/2 it carries floor(1) = 1, not 0 + 0
+    t2 = w.Topology("par", 2, np.array([0, 0, 1], dtype=np.int32), np.array([1, 1, 0], dtype=np.int32),
+                    np.array([1, 1, 2], dtype=np.int32), np.array([1, 1], dtype=np.uint8))
+    assert o.aux_maxflow_batch_floor(t2, [1], [1], [2], [1])[0] == 2      # k direct + 1 through the link
+    assert o.fixed_k_binary_search(t2, 1) == Fraction(1, 2)
+
+
+@pytest.mark.parametrize("n,c,k", [(4, 3, 1), (5, 2, 3), (6, 4, 2)])
+def test_fixed_k_textbook_shapes(n, c, k):
+    # complete digraph, every link c: a node's n-1 in-links carry floor(U c) each and must bring in (n-1) k
+    # (cut around one node), and floor(U c) = k on every link suffices by symmetry: U* = k / c
+    assert o.fixed_k_binary_search(w.complete_digraph(n, c), k) == Fraction(k, c)
+    # directed ring, every link c: the link into v carries the other n-1 nodes' k units: U* = (n-1) k / c
+    assert o.fixed_k_binary_search(w.directed_ring(n, c), k) == Fraction((n - 1) * k, c)
