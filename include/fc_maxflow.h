@@ -213,6 +213,42 @@ int fc_search_with_verdicts(int32_t n_compute, int64_t min_in_bw, int32_t gcd_bw
                             fc_rational *inv_xstar, fc_rational *U, int64_t *k,
                             int32_t *rounds_or_null);
 
+/* ------------------------------------------------------------------------------------------
+ * Fixed k (Section 5.5, Appendix E.4, Algorithm 3).  With k trees per compute node fixed, a real
+ * multiplier U is achievable iff  min over v in V_c of F(s, v) >= N * k  in the network whose
+ * topology arcs have capacity floor(U * b_e) and whose arcs (s, c) have capacity k (Theorems 11
+ * and 12); the communication time is M / (N k) * U.  A "link" e is one ordered vertex pair with the
+ * summed bandwidth of its parallel input arcs, as everywhere in this library; the floor is per link.
+ *
+ * fc_maxflow_batch_floor / fc_feasible_floor are fc_maxflow_batch / fc_feasible with the rational
+ * multiplier U_j = mult_num[j] / mult_den[j] (device int32 arrays; a problem or candidate with
+ * mult_den < 1 is malformed like one with mult_num < 1).  Everything else -- outputs, workspace
+ * sizes (the same *_workspace_bytes functions), stream and error behaviour -- is as above; the
+ * tree_certificate option has no effect here.
+ *
+ * fc_fixed_k_search: U* = 1 / y*, the smallest achievable U for this k, as a reduced fraction;
+ * its denominator is at most max_e b_e because some U* b_e is an integer.  Same search driver,
+ * trace arguments and errors as fc_opt_throughput_search (trace_num / trace_den hold the tested
+ * multipliers); FC_EOVERFLOW when (N - 1) * k * max_e b_e or N * k does not fit 31 bits.
+ * fc_fixed_k_search_with_verdicts is the host-only search logic: `verdicts(ctx, n, num, den, out)`
+ * must set out[i] = 1 iff num[i] / den[i] >= U*. */
+int fc_maxflow_batch_floor(const fc_graph *g, int64_t n_problems, const int32_t *d_sink,
+                           const int32_t *d_mult_num, const int32_t *d_mult_den, const int32_t *d_src_cap,
+                           int32_t *d_flow_out, void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                           const fc_options *options_or_null, fc_stats *stats_or_null);
+int fc_feasible_floor(const fc_graph *g, int32_t n_candidates, const int32_t *d_mult_num,
+                      const int32_t *d_mult_den, const int32_t *d_src_cap, uint8_t *d_feasible_out,
+                      int32_t *d_witness_sink_or_null, int32_t *d_flows_or_null, void *d_workspace,
+                      size_t workspace_bytes, void *hip_stream, const fc_options *options_or_null,
+                      fc_stats *stats_or_null);
+int fc_fixed_k_search(const fc_graph *g, int32_t k, int32_t candidates_per_round, fc_rational *U_star,
+                      int32_t *rounds_or_null, void *hip_stream, const fc_options *options_or_null,
+                      int32_t *trace_num, int32_t *trace_den, uint8_t *trace_verdict, int32_t trace_capacity,
+                      int32_t *trace_len_or_null);
+int fc_fixed_k_search_with_verdicts(int32_t n_compute, int64_t min_in_bw, int32_t max_bw, int32_t k,
+                                    int32_t candidates_per_round, fc_verdict_fn verdicts, void *ctx,
+                                    fc_rational *U_star, int32_t *rounds_or_null);
+
 const char *fc_strerror(int code);
 
 #ifdef __cplusplus

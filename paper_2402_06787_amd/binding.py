@@ -22,7 +22,8 @@ FC_EWORKSPACE, FC_EDEVICE, FC_ENOCONVERGE, FC_EUNSUPPORTED = -5, -6, -7, -8
 FC_FLOW_INVALID, FC_FLOW_NOCONVERGE, FC_FLOW_UNSUPPORTED = -1, -2, -3
 
 EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_free", "fc_graph_info", "fc_graph_csr",
-            "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_feasible_workspace_bytes",
+            "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_maxflow_batch_floor", "fc_feasible_workspace_bytes",
+            "fc_feasible_floor", "fc_fixed_k_search", "fc_fixed_k_search_with_verdicts",
             "fc_feasible", "fc_opt_throughput_search", "fc_search_with_verdicts", "fc_strerror"]
 
 
@@ -97,6 +98,16 @@ def load_library():
     lib.fc_search_with_verdicts.restype = c.c_int
     lib.fc_search_with_verdicts.argtypes = [i32, i64, i32, i32, VERDICT_FN, vp, c.POINTER(fc_rational),
                                             c.POINTER(fc_rational), c.POINTER(i64), c.POINTER(i32)]
+    lib.fc_maxflow_batch_floor.restype = c.c_int
+    lib.fc_maxflow_batch_floor.argtypes = [vp, i64, vp, vp, vp, vp, vp, vp, sz, vp, c.POINTER(fc_options), c.POINTER(fc_stats)]
+    lib.fc_feasible_floor.restype = c.c_int
+    lib.fc_feasible_floor.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp, c.POINTER(fc_options), c.POINTER(fc_stats)]
+    lib.fc_fixed_k_search.restype = c.c_int
+    lib.fc_fixed_k_search.argtypes = [vp, i32, i32, c.POINTER(fc_rational), c.POINTER(i32), vp, c.POINTER(fc_options),
+                                      vp, vp, vp, i32, c.POINTER(i32)]
+    lib.fc_fixed_k_search_with_verdicts.restype = c.c_int
+    lib.fc_fixed_k_search_with_verdicts.argtypes = [i32, i64, i32, i32, i32, VERDICT_FN, vp, c.POINTER(fc_rational),
+                                                    c.POINTER(i32)]
     lib.fc_strerror.restype = c.c_char_p
     lib.fc_strerror.argtypes = [c.c_int]
     _lib = lib
@@ -319,3 +330,93 @@ def fc_search_with_verdicts(n_compute: int, min_in_bw: int, gcd_bw: int, candida
     _check(rc, "fc_search_with_verdicts")
     return {"inv_xstar": Fraction(r1.num, r1.den), "U": Fraction(r2.num, r2.den), "k": int(kk.value),
             "rounds": int(rounds.value)}
+
+
+# ------------------------------------------------------------------ fixed k (rational multipliers, floor capacities)
+
+def fc_maxflow_batch_floor(g: Graph, d_sink, d_mult_num, d_mult_den, d_src_cap, d_flow_out=None, d_workspace=None,
+                           stream=None, options=None, want_stats=False):
+    """fc_maxflow_batch with the rational multiplier num/den per problem.  Returns (d_flow_out, stats or None)."""
+    import torch
+    P = int(d_sink.numel())
+    if d_flow_out is None:
+        d_flow_out = torch.empty(P, dtype=torch.int32, device=d_sink.device)
+    need = fc_maxflow_batch_workspace_bytes(g, P)
+    if d_workspace is None:
+        d_workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=d_sink.device)
+    st = fc_stats() if want_stats else None
+    rc = load_library().fc_maxflow_batch_floor(
+        g.handle, P, _dev_ptr(d_sink, torch.int32, P, "d_sink"), _dev_ptr(d_mult_num, torch.int32, P, "d_mult_num"),
+        _dev_ptr(d_mult_den, torch.int32, P, "d_mult_den"), _dev_ptr(d_src_cap, torch.int32, P, "d_src_cap"),
+        _dev_ptr(d_flow_out, torch.int32, P, "d_flow_out"), ctypes.c_void_p(d_workspace.data_ptr()), d_workspace.numel(),
+        _stream_ptr(stream), _opts(options), ctypes.byref(st) if st is not None else None)
+    _check(rc, "fc_maxflow_batch_floor")
+    return d_flow_out, (st.as_dict() if st is not None else None)
+
+
+def fc_feasible_floor(g: Graph, d_mult_num, d_mult_den, d_src_cap, want_flows=False, want_witness=True, d_workspace=None,
+                      stream=None, options=None, want_stats=False):
+    """fc_feasible with the rational multiplier num/den per candidate; same result dict."""
+    import torch
+    C = int(d_mult_num.numel())
+    dev = d_mult_num.device
+    N = fc_graph_info(g).n_compute
+    feas = torch.empty(C, dtype=torch.uint8, device=dev)
+    wit = torch.empty(C, dtype=torch.int32, device=dev) if want_witness else None
+    flows = torch.empty(C * N, dtype=torch.int32, device=dev) if want_flows else None
+    need = fc_feasible_workspace_bytes(g, C)
+    if d_workspace is None:
+        d_workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    st = fc_stats() if want_stats else None
+    rc = load_library().fc_feasible_floor(
+        g.handle, C, _dev_ptr(d_mult_num, torch.int32, C, "d_mult_num"), _dev_ptr(d_mult_den, torch.int32, C, "d_mult_den"),
+        _dev_ptr(d_src_cap, torch.int32, C, "d_src_cap"), _dev_ptr(feas, torch.uint8, C, "feasible"),
+        _dev_ptr(wit, torch.int32, C, "witness"), _dev_ptr(flows, torch.int32, C * N, "flows"),
+        ctypes.c_void_p(d_workspace.data_ptr()), d_workspace.numel(), _stream_ptr(stream), _opts(options),
+        ctypes.byref(st) if st is not None else None)
+    _check(rc, "fc_feasible_floor")
+    return {"feasible": feas, "witness": wit, "flows": flows.view(C, N) if flows is not None else None,
+            "stats": st.as_dict() if st is not None else None}
+
+
+def fc_fixed_k_search(g: Graph, k: int, candidates_per_round: int = 16, stream=None, options=None,
+                      trace_capacity: int = 4096):
+    """Returns dict(U_star=Fraction, rounds=int, trace=[(num, den, verdict), ...])."""
+    c = ctypes
+    r, rounds, tlen = fc_rational(), c.c_int32(), c.c_int32()
+    tn = np.zeros(trace_capacity, np.int32); td = np.zeros(trace_capacity, np.int32)
+    tv = np.zeros(trace_capacity, np.uint8)
+    rc = load_library().fc_fixed_k_search(
+        g.handle, int(k), int(candidates_per_round), c.byref(r), c.byref(rounds), _stream_ptr(stream), _opts(options),
+        _host_ptr(tn), _host_ptr(td), _host_ptr(tv), trace_capacity, c.byref(tlen))
+    _check(rc, "fc_fixed_k_search")
+    nt = min(tlen.value, trace_capacity)
+    return {"U_star": Fraction(r.num, r.den), "rounds": int(rounds.value),
+            "trace": [(int(tn[i]), int(td[i]), int(tv[i])) for i in range(nt)], "trace_len": int(tlen.value)}
+
+
+def fc_fixed_k_search_with_verdicts(n_compute: int, min_in_bw: int, max_bw: int, k: int, candidates_per_round: int,
+                                    verdict_fn):
+    """Host-only search logic of the fixed-k search.  `verdict_fn(list of (num, den))` returns 0/1 verdicts
+    (1 iff num/den >= U*); returns dict(U_star, rounds)."""
+    c = ctypes
+    err = []
+
+    def _cb(_ctx, n, pn, pd, pout):
+        try:
+            res = verdict_fn([(int(pn[i]), int(pd[i])) for i in range(n)])
+            for i in range(n):
+                pout[i] = 1 if res[i] else 0
+            return FC_OK
+        except Exception as exc:            # never let an exception cross the C boundary
+            err.append(exc)
+            return FC_EINVAL
+
+    cb = VERDICT_FN(_cb)
+    r, rounds = fc_rational(), c.c_int32()
+    rc = load_library().fc_fixed_k_search_with_verdicts(int(n_compute), int(min_in_bw), int(max_bw), int(k),
+                                                       int(candidates_per_round), cb, None, c.byref(r), c.byref(rounds))
+    if err:
+        raise err[0]
+    _check(rc, "fc_fixed_k_search_with_verdicts")
+    return {"U_star": Fraction(r.num, r.den), "rounds": int(rounds.value)}

@@ -52,6 +52,7 @@ struct KParams {
     const uint16_t *level_off;   // [n*64] level boundaries in `order` per sink
     const int32_t *tree_ratio;   // [n*2] per sink {num, den}: first-arc tree certificate, or null (off)
     const int32_t *sink, *U, *k;
+    const int32_t *Uden;         // rational multipliers U_j / Uden_j (kernels built for floor capacities), else null
     int32_t *flow_out;
     uint32_t *stats;             // [P * FC_NSTAT] or null
     int32_t gr_steps, gr_relabels, gr_rises, tight_pct, use_gap, max_steps;
@@ -61,7 +62,7 @@ struct KParams {
     // candidate x sink launches (fc_feasible): workgroup b solves candidate b % cand_C for the sink that
     // has place b / cand_C in the order; the problem list is never written out
     int32_t cand_C;              // 0: plain problem list
-    const int32_t *cand_U, *cand_k, *compute_ids;
+    const int32_t *cand_U, *cand_k, *cand_D, *compute_ids;
     uint32_t *sink_cost;         // [n] what the last problem of each sink cost (feeds the next launch's order)
 };
 
@@ -97,12 +98,32 @@ __device__ __forceinline__ ArcRec load_arc(const KParams &p, int32_t a) {
     return decode_arc<COMPACT>(load_arc_raw<COMPACT>(p, a));
 }
 
-// Capacity of a topology arc in one problem: U * b_e clamped at N * k (no flow needs more than s
-// can emit).  b_e > floor(N*k / U) is exactly the case U * b_e > N*k, so 32-bit arithmetic suffices.
+// Capacity of a topology arc in one problem, clamped at N * k (no flow needs more than s can emit).
+// Integer multiplier (Section 5.2, Appendix E.1): U * b_e; b_e > floor(N*k / U) is exactly the case
+// U * b_e > N*k, so 32-bit arithmetic suffices.  Rational multiplier U / D (fixed k, Section 5.5 /
+// Algorithm 3): floor(U * b_e / D); the quotient comes from a double-precision estimate corrected by
+// the exact remainder (the product is below N*k*D < 2^62 and the quotient below 2^31, so the
+// estimate is off by at most one).
+template <bool RAT>
 struct ArcCap {
-    int32_t U, NK, sat;
-    __device__ __forceinline__ ArcCap(int32_t U_, int32_t NK_) : U(U_), NK(NK_), sat(NK_ / U_) {}
-    __device__ __forceinline__ int32_t operator()(int32_t bw) const { return bw > sat ? NK : U * bw; }
+    int32_t U, NK, sat, D; double invD;
+    __device__ __forceinline__ ArcCap(int32_t U_, int32_t D_, int32_t NK_) : U(U_), NK(NK_), sat(0), D(D_), invD(1.0) {
+        if (!RAT) sat = NK_ / U_;
+        else {                               // floor(U b / D) >= N k  <=>  b >= ceil(N k D / U)
+            const long long lim = ((long long)NK_ * D_ + U_ - 1) / U_;
+            sat = lim - 1 > 0x7fffffffll ? 0x7fffffff : int32_t(lim - 1);
+            invD = 1.0 / double(D_);
+        }
+    }
+    __device__ __forceinline__ int32_t operator()(int32_t bw) const {
+        if (!RAT) return bw > sat ? NK : U * bw;
+        if (bw > sat) return NK;
+        const long long prod = (long long)U * (long long)bw;
+        long long q = (long long)(double(prod) * invD);
+        const long long r = prod - q * D;
+        if (r < 0) --q; else if (r >= D) ++q;
+        return int32_t(q);
+    }
 };
 
 // Workgroup barrier for code whose lanes communicate through LDS only: it waits for this wave's LDS
@@ -310,8 +331,8 @@ __device__ __forceinline__ int32_t rebuild_pending(const State<COMPACT> &st, int
 // p.gr_sub records, sized on the host so that at most 2n entries exist at a time), a group of
 // p.gr_lanes lanes takes K entries at a time and has the K record loads in flight before it looks
 // at the first.  A record carries a flag when it is the last of its row, so no row bounds are needed.
-template <bool COMPACT>
-__device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32_t t, const ArcCap &arc_cap,
+template <bool COMPACT, bool RAT>
+__device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32_t t, const ArcCap<RAT> &arc_cap,
                                uint32_t &gr_scans FC_GRDBG_PARAM) {
     using W = typename State<COMPACT>::W;
 #ifdef FC_GRDETAIL
@@ -437,13 +458,13 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
 // Group part: G lanes scan the residual row of one listed vertex in chunks, give all excess to the
 // first admissible arc when it suffices, else split it by a segmented prefix sum in row order, and
 // collect the smallest residual-neighbour height for the relabel in the same scan.
-template <bool COMPACT, int G>
+template <bool COMPACT, bool RAT, int G>
 __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) fc_push_relabel_kernel(KParams p) {
     using W = typename State<COMPACT>::W;
     constexpr int32_t NEWH = State<COMPACT>::NEWH;
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n, m0 = p.m0;
-    int32_t j, t, U, k;
+    int32_t j, t, U, k, D = 1;
     if (p.cand_C) {
         // Workgroups go to the 8 XCDs (each with an L2 of its own) round-robin by index.  All candidates
         // of one sink read that sink's tables, so they are given indices that are equal modulo 8:
@@ -454,14 +475,16 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
         if (place >= p.N) return;                         // the last group of eight may be short
         const int32_t i = p.order ? p.order[place] : place;
         j = c * p.N + i; t = p.compute_ids[i]; U = p.cand_U[c]; k = p.cand_k[c];
+        if (RAT) D = p.cand_D[c];
     } else {
         j = p.order ? p.order[blockIdx.x] : int32_t(blockIdx.x);
         t = p.sink[j]; U = p.U[j]; k = p.k[j];
+        if (RAT) D = p.Uden[j];
     }
 
     // ---- problem and its validity (uniform over the workgroup)
     const long long NKll = (long long)p.N * (long long)k;
-    const bool valid = t >= 0 && t < n && U >= 1 && k >= 1 && NKll < (1ll << 31);
+    const bool valid = t >= 0 && t < n && U >= 1 && k >= 1 && D >= 1 && NKll < (1ll << 31);
     if (!valid) {                       // both layouts write the same marker
         if (tid == 0) p.flow_out[j] = FC_FLOW_INVALID;
         if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
@@ -480,7 +503,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
         }
     } else if (small && p.arc_compact != nullptr) return;
     const int32_t NK = int32_t(NKll);
-    const ArcCap arc_cap(U, NK);
+    const ArcCap<RAT> arc_cap(U, D, NK);
 
     // The first pass sends every compute node's k units down the sink's first-arc tree; the arc below
     // vertex v then carries k * (compute nodes above it).  If even the most loaded arc, relative to
@@ -555,7 +578,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             }
         }
         if (!have_labels) {
-            global_relabel<COMPACT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG);
+            global_relabel<COMPACT, RAT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG);
             if (tid == 0) ++c_gr;
         }
     }
@@ -582,7 +605,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     // first pass: such problems get exact heights as soon as the working level first moves up
     int32_t rise_limit = p.gr_rises;
     if (p.tight_pct > 0) {
-        const long long have = (long long)U * (long long)p.in_bw[t] + (p.is_compute[t] ? k : 0);
+        const long long have = (long long)U * (long long)p.in_bw[t] / D + (p.is_compute[t] ? k : 0);
         if (have * 100ll < NKll * (long long)p.tight_pct) rise_limit = 1;
     }
     bool failed = false;
@@ -796,7 +819,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             cur ^= 1;
         }
         if (!fast && rel_since > 0 && (rel_since >= p.gr_relabels || steps_since >= p.gr_steps || rises >= rise_limit) && d >= 1) {
-            global_relabel<COMPACT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG);
+            global_relabel<COMPACT, RAT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG);
             if (tid == 0) ++c_gr;
             rel_since = 0; steps_since = 0; rises = 0;
             d = rebuild_pending(st, n, t, cur ^ 1);
@@ -901,8 +924,10 @@ __device__ __forceinline__ void order_bucket_bases(const int32_t *hist, int32_t 
 __global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, int32_t N, const int32_t *sink,
                                                         const int32_t *U, const int32_t *k, const int32_t *in_bw,
                                                         const uint8_t *is_compute, const uint32_t *sink_cost,
-                                                        int32_t *order) {
+                                                        int32_t *order, const int32_t *Uden) {
     constexpr int NB = FC_ORDER_BUCKETS, R = 8;
+    // a rational multiplier U / Uden only enters the guess for sinks without history: its integer part will do
+    auto mult = [&](long long jj) { const int32_t u = U[jj]; if (!Uden) return u; const int32_t dd = Uden[jj]; return dd >= 1 && u >= dd ? u / dd : (u >= 1 && dd >= 1 ? 1 : 0); };
     __shared__ int32_t hist[NB], base[NB];
     const int32_t tid = threadIdx.x, T = blockDim.x;
     for (int32_t b = tid; b < NB; b += T) hist[b] = 0;
@@ -913,7 +938,7 @@ __global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, 
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const long long jj = j0 + (long long)r * T + tid;
-            b[r] = jj < P ? order_bucket(sink[jj], U[jj], k[jj], n, N, in_bw, is_compute, sink_cost) : -1;
+            b[r] = jj < P ? order_bucket(sink[jj], mult(jj), k[jj], n, N, in_bw, is_compute, sink_cost) : -1;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) (void)wave_bucket_add(hist, b[r], b[r] >= 0);
@@ -926,7 +951,7 @@ __global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, 
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const long long jj = j0 + (long long)r * T + tid;
-            b[r] = jj < P ? order_bucket(sink[jj], U[jj], k[jj], n, N, in_bw, is_compute, sink_cost) : -1;
+            b[r] = jj < P ? order_bucket(sink[jj], mult(jj), k[jj], n, N, in_bw, is_compute, sink_cost) : -1;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -945,13 +970,14 @@ __global__ void __launch_bounds__(1024) fc_order_sinks_kernel(int32_t N, int32_t
                                                               const int32_t *__restrict__ in_bw,
                                                               const uint8_t *__restrict__ is_compute,
                                                               const uint32_t *__restrict__ sink_cost,
-                                                              int32_t *__restrict__ order) {
+                                                              int32_t *__restrict__ order, const int32_t *__restrict__ cD) {
     constexpr int NB = FC_ORDER_BUCKETS, R = 4;
     __shared__ int32_t hist[NB], base[NB];
     const int32_t tid = threadIdx.x, T = blockDim.x;
     for (int32_t b = tid; b < NB; b += T) hist[b] = 0;
     __syncthreads();
-    const int32_t u0 = cU[0], k0 = ck[0];
+    const int32_t d0 = cD ? cD[0] : 1, k0 = ck[0];
+    const int32_t u0 = d0 >= 1 && cU[0] >= d0 ? cU[0] / d0 : (cU[0] >= 1 && d0 >= 1 ? 1 : 0);
     for (int32_t i0 = 0; i0 < N; i0 += R * T) {
         int32_t b[R];
 #pragma unroll
@@ -982,15 +1008,15 @@ __global__ void __launch_bounds__(1024) fc_order_sinks_kernel(int32_t N, int32_t
 
 // feasible_c = AND over sinks of [F(s, v) >= N * k_c] (Theorem 1 / Theorem 3); one workgroup per candidate
 __global__ void __launch_bounds__(256) fc_verdict_kernel(int32_t N, const int32_t *compute_ids, const int32_t *ck,
-                                                         const int32_t *cU, const int32_t *flows, uint8_t *feasible,
-                                                         int32_t *witness) {
+                                                         const int32_t *cU, const int32_t *cD, const int32_t *flows,
+                                                         uint8_t *feasible, int32_t *witness) {
     __shared__ int32_t s_wit;
     const int32_t c = blockIdx.x, tid = threadIdx.x;
     if (tid == 0) s_wit = 0x7fffffff;
     __syncthreads();
     const int32_t k = ck[c], U = cU[c];
     const long long need = (long long)N * (long long)k;
-    const bool ok_cand = U >= 1 && k >= 1 && need < (1ll << 31);
+    const bool ok_cand = U >= 1 && k >= 1 && (!cD || cD[c] >= 1) && need < (1ll << 31);
     int32_t best = 0x7fffffff;
     for (int32_t s = tid; s < N; s += blockDim.x) {
         int32_t fl = flows[size_t(c) * size_t(N) + size_t(s)];
@@ -1068,9 +1094,9 @@ int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
     return FC_OK;
 }
 
-template <bool COMPACT, int G>
+template <bool COMPACT, bool RAT, int G>
 int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_t stream) {
-    auto kern = fc_push_relabel_kernel<COMPACT, G>;
+    auto kern = fc_push_relabel_kernel<COMPACT, RAT, G>;
     if (const char *pad = getenv("FC_LDS_PAD")) lds += size_t(atol(pad));     // tuning aid: occupancy experiments
     static size_t lds_allowed = 0;                  // per instantiation; raised on demand
     if (lds > lds_allowed) {
@@ -1082,14 +1108,14 @@ int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_
     return FC_OK;
 }
 
-template <bool COMPACT>
+template <bool COMPACT, bool RAT>
 int launch_g(const KParams &kp, long long P, int32_t T, int32_t G, size_t lds, hipStream_t stream) {
     switch (G) {
-        case 4: return launch_one<COMPACT, 4>(kp, P, T, lds, stream);
-        case 8: return launch_one<COMPACT, 8>(kp, P, T, lds, stream);
-        case 16: return launch_one<COMPACT, 16>(kp, P, T, lds, stream);
-        case 32: return launch_one<COMPACT, 32>(kp, P, T, lds, stream);
-        case 64: return launch_one<COMPACT, 64>(kp, P, T, lds, stream);
+        case 4: return launch_one<COMPACT, RAT, 4>(kp, P, T, lds, stream);
+        case 8: return launch_one<COMPACT, RAT, 8>(kp, P, T, lds, stream);
+        case 16: return launch_one<COMPACT, RAT, 16>(kp, P, T, lds, stream);
+        case 32: return launch_one<COMPACT, RAT, 32>(kp, P, T, lds, stream);
+        case 64: return launch_one<COMPACT, RAT, 64>(kp, P, T, lds, stream);
     }
     return FC_EINVAL;
 }
@@ -1098,14 +1124,15 @@ struct StatsScratch { uint32_t *per_problem; unsigned long long *totals; };
 
 // small launches fit the machine at once: order is moot
 // problems given as candidates x compute nodes (problem c * N + i) instead of a list
-struct CandidateGrid { int32_t C; const int32_t *d_U, *d_k; };
+struct CandidateGrid { int32_t C; const int32_t *d_U, *d_k, *d_D; };    // d_D: denominators of rational multipliers, or null
 
 bool wants_order(const fc_graph *g, const Resolved &opt, long long P) { return opt.schedule && P > 2ll * g->n_cu; }
 
 // Launch the solver kernels for P problems.  stats_ws: null, or room for P*FC_NSTAT u32 + FC_NSTAT u64.
 int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32_t *d_U, const int32_t *d_k,
               int32_t *d_flow, const Resolved &opt, hipStream_t stream, uint32_t *d_stats_pp, int32_t *d_order,
-              const CandidateGrid *grid = nullptr, hipEvent_t ev_solver_start = nullptr) {
+              const CandidateGrid *grid = nullptr, hipEvent_t ev_solver_start = nullptr, const int32_t *d_Uden = nullptr) {
+    const bool rational = grid ? grid->d_D != nullptr : d_Uden != nullptr;
     if (P > (1ll << 30)) return FC_EINVAL;
     KParams kp;
     kp.n = g->n; kp.N = g->N; kp.m0 = int32_t(g->m0);
@@ -1131,23 +1158,23 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     kp.label_hmax = g->d_label_hmax;
     kp.p1 = opt.use_labels ? reinterpret_cast<const uint4 *>(g->d_p1) : nullptr;
     kp.level_off = g->d_level_off;
-    kp.tree_ratio = opt.tree_certificate && opt.use_labels ? g->d_tree_ratio : nullptr;
-    kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.flow_out = d_flow; kp.stats = d_stats_pp;
+    kp.tree_ratio = opt.tree_certificate && opt.use_labels && !rational ? g->d_tree_ratio : nullptr;   // the certificate's ratio test needs exact capacities U * b
+    kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.Uden = d_Uden; kp.flow_out = d_flow; kp.stats = d_stats_pp;
     kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.gr_rises = opt.gr_rises; kp.tight_pct = opt.tight_pct; kp.in_bw = g->d_in_bw; kp.sink_cost = g->d_sink_cost; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
     kp.wide_available = wide_possible ? 1 : 0;
     kp.order = nullptr;
-    kp.cand_C = 0; kp.cand_U = kp.cand_k = nullptr; kp.compute_ids = g->d_compute_ids;
+    kp.cand_C = 0; kp.cand_U = kp.cand_k = kp.cand_D = nullptr; kp.compute_ids = g->d_compute_ids;
     if (grid) {
-        kp.cand_C = grid->C; kp.cand_U = grid->d_U; kp.cand_k = grid->d_k;
+        kp.cand_C = grid->C; kp.cand_U = grid->d_U; kp.cand_k = grid->d_k; kp.cand_D = grid->d_D;
         if (wants_order(g, opt, P)) {
             hipLaunchKernelGGL(fc_order_sinks_kernel, dim3(1), dim3(1024), 0, stream, g->N, g->n, g->d_compute_ids,
-                               grid->d_U, grid->d_k, g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order);
+                               grid->d_U, grid->d_k, g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, grid->d_D);
             HIP_TRY(hipGetLastError());
             kp.order = d_order;
         }
     } else if (wants_order(g, opt, P)) {
         hipLaunchKernelGGL(fc_order_kernel, dim3(1), dim3(1024), 0, stream, P, g->n, g->N, d_sink, d_U, d_k,
-                           g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order);
+                           g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, d_Uden);
         HIP_TRY(hipGetLastError());
         kp.order = d_order;
     }
@@ -1155,11 +1182,13 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     // grid: one workgroup per problem; the candidate grid is padded to whole groups of eight sinks
     const long long grid_wgs = grid ? (long long)((g->N + 7) / 8) * 8 * grid->C : P;
     if (compact_possible) {
-        int rc = launch_g<true>(kp, grid_wgs, opt.T, opt.G, lds_bytes(g, true), stream);
+        int rc = rational ? launch_g<true, true>(kp, grid_wgs, opt.T, opt.G, lds_bytes(g, true), stream)
+                          : launch_g<true, false>(kp, grid_wgs, opt.T, opt.G, lds_bytes(g, true), stream);
         if (rc != FC_OK) return rc;
     }
     if (wide_possible) {
-        int rc = launch_g<false>(kp, grid_wgs, opt.T, opt.G, lds_bytes(g, false), stream);
+        int rc = rational ? launch_g<false, true>(kp, grid_wgs, opt.T, opt.G, lds_bytes(g, false), stream)
+                          : launch_g<false, false>(kp, grid_wgs, opt.T, opt.G, lds_bytes(g, false), stream);
         if (rc != FC_OK) return rc;
     }
     return FC_OK;
@@ -1290,10 +1319,11 @@ extern "C" size_t fc_maxflow_batch_workspace_bytes(const fc_graph *g, int64_t n_
     return stats_bytes(n_problems);
 }
 
-extern "C" int fc_maxflow_batch(const fc_graph *g, int64_t n_problems, const int32_t *d_sink,
-                                const int32_t *d_edge_mult, const int32_t *d_src_cap, int32_t *d_flow_out,
-                                void *d_workspace, size_t workspace_bytes, void *hip_stream,
-                                const fc_options *options_or_null, fc_stats *stats_or_null) {
+namespace {
+int maxflow_batch_impl(const fc_graph *g, int64_t n_problems, const int32_t *d_sink,
+                       const int32_t *d_edge_mult, const int32_t *d_mult_den, const int32_t *d_src_cap, int32_t *d_flow_out,
+                       void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                       const fc_options *options_or_null, fc_stats *stats_or_null) {
     if (!g || n_problems < 0) return FC_EINVAL;
     if (!g->on_device) return FC_EDEVICE;
     Resolved opt;
@@ -1306,18 +1336,36 @@ extern "C" int fc_maxflow_batch(const fc_graph *g, int64_t n_problems, const int
     uint32_t *d_pp = reinterpret_cast<uint32_t *>(d_workspace);
     unsigned long long *d_tot = reinterpret_cast<unsigned long long *>(reinterpret_cast<unsigned char *>(d_workspace) + align_up(size_t(n_problems) * FC_NSTAT * 4, 256));
     int32_t *d_order = reinterpret_cast<int32_t *>(reinterpret_cast<unsigned char *>(d_workspace) + ws_order_off(n_problems));
-    if (!stats_or_null) return run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, nullptr, d_order);
+    if (!stats_or_null) return run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, nullptr, d_order, nullptr, nullptr, d_mult_den);
 
     hipEvent_t ev0, ev1;
     HIP_TRY(hipEventCreate(&ev0));
     if (hipEventCreate(&ev1) != hipSuccess) { (void)hipEventDestroy(ev0); return FC_EDEVICE; }
     auto done = [&](int code) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); return code; };
-    rc = run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, d_pp, d_order, nullptr, ev0);
+    rc = run_batch(g, n_problems, d_sink, d_edge_mult, d_src_cap, d_flow_out, opt, stream, d_pp, d_order, nullptr, ev0, d_mult_den);
     if (rc != FC_OK) return done(rc);
     if (hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
     rc = fill_stats(n_problems, d_pp, d_tot, stream, ev0, ev1, stats_or_null);
     if (rc != FC_OK) return done(rc);
     return done(stats_or_null->not_converged ? FC_ENOCONVERGE : FC_OK);
+}
+}  // namespace
+
+extern "C" int fc_maxflow_batch(const fc_graph *g, int64_t n_problems, const int32_t *d_sink,
+                                const int32_t *d_edge_mult, const int32_t *d_src_cap, int32_t *d_flow_out,
+                                void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                                const fc_options *options_or_null, fc_stats *stats_or_null) {
+    return maxflow_batch_impl(g, n_problems, d_sink, d_edge_mult, nullptr, d_src_cap, d_flow_out, d_workspace,
+                              workspace_bytes, hip_stream, options_or_null, stats_or_null);
+}
+
+extern "C" int fc_maxflow_batch_floor(const fc_graph *g, int64_t n_problems, const int32_t *d_sink,
+                                      const int32_t *d_mult_num, const int32_t *d_mult_den, const int32_t *d_src_cap,
+                                      int32_t *d_flow_out, void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                                      const fc_options *options_or_null, fc_stats *stats_or_null) {
+    if (n_problems > 0 && !d_mult_den) return FC_EINVAL;
+    return maxflow_batch_impl(g, n_problems, d_sink, d_mult_num, d_mult_den, d_src_cap, d_flow_out, d_workspace,
+                              workspace_bytes, hip_stream, options_or_null, stats_or_null);
 }
 
 extern "C" size_t fc_feasible_workspace_bytes(const fc_graph *g, int32_t n_candidates) {
@@ -1326,7 +1374,8 @@ extern "C" size_t fc_feasible_workspace_bytes(const fc_graph *g, int32_t n_candi
     return align_up(P * 4, 256) + stats_bytes((long long)P);
 }
 
-extern "C" int fc_feasible(const fc_graph *g, int32_t n_candidates, const int32_t *d_edge_mult,
+namespace {
+int feasible_impl(const fc_graph *g, int32_t n_candidates, const int32_t *d_edge_mult, const int32_t *d_mult_den,
                            const int32_t *d_src_cap, uint8_t *d_feasible_out, int32_t *d_witness_sink_or_null,
                            int32_t *d_flows_or_null, void *d_workspace, size_t workspace_bytes,
                            void *hip_stream, const fc_options *options_or_null, fc_stats *stats_or_null) {
@@ -1356,17 +1405,36 @@ extern "C" int fc_feasible(const fc_graph *g, int32_t n_candidates, const int32_
     int32_t *d_order = reinterpret_cast<int32_t *>(ws + slab + ws_order_off(P));
     // the problem list (candidate c, compute node i) -> c * N + i is never written out: the solver
     // derives each workgroup's problem from its index.  device_ms brackets the solver kernel(s) only.
-    const CandidateGrid grid{n_candidates, d_edge_mult, d_src_cap};
+    const CandidateGrid grid{n_candidates, d_edge_mult, d_src_cap, d_mult_den};
     rc = run_batch(g, P, nullptr, nullptr, nullptr, d_flow, opt, stream, stats_or_null ? d_pp : nullptr, d_order, &grid, ev0);
     if (rc != FC_OK) return done(rc);
     if (stats_or_null && hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
     hipLaunchKernelGGL(fc_verdict_kernel, dim3(unsigned(n_candidates)), dim3(256), 0, stream, g->N, g->d_compute_ids,
-                       d_src_cap, d_edge_mult, d_flow, d_feasible_out, d_witness_sink_or_null);
+                       d_src_cap, d_edge_mult, d_mult_den, d_flow, d_feasible_out, d_witness_sink_or_null);
     if (hipGetLastError() != hipSuccess) return done(FC_EDEVICE);
     if (!stats_or_null) return done(FC_OK);
     rc = fill_stats(P, d_pp, d_tot, stream, ev0, ev1, stats_or_null);
     if (rc != FC_OK) return done(rc);
     return done(stats_or_null->not_converged ? FC_ENOCONVERGE : FC_OK);
+}
+}  // namespace
+
+extern "C" int fc_feasible(const fc_graph *g, int32_t n_candidates, const int32_t *d_edge_mult,
+                           const int32_t *d_src_cap, uint8_t *d_feasible_out, int32_t *d_witness_sink_or_null,
+                           int32_t *d_flows_or_null, void *d_workspace, size_t workspace_bytes,
+                           void *hip_stream, const fc_options *options_or_null, fc_stats *stats_or_null) {
+    return feasible_impl(g, n_candidates, d_edge_mult, nullptr, d_src_cap, d_feasible_out, d_witness_sink_or_null,
+                         d_flows_or_null, d_workspace, workspace_bytes, hip_stream, options_or_null, stats_or_null);
+}
+
+extern "C" int fc_feasible_floor(const fc_graph *g, int32_t n_candidates, const int32_t *d_mult_num,
+                                 const int32_t *d_mult_den, const int32_t *d_src_cap, uint8_t *d_feasible_out,
+                                 int32_t *d_witness_sink_or_null, int32_t *d_flows_or_null, void *d_workspace,
+                                 size_t workspace_bytes, void *hip_stream, const fc_options *options_or_null,
+                                 fc_stats *stats_or_null) {
+    if (n_candidates > 0 && !d_mult_den) return FC_EINVAL;
+    return feasible_impl(g, n_candidates, d_mult_num, d_mult_den, d_src_cap, d_feasible_out, d_witness_sink_or_null,
+                         d_flows_or_null, d_workspace, workspace_bytes, hip_stream, options_or_null, stats_or_null);
 }
 
 namespace {
@@ -1374,6 +1442,7 @@ struct SearchCtx {
     const fc_graph *g; hipStream_t stream; const fc_options *opt;
     int32_t *d_U, *d_k; uint8_t *d_v; void *d_ws; size_t ws_bytes; int32_t cap;
     int32_t *tU, *tk; uint8_t *tv; int32_t tcap; int32_t tlen;
+    int32_t fixed_k;                   // > 0: candidates are rational multipliers num / den tested with this k
 };
 int search_verdicts(void *vctx, int32_t n, const int32_t *U, const int32_t *k, uint8_t *out) {
     SearchCtx *c = static_cast<SearchCtx *>(vctx);
@@ -1382,10 +1451,20 @@ int search_verdicts(void *vctx, int32_t n, const int32_t *U, const int32_t *k, u
     if (c->opt) o = *c->opt;
     o.src_cap_bound = 0;
     if (o.tree_certificate == 0) o.tree_certificate = 1;       // the search needs verdicts, not counters
-    for (int32_t i = 0; i < n; ++i) o.src_cap_bound = std::max(o.src_cap_bound, k[i]);
+    int rc;
     HIP_TRY(hipMemcpyAsync(c->d_U, U, sizeof(int32_t) * size_t(n), hipMemcpyHostToDevice, c->stream));
     HIP_TRY(hipMemcpyAsync(c->d_k, k, sizeof(int32_t) * size_t(n), hipMemcpyHostToDevice, c->stream));
-    int rc = fc_feasible(c->g, n, c->d_U, c->d_k, c->d_v, nullptr, nullptr, c->d_ws, c->ws_bytes, c->stream, &o, nullptr);
+    if (c->fixed_k > 0) {              // k[] holds the denominators; the source arcs are the fixed k
+        o.src_cap_bound = c->fixed_k;
+        std::vector<int32_t> kk(size_t(n), c->fixed_k);
+        int32_t *d_fixed = c->d_U + c->cap;
+        HIP_TRY(hipMemcpyAsync(d_fixed, kk.data(), sizeof(int32_t) * size_t(n), hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(hipStreamSynchronize(c->stream));               // kk goes out of scope
+        rc = fc_feasible_floor(c->g, n, c->d_U, c->d_k, d_fixed, c->d_v, nullptr, nullptr, c->d_ws, c->ws_bytes, c->stream, &o, nullptr);
+    } else {
+        for (int32_t i = 0; i < n; ++i) o.src_cap_bound = std::max(o.src_cap_bound, k[i]);
+        rc = fc_feasible(c->g, n, c->d_U, c->d_k, c->d_v, nullptr, nullptr, c->d_ws, c->ws_bytes, c->stream, &o, nullptr);
+    }
     if (rc != FC_OK) return rc;
     HIP_TRY(hipMemcpyAsync(out, c->d_v, size_t(n), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
@@ -1419,13 +1498,43 @@ extern "C" int fc_opt_throughput_search(const fc_graph *g, int32_t candidates_pe
         if (c.d_U) (void)hipFree(c.d_U); if (c.d_k) (void)hipFree(c.d_k);
         if (c.d_v) (void)hipFree(c.d_v); if (c.d_ws) (void)hipFree(c.d_ws);
     };
-    if (hipMalloc(&c.d_U, sizeof(int32_t) * size_t(c.cap)) != hipSuccess || hipMalloc(&c.d_k, sizeof(int32_t) * size_t(c.cap)) != hipSuccess ||
+    if (hipMalloc(&c.d_U, sizeof(int32_t) * 2 * size_t(c.cap)) != hipSuccess || hipMalloc(&c.d_k, sizeof(int32_t) * size_t(c.cap)) != hipSuccess ||
         hipMalloc(&c.d_v, size_t(c.cap)) != hipSuccess || hipMalloc(&c.d_ws, c.ws_bytes) != hipSuccess) { cleanup(); return FC_EDEVICE; }
     fc_rational r1, r2; int64_t kk = 0; int32_t rounds = 0;
     rc = fc_search_with_verdicts(g->N, g->min_in_bw, g->gcd_bw, candidates_per_round, search_verdicts, &c, &r1, &r2, &kk, &rounds);
     cleanup();
     if (rc != FC_OK) return rc;
     *inv_xstar = r1; *U = r2; *k = kk;
+    if (rounds_or_null) *rounds_or_null = rounds;
+    if (trace_len_or_null) *trace_len_or_null = c.tlen;
+    return FC_OK;
+}
+
+extern "C" int fc_fixed_k_search(const fc_graph *g, int32_t k, int32_t candidates_per_round, fc_rational *U_star,
+                                 int32_t *rounds_or_null, void *hip_stream, const fc_options *options_or_null,
+                                 int32_t *trace_num, int32_t *trace_den, uint8_t *trace_verdict, int32_t trace_capacity,
+                                 int32_t *trace_len_or_null) {
+    if (!g || !U_star || k < 1 || candidates_per_round < 1 || candidates_per_round > 4096 || trace_capacity < 0) return FC_EINVAL;
+    if (!g->on_device) return FC_EDEVICE;
+    Resolved opt;
+    int rc = resolve_options(g, options_or_null, &opt);
+    if (rc != FC_OK) return rc;
+    SearchCtx c; std::memset(&c, 0, sizeof c);
+    c.g = g; c.stream = reinterpret_cast<hipStream_t>(hip_stream); c.opt = options_or_null; c.fixed_k = k;
+    c.cap = std::max<int32_t>(candidates_per_round, 2);
+    c.tU = trace_num; c.tk = trace_den; c.tv = trace_verdict; c.tcap = trace_capacity; c.tlen = 0;
+    c.ws_bytes = fc_feasible_workspace_bytes(g, c.cap);
+    auto cleanup = [&]() {
+        if (c.d_U) (void)hipFree(c.d_U); if (c.d_k) (void)hipFree(c.d_k);
+        if (c.d_v) (void)hipFree(c.d_v); if (c.d_ws) (void)hipFree(c.d_ws);
+    };
+    if (hipMalloc(&c.d_U, sizeof(int32_t) * 2 * size_t(c.cap)) != hipSuccess || hipMalloc(&c.d_k, sizeof(int32_t) * size_t(c.cap)) != hipSuccess ||
+        hipMalloc(&c.d_v, size_t(c.cap)) != hipSuccess || hipMalloc(&c.d_ws, c.ws_bytes) != hipSuccess) { cleanup(); return FC_EDEVICE; }
+    fc_rational r; int32_t rounds = 0;
+    rc = fc_fixed_k_search_with_verdicts(g->N, g->min_in_bw, g->max_bw, k, candidates_per_round, search_verdicts, &c, &r, &rounds);
+    cleanup();
+    if (rc != FC_OK) return rc;
+    *U_star = r;
     if (rounds_or_null) *rounds_or_null = rounds;
     if (trace_len_or_null) *trace_len_or_null = c.tlen;
     return FC_OK;

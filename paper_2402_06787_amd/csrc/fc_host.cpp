@@ -279,6 +279,86 @@ void pick_probes(int64_t lo, int64_t hi, int32_t c, std::vector<int64_t> &out) {
 
 }  // namespace
 
+namespace {
+
+// The smallest fraction p/q with q <= den_bound for which the (monotone) verdict is "feasible",
+// known to lie in (floor_below, top]: `top` itself is feasible (the caller has tested it) and the
+// integer `floor_below` is infeasible without a test.  Stern-Brocot walk: keep neighbours lo
+// (infeasible) < answer <= hi (feasible); every fraction strictly between them has denominator
+// >= q_lo + q_hi, so once that exceeds den_bound the answer is hi.  Each round tests up to C
+// fractions on the two runs (lo + i hi) and (i lo + hi), splitting the run index multi-way.
+int smallest_feasible_fraction(int64_t top, int64_t floor_below, int64_t den_bound, int32_t C, fc_verdict_fn verdicts,
+                               void *ctx, Frac *answer, int32_t *rounds_io) {
+    const int64_t B = den_bound;
+    int32_t rounds = *rounds_io;
+    std::vector<int32_t> cu, ck; std::vector<uint8_t> cv;
+    Frac lo{floor_below, 1}, hi{1, 0};               // hi = +infinity
+    int dir = 0;                                     // 0: no run open; +1: towards hi; -1: towards lo
+    int64_t run_lo = 0, run_hi = 0;                  // open run: index run_lo continues, run_hi stops
+    int64_t imax_r = 0, imax_l = 0;
+    for (;;) {
+        if (dir == 0) {
+            if (hi.q != 0 && lo.q + hi.q > B) break;                 // no fraction left between them
+            imax_r = hi.q == 0 ? top - lo.p - 1 : (B - lo.q) / hi.q;   // (lo.p + i)/1 with i > imax_r is >= top
+            imax_l = (B - hi.q) / lo.q;
+            if (hi.q == 0 && imax_r < 1) { hi = Frac{top, 1}; continue; }  // lo.p + 1 == top, already tested
+        }
+        std::vector<int64_t> pr, pl;                 // probe indices on the two runs
+        if (dir == 0) {
+            pr.push_back(1);                          // the mediant, shared by both runs
+            int32_t cl = (C - 1) / 2, cr = C - 1 - cl;
+            pick_probes(1, imax_r + 1, cr, pr);
+            pick_probes(1, imax_l + 1, cl, pl);
+        } else if (dir > 0) pick_probes(run_lo, run_hi, C, pr);
+        else pick_probes(run_lo, run_hi, C, pl);
+
+        cu.clear(); ck.clear();
+        for (int64_t i : pr) { cu.push_back(int32_t(lo.p + i * hi.p)); ck.push_back(int32_t(lo.q + i * hi.q)); }
+        for (int64_t i : pl) { cu.push_back(int32_t(i * lo.p + hi.p)); ck.push_back(int32_t(i * lo.q + hi.q)); }
+        cv.assign(cu.size(), 0);
+        int rc = verdicts(ctx, int32_t(cu.size()), cu.data(), ck.data(), cv.data());
+        ++rounds;
+        if (rc != FC_OK) return rc;
+        const uint8_t *vr = cv.data(), *vl = cv.data() + pr.size();
+
+        if (dir == 0) {
+            dir = vr[0] ? -1 : +1;
+            if (dir > 0) { run_lo = 0; run_hi = imax_r + 1; }
+            else { run_lo = 1; run_hi = imax_l + 1; }   // index 1 (the mediant) is feasible
+        }
+        if (dir > 0) {               // towards hi: infeasible ... infeasible feasible ... feasible
+            for (size_t j = 0; j < pr.size(); ++j) {
+                if (!vr[j]) run_lo = std::max(run_lo, pr[j]);
+                else run_hi = std::min(run_hi, pr[j]);
+            }
+        } else {                     // towards lo: feasible ... feasible infeasible ... infeasible
+            for (size_t j = 0; j < pl.size(); ++j) {
+                if (vl[j]) run_lo = std::max(run_lo, pl[j]);
+                else run_hi = std::min(run_hi, pl[j]);
+            }
+        }
+        if (run_lo >= run_hi) return FC_ENOCONVERGE;    // verdicts were not monotone
+        if (run_hi == run_lo + 1) {                     // run resolved: move the pair
+            if (dir > 0) {
+                Frac nlo{lo.p + run_lo * hi.p, lo.q + run_lo * hi.q};
+                if (run_hi <= imax_r) hi = Frac{lo.p + run_hi * hi.p, lo.q + run_hi * hi.q};
+                else if (hi.q == 0) hi = Frac{top, 1};
+                lo = nlo;
+            } else {
+                Frac nhi{run_lo * lo.p + hi.p, run_lo * lo.q + hi.q};
+                if (run_hi <= imax_l) lo = Frac{run_hi * lo.p + hi.p, run_hi * lo.q + hi.q};
+                hi = nhi;
+            }
+            dir = 0;
+        }
+    }
+    *answer = hi;
+    *rounds_io = rounds;
+    return FC_OK;
+}
+
+}  // namespace
+
 extern "C" int fc_search_with_verdicts(int32_t n_compute, int64_t min_in_bw, int32_t gcd_bw,
                                        int32_t candidates_per_round, fc_verdict_fn verdicts, void *ctx,
                                        fc_rational *inv_xstar, fc_rational *U, int64_t *k,
@@ -291,81 +371,51 @@ extern "C" int fc_search_with_verdicts(int32_t n_compute, int64_t min_in_bw, int
     const int32_t C = std::max<int32_t>(candidates_per_round, 2);
     int32_t rounds = 0;
     try {
-        std::vector<int32_t> cu, ck; std::vector<uint8_t> cv;
         // upper end of the paper's initial range: 1/x = N-1 must be feasible (B^+(S) >= 1 for all S)
-        cu.assign(1, int32_t(N - 1)); ck.assign(1, 1); cv.assign(1, 0);
-        int rc = verdicts(ctx, 1, cu.data(), ck.data(), cv.data());
+        int32_t cu = int32_t(N - 1), ck = 1; uint8_t cv = 0;
+        int rc = verdicts(ctx, 1, &cu, &ck, &cv);
         ++rounds;
         if (rc != FC_OK) return rc;
-        if (!cv[0]) return FC_EDISCONNECTED;
-
-        // lower end: (N-1)/B <= 1/x*, so the integer just below it is infeasible without a test
-        int64_t a0 = (N - 1 + B - 1) / B - 1;
-        Frac lo{a0, 1}, hi{1, 0};                        // hi = +infinity
-        int dir = 0;                                     // 0: no run open; +1: towards hi; -1: towards lo
-        int64_t run_lo = 0, run_hi = 0;                  // open run: index run_lo continues, run_hi stops
-        int64_t imax_r = 0, imax_l = 0;
-        for (;;) {
-            if (dir == 0) {
-                if (hi.q != 0 && lo.q + hi.q > B) break;                 // no fraction left between them
-                imax_r = hi.q == 0 ? (N - 1) - lo.p - 1 : (B - lo.q) / hi.q;   // (lo.p + i)/1 with i > imax_r is >= N-1
-                imax_l = (B - hi.q) / lo.q;
-                if (hi.q == 0 && imax_r < 1) { hi = Frac{N - 1, 1}; continue; }  // lo.p + 1 == N-1, already tested
-            }
-            std::vector<int64_t> pr, pl;                 // probe indices on the two runs
-            if (dir == 0) {
-                pr.push_back(1);                          // the mediant, shared by both runs
-                int32_t cl = (C - 1) / 2, cr = C - 1 - cl;
-                pick_probes(1, imax_r + 1, cr, pr);
-                pick_probes(1, imax_l + 1, cl, pl);
-            } else if (dir > 0) pick_probes(run_lo, run_hi, C, pr);
-            else pick_probes(run_lo, run_hi, C, pl);
-
-            cu.clear(); ck.clear();
-            for (int64_t i : pr) { cu.push_back(int32_t(lo.p + i * hi.p)); ck.push_back(int32_t(lo.q + i * hi.q)); }
-            for (int64_t i : pl) { cu.push_back(int32_t(i * lo.p + hi.p)); ck.push_back(int32_t(i * lo.q + hi.q)); }
-            cv.assign(cu.size(), 0);
-            rc = verdicts(ctx, int32_t(cu.size()), cu.data(), ck.data(), cv.data());
-            ++rounds;
-            if (rc != FC_OK) return rc;
-            const uint8_t *vr = cv.data(), *vl = cv.data() + pr.size();
-
-            if (dir == 0) {
-                dir = vr[0] ? -1 : +1;
-                if (dir > 0) { run_lo = 0; run_hi = imax_r + 1; }
-                else { run_lo = 1; run_hi = imax_l + 1; }   // index 1 (the mediant) is feasible
-            }
-            if (dir > 0) {               // towards hi: infeasible ... infeasible feasible ... feasible
-                for (size_t j = 0; j < pr.size(); ++j) {
-                    if (!vr[j]) run_lo = std::max(run_lo, pr[j]);
-                    else run_hi = std::min(run_hi, pr[j]);
-                }
-            } else {                     // towards lo: feasible ... feasible infeasible ... infeasible
-                for (size_t j = 0; j < pl.size(); ++j) {
-                    if (vl[j]) run_lo = std::max(run_lo, pl[j]);
-                    else run_hi = std::min(run_hi, pl[j]);
-                }
-            }
-            if (run_lo >= run_hi) return FC_ENOCONVERGE;    // verdicts were not monotone
-            if (run_hi == run_lo + 1) {                     // run resolved: move the pair
-                if (dir > 0) {
-                    Frac nlo{lo.p + run_lo * hi.p, lo.q + run_lo * hi.q};
-                    if (run_hi <= imax_r) hi = Frac{lo.p + run_hi * hi.p, lo.q + run_hi * hi.q};
-                    else if (hi.q == 0) hi = Frac{N - 1, 1};
-                    lo = nlo;
-                } else {
-                    Frac nhi{run_lo * lo.p + hi.p, run_lo * lo.q + hi.q};
-                    if (run_hi <= imax_l) lo = Frac{run_hi * lo.p + hi.p, run_hi * lo.q + hi.q};
-                    hi = nhi;
-                }
-                dir = 0;
-            }
-        }
+        if (!cv) return FC_EDISCONNECTED;
+        // lower end: (N-1)/B <= 1/x*, so the integer just below it is infeasible without a test;
+        // the denominator of 1/x* is at most B (Appendix E.1)
+        Frac hi{0, 1};
+        rc = smallest_feasible_fraction(N - 1, (N - 1 + B - 1) / B - 1, B, C, verdicts, ctx, &hi, &rounds);
+        if (rc != FC_OK) return rc;
         int64_t g = gcd64(hi.q, gcd_bw);                 // Proposition 3
         if (g < 1) g = 1;
         inv_xstar->num = hi.p; inv_xstar->den = hi.q;
         U->num = hi.p; U->den = g;
         *k = hi.q / g;
+        if (rounds_or_null) *rounds_or_null = rounds;
+        return FC_OK;
+    } catch (const std::bad_alloc &) {
+        return FC_ENOMEM;
+    }
+}
+
+extern "C" int fc_fixed_k_search_with_verdicts(int32_t n_compute, int64_t min_in_bw, int32_t max_bw, int32_t k,
+                                               int32_t candidates_per_round, fc_verdict_fn verdicts, void *ctx,
+                                               fc_rational *U_star, int32_t *rounds_or_null) {
+    if (!verdicts || !U_star || n_compute < 2 || candidates_per_round < 1 || k < 1 || max_bw < 0) return FC_EINVAL;
+    const int64_t N = n_compute, B = min_in_bw, top = (N - 1) * int64_t(k);
+    if (B < 1 || max_bw < 1) return FC_EDISCONNECTED;
+    // every candidate p/q has q <= max_bw and p/q <= top: p must fit 32 bits, and so must N * k
+    if (top * int64_t(max_bw) >= (int64_t(1) << 31) || N * int64_t(k) >= (int64_t(1) << 31)) return FC_EOVERFLOW;
+    const int32_t C = std::max<int32_t>(candidates_per_round, 2);
+    int32_t rounds = 0;
+    try {
+        // upper end of the range of Algorithm 3: U = (N-1) k must be feasible
+        int32_t cu = int32_t(top), cd = 1; uint8_t cv = 0;
+        int rc = verdicts(ctx, 1, &cu, &cd, &cv);
+        ++rounds;
+        if (rc != FC_OK) return rc;
+        if (!cv) return FC_EDISCONNECTED;
+        // lower end: U* >= (N-1) k / B; at U* some U* b_e is an integer, so its denominator is at most max_bw
+        Frac hi{0, 1};
+        rc = smallest_feasible_fraction(top, (top + B - 1) / B - 1, max_bw, C, verdicts, ctx, &hi, &rounds);
+        if (rc != FC_OK) return rc;
+        U_star->num = hi.p; U_star->den = hi.q;
         if (rounds_or_null) *rounds_or_null = rounds;
         return FC_OK;
     } catch (const std::bad_alloc &) {

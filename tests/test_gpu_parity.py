@@ -300,3 +300,112 @@ def test_scaling_identity_on_gpu():
         for t in (2, 7, 1000):
             got, _ = _gpu_flows(g, pl.sink, pl.edge_mult * t, pl.src_cap * t)
             assert (got == t * base).all()
+
+
+# ------------------------------------------------------------------ fixed k: floor(U b_e) capacities, Algorithm 3
+
+def _gpu_flows_floor(g, sink, num, den, k, options=None, want_stats=False):
+    flows, stats = fc.fc_maxflow_batch_floor(g, _dev(sink), _dev(num), _dev(den), _dev(k), options=options,
+                                            want_stats=want_stats)
+    torch.cuda.synchronize()
+    return flows.cpu().numpy().astype(np.int64), stats
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_floor_capacity_flows_match_oracle(cfg):
+    topo = w.config_topology(cfg)
+    N = topo.n_compute
+    inv = Fraction(*_optimum(cfg, topo))
+    rng = np.random.default_rng(500 + cfg)
+    # per k, multipliers scattered around k / x* (where verdicts flip) with assorted denominators
+    nums, dens, ks = [], [], []
+    for k in (1, 2, 3, 7):
+        for den in (1, 2, 3, 5, 64, 97, 1000):
+            centre = inv * k * den
+            for off in (-3, -1, 0, 1, 4):
+                nums.append(max(1, int(centre) + off)); dens.append(den); ks.append(k)
+    nums, dens, ks = (np.array(a, dtype=np.int64) for a in (nums, dens, ks))
+    if cfg == 5:                                           # 140 candidates x 1024 sinks is a lot for the oracle: sample
+        pick = np.sort(rng.choice(len(nums), 24, replace=False)); nums, dens, ks = nums[pick], dens[pick], ks[pick]
+    comp = topo.compute_nodes
+    sink = np.tile(comp, len(nums)); num = np.repeat(nums, N); den = np.repeat(dens, N); k = np.repeat(ks, N)
+    want = o.aux_maxflow_batch_floor(topo, sink, num, den, k, threads=16)
+    with _upload(topo) as g:
+        got, stats = _gpu_flows_floor(g, sink, num, den, k, want_stats=True)
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, (cfg, bad[:8], got[bad[:8]], want[bad[:8]])
+        assert stats["not_converged"] == 0
+        # a denominator of 1 is the integer path
+        a, _ = _gpu_flows(g, sink[: 4 * N], num[: 4 * N], k[: 4 * N])
+        b, _ = _gpu_flows_floor(g, sink[: 4 * N], num[: 4 * N], np.ones(4 * N), k[: 4 * N])
+        assert (a == b).all()
+        # verdict form of the same thing
+        res = fc.fc_feasible_floor(g, _dev(nums), _dev(dens), _dev(ks), want_flows=True)
+        torch.cuda.synchronize()
+        flows = res["flows"].cpu().numpy().astype(np.int64)
+        assert (flows.reshape(-1) == want).all()
+        feas = res["feasible"].cpu().numpy()
+        assert (feas == (want.reshape(len(nums), N) >= N * ks[:, None]).all(axis=1)).all()
+
+
+def test_floor_capacity_on_tiny_random_graphs_and_malformed_input():
+    for seed in range(60):
+        topo = w.random_tiny(seed, n_vertices=None if seed % 3 else 12, strongly_connected=(seed % 4 != 3))
+        rng = np.random.default_rng(900 + seed)
+        P = 64
+        sink = rng.integers(0, topo.n_vertices, P).astype(np.int32)
+        num = rng.integers(1, 200, P).astype(np.int64)
+        den = rng.integers(1, 40, P).astype(np.int64)
+        k = rng.integers(1, 30, P).astype(np.int64)
+        k[::7] = rng.integers(20000, 3000000, k[::7].shape)                    # N*k > 65535: 32-bit state
+        num[::11] = rng.integers(1 << 20, 1 << 30, num[::11].shape)            # products beyond 32 bits
+        den[::13] = rng.integers(1 << 20, 1 << 30, den[::13].shape)            # multipliers far below 1: most links floor to 0
+        want = o.aux_maxflow_batch_floor(topo, sink, num, den, k, algo="edmonds_karp" if seed % 2 else "dinic")
+        with _upload(topo) as g:
+            got, _ = _gpu_flows_floor(g, sink, num, den, k)
+            assert (got == want).all(), (seed, np.flatnonzero(got != want)[:5])
+            if seed % 6 == 0:
+                got2, _ = _gpu_flows_floor(g, sink, num, den, k, options={"force_wide": 1, "use_label_table": 2})
+                assert (got2 == want).all(), seed
+            if seed == 0:
+                den_bad = den.copy(); den_bad[3] = 0; den_bad[9] = -5
+                got3, _ = _gpu_flows_floor(g, sink, num, den_bad, k)
+                assert got3[3] == fc.FC_FLOW_INVALID and got3[9] == fc.FC_FLOW_INVALID
+                keep = np.ones(P, dtype=bool); keep[[3, 9]] = False
+                assert (got3[keep] == want[keep]).all()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_fixed_k_search_matches_oracle_on_configs(cfg):
+    topo = w.config_topology(cfg)
+    inv = Fraction(*_optimum(cfg, topo))
+    bmin = int(o.links(topo)[2].min())
+    with _upload(topo) as g:
+        for k in ((1, 2, 5) if cfg < 5 else (2,)):
+            want = o.fixed_k_binary_search(topo, k, threads=16)
+            res = fc.fc_fixed_k_search(g, k, 16 if k != 2 else 3)
+            assert res["U_star"] == want, (cfg, k)
+            assert inv <= want / k <= inv + Fraction(1, k * bmin)              # Theorem 13 and the optimum
+            trace = res["trace"] if cfg < 5 else res["trace"][:: max(1, len(res["trace"]) // 6)]
+            for num, den, v in trace:                                          # every verdict the GPU produced
+                assert bool(v) == o.fixed_k_feasible(topo, Fraction(num, den), k, threads=16)[0], (num, den)
+    # the paper's worked example: k = 1 at U = 1/b (Section 5.2, "Determine k")
+    for b in (1, 3):
+        with _upload(w.paper_example_switch(b)) as g:
+            assert fc.fc_fixed_k_search(g, 1, 8)["U_star"] == Fraction(1, b)
+            assert fc.fc_fixed_k_search(g, 4, 2)["U_star"] == Fraction(4, b)
+
+
+def test_fixed_k_search_on_random_and_disconnected_graphs():
+    for seed in range(40):
+        topo = w.random_tiny(700 + seed, max_cap=6, strongly_connected=(seed % 4 != 3))
+        k = 1 + seed % 3
+        with _upload(topo) as g:
+            try:
+                want = o.fixed_k_binary_search(topo, k)
+            except o.Disconnected:
+                with pytest.raises(fc.FcError) as ei:
+                    fc.fc_fixed_k_search(g, k, 5)
+                assert ei.value.code == fc.FC_EDISCONNECTED
+                continue
+            assert fc.fc_fixed_k_search(g, k, 1 + seed % 7)["U_star"] == want, seed

@@ -172,3 +172,63 @@ def test_search_driver_synthetic_optima():
     with pytest.raises(fc.FcError) as ei:        # (N-1)*B must fit 31 bits
         fc.fc_search_with_verdicts(70000, 70000, 1, 8, lambda c: [True] * len(c))
     assert ei.value.code == fc.FC_EOVERFLOW
+
+
+# ---------------------------------------------------------------- fixed-k search driver (Algorithm 3) with oracle verdicts
+
+def _fixed_k_with_oracle(topo, k, cpr):
+    info = fc.fc_graph_info(fc.fc_graph_build(topo.n_vertices, topo.tail, topo.head, topo.bandwidth, topo.is_compute))
+    seen = []
+
+    def verdicts(cands):
+        out = []
+        for num, den in cands:
+            ok, _ = o.fixed_k_feasible(topo, Fraction(num, den), k)
+            seen.append((Fraction(num, den), ok))
+            out.append(ok)
+        return out
+
+    res = fc.fc_fixed_k_search_with_verdicts(info.n_compute, info.min_in_bw_compute, info.max_bw, k, cpr, verdicts)
+    return res, seen, info
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_fixed_k_driver_matches_oracle_on_tiny_graphs(seed):
+    topo = w.random_tiny(300 + seed, max_cap=6, strongly_connected=(seed % 5 != 4))
+    cpr = [1, 2, 3, 5, 16][seed % 5]
+    k = 1 + seed % 4
+    try:
+        want = o.fixed_k_binary_search(topo, k)
+    except o.Disconnected:
+        with pytest.raises(fc.FcError) as ei:
+            _fixed_k_with_oracle(topo, k, cpr)
+        assert ei.value.code == fc.FC_EDISCONNECTED
+        return
+    res, seen, info = _fixed_k_with_oracle(topo, k, cpr)
+    assert res["U_star"] == want
+    assert info.max_bw == int(o.links(topo)[2].max())            # the library's links are the oracle's links
+    for frac, ok in seen:                                        # Theorem 12: feasible iff U >= U*
+        assert ok == (frac >= want) and frac.denominator <= info.max_bw
+
+
+def test_fixed_k_driver_synthetic_optima_and_errors():
+    # any p/q in [(N-1)k/B, (N-1)k] with q <= max b must be found exactly, for any batch width
+    N, B, bmax, k = 12, 9, 31, 3
+    rng = np.random.default_rng(8)
+    for _ in range(200):
+        q = int(rng.integers(1, bmax + 1))
+        lo = -(-(N - 1) * k * q // B)
+        p = int(rng.integers(lo, (N - 1) * k * q + 1))
+        want = Fraction(p, q)
+        cpr = int(rng.integers(1, 20))
+        res = fc.fc_fixed_k_search_with_verdicts(N, B, bmax, k, cpr, lambda c: [Fraction(a, b) >= want for a, b in c])
+        assert res["U_star"] == want
+    with pytest.raises(fc.FcError) as ei:
+        fc.fc_fixed_k_search_with_verdicts(N, B, bmax, k, 8, lambda c: [False] * len(c))
+    assert ei.value.code == fc.FC_EDISCONNECTED
+    with pytest.raises(fc.FcError) as ei:                        # (N-1) k max_b must fit 31 bits
+        fc.fc_fixed_k_search_with_verdicts(1000, 50, 100000, 50, 8, lambda c: [True] * len(c))
+    assert ei.value.code == fc.FC_EOVERFLOW
+    with pytest.raises(fc.FcError) as ei:
+        fc.fc_fixed_k_search_with_verdicts(N, B, bmax, 0, 8, lambda c: [True] * len(c))
+    assert ei.value.code == fc.FC_EINVAL
