@@ -13,6 +13,8 @@ the paper (ForestColl, arXiv 2402.06787):
   (`optimality_binary_search`), or by enumerating every cut of the bound (star) of
   Section 4 (`brute_inv_xstar`).
 * (U, k) by the gcd rule of Section 5.2 "Determine k" / Proposition 3 (`smallest_U_k`).
+* edge splitting (Appendix E.2): the 2N max-flows and gamma of Theorem 10 (`split_flows`,
+  `split_gamma`), gamma by its definition (`brute_split_gamma`), the split graph (`split_off`).
 * the fixed-k variant (Section 5.5, Appendix E.4): the verdict on the network with capacities
   floor(U b_e) for a rational U (`fixed_k_feasible`), U* by Algorithm 3 taken literally in
   exact rationals (`fixed_k_binary_search`), or by trying every fraction j / b_e
@@ -349,6 +351,93 @@ def brute_fixed_k(topo, k, algo="dinic"):
         if fixed_k_feasible(topo, U, k, algo)[0]:
             return U
     raise AssertionError("the upper end of the range was feasible")
+
+
+# ------------------------------------------------------------------ edge splitting (Appendix E.2, Theorem 10)
+
+def link_capacities(topo):
+    """{(tail, head): bandwidth} over the links."""
+    tail, head, bw = links(topo)
+    return {(int(t), int(h)): int(b) for t, h, b in zip(tail.tolist(), head.tolist(), bw.tolist())}
+
+
+def is_eulerian(topo):
+    """Every vertex has equal in- and out-capacity (the precondition of the edge-splitting theorems)."""
+    bal = [0] * topo.n_vertices
+    for (t, h), b in link_capacities(topo).items():
+        bal[t] -= b
+        bal[h] += b
+    return all(x == 0 for x in bal)
+
+
+def unbounded(topo, k):
+    """A finite stand-in for the infinite capacities of the split-off networks: more than every finite
+    cut can carry (all link capacities plus all source arcs), so a flow of at least this much means
+    an all-infinite path.  Flow values are reported capped at it."""
+    return sum(link_capacities(topo).values()) + topo.n_compute * int(k) + 1
+
+
+def split_flows(topo, k, u, w, t, algo="dinic"):
+    """The 2N max-flows of Theorem 10 for splitting off e = (u, w), f = (w, t) in the integer-capacity
+    digraph D = topo (capacities are the link bandwidths).  With s joined to every compute node by k:
+      F1[v] = F(u, w; D_k + infinite arcs (u, s), (u, t), (v, w)),
+      F2[v] = F(w, t; D_k + infinite arcs (w, s), (u, t), (v, t)),   v over the compute nodes,
+    each capped at `unbounded`.  Returns (F1, F2) as int64 arrays in compute-node order."""
+    u, w, t, k = int(u), int(w), int(t), int(k)
+    cap = link_capacities(topo)
+    if (u, w) not in cap or (w, t) not in cap:
+        raise ValueError("e = (u, w) and f = (w, t) must be links of the graph")
+    comp = [v for v in range(topo.n_vertices) if topo.is_compute[v]]
+    s = topo.n_vertices
+    INF = unbounded(topo, k)
+    base = [(a, b, c) for (a, b), c in sorted(cap.items())] + [(s, c, k) for c in comp]
+
+    def flow(extra, src, dst):
+        arcs = base + [(a, b, INF) for a, b in extra if a != b]
+        tail = np.array([a for a, _, _ in arcs], dtype=np.int32)
+        head = np.array([b for _, b, _ in arcs], dtype=np.int32)
+        return min(INF, maxflow(topo.n_vertices + 1, tail, head, [c for _, _, c in arcs], src, dst, algo))
+
+    F1 = np.array([flow([(u, s), (u, t), (v, w)], u, w) for v in comp], dtype=np.int64)
+    F2 = np.array([flow([(w, s), (u, t), (v, t)], w, t) for v in comp], dtype=np.int64)
+    return F1, F2
+
+
+def split_gamma(topo, k, u, w, t, algo="dinic"):
+    """gamma of Theorem 10: the most capacity of e = (u, w) and f = (w, t) that can be replaced by a
+    direct arc (u, t) while min over compute nodes v of F(s, v) stays >= N k."""
+    cap = link_capacities(topo)
+    F1, F2 = split_flows(topo, k, u, w, t, algo)
+    Nk = topo.n_compute * int(k)
+    return int(min(cap[(int(u), int(w))], cap[(int(w), int(t))], int(F1.min()) - Nk, int(F2.min()) - Nk))
+
+
+def split_off(topo, u, w, t, amount):
+    """D^{ef}: `amount` of the capacity of (u, w) and of (w, t) replaced by capacity on (u, t)."""
+    from workloads import Topology
+    u, w, t, amount = int(u), int(w), int(t), int(amount)
+    cap = link_capacities(topo)
+    assert 0 <= amount <= min(cap[(u, w)], cap[(w, t)])
+    cap[(u, w)] -= amount
+    cap[(w, t)] -= amount
+    if u != t:                                          # splitting off a detour u -> w -> u just removes it
+        cap[(u, t)] = cap.get((u, t), 0) + amount
+    keys = sorted(key for key, c in cap.items() if c > 0)
+    return Topology(topo.name + "_split", topo.n_vertices, np.array([a for a, _ in keys], dtype=np.int32),
+                    np.array([b for _, b in keys], dtype=np.int32), np.array([cap[key] for key in keys], dtype=np.int32),
+                    np.array(topo.is_compute, dtype=np.uint8))
+
+
+def brute_split_gamma(topo, k, u, w, t, algo="dinic"):
+    """gamma by its definition: try every amount 0..min(c_e, c_f), split it off, and test Theorem 1's
+    condition on the result; the feasible amounts must form a prefix and gamma is the largest."""
+    cap = link_capacities(topo)
+    top = min(cap[(int(u), int(w))], cap[(int(w), int(t))])
+    ok = [feasible(split_off(topo, u, w, t, a), 1, k, algo)[0] for a in range(top + 1)]
+    assert ok[0], "the graph itself must satisfy min F(s, v) >= N k"
+    best = max(a for a in range(top + 1) if ok[a])
+    assert all(ok[: best + 1]), "feasible split amounts form a prefix"
+    return best
 
 
 # ------------------------------------------------------------------ brute force (tiny graphs only)

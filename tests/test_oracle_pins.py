@@ -344,3 +344,105 @@ def test_fixed_k_textbook_shapes(n, c, k):
     assert o.fixed_k_binary_search(w.complete_digraph(n, c), k) == Fraction(k, c)
     # directed ring, every link c: the link into v carries the other n-1 nodes' k units: U* = (n-1) k / c
     assert o.fixed_k_binary_search(w.directed_ring(n, c), k) == Fraction((n - 1) * k, c)
+
+
+# ---------------------------------------------------------------- edge splitting (Appendix E.2, Theorem 10)
+
+def _scaled_eulerian(seed):
+    """A small bidirectional (hence Eulerian) graph with switches, scaled by Proposition 3's (U, k) so
+    that min_v F(s, v) >= N k holds with integer capacities U b_e -- the input of the edge-splitting stage."""
+    rng = np.random.default_rng(4000 + seed)
+    base = w.random_tiny(4000 + seed, n_vertices=int(rng.integers(4, 8)), max_cap=4, density=0.35)
+    if base.is_compute.all():
+        base.is_compute[int(rng.integers(0, base.n_vertices))] = 0
+        if base.is_compute.sum() < 2:
+            return None
+    cap = {}
+    for t, h, b in zip(base.tail.tolist(), base.head.tolist(), base.bandwidth.tolist()):
+        if t != h and b > 0:
+            key = (min(t, h), max(t, h))
+            cap[key] = cap.get(key, 0) + int(b)
+    tail = [a for a, b in cap] + [b for a, b in cap]
+    head = [b for a, b in cap] + [a for a, b in cap]
+    bw = list(cap.values()) * 2
+    sym = w.Topology(f"euler{seed}", base.n_vertices, np.array(tail, dtype=np.int32), np.array(head, dtype=np.int32),
+                     np.array(bw, dtype=np.int32), base.is_compute.copy())
+    try:
+        inv = o.optimality_binary_search(sym)
+    except o.Disconnected:
+        return None
+    U, k = o.smallest_U_k(inv, sym.bandwidth)
+    scaled = w.Topology(sym.name, sym.n_vertices, sym.tail, sym.head,
+                        np.array([int(U * int(b)) for b in sym.bandwidth], dtype=np.int32), sym.is_compute)
+    assert o.is_eulerian(scaled) and o.feasible(scaled, 1, k)[0]
+    return scaled, k
+
+
+@pytest.mark.parametrize("b", [1, 2])
+def test_edge_splitting_of_the_paper_example(b):
+    # Appendix E.2, the stages figure: in each box split off all 10b of (c_j, w_i), (w_i, c_{j+1}) to form a ring,
+    # across boxes all b of (c_{1,j}, w_0), (w_0, c_{2,j}) and back; the result is the switch-free topology of
+    # the figure, and the optimum 1/x* = 1/b is unchanged.  D = G({U b_e}) with U = 1/b, k = 1: capacities {10, 1}.
+    D = w.paper_example_switch(1)
+    k = 1
+    for box in range(2):
+        for j in range(4):
+            u, t, sw = 4 * box + j, 4 * box + (j + 1) % 4, 8 + box
+            assert o.split_gamma(D, k, u, sw, t) == 10
+            D = o.split_off(D, u, sw, t, 10)
+    for j in range(4):
+        for u, t in ((j, 4 + j), (4 + j, j)):
+            assert o.split_gamma(D, k, u, 10, t) == 1
+            D = o.split_off(D, u, 10, t, 1)
+    want = w.paper_example_split(1)
+    assert o.link_capacities(D) == o.link_capacities(want)
+    assert o.feasible(D, 1, k)[0] and o.optimality_binary_search(w.paper_example_split(b)) == Fraction(1, b)
+    # capacity that leaves a box cannot be split onto an in-box pair: nothing can be taken
+    assert o.split_gamma(w.paper_example_switch(1), 1, 0, 10, 1) == 0
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_split_gamma_formula_equals_its_definition(seed):
+    made = _scaled_eulerian(seed)
+    if made is None:
+        return
+    D, k = made
+    cap = o.link_capacities(D)
+    switches = [v for v in range(D.n_vertices) if not D.is_compute[v]]
+    pairs = [(u, sw, t) for sw in switches for (u, x) in cap if x == sw for (y, t) in cap if y == sw]
+    rng = np.random.default_rng(seed)
+    for i in rng.permutation(len(pairs))[:6]:
+        u, sw, t = pairs[int(i)]
+        g_formula = o.split_gamma(D, k, u, sw, t, algo=ALGOS[seed % 2])
+        assert g_formula == o.brute_split_gamma(D, k, u, sw, t, algo=ALGOS[(seed + 1) % 2]), (seed, u, sw, t)
+        F1, F2 = o.split_flows(D, k, u, sw, t)
+        assert (F1 >= D.n_compute * k).all() and (F2 >= D.n_compute * k).all()     # gamma >= 0 under the preconditions
+        after = o.split_off(D, u, sw, t, g_formula)
+        assert o.is_eulerian(after) and o.feasible(after, 1, k)[0]
+
+
+def test_switch_removal_by_repeated_splitting_keeps_the_optimum():
+    # Algorithm 2's loop with the oracle's gamma: every switch ends isolated and Theorem 1's condition still holds
+    done = 0
+    for seed in range(12):
+        made = _scaled_eulerian(100 + seed)
+        if made is None:
+            continue
+        D, k = made
+        for sw in [v for v in range(D.n_vertices) if not D.is_compute[v]]:
+            for (y, t) in [key for key in o.link_capacities(D) if key[0] == sw]:
+                for (u, x) in [key for key in o.link_capacities(D) if key[1] == sw]:
+                    cap = o.link_capacities(D)
+                    if (sw, t) not in cap:
+                        break
+                    if (u, sw) not in cap:
+                        continue
+                    g = o.split_gamma(D, k, u, sw, t)
+                    if g > 0:
+                        D = o.split_off(D, u, sw, t, g)
+                assert (sw, t) not in o.link_capacities(D)            # Theorem 9: f can always be split off completely
+        cap = o.link_capacities(D)
+        assert all(D.is_compute[a] and D.is_compute[b] for a, b in cap)
+        assert o.feasible(D, 1, k)[0]
+        done += 1
+    assert done >= 6
