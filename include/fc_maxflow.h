@@ -249,6 +249,31 @@ int fc_fixed_k_search_with_verdicts(int32_t n_compute, int64_t min_in_bw, int32_
                                     int32_t candidates_per_round, fc_verdict_fn verdicts, void *ctx,
                                     fc_rational *U_star, int32_t *rounds_or_null);
 
+/* ------------------------------------------------------------------------------------------
+ * Edge splitting (Appendix E.2, Theorem 10).  D is the uploaded graph with every link capacity
+ * multiplied by the integer U (the stage works on G({U b_e}); rescale the bandwidths first when
+ * Proposition 3's U is a fraction), k the number of trees per compute node.  For pair i,
+ * e = (u_i, w_i), f = (w_i, t_i) with w_i a switch node, gamma_i is the most capacity of e and f that can
+ * be replaced by a direct arc (u_i, t_i) while  min over v in V_c of F(s, v) >= N k  keeps holding:
+ *   gamma = min{ c(e), c(f),  min_v F(u, w; D_k + unbounded arcs (u,s), (u,t), (v,w)) - N k,
+ *                             min_v F(w, t; D_k + unbounded arcs (w,s), (u,t), (v,t)) - N k },
+ * 2N max-flows per pair, all pairs in one launch.  The theorem assumes D Eulerian (fc_graph_info
+ * reports it) and the condition holding in D; neither is checked -- gamma is then just the formula.
+ *
+ * d_u, d_w, d_t: device int32 [n_pairs].  d_gamma_out: device int32 [n_pairs]; FC_GAMMA_INVALID for a pair
+ * that is not two links through a switch node.  d_flows_or_null: device int32 [n_pairs][2][N], the two
+ * families of flows in compute-node order; "unbounded" (a path of unbounded arcs exists) is reported as
+ * the one value U * (sum of all b_e) + N k + 1, which exceeds every finite cut.  That value must stay
+ * below 2^30 (FC_EOVERFLOW), and the 32-bit on-chip state must fit (FC_EUNSUPPORTED).  Workspace,
+ * stream, options and stats as for fc_maxflow_batch (no per-sink tables, launch order or certificate
+ * apply to these problems). */
+#define FC_GAMMA_INVALID (-2147483647 - 1)
+size_t fc_split_gamma_workspace_bytes(const fc_graph *g, int64_t n_pairs);
+int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int64_t n_pairs, const int32_t *d_u,
+                         const int32_t *d_w, const int32_t *d_t, int32_t *d_gamma_out, int32_t *d_flows_or_null,
+                         void *d_workspace, size_t workspace_bytes, void *hip_stream,
+                         const fc_options *options_or_null, fc_stats *stats_or_null);
+
 const char *fc_strerror(int code);
 
 #ifdef __cplusplus

@@ -20,10 +20,12 @@ FC_OK = 0
 FC_EINVAL, FC_EOVERFLOW, FC_EDISCONNECTED, FC_ENOMEM = -1, -2, -3, -4
 FC_EWORKSPACE, FC_EDEVICE, FC_ENOCONVERGE, FC_EUNSUPPORTED = -5, -6, -7, -8
 FC_FLOW_INVALID, FC_FLOW_NOCONVERGE, FC_FLOW_UNSUPPORTED = -1, -2, -3
+FC_GAMMA_INVALID = -2147483648
 
 EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_free", "fc_graph_info", "fc_graph_csr",
             "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_maxflow_batch_floor", "fc_feasible_workspace_bytes",
             "fc_feasible_floor", "fc_fixed_k_search", "fc_fixed_k_search_with_verdicts",
+            "fc_split_gamma_workspace_bytes", "fc_split_gamma_batch",
             "fc_feasible", "fc_opt_throughput_search", "fc_search_with_verdicts", "fc_strerror"]
 
 
@@ -108,6 +110,10 @@ def load_library():
     lib.fc_fixed_k_search_with_verdicts.restype = c.c_int
     lib.fc_fixed_k_search_with_verdicts.argtypes = [i32, i64, i32, i32, i32, VERDICT_FN, vp, c.POINTER(fc_rational),
                                                     c.POINTER(i32)]
+    lib.fc_split_gamma_workspace_bytes.restype = sz
+    lib.fc_split_gamma_workspace_bytes.argtypes = [vp, i64]
+    lib.fc_split_gamma_batch.restype = c.c_int
+    lib.fc_split_gamma_batch.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp, vp, vp, sz, vp, c.POINTER(fc_options), c.POINTER(fc_stats)]
     lib.fc_strerror.restype = c.c_char_p
     lib.fc_strerror.argtypes = [c.c_int]
     _lib = lib
@@ -420,3 +426,33 @@ def fc_fixed_k_search_with_verdicts(n_compute: int, min_in_bw: int, max_bw: int,
         raise err[0]
     _check(rc, "fc_fixed_k_search_with_verdicts")
     return {"U_star": Fraction(r.num, r.den), "rounds": int(rounds.value)}
+
+
+# ------------------------------------------------------------------ edge splitting (gamma of Theorem 10)
+
+def fc_split_gamma_workspace_bytes(g: Graph, n_pairs: int) -> int:
+    return int(load_library().fc_split_gamma_workspace_bytes(g.handle, int(n_pairs)))
+
+
+def fc_split_gamma_batch(g: Graph, U: int, k: int, d_u, d_w, d_t, want_flows=False, d_workspace=None, stream=None,
+                         options=None, want_stats=False):
+    """gamma for every pair e = (u, w), f = (w, t) in G({U b_e}).  Returns dict(gamma=int32 tensor,
+    flows=int32 [n_pairs, 2, N] or None, stats)."""
+    import torch
+    n_pairs = int(d_u.numel())
+    dev = d_u.device
+    N = fc_graph_info(g).n_compute
+    gamma = torch.empty(n_pairs, dtype=torch.int32, device=dev)
+    flows = torch.empty(n_pairs * 2 * N, dtype=torch.int32, device=dev) if want_flows else None
+    need = fc_split_gamma_workspace_bytes(g, n_pairs)
+    if d_workspace is None:
+        d_workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    st = fc_stats() if want_stats else None
+    rc = load_library().fc_split_gamma_batch(
+        g.handle, int(U), int(k), n_pairs, _dev_ptr(d_u, torch.int32, n_pairs, "d_u"), _dev_ptr(d_w, torch.int32, n_pairs, "d_w"),
+        _dev_ptr(d_t, torch.int32, n_pairs, "d_t"), _dev_ptr(gamma, torch.int32, n_pairs, "gamma"),
+        _dev_ptr(flows, torch.int32, n_pairs * 2 * N, "flows"), ctypes.c_void_p(d_workspace.data_ptr()), d_workspace.numel(),
+        _stream_ptr(stream), _opts(options), ctypes.byref(st) if st is not None else None)
+    _check(rc, "fc_split_gamma_batch")
+    return {"gamma": gamma, "flows": flows.view(n_pairs, 2, N) if flows is not None else None,
+            "stats": st.as_dict() if st is not None else None}

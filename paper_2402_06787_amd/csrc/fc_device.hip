@@ -63,6 +63,12 @@ struct KParams {
     // has place b / cand_C in the order; the problem list is never written out
     int32_t cand_C;              // 0: plain problem list
     const int32_t *cand_U, *cand_k, *cand_D, *compute_ids;
+    // edge-splitting launches (Theorem 10): workgroup (i * 2 + type) * N + a solves, for pair i = (u, w, t)
+    // and the a-th compute node v, F(u, w) with unbounded arcs (u, s), (u, t), (v, w) (type 0) or F(w, t) with
+    // unbounded arcs (w, s), (u, t), (v, t) (type 1); multiplier split_U and source arcs split_k for all
+    const int32_t *split_u, *split_w, *split_t;
+    int32_t split_U, split_k;
+    long long sum_bw;            // sum of all link bandwidths (bounds every finite cut)
     uint32_t *sink_cost;         // [n] what the last problem of each sink cost (feeds the next launch's order)
 };
 
@@ -331,9 +337,11 @@ __device__ __forceinline__ int32_t rebuild_pending(const State<COMPACT> &st, int
 // p.gr_sub records, sized on the host so that at most 2n entries exist at a time), a group of
 // p.gr_lanes lanes takes K entries at a time and has the K record loads in flight before it looks
 // at the first.  A record carries a flag when it is the last of its row, so no row bounds are needed.
+// `src`, `sa`, `sb` (each -1 when absent): a vertex that never gets a height (an explicit source)
+// and two vertices joined to the sink by an unbounded arc (distance 1).
 template <bool COMPACT, bool RAT>
 __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32_t t, const ArcCap<RAT> &arc_cap,
-                               uint32_t &gr_scans FC_GRDBG_PARAM) {
+                               uint32_t &gr_scans FC_GRDBG_PARAM, int32_t src = -1, int32_t sa = -1, int32_t sb = -1) {
     using W = typename State<COMPACT>::W;
 #ifdef FC_GRDETAIL
     long long gtick_ = clock64();
@@ -350,7 +358,7 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
     const int32_t last_rec = p.n_rec - 1;
     W *const work = st.list0;              // list0 and list1 are adjacent
     lds_barrier();                         // slower wavefronts may still be reading what is overwritten here
-    for (int32_t v = tid; v < n; v += T) st.h[v] = W(v == t ? 0 : n);
+    for (int32_t v = tid; v < n; v += T) st.h[v] = W(v == t ? 0 : ((v == sa || v == sb) && v != src ? 1 : n));
     for (int32_t i = tid; i < FC_LVLS; i += T) st.sh->lvl[i] = 0;
     if (tid == 0) { st.sh->cnt[0] = 0; st.sh->down[0] = 0; }
     lds_barrier();
@@ -418,7 +426,7 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
                     live[q] = live[q] && ends == 0ull;
                     const int32_t fv = int32_t(st.f[r.pair]);
                     const int32_t res = r.fwd ? fv : arc_cap(r.bw) - fv;                 // residual of r.w -> frontier vertex
-                    x[q] = valid && res > 0 ? r.w : t;
+                    x[q] = valid && res > 0 && r.w != src ? r.w : t;
                     if (valid) ++gr_scans;
                 }
                 int32_t hx[K];
@@ -458,14 +466,28 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
 // Group part: G lanes scan the residual row of one listed vertex in chunks, give all excess to the
 // first admissible arc when it suffices, else split it by a segmented prefix sum in row order, and
 // collect the smallest residual-neighbour height for the relabel in the same scan.
-template <bool COMPACT, bool RAT, int G>
+template <bool COMPACT, bool RAT, bool GEN, int G>
 __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) fc_push_relabel_kernel(KParams p) {
+    static_assert(!GEN || (!COMPACT && !RAT), "the edge-splitting problems use the 32-bit state and integer multipliers");
     using W = typename State<COMPACT>::W;
     constexpr int32_t NEWH = State<COMPACT>::NEWH;
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n, m0 = p.m0;
     int32_t j, t, U, k, D = 1;
-    if (p.cand_C) {
+    int32_t src = -1, supply = -1, sa = -1, sb = -1;     // edge-splitting problems only (see KParams)
+    if (GEN) {
+        const int32_t a = int32_t(blockIdx.x) % p.N, it = int32_t(blockIdx.x) / p.N;
+        const int32_t i = it >> 1, v = p.compute_ids[a];
+        const int32_t pu = p.split_u[i], pw = p.split_w[i], pt = p.split_t[i];
+        j = int32_t(blockIdx.x); U = p.split_U; k = p.split_k;
+        if (pu < 0 || pu >= n || pw < 0 || pw >= n || pt < 0 || pt >= n || pu == pw || pw == pt) {
+            if (tid == 0) p.flow_out[j] = FC_FLOW_INVALID;
+            if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
+            return;
+        }
+        if ((it & 1) == 0) { src = pu; t = pw; supply = pt != pu ? pt : -1; sa = v; }
+        else { src = pw; t = pt; sa = pu != pt ? pu : -1; sb = v != pt ? v : -1; }
+    } else if (p.cand_C) {
         // Workgroups go to the 8 XCDs (each with an L2 of its own) round-robin by index.  All candidates
         // of one sink read that sink's tables, so they are given indices that are equal modulo 8:
         // eight sinks are in flight side by side, one per XCD, each with its candidates one after another.
@@ -493,7 +515,15 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     // the 16-bit layout holds flows up to 65535 = largest N*k it accepts; larger problems are left
     // to the 32-bit kernel, which in turn skips the ones the 16-bit kernel took
     const bool small = NKll <= 65535ll;
-    if (COMPACT) {
+    if (GEN) {
+        // "unbounded" = more than every finite cut carries: all link capacities plus all source arcs, plus one
+        const long long big = (long long)U * p.sum_bw + NKll + 1;
+        if (big >= (1ll << 30)) {
+            if (tid == 0) p.flow_out[j] = FC_FLOW_UNSUPPORTED;
+            if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
+            return;
+        }
+    } else if (COMPACT) {
         if (!small) {
             if (!p.wide_available) {
                 if (tid == 0) p.flow_out[j] = FC_FLOW_UNSUPPORTED;
@@ -502,8 +532,15 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             return;
         }
     } else if (small && p.arc_compact != nullptr) return;
-    const int32_t NK = int32_t(NKll);
+    // NK: what the sink can hold at most -- N * k, or the "unbounded" value of an edge-splitting problem;
+    // capacities are clamped at it and the run ends when the sink holds it
+    const int32_t NK = GEN ? int32_t((long long)U * p.sum_bw + NKll + 1) : int32_t(NKll);
     const ArcCap<RAT> arc_cap(U, D, NK);
+    if (GEN && (sa == src || sb == src)) {               // an unbounded arc from the source straight into the sink
+        if (tid == 0) p.flow_out[j] = NK;
+        if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
+        return;
+    }
 
     // The first pass sends every compute node's k units down the sink's first-arc tree; the arc below
     // vertex v then carries k * (compute nodes above it).  If even the most loaded arc, relative to
@@ -577,8 +614,21 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
                 if (hv >= 1 && hv < FC_LVLS) atomicAdd(&st.sh->lvl[hv], 1);
             }
         }
+        if (GEN) {
+            // preflow of an explicit source: its unbounded arc into s is what gave every compute node k; its
+            // unbounded arc to `supply` and its own arcs are saturated here.  Nothing ever returns to it.
+            if (tid == 0 && supply >= 0) st.excess_add_noret(supply, NK);
+            for (int32_t a = int32_t(st.rp[src]) + tid; a < int32_t(st.rp[src + 1]); a += T) {
+                const ArcRec r = load_arc<COMPACT>(p, a);
+                const int32_t cap = r.fwd ? arc_cap(r.bw) : 0;
+                if (cap > 0) { st.f[r.pair] = W(cap); st.excess_add_noret(r.w, cap); }
+            }
+            lds_barrier();
+            if (tid == 0) st.e[src] = W(0);
+            lds_barrier();
+        }
         if (!have_labels) {
-            global_relabel<COMPACT, RAT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG);
+            global_relabel<COMPACT, RAT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG, src, sa, sb);
             if (tid == 0) ++c_gr;
         }
     }
@@ -604,14 +654,14 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     // a sink whose own cut has little slack tends to leave much excess stranded next to it after the
     // first pass: such problems get exact heights as soon as the working level first moves up
     int32_t rise_limit = p.gr_rises;
-    if (p.tight_pct > 0) {
+    if (p.tight_pct > 0 && !GEN) {
         const long long have = (long long)U * (long long)p.in_bw[t] / D + (p.is_compute[t] ? k : 0);
         if (have * 100ll < NKll * (long long)p.tight_pct) rise_limit = 1;
     }
     bool failed = false;
 
     // ---- steps: one height level each
-    while (d >= 1 && st.excess(t) != NK) {
+    while (d >= 1 && st.excess(t) < NK) {
         const int32_t sp = total_steps & 1;
         FC_TICK(t_other);
         int32_t cnt, lvltot = 0;
@@ -697,6 +747,10 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             int32_t rem = ex;
             int32_t minh = 0x7fffffff;
             if (lg == 0) ++c_dis;
+            if (GEN && (u == sa || u == sb)) {            // joined to the sink by an unbounded arc: everything goes there
+                if (lg == 0) { st.excess_add_noret(t, ex); st.excess_sub(u, ex); ++c_push; }
+                continue;
+            }
             for (int32_t base = beg; base < end && rem > 0; base += G) {
                 const int32_t a = base + lg;
                 int32_t ra = 0, hw = 0, fv = 0;
@@ -795,7 +849,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             }
         }
         FC_TICK(t_post);
-        if (st.excess(t) == NK) break;
+        if (st.excess(t) >= NK) break;
         if (total_steps >= p.max_steps) { failed = true; break; }
 
         // ---- next level
@@ -819,7 +873,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             cur ^= 1;
         }
         if (!fast && rel_since > 0 && (rel_since >= p.gr_relabels || steps_since >= p.gr_steps || rises >= rise_limit) && d >= 1) {
-            global_relabel<COMPACT, RAT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG);
+            global_relabel<COMPACT, RAT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG, src, sa, sb);
             if (tid == 0) ++c_gr;
             rel_since = 0; steps_since = 0; rises = 0;
             d = rebuild_pending(st, n, t, cur ^ 1);
@@ -832,8 +886,9 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
 
     lds_barrier();
     if (tid == 0) {
-        p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : st.excess(t);
-        p.sink_cost[t] = uint32_t(total_steps) + 6u * c_gr + 1u;
+        const int32_t et = st.excess(t);
+        p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : (GEN && et > NK ? NK : et);    // "unbounded" is reported as one value
+        if (!GEN) p.sink_cost[t] = uint32_t(total_steps) + 6u * c_gr + 1u;
     }
     if (p.stats) {
 #ifndef FC_PHASE_TIMING
@@ -1094,9 +1149,9 @@ int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
     return FC_OK;
 }
 
-template <bool COMPACT, bool RAT, int G>
+template <bool COMPACT, bool RAT, bool GEN, int G>
 int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_t stream) {
-    auto kern = fc_push_relabel_kernel<COMPACT, RAT, G>;
+    auto kern = fc_push_relabel_kernel<COMPACT, RAT, GEN, G>;
     if (const char *pad = getenv("FC_LDS_PAD")) lds += size_t(atol(pad));     // tuning aid: occupancy experiments
     static size_t lds_allowed = 0;                  // per instantiation; raised on demand
     if (lds > lds_allowed) {
@@ -1108,14 +1163,14 @@ int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_
     return FC_OK;
 }
 
-template <bool COMPACT, bool RAT>
+template <bool COMPACT, bool RAT, bool GEN = false>
 int launch_g(const KParams &kp, long long P, int32_t T, int32_t G, size_t lds, hipStream_t stream) {
     switch (G) {
-        case 4: return launch_one<COMPACT, RAT, 4>(kp, P, T, lds, stream);
-        case 8: return launch_one<COMPACT, RAT, 8>(kp, P, T, lds, stream);
-        case 16: return launch_one<COMPACT, RAT, 16>(kp, P, T, lds, stream);
-        case 32: return launch_one<COMPACT, RAT, 32>(kp, P, T, lds, stream);
-        case 64: return launch_one<COMPACT, RAT, 64>(kp, P, T, lds, stream);
+        case 4: return launch_one<COMPACT, RAT, GEN, 4>(kp, P, T, lds, stream);
+        case 8: return launch_one<COMPACT, RAT, GEN, 8>(kp, P, T, lds, stream);
+        case 16: return launch_one<COMPACT, RAT, GEN, 16>(kp, P, T, lds, stream);
+        case 32: return launch_one<COMPACT, RAT, GEN, 32>(kp, P, T, lds, stream);
+        case 64: return launch_one<COMPACT, RAT, GEN, 64>(kp, P, T, lds, stream);
     }
     return FC_EINVAL;
 }
@@ -1128,6 +1183,27 @@ struct CandidateGrid { int32_t C; const int32_t *d_U, *d_k, *d_D; };    // d_D: 
 
 bool wants_order(const fc_graph *g, const Resolved &opt, long long P) { return opt.schedule && P > 2ll * g->n_cu; }
 
+// the fields every launch shares: topology, heuristics, nothing problem-specific
+void common_params(const fc_graph *g, const Resolved &opt, KParams *kp) {
+    std::memset(kp, 0, sizeof *kp);
+    kp->n = g->n; kp->N = g->N; kp->m0 = int32_t(g->m0);
+    kp->n_rec = std::max<int32_t>(1, int32_t(2 * g->m0));
+    {   // work-list entries of a global relabel: at most n (one per frontier vertex) + records / span <= 2n
+        const long long rec = 2 * g->m0, nn = std::max<int32_t>(1, g->n);
+        int32_t lanes = 4, shift = 2;
+        while (lanes < 64 && (long long)lanes * nn < rec) { lanes *= 2; ++shift; }
+        kp->gr_lanes = lanes; kp->gr_shift = shift;
+        kp->gr_sub = int32_t(std::max<long long>(1, (rec + (long long)lanes * nn - 1) / ((long long)lanes * nn)));
+    }
+    kp->row_ptr = g->d_row_ptr;
+    kp->arc_wide = reinterpret_cast<const int4 *>(g->d_arc_wide);
+    kp->is_compute = g->d_is_compute;
+    kp->compute_ids = g->d_compute_ids;
+    kp->in_bw = g->d_in_bw; kp->sink_cost = g->d_sink_cost; kp->sum_bw = g->sum_bw;
+    kp->gr_steps = opt.gr_steps; kp->gr_relabels = opt.gr_relabels; kp->gr_rises = opt.gr_rises;
+    kp->tight_pct = opt.tight_pct; kp->use_gap = opt.use_gap; kp->max_steps = opt.max_steps;
+}
+
 // Launch the solver kernels for P problems.  stats_ws: null, or room for P*FC_NSTAT u32 + FC_NSTAT u64.
 int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32_t *d_U, const int32_t *d_k,
               int32_t *d_flow, const Resolved &opt, hipStream_t stream, uint32_t *d_stats_pp, int32_t *d_order,
@@ -1135,17 +1211,7 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     const bool rational = grid ? grid->d_D != nullptr : d_Uden != nullptr;
     if (P > (1ll << 30)) return FC_EINVAL;
     KParams kp;
-    kp.n = g->n; kp.N = g->N; kp.m0 = int32_t(g->m0);
-    kp.n_rec = std::max<int32_t>(1, int32_t(2 * g->m0));
-    {   // work-list entries of a global relabel: at most n (one per frontier vertex) + records / span <= 2n
-        const long long rec = 2 * g->m0, nn = std::max<int32_t>(1, g->n);
-        int32_t lanes = 4, shift = 2;
-        while (lanes < 64 && (long long)lanes * nn < rec) { lanes *= 2; ++shift; }
-        kp.gr_lanes = lanes; kp.gr_shift = shift;
-        kp.gr_sub = int32_t(std::max<long long>(1, (rec + (long long)lanes * nn - 1) / ((long long)lanes * nn)));
-    }
-    kp.row_ptr = g->d_row_ptr;
-    kp.arc_wide = reinterpret_cast<const int4 *>(g->d_arc_wide);
+    common_params(g, opt, &kp);
     const bool compact_possible = !opt.force_wide && g->d_arc_compact != nullptr &&
                                   lds_bytes(g, true) <= size_t(g->lds_limit);
     bool wide_possible = lds_bytes(g, false) <= size_t(g->lds_limit);
@@ -1153,17 +1219,13 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     // the caller vouches that every N * k_j fits the 16-bit layout: skip the 32-bit launch
     if (compact_possible && opt.src_cap_bound > 0 && (long long)g->N * opt.src_cap_bound <= 65535ll) wide_possible = false;
     kp.arc_compact = compact_possible ? reinterpret_cast<const uint2 *>(g->d_arc_compact) : nullptr;
-    kp.is_compute = g->d_is_compute;
     kp.labels = opt.use_labels ? g->d_labels : nullptr;
     kp.label_hmax = g->d_label_hmax;
     kp.p1 = opt.use_labels ? reinterpret_cast<const uint4 *>(g->d_p1) : nullptr;
     kp.level_off = g->d_level_off;
     kp.tree_ratio = opt.tree_certificate && opt.use_labels && !rational ? g->d_tree_ratio : nullptr;   // the certificate's ratio test needs exact capacities U * b
     kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.Uden = d_Uden; kp.flow_out = d_flow; kp.stats = d_stats_pp;
-    kp.gr_steps = opt.gr_steps; kp.gr_relabels = opt.gr_relabels; kp.gr_rises = opt.gr_rises; kp.tight_pct = opt.tight_pct; kp.in_bw = g->d_in_bw; kp.sink_cost = g->d_sink_cost; kp.use_gap = opt.use_gap; kp.max_steps = opt.max_steps;
     kp.wide_available = wide_possible ? 1 : 0;
-    kp.order = nullptr;
-    kp.cand_C = 0; kp.cand_U = kp.cand_k = kp.cand_D = nullptr; kp.compute_ids = g->d_compute_ids;
     if (grid) {
         kp.cand_C = grid->C; kp.cand_U = grid->d_U; kp.cand_k = grid->d_k; kp.cand_D = grid->d_D;
         if (wants_order(g, opt, P)) {
@@ -1508,6 +1570,97 @@ extern "C" int fc_opt_throughput_search(const fc_graph *g, int32_t candidates_pe
     if (rounds_or_null) *rounds_or_null = rounds;
     if (trace_len_or_null) *trace_len_or_null = c.tlen;
     return FC_OK;
+}
+
+namespace {
+// gamma of Theorem 10 for one pair per workgroup: the smaller of the two capacities and of the two
+// slacks  min_v F - N k  over the pair's 2N flows.
+__global__ void __launch_bounds__(256) fc_split_gamma_kernel(int32_t N, int32_t n, int32_t U, int32_t k,
+                                                             const int32_t *pu, const int32_t *pw, const int32_t *pt,
+                                                             const int32_t *flows, const int32_t *row_ptr, const int4 *arcs,
+                                                             const uint8_t *is_compute, int32_t *gamma) {
+    __shared__ int32_t s_min, s_bad;
+    const int32_t i = blockIdx.x, tid = threadIdx.x;
+    if (tid == 0) { s_min = 0x7fffffff; s_bad = 0; }
+    __syncthreads();
+    int32_t best = 0x7fffffff, bad = 0;
+    for (int32_t r = tid; r < 2 * N; r += blockDim.x) {
+        const int32_t fl = flows[size_t(i) * size_t(2 * N) + size_t(r)];
+        if (fl < 0) bad = 1; else if (fl < best) best = fl;
+    }
+    if (bad) atomicOr(&s_bad, 1);
+    if (best != 0x7fffffff) atomicMin(&s_min, best);
+    __syncthreads();
+    if (tid == 0) {
+        const int32_t u = pu[i], w = pw[i], t = pt[i];
+        long long ce = -1, cf = -1;
+        if (!s_bad && u >= 0 && u < n && w >= 0 && w < n && t >= 0 && t < n && !is_compute[w]) {
+            for (int32_t a = row_ptr[u]; a < row_ptr[u + 1]; ++a) if ((arcs[a].w & 1) && arcs[a].x == w) ce = (long long)U * arcs[a].z;
+            for (int32_t a = row_ptr[w]; a < row_ptr[w + 1]; ++a) if ((arcs[a].w & 1) && arcs[a].x == t) cf = (long long)U * arcs[a].z;
+        }
+        if (ce < 1 || cf < 1) gamma[i] = FC_GAMMA_INVALID;           // not two links through a switch, or a failed flow
+        else {
+            long long gm = (long long)s_min - (long long)N * k;
+            if (ce < gm) gm = ce;
+            if (cf < gm) gm = cf;
+            gamma[i] = int32_t(gm);
+        }
+    }
+}
+}  // namespace
+
+extern "C" size_t fc_split_gamma_workspace_bytes(const fc_graph *g, int64_t n_pairs) {
+    if (!g || n_pairs < 0) return 0;
+    const long long P = (long long)n_pairs * 2 * g->N;
+    return align_up(size_t(P) * 4, 256) + stats_bytes(P);
+}
+
+extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int64_t n_pairs, const int32_t *d_u,
+                                    const int32_t *d_w, const int32_t *d_t, int32_t *d_gamma_out,
+                                    int32_t *d_flows_or_null, void *d_workspace, size_t workspace_bytes,
+                                    void *hip_stream, const fc_options *options_or_null, fc_stats *stats_or_null) {
+    if (!g || n_pairs < 0 || U < 1 || k < 1) return FC_EINVAL;
+    if (!g->on_device) return FC_EDEVICE;
+    Resolved opt;
+    int rc = resolve_options(g, options_or_null, &opt);
+    if (rc != FC_OK) return rc;
+    if (n_pairs == 0) { if (stats_or_null) std::memset(stats_or_null, 0, sizeof *stats_or_null); return FC_OK; }
+    if (!d_u || !d_w || !d_t || !d_gamma_out) return FC_EINVAL;
+    const long long P = (long long)n_pairs * 2 * g->N;
+    if (P > (1ll << 30)) return FC_EINVAL;
+    if ((long long)U * g->sum_bw + (long long)g->N * k + 1 >= (1ll << 30)) return FC_EOVERFLOW;
+    if (lds_bytes(g, false) > size_t(g->lds_limit)) return FC_EUNSUPPORTED;      // these problems use the 32-bit state
+    if (!d_workspace || workspace_bytes < fc_split_gamma_workspace_bytes(g, n_pairs) || (reinterpret_cast<uintptr_t>(d_workspace) & 255u)) return FC_EWORKSPACE;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    unsigned char *ws = reinterpret_cast<unsigned char *>(d_workspace);
+    const size_t slab = align_up(size_t(P) * 4, 256);
+    int32_t *d_flow = d_flows_or_null ? d_flows_or_null : reinterpret_cast<int32_t *>(ws);
+    uint32_t *d_pp = reinterpret_cast<uint32_t *>(ws + slab);
+    unsigned long long *d_tot = reinterpret_cast<unsigned long long *>(ws + slab + ws_totals_off(P));
+
+    KParams kp;
+    common_params(g, opt, &kp);                          // no per-sink tables, no launch order: every field left null
+    kp.split_u = d_u; kp.split_w = d_w; kp.split_t = d_t; kp.split_U = U; kp.split_k = k;
+    kp.flow_out = d_flow; kp.stats = stats_or_null ? d_pp : nullptr;
+    kp.wide_available = 1;
+
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    if (stats_or_null) {
+        HIP_TRY(hipEventCreate(&ev0));
+        if (hipEventCreate(&ev1) != hipSuccess) { (void)hipEventDestroy(ev0); return FC_EDEVICE; }
+    }
+    auto done = [&](int code) { if (ev0) (void)hipEventDestroy(ev0); if (ev1) (void)hipEventDestroy(ev1); return code; };
+    if (stats_or_null && hipEventRecord(ev0, stream) != hipSuccess) return done(FC_EDEVICE);
+    rc = launch_g<false, false, true>(kp, P, opt.T, opt.G, lds_bytes(g, false), stream);
+    if (rc != FC_OK) return done(rc);
+    if (stats_or_null && hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
+    hipLaunchKernelGGL(fc_split_gamma_kernel, dim3(unsigned(n_pairs)), dim3(256), 0, stream, g->N, g->n, U, k, d_u, d_w, d_t,
+                       d_flow, g->d_row_ptr, reinterpret_cast<const int4 *>(g->d_arc_wide), g->d_is_compute, d_gamma_out);
+    if (hipGetLastError() != hipSuccess) return done(FC_EDEVICE);
+    if (!stats_or_null) return done(FC_OK);
+    rc = fill_stats(P, d_pp, d_tot, stream, ev0, ev1, stats_or_null);
+    if (rc != FC_OK) return done(rc);
+    return done(stats_or_null->not_converged ? FC_ENOCONVERGE : FC_OK);
 }
 
 extern "C" int fc_fixed_k_search(const fc_graph *g, int32_t k, int32_t candidates_per_round, fc_rational *U_star,

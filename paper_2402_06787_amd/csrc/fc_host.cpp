@@ -76,6 +76,7 @@ int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const
             if (g->is_compute[v] && (min_in < 0 || in_bw[v] < min_in)) min_in = in_bw[v];
         }
         g->min_in_bw = min_in; g->max_bw = int32_t(mx); g->gcd_bw = int32_t(gc); g->eulerian = eul;
+        for (const Arc &a : arcs) g->sum_bw += a.b;
         g->in_bw.resize(size_t(n_vertices));
         for (int32_t v = 0; v < n_vertices; ++v) g->in_bw[v] = int32_t(in_bw[v]);
 

@@ -19,6 +19,7 @@ struct fc_graph {
     std::vector<uint8_t> is_compute;   // [n]
     std::vector<int32_t> compute_ids;  // [N] increasing
     std::vector<int32_t> in_bw;        // [n] in-bandwidth B^-(v) of every vertex
+    int64_t sum_bw = 0;                // sum of all link bandwidths
     int64_t min_in_bw = 0;         // min over compute nodes of B^-(v)
     int32_t max_bw = 0, gcd_bw = 0, eulerian = 0;
     int32_t max_row = 0;           // longest residual row

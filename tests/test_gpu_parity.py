@@ -409,3 +409,99 @@ def test_fixed_k_search_on_random_and_disconnected_graphs():
                 assert ei.value.code == fc.FC_EDISCONNECTED
                 continue
             assert fc.fc_fixed_k_search(g, k, 1 + seed % 7)["U_star"] == want, seed
+
+
+# ------------------------------------------------------------------ edge splitting: gamma of Theorem 10 (Appendix E.2)
+
+def _switch_pairs(topo):
+    cap = o.link_capacities(topo)
+    switches = [v for v in range(topo.n_vertices) if not topo.is_compute[v]]
+    return [(u, sw, t) for sw in switches for (u, x) in sorted(cap) if x == sw for (y, t) in sorted(cap) if y == sw]
+
+
+def _gamma_on_gpu(topo, U, k, pairs, want_flows=True):
+    pu, pw, pt = (np.array([p[i] for p in pairs], dtype=np.int32) for i in range(3))
+    with _upload(topo) as g:
+        res = fc.fc_split_gamma_batch(g, U, k, _dev(pu), _dev(pw), _dev(pt), want_flows=want_flows, want_stats=True)
+        torch.cuda.synchronize()
+    assert res["stats"]["not_converged"] == 0
+    return res["gamma"].cpu().numpy().astype(np.int64), (res["flows"].cpu().numpy().astype(np.int64) if want_flows else None)
+
+
+def _scaled(topo, U):
+    return w.Topology(topo.name, topo.n_vertices, topo.tail, topo.head,
+                      (np.asarray(topo.bandwidth, dtype=np.int64) * int(U)).astype(np.int32), topo.is_compute)
+
+
+def test_split_gamma_on_the_paper_example():
+    # Appendix E.2, stages figure: 10 b inside a box, b across boxes, nothing from the spine back into the same box
+    for U, k, b in ((1, 1, 1), (3, 3, 1), (1, 2, 2)):
+        topo = w.paper_example_switch(b)
+        pairs = _switch_pairs(topo)
+        got, flows = _gamma_on_gpu(topo, U, k, pairs)
+        D = _scaled(topo, U)
+        for i, (u, sw, t) in enumerate(pairs):
+            F1, F2 = o.split_flows(D, k, u, sw, t)
+            assert (flows[i, 0] == F1).all() and (flows[i, 1] == F2).all(), (U, k, b, u, sw, t)
+            assert got[i] == o.split_gamma(D, k, u, sw, t)
+        idx = {p: i for i, p in enumerate(pairs)}
+        if (U, k, b) == (1, 1, 1):
+            assert got[idx[(0, 8, 1)]] == 10 and got[idx[(0, 10, 4)]] == 1 and got[idx[(0, 10, 1)]] == 0
+
+
+def test_split_gamma_matches_oracle_on_random_eulerian_graphs():
+    checked = 0
+    for seed in range(40):
+        rng = np.random.default_rng(6000 + seed)
+        base = w.random_tiny(6000 + seed, n_vertices=int(rng.integers(4, 10)), max_cap=5, density=0.4)
+        if base.is_compute.all():
+            continue
+        cap = {}
+        for t, h, b in zip(base.tail.tolist(), base.head.tolist(), base.bandwidth.tolist()):
+            if t != h and b > 0:
+                key = (min(t, h), max(t, h)); cap[key] = cap.get(key, 0) + int(b)
+        tail = [a for a, b in cap] + [b for a, b in cap]; head = [b for a, b in cap] + [a for a, b in cap]
+        sym = w.Topology(f"euler{seed}", base.n_vertices, np.array(tail, dtype=np.int32), np.array(head, dtype=np.int32),
+                         np.array(list(cap.values()) * 2, dtype=np.int32), base.is_compute.copy())
+        try:
+            inv = o.optimality_binary_search(sym)
+        except o.Disconnected:
+            continue
+        Uq, k = o.smallest_U_k(inv, sym.bandwidth)
+        # integer multiplier for the library: scale k too when Proposition 3's U is a fraction
+        U, kk = Uq.numerator, k * Uq.denominator
+        pairs = _switch_pairs(sym)
+        if not pairs:
+            continue
+        # a pair that is no pair: (compute node in the middle) and (a missing link)
+        comp = [v for v in range(sym.n_vertices) if sym.is_compute[v]]
+        bogus = [(pairs[0][0], comp[0], pairs[0][2]), (pairs[0][1], pairs[0][1], pairs[0][2]), (-1, pairs[0][1], 99)]
+        got, flows = _gamma_on_gpu(sym, U, kk, pairs + bogus)
+        D = _scaled(sym, U)
+        for i, (u, sw, t) in enumerate(pairs):
+            F1, F2 = o.split_flows(D, kk, u, sw, t, algo="edmonds_karp" if seed % 2 else "dinic")
+            assert (flows[i, 0] == F1).all() and (flows[i, 1] == F2).all(), (seed, u, sw, t)
+            assert got[i] == o.split_gamma(D, kk, u, sw, t), (seed, u, sw, t)
+            assert got[i] >= 0
+        assert (got[len(pairs):] == fc.FC_GAMMA_INVALID).all()
+        checked += len(pairs)
+    assert checked > 200
+
+
+@pytest.mark.parametrize("cfg", [1, 3, 4])
+def test_split_gamma_on_configs(cfg):
+    # bidirectional (Eulerian) configs at their optimum (U, k) from Proposition 3; a sample of pairs per switch kind
+    topo = w.config_topology(cfg)
+    assert o.is_eulerian(topo)
+    inv = Fraction(*_optimum(cfg, topo))
+    Uq, k = o.smallest_U_k(inv, topo.bandwidth)
+    U, kk = Uq.numerator, k * Uq.denominator
+    pairs = _switch_pairs(topo)
+    rng = np.random.default_rng(cfg)
+    pick = [pairs[int(i)] for i in rng.permutation(len(pairs))[: (24 if cfg < 4 else 6)]]
+    got, flows = _gamma_on_gpu(topo, U, kk, pick)
+    D = _scaled(topo, U)
+    for i, (u, sw, t) in enumerate(pick):
+        F1, F2 = o.split_flows(D, kk, u, sw, t)
+        assert (flows[i, 0] == F1).all() and (flows[i, 1] == F2).all(), (cfg, u, sw, t)
+        assert got[i] == o.split_gamma(D, kk, u, sw, t)
