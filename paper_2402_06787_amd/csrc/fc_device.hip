@@ -1651,7 +1651,9 @@ extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int
     }
     auto done = [&](int code) { if (ev0) (void)hipEventDestroy(ev0); if (ev1) (void)hipEventDestroy(ev1); return code; };
     if (stats_or_null && hipEventRecord(ev0, stream) != hipSuccess) return done(FC_EDEVICE);
-    rc = launch_g<false, false, true>(kp, P, opt.T, opt.G, lds_bytes(g, false), stream);
+    // these problems start without tables, in worklist mode: fewer wavefronts per problem pay off
+    const int32_t T_gen = (options_or_null && options_or_null->threads_per_problem) ? opt.T : (g->n >= 256 ? 128 : 64);
+    rc = launch_g<false, false, true>(kp, P, T_gen, opt.G, lds_bytes(g, false), stream);
     if (rc != FC_OK) return done(rc);
     if (stats_or_null && hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
     hipLaunchKernelGGL(fc_split_gamma_kernel, dim3(unsigned(n_pairs)), dim3(256), 0, stream, g->N, g->n, U, k, d_u, d_w, d_t,
