@@ -14,7 +14,8 @@ the paper (ForestColl, arXiv 2402.06787):
   Section 4 (`brute_inv_xstar`).
 * (U, k) by the gcd rule of Section 5.2 "Determine k" / Proposition 3 (`smallest_U_k`).
 * edge splitting (Appendix E.2): the 2N max-flows and gamma of Theorem 10 (`split_flows`,
-  `split_gamma`), gamma by its definition (`brute_split_gamma`), the split graph (`split_off`).
+  `split_gamma`), gamma by its definition (`brute_split_gamma`), the split graph (`split_off`), and the loop of
+  Algorithm 2 around them (`remove_switches`).
 * the fixed-k variant (Section 5.5, Appendix E.4): the verdict on the network with capacities
   floor(U b_e) for a rational U (`fixed_k_feasible`), U* by Algorithm 3 taken literally in
   exact rationals (`fixed_k_binary_search`), or by trying every fraction j / b_e
@@ -438,6 +439,34 @@ def brute_split_gamma(topo, k, u, w, t, algo="dinic"):
     best = max(a for a in range(top + 1) if ok[a])
     assert all(ok[: best + 1]), "feasible split amounts form a prefix"
     return best
+
+
+def remove_switches(topo, k, algo="dinic"):
+    """Algorithm 2 (Remove Switch Nodes) on the integer-capacity Eulerian digraph D = topo: for every
+    switch w, every egress link f = (w, t) and every ingress link e = (u, w), split off gamma (Theorem 10)
+    when it is positive.  Switches, egress heads and ingress tails are visited in increasing id order;
+    the links of w are listed when the loop over them starts, as in the pseudocode.  Returns (D*, table)
+    with D* the resulting compute-only digraph and table[(u, t)][w] the capacity of (u, t) that is
+    routed through switch w (the path recovery table)."""
+    D = topo
+    table = {}
+    for w in [v for v in range(topo.n_vertices) if not topo.is_compute[v]]:
+        for t in sorted(h for (a, h) in link_capacities(D) if a == w):
+            for u in sorted(a for (a, h) in link_capacities(D) if h == w):
+                cap = link_capacities(D)
+                if (w, t) not in cap:
+                    break                                   # f has been used up
+                if (u, w) not in cap:
+                    continue
+                g = split_gamma(D, k, u, w, t, algo)
+                if g > 0:
+                    D = split_off(D, u, w, t, g)
+                    if u != t:
+                        table.setdefault((u, t), {})
+                        table[(u, t)][w] = table[(u, t)].get(w, 0) + g
+            if (w, t) in link_capacities(D):
+                raise AssertionError("an egress link of a switch could not be split off completely (Theorem 9)")
+    return D, table
 
 
 # ------------------------------------------------------------------ brute force (tiny graphs only)

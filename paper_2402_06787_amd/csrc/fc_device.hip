@@ -1152,7 +1152,9 @@ int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
 template <bool COMPACT, bool RAT, bool GEN, int G>
 int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_t stream) {
     auto kern = fc_push_relabel_kernel<COMPACT, RAT, GEN, G>;
-    if (const char *pad = getenv("FC_LDS_PAD")) lds += size_t(atol(pad));     // tuning aid: occupancy experiments
+#ifdef FC_TUNING_BUILD
+    if (const char *pad = getenv("FC_LDS_PAD")) lds += size_t(atol(pad));     // occupancy experiments: request more LDS than needed
+#endif
     static size_t lds_allowed = 0;                  // per instantiation; raised on demand
     if (lds > lds_allowed) {
         HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));

@@ -180,14 +180,13 @@ int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &
                 for (int32_t i = 0; i < lvl_start[0]; ++i) {             // order[] is by decreasing level
                     const int32_t v = order[i];
                     double best = 0; int32_t best_r = -1;
-                    static const bool first_only = std::getenv("FC_TREE_FIRST") != nullptr;   // tuning aid: unbalanced tree
                     for (int32_t r = g->row_ptr[v]; r < g->row_ptr[v + 1]; ++r) {
                         if (!g->fwd[r]) continue;
                         const int32_t q = g->other[r];
                         if (dist[q] + 1 != dist[v]) continue;
                         double cost = double(wt[v]) / double(g->bw[r]);
                         if (q != t && cap_down[q] > 0) cost = std::max(cost, double(load[q] + wt[v]) / double(cap_down[q]));
-                        if (best_r < 0 || (cost < best && !first_only)) { best = cost; best_r = r; }
+                        if (best_r < 0 || cost < best) { best = cost; best_r = r; }
                     }
                     parent_rec[v] = best_r;                               // exists: v has a finite label >= 1
                     const int32_t q = g->other[best_r];

@@ -446,3 +446,45 @@ def test_switch_removal_by_repeated_splitting_keeps_the_optimum():
         assert o.feasible(D, 1, k)[0]
         done += 1
     assert done >= 6
+
+
+def _check_switch_removal(D, k, Dstar, table):
+    cap0, cap1 = o.link_capacities(D), o.link_capacities(Dstar)
+    assert all(D.is_compute[a] and D.is_compute[b] for a, b in cap1)          # every switch is isolated
+    assert o.is_eulerian(Dstar) and o.feasible(Dstar, 1, k)[0]                  # Theorem 9: the condition survives
+    # the table accounts for exactly the capacity that was added between compute nodes (a link that touches a
+    # switch may be created by one split and used up by a later one: the recovery of paths is recursive) ...
+    for key in set(cap1) | set(table):
+        if D.is_compute[key[0]] and D.is_compute[key[1]]:
+            assert cap1.get(key, 0) == cap0.get(key, 0) + sum(table.get(key, {}).values()), key
+    # ... and no switch relays more than entered it
+    total_in = sum(c for (a, b), c in cap0.items() if not D.is_compute[b])
+    for sw in [v for v in range(D.n_vertices) if not D.is_compute[v]]:
+        relayed = sum(amount for routes in table.values() for s2, amount in routes.items() if s2 == sw)
+        assert relayed <= total_in           # what a switch relays entered some switch (its own links, or links made for it)
+
+
+def test_remove_switches_on_the_paper_example():
+    for b, U, k in ((1, 1, 1), (2, 1, 2)):
+        D = w.paper_example_switch(b)
+        D = w.Topology(D.name, D.n_vertices, D.tail, D.head, (D.bandwidth * U).astype(np.int32), D.is_compute)
+        Dstar, table = o.remove_switches(D, k)
+        _check_switch_removal(D, k, Dstar, table)
+        # in-box traffic stays on the box switch, cross-box traffic goes over the spine (the remark under the stages figure)
+        for (u, t), routes in table.items():
+            for sw in routes:
+                assert sw == (8 + u // 4 if u // 4 == t // 4 else 10), (u, t, sw)
+        # the optimum of the example survives the removal: 1/x* = 1/b, so with these capacities k / U trees fit
+        assert o.optimality_binary_search(Dstar) == Fraction(U, k * b) * b
+
+
+@pytest.mark.parametrize("seed", range(25))
+def test_remove_switches_on_random_eulerian_graphs(seed):
+    made = _scaled_eulerian(200 + seed)
+    if made is None:
+        return
+    D, k = made
+    Dstar, table = o.remove_switches(D, k, algo=ALGOS[seed % 2])
+    _check_switch_removal(D, k, Dstar, table)
+    # the optimum cannot improve, and D itself was at its optimum 1/x* = 1/k (scaled by Proposition 3)
+    assert o.optimality_binary_search(Dstar) == o.optimality_binary_search(D) == Fraction(1, k)
