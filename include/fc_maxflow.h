@@ -274,6 +274,23 @@ int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int64_t n_pair
                          void *d_workspace, size_t workspace_bytes, void *hip_stream,
                          const fc_options *options_or_null, fc_stats *stats_or_null);
 
+/* Algorithm 2 (Remove Switch Nodes, Appendix E.2) on the integer-capacity Eulerian digraph D given as host
+ * arrays (capacity = number of multi-edges; parallel arcs add, self-loops and zero capacities are ignored): for
+ * every switch w, every egress link f = (w, t) and every ingress link e = (u, w), in increasing id order, split
+ * off gamma (fc_split_gamma_batch, U = 1) when it is positive.  Outputs (host, caller-allocated): the links of the
+ * compute-only digraph D* and the path recovery table as rows (u, t, w, amount): `amount` of the capacity of
+ * (u, t) was routed through switch w.  *n_out / *n_routes receive the row counts; if a capacity argument is too
+ * small the call returns FC_EWORKSPACE with the counts set and nothing else written.  n_batches_or_null counts the
+ * gamma launches.  Every batch re-uploads the current graph, so this is a driver for graphs that fit the 32-bit
+ * on-chip state, not a tuned stage.  Errors: FC_EINVAL (also: D not Eulerian), FC_ENOCONVERGE (an egress link
+ * could not be used up: min_v F(s, v) >= N k did not hold in D), FC_EOVERFLOW, FC_EUNSUPPORTED, FC_EDEVICE, FC_ENOMEM. */
+int fc_remove_switches(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
+                       const int32_t *capacity, const uint8_t *is_compute, int32_t k,
+                       int64_t out_capacity, int64_t *n_out, int32_t *out_tail, int32_t *out_head, int32_t *out_cap,
+                       int64_t route_capacity, int64_t *n_routes, int32_t *route_u, int32_t *route_t,
+                       int32_t *route_w, int32_t *route_amount, int64_t *n_batches_or_null,
+                       void *hip_stream, const fc_options *options_or_null);
+
 const char *fc_strerror(int code);
 
 #ifdef __cplusplus

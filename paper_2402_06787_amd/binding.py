@@ -25,7 +25,7 @@ FC_GAMMA_INVALID = -2147483648
 EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_free", "fc_graph_info", "fc_graph_csr",
             "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_maxflow_batch_floor", "fc_feasible_workspace_bytes",
             "fc_feasible_floor", "fc_fixed_k_search", "fc_fixed_k_search_with_verdicts",
-            "fc_split_gamma_workspace_bytes", "fc_split_gamma_batch",
+            "fc_split_gamma_workspace_bytes", "fc_split_gamma_batch", "fc_remove_switches",
             "fc_feasible", "fc_opt_throughput_search", "fc_search_with_verdicts", "fc_strerror"]
 
 
@@ -114,6 +114,9 @@ def load_library():
     lib.fc_split_gamma_workspace_bytes.argtypes = [vp, i64]
     lib.fc_split_gamma_batch.restype = c.c_int
     lib.fc_split_gamma_batch.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp, vp, vp, sz, vp, c.POINTER(fc_options), c.POINTER(fc_stats)]
+    lib.fc_remove_switches.restype = c.c_int
+    lib.fc_remove_switches.argtypes = [i32, i64, vp, vp, vp, vp, i32, i64, c.POINTER(i64), vp, vp, vp,
+                                       i64, c.POINTER(i64), vp, vp, vp, vp, c.POINTER(i64), vp, c.POINTER(fc_options)]
     lib.fc_strerror.restype = c.c_char_p
     lib.fc_strerror.argtypes = [c.c_int]
     _lib = lib
@@ -456,3 +459,31 @@ def fc_split_gamma_batch(g: Graph, U: int, k: int, d_u, d_w, d_t, want_flows=Fal
     _check(rc, "fc_split_gamma_batch")
     return {"gamma": gamma, "flows": flows.view(n_pairs, 2, N) if flows is not None else None,
             "stats": st.as_dict() if st is not None else None}
+
+
+def fc_remove_switches(n_vertices, tail, head, capacity, is_compute, k: int, stream=None, options=None):
+    """Algorithm 2 on the integer-capacity Eulerian digraph given as host arrays.  Returns dict(links={(u, t): cap},
+    table={(u, t): {w: amount}}, batches=int)."""
+    c = ctypes
+    lib = load_library()
+    tail = _np(tail, np.int32); head = _np(head, np.int32); capacity = _np(capacity, np.int32)
+    is_compute = _np(is_compute, np.uint8)
+    n_out, n_routes, batches = c.c_int64(0), c.c_int64(0), c.c_int64(0)
+    out_cap, route_cap = 0, 0
+    for _ in range(2):                                   # first call sizes the outputs when they do not fit
+        ot = np.zeros(max(out_cap, 1), np.int32); oh = np.zeros_like(ot); oc = np.zeros_like(ot)
+        ru = np.zeros(max(route_cap, 1), np.int32); rt = np.zeros_like(ru); rw = np.zeros_like(ru); ra = np.zeros_like(ru)
+        rc = lib.fc_remove_switches(int(n_vertices), int(tail.shape[0]), _host_ptr(tail), _host_ptr(head), _host_ptr(capacity),
+                                    _host_ptr(is_compute), int(k), out_cap, c.byref(n_out), _host_ptr(ot), _host_ptr(oh),
+                                    _host_ptr(oc), route_cap, c.byref(n_routes), _host_ptr(ru), _host_ptr(rt), _host_ptr(rw),
+                                    _host_ptr(ra), c.byref(batches), _stream_ptr(stream), _opts(options))
+        if rc == FC_EWORKSPACE and (n_out.value > out_cap or n_routes.value > route_cap):
+            out_cap, route_cap = int(n_out.value), int(n_routes.value)
+            continue
+        break
+    _check(rc, "fc_remove_switches")
+    links = {(int(ot[i]), int(oh[i])): int(oc[i]) for i in range(n_out.value)}
+    table = {}
+    for i in range(n_routes.value):
+        table.setdefault((int(ru[i]), int(rt[i])), {})[int(rw[i])] = int(ra[i])
+    return {"links": links, "table": table, "batches": int(batches.value)}

@@ -20,6 +20,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <map>
 #include <vector>
 
 #include "fc_internal.h"
@@ -1286,8 +1287,10 @@ size_t stats_bytes(long long P) { return ws_order_off(P) + align_up(size_t(P) * 
 
 // ------------------------------------------------------------------------------------------ C ABI
 
-extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
-                               const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out) {
+namespace {
+// with_tables = false skips the per-sink tables (for graphs that are only used by calls that cannot use them)
+int upload_impl(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
+                const int32_t *bandwidth, const uint8_t *is_compute, bool with_tables, fc_graph **out) {
     if (!out) return FC_EINVAL;
     fc_graph *g = nullptr;
     int rc = fc_host_build(n_vertices, n_arcs, tail, head, bandwidth, is_compute, &g);
@@ -1332,7 +1335,7 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
         // per-sink tables (built on the host from the topology alone), while they stay small: exact
         // initial labels (n^2 x 2 bytes) and, for graphs that fit the 16-bit record layout, first-pass
         // entries in level order (n^2 x 16 bytes)
-        if (n <= 8192) {
+        if (with_tables && n <= 8192) {
             const bool with_p1 = compact_ids_fit(g) && n <= 4096;
             std::vector<uint16_t> labels, hmax, level_off; std::vector<uint32_t> p1; std::vector<int32_t> tree_ratio;
             bool too_deep = false;
@@ -1356,6 +1359,12 @@ extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t
     }
     *out = g;
     return FC_OK;
+}
+}  // namespace
+
+extern "C" int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
+                               const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out) {
+    return upload_impl(n_vertices, n_arcs, tail, head, bandwidth, is_compute, true, out);
 }
 
 extern "C" int fc_graph_free(fc_graph *g) {
@@ -1695,4 +1704,118 @@ extern "C" int fc_fixed_k_search(const fc_graph *g, int32_t k, int32_t candidate
     if (rounds_or_null) *rounds_or_null = rounds;
     if (trace_len_or_null) *trace_len_or_null = c.tlen;
     return FC_OK;
+}
+
+// Algorithm 2 (Remove Switch Nodes, Appendix E.2) around the gamma batches: host loop, one batch per accepted
+// split.  For a fixed egress link f = (w, t) the gammas of all remaining ingress links are evaluated on the
+// current graph in one launch; the first positive one (in ingress order) is applied -- the ones before it are
+// zero on this very graph, exactly what the one-at-a-time loop of the pseudocode would have found -- and the
+// rest is evaluated again on the new graph.
+extern "C" int fc_remove_switches(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
+                                  const int32_t *capacity, const uint8_t *is_compute, int32_t k,
+                                  int64_t out_capacity, int64_t *n_out, int32_t *out_tail, int32_t *out_head, int32_t *out_cap,
+                                  int64_t route_capacity, int64_t *n_routes, int32_t *route_u, int32_t *route_t,
+                                  int32_t *route_w, int32_t *route_amount, int64_t *n_batches_or_null,
+                                  void *hip_stream, const fc_options *options_or_null) {
+    if (n_vertices < 1 || n_arcs < 0 || k < 1 || !is_compute || !n_out || !n_routes || out_capacity < 0 || route_capacity < 0 ||
+        (n_arcs > 0 && (!tail || !head || !capacity))) return FC_EINVAL;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    typedef std::pair<int32_t, int32_t> Key;
+    try {
+        std::map<Key, long long> cap;
+        for (int64_t i = 0; i < n_arcs; ++i) {
+            if (tail[i] < 0 || tail[i] >= n_vertices || head[i] < 0 || head[i] >= n_vertices || capacity[i] < 0) return FC_EINVAL;
+            if (tail[i] != head[i] && capacity[i] > 0) cap[Key(tail[i], head[i])] += capacity[i];
+        }
+        {   // Theorems 9 and 10 are about Eulerian digraphs
+            std::vector<long long> bal(size_t(n_vertices), 0);
+            for (const auto &kv : cap) { bal[size_t(kv.first.first)] -= kv.second; bal[size_t(kv.first.second)] += kv.second; }
+            for (long long b : bal) if (b != 0) return FC_EINVAL;
+        }
+        std::map<Key, std::map<int32_t, long long>> table;
+        int64_t batches = 0;
+        std::vector<int32_t> at, ah, ab, pu, pw, pt, gam;
+        int32_t *d_pairs = nullptr, *d_gamma = nullptr; void *d_ws = nullptr; size_t ws_have = 0; int64_t pairs_have = 0;
+        auto cleanup = [&]() { if (d_pairs) (void)hipFree(d_pairs); if (d_gamma) (void)hipFree(d_gamma); if (d_ws) (void)hipFree(d_ws); };
+        for (int32_t w = 0; w < n_vertices; ++w) {
+            if (is_compute[w]) continue;
+            std::vector<int32_t> egress;
+            for (auto it = cap.lower_bound(Key(w, 0)); it != cap.end() && it->first.first == w; ++it) egress.push_back(it->first.second);
+            for (int32_t t : egress) {
+                std::vector<int32_t> ingress;
+                for (const auto &kv : cap) if (kv.first.second == w) ingress.push_back(kv.first.first);
+                size_t pos = 0;
+                while (pos < ingress.size() && cap.count(Key(w, t))) {
+                    pu.clear(); pw.clear(); pt.clear();
+                    std::vector<size_t> which;
+                    for (size_t j = pos; j < ingress.size(); ++j)
+                        if (cap.count(Key(ingress[j], w))) { pu.push_back(ingress[j]); pw.push_back(w); pt.push_back(t); which.push_back(j); }
+                    if (pu.empty()) break;
+                    at.clear(); ah.clear(); ab.clear();
+                    for (const auto &kv : cap) {
+                        if (kv.second >= (1ll << 31)) { cleanup(); return FC_EOVERFLOW; }
+                        at.push_back(kv.first.first); ah.push_back(kv.first.second); ab.push_back(int32_t(kv.second));
+                    }
+                    fc_graph *g = nullptr;
+                    int rc = upload_impl(n_vertices, int64_t(at.size()), at.data(), ah.data(), ab.data(), is_compute, false, &g);
+                    if (rc != FC_OK) { cleanup(); return rc; }
+                    const int64_t np = int64_t(pu.size());
+                    const size_t need = fc_split_gamma_workspace_bytes(g, np);
+                    if (np > pairs_have) {
+                        if (d_pairs) (void)hipFree(d_pairs); if (d_gamma) (void)hipFree(d_gamma);
+                        d_pairs = nullptr; d_gamma = nullptr; pairs_have = 0;
+                        if (hipMalloc(&d_pairs, sizeof(int32_t) * 3 * size_t(np)) != hipSuccess || hipMalloc(&d_gamma, sizeof(int32_t) * size_t(np)) != hipSuccess) { fc_graph_free(g); cleanup(); return FC_EDEVICE; }
+                        pairs_have = np;
+                    }
+                    if (need > ws_have) {
+                        if (d_ws) (void)hipFree(d_ws);
+                        d_ws = nullptr; ws_have = 0;
+                        if (hipMalloc(&d_ws, need) != hipSuccess) { fc_graph_free(g); cleanup(); return FC_EDEVICE; }
+                        ws_have = need;
+                    }
+                    bool ok = hipMemcpyAsync(d_pairs, pu.data(), sizeof(int32_t) * size_t(np), hipMemcpyHostToDevice, stream) == hipSuccess &&
+                              hipMemcpyAsync(d_pairs + np, pw.data(), sizeof(int32_t) * size_t(np), hipMemcpyHostToDevice, stream) == hipSuccess &&
+                              hipMemcpyAsync(d_pairs + 2 * np, pt.data(), sizeof(int32_t) * size_t(np), hipMemcpyHostToDevice, stream) == hipSuccess;
+                    if (ok) {
+                        rc = fc_split_gamma_batch(g, 1, k, np, d_pairs, d_pairs + np, d_pairs + 2 * np, d_gamma, nullptr, d_ws, ws_have, stream, options_or_null, nullptr);
+                        gam.assign(size_t(np), 0);
+                        ok = rc == FC_OK && hipMemcpyAsync(gam.data(), d_gamma, sizeof(int32_t) * size_t(np), hipMemcpyDeviceToHost, stream) == hipSuccess &&
+                             hipStreamSynchronize(stream) == hipSuccess;
+                    }
+                    fc_graph_free(g);
+                    ++batches;
+                    if (!ok) { cleanup(); return rc != FC_OK ? rc : FC_EDEVICE; }
+                    size_t hit = which.size();
+                    for (size_t q = 0; q < which.size(); ++q) {
+                        if (gam[q] < 0) { cleanup(); return FC_ENOCONVERGE; }     // invalid, or min_v F(s, v) >= N k does not hold in D
+                        if (gam[q] > 0) { hit = q; break; }
+                    }
+                    if (hit == which.size()) break;                          // no ingress link can give anything to f
+                    const int32_t u = pu[hit]; const long long gmm = gam[hit];
+                    auto take = [&](Key key) { auto it = cap.find(key); it->second -= gmm; if (it->second == 0) cap.erase(it); };
+                    take(Key(u, w)); take(Key(w, t));
+                    if (u != t) { cap[Key(u, t)] += gmm; table[Key(u, t)][w] += gmm; }   // a detour u -> w -> u just disappears
+                    pos = which[hit] + 1;
+                }
+                if (cap.count(Key(w, t))) { cleanup(); return FC_ENOCONVERGE; }   // Theorem 9 promises f can be used up: the input broke its conditions
+            }
+        }
+        cleanup();
+        int64_t nr = 0;
+        for (const auto &kv : table) nr += int64_t(kv.second.size());
+        *n_out = int64_t(cap.size()); *n_routes = nr;
+        if (n_batches_or_null) *n_batches_or_null = batches;
+        if (int64_t(cap.size()) > out_capacity || nr > route_capacity) return FC_EWORKSPACE;    // sizes are set: call again with room
+        int64_t i = 0;
+        for (const auto &kv : cap) {
+            if (kv.second >= (1ll << 31)) return FC_EOVERFLOW;
+            out_tail[i] = kv.first.first; out_head[i] = kv.first.second; out_cap[i] = int32_t(kv.second); ++i;
+        }
+        i = 0;
+        for (const auto &kv : table)
+            for (const auto &rw : kv.second) { route_u[i] = kv.first.first; route_t[i] = kv.first.second; route_w[i] = rw.first; route_amount[i] = int32_t(rw.second); ++i; }
+        return FC_OK;
+    } catch (const std::bad_alloc &) {
+        return FC_ENOMEM;
+    }
 }

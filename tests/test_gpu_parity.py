@@ -505,3 +505,73 @@ def test_split_gamma_on_configs(cfg):
         F1, F2 = o.split_flows(D, kk, u, sw, t)
         assert (flows[i, 0] == F1).all() and (flows[i, 1] == F2).all(), (cfg, u, sw, t)
         assert got[i] == o.split_gamma(D, kk, u, sw, t)
+
+
+# ------------------------------------------------------------------ Algorithm 2: the switch-removal loop around the gamma batches
+
+def _remove_on_gpu(D, k):
+    return fc.fc_remove_switches(D.n_vertices, D.tail, D.head, D.bandwidth, D.is_compute, k)
+
+
+def test_remove_switches_matches_oracle_on_the_paper_example():
+    for b, U, k in ((1, 1, 1), (2, 3, 6)):
+        D = _scaled(w.paper_example_switch(b), U)
+        want, table = o.remove_switches(D, k)
+        got = _remove_on_gpu(D, k)
+        assert got["links"] == o.link_capacities(want) and got["table"] == table
+        assert got["batches"] >= 1
+
+
+def test_remove_switches_matches_oracle_on_random_eulerian_graphs():
+    done = 0
+    for seed in range(30):
+        rng = np.random.default_rng(8000 + seed)
+        base = w.random_tiny(8000 + seed, n_vertices=int(rng.integers(4, 9)), max_cap=4, density=0.4)
+        if base.is_compute.all():
+            continue
+        cap = {}
+        for t, h, b in zip(base.tail.tolist(), base.head.tolist(), base.bandwidth.tolist()):
+            if t != h and b > 0:
+                key = (min(t, h), max(t, h)); cap[key] = cap.get(key, 0) + int(b)
+        tail = [a for a, b in cap] + [b for a, b in cap]; head = [b for a, b in cap] + [a for a, b in cap]
+        sym = w.Topology(f"euler{seed}", base.n_vertices, np.array(tail, dtype=np.int32), np.array(head, dtype=np.int32),
+                         np.array(list(cap.values()) * 2, dtype=np.int32), base.is_compute.copy())
+        try:
+            inv = o.optimality_binary_search(sym)
+        except o.Disconnected:
+            continue
+        Uq, k = o.smallest_U_k(inv, sym.bandwidth)
+        D = _scaled(sym, Uq.numerator)
+        kk = k * Uq.denominator
+        want, table = o.remove_switches(D, kk, algo="edmonds_karp" if seed % 2 else "dinic")
+        got = _remove_on_gpu(D, kk)
+        assert got["links"] == o.link_capacities(want), seed
+        assert got["table"] == table, seed
+        done += 1
+    assert done >= 15
+    # not Eulerian: refused; Eulerian but the condition min F >= N k fails: reported
+    bad = w.directed_ring(4, 3)
+    bad = w.Topology("noneuler", 4, np.append(bad.tail, 0).astype(np.int32), np.append(bad.head, 2).astype(np.int32),
+                     np.append(bad.bandwidth, 1).astype(np.int32), bad.is_compute)
+    with pytest.raises(fc.FcError) as ei:
+        _remove_on_gpu(bad, 1)
+    assert ei.value.code == fc.FC_EINVAL
+    D = w.paper_example_switch(1)
+    with pytest.raises(fc.FcError) as ei:
+        _remove_on_gpu(D, 3)                               # the example carries k = 1 at these capacities, not 3
+    assert ei.value.code == fc.FC_ENOCONVERGE
+
+
+def test_remove_switches_on_config1():
+    topo = w.config_topology(1)
+    inv = Fraction(*_optimum(1, topo))
+    Uq, k = o.smallest_U_k(inv, topo.bandwidth)
+    D = _scaled(topo, Uq.numerator)
+    kk = k * Uq.denominator
+    want, table = o.remove_switches(D, kk)
+    got = _remove_on_gpu(D, kk)
+    assert got["links"] == o.link_capacities(want) and got["table"] == table
+    Dstar = w.Topology("star", D.n_vertices, np.array([a for a, _ in got["links"]], dtype=np.int32),
+                       np.array([b for _, b in got["links"]], dtype=np.int32),
+                       np.array(list(got["links"].values()), dtype=np.int32), D.is_compute)
+    assert o.feasible(Dstar, 1, kk)[0] and o.is_eulerian(Dstar)
