@@ -8,7 +8,7 @@ paper's Section 5.2 (preflow initialisation, discharge sweeps, relabeling, termi
 the per-candidate verdict reduction of Theorem 1.  The topology is uploaded once, outside the
 timed region; candidate arrays are resident in HBM when the clock starts.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (max-flow solves per second), roofline, cpu_baseline and side measurements.
 """
 import argparse
 import json

@@ -12,6 +12,11 @@
 // (excess k_j at every compute node, the sink included) and, because s keeps the largest height,
 // nothing is ever pushed back to it.  F(s, v_j) is the excess collected at the sink when no
 // vertex that can still reach the sink holds excess (min-cut theorem, Appendix E preamble).
+//
+// The same kernel is instantiated three ways: integer multipliers U (Section 5.2, Appendix E.1),
+// rational multipliers with capacities floor(U b_e) (fixed k, Section 5.5 / Algorithm 3), and the
+// max-flows with an explicit source and unbounded arcs that edge splitting needs (Appendix E.2,
+// Theorem 10).  Host code at the end: option handling, launches, and the entry points.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -467,6 +472,9 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
 // Group part: G lanes scan the residual row of one listed vertex in chunks, give all excess to the
 // first admissible arc when it suffices, else split it by a segmented prefix sum in row order, and
 // collect the smallest residual-neighbour height for the relabel in the same scan.
+//
+// Template flags: COMPACT = 16-bit on-chip state, RAT = rational multipliers (floor capacities),
+// GEN = an edge-splitting problem (explicit source, "unbounded" arcs, no tables), G = lanes per vertex.
 template <bool COMPACT, bool RAT, bool GEN, int G>
 __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) fc_push_relabel_kernel(KParams p) {
     static_assert(!GEN || (!COMPACT && !RAT), "the edge-splitting problems use the 32-bit state and integer multipliers");
