@@ -65,6 +65,7 @@ struct KParams {
     const int32_t *in_bw;        // [n] in-bandwidth of every vertex
     int32_t wide_available;      // the 32-bit-state kernel is launched too
     const int32_t *order;        // workgroup -> problem (hardest first), or null for the identity
+    int32_t n_order;             // entries of `order`: an entry outside [0, n_order) is never followed
     // candidate x sink launches (fc_feasible): workgroup b solves candidate b % cand_C for the sink that
     // has place b / cand_C in the order; the problem list is never written out
     int32_t cand_C;              // 0: plain problem list
@@ -505,10 +506,12 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
         const int32_t place = oct * 8 + xcd;
         if (place >= p.N) return;                         // the last group of eight may be short
         const int32_t i = p.order ? p.order[place] : place;
+        if (p.order && (i < 0 || i >= p.n_order)) return;
         j = c * p.N + i; t = p.compute_ids[i]; U = p.cand_U[c]; k = p.cand_k[c];
         if (RAT) D = p.cand_D[c];
     } else {
         j = p.order ? p.order[blockIdx.x] : int32_t(blockIdx.x);
+        if (p.order && (j < 0 || j >= p.n_order)) return;
         t = p.sink[j]; U = p.U[j]; k = p.k[j];
         if (RAT) D = p.Uden[j];
     }
@@ -988,7 +991,7 @@ __device__ __forceinline__ void order_bucket_bases(const int32_t *hist, int32_t 
 __global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, int32_t N, const int32_t *sink,
                                                         const int32_t *U, const int32_t *k, const int32_t *in_bw,
                                                         const uint8_t *is_compute, const uint32_t *sink_cost,
-                                                        int32_t *order, const int32_t *Uden) {
+                                                        int32_t *order, const int32_t *Uden, uint8_t *keys) {
     constexpr int NB = FC_ORDER_BUCKETS, R = 8;
     // a rational multiplier U / Uden only enters the guess for sinks without history: its integer part will do
     auto mult = [&](long long jj) { const int32_t u = U[jj]; if (!Uden) return u; const int32_t dd = Uden[jj]; return dd >= 1 && u >= dd ? u / dd : (u >= 1 && dd >= 1 ? 1 : 0); };
@@ -1005,7 +1008,12 @@ __global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, 
             b[r] = jj < P ? order_bucket(sink[jj], mult(jj), k[jj], n, N, in_bw, is_compute, sink_cost) : -1;
         }
 #pragma unroll
-        for (int r = 0; r < R; ++r) (void)wave_bucket_add(hist, b[r], b[r] >= 0);
+        for (int r = 0; r < R; ++r) {
+            (void)wave_bucket_add(hist, b[r], b[r] >= 0);
+            // the key is kept: the cost hints may change under a concurrent call on another stream, and the
+            // second pass must see the very buckets the first one counted
+            if (b[r] >= 0) keys[j0 + (long long)r * T + tid] = uint8_t(b[r]);
+        }
     }
     __syncthreads();
     if (tid < 64) order_bucket_bases(hist, base, tid);
@@ -1015,7 +1023,7 @@ __global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, 
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const long long jj = j0 + (long long)r * T + tid;
-            b[r] = jj < P ? order_bucket(sink[jj], mult(jj), k[jj], n, N, in_bw, is_compute, sink_cost) : -1;
+            b[r] = jj < P ? int32_t(keys[jj]) : -1;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -1034,7 +1042,8 @@ __global__ void __launch_bounds__(1024) fc_order_sinks_kernel(int32_t N, int32_t
                                                               const int32_t *__restrict__ in_bw,
                                                               const uint8_t *__restrict__ is_compute,
                                                               const uint32_t *__restrict__ sink_cost,
-                                                              int32_t *__restrict__ order, const int32_t *__restrict__ cD) {
+                                                              int32_t *__restrict__ order, const int32_t *__restrict__ cD,
+                                                              uint8_t *__restrict__ keys) {
     constexpr int NB = FC_ORDER_BUCKETS, R = 4;
     __shared__ int32_t hist[NB], base[NB];
     const int32_t tid = threadIdx.x, T = blockDim.x;
@@ -1050,7 +1059,10 @@ __global__ void __launch_bounds__(1024) fc_order_sinks_kernel(int32_t N, int32_t
             b[r] = i < N ? order_bucket(compute_ids[i], u0, k0, n, N, in_bw, is_compute, sink_cost) : -1;
         }
 #pragma unroll
-        for (int r = 0; r < R; ++r) (void)wave_bucket_add(hist, b[r], b[r] >= 0);
+        for (int r = 0; r < R; ++r) {
+            (void)wave_bucket_add(hist, b[r], b[r] >= 0);
+            if (b[r] >= 0) keys[i0 + r * T + tid] = uint8_t(b[r]);       // kept for the second pass (see fc_order_kernel)
+        }
     }
     __syncthreads();
     if (tid < 64) order_bucket_bases(hist, base, tid);
@@ -1060,7 +1072,7 @@ __global__ void __launch_bounds__(1024) fc_order_sinks_kernel(int32_t N, int32_t
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int32_t i = i0 + r * T + tid;
-            b[r] = i < N ? order_bucket(compute_ids[i], u0, k0, n, N, in_bw, is_compute, sink_cost) : -1;
+            b[r] = i < N ? int32_t(keys[i]) : -1;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -1164,10 +1176,14 @@ int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_
 #ifdef FC_TUNING_BUILD
     if (const char *pad = getenv("FC_LDS_PAD")) lds += size_t(atol(pad));     // occupancy experiments: request more LDS than needed
 #endif
-    static size_t lds_allowed = 0;                  // per instantiation; raised on demand
-    if (lds > lds_allowed) {
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
-        lds_allowed = lds;
+    {   // the LDS a kernel may request is raised on demand, once per instantiation and size; host threads may race here
+        static std::mutex guard;
+        static size_t lds_allowed = 0;
+        std::lock_guard<std::mutex> lock(guard);
+        if (lds > lds_allowed) {
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)));
+            lds_allowed = lds;
+        }
     }
     hipLaunchKernelGGL(kern, dim3(unsigned(P)), dim3(unsigned(T)), lds, stream, kp);
     HIP_TRY(hipGetLastError());
@@ -1185,6 +1201,12 @@ int launch_g(const KParams &kp, long long P, int32_t T, int32_t G, size_t lds, h
     }
     return FC_EINVAL;
 }
+
+// caller-provided scratch of a batch call: [per-problem counters][totals, 256 B][launch order][sort keys]
+size_t ws_totals_off(long long P) { return align_up(size_t(P) * FC_NSTAT * 4, 256); }
+size_t ws_order_off(long long P) { return ws_totals_off(P) + 256; }
+size_t ws_keys_index(long long P) { return align_up(size_t(P) * 4, 256) / 4; }     // sort keys, one byte per problem, after the order (int32 units)
+size_t stats_bytes(long long P) { return ws_order_off(P) + align_up(size_t(P) * 4, 256) + align_up(size_t(P), 256); }
 
 struct StatsScratch { uint32_t *per_problem; unsigned long long *totals; };
 
@@ -1241,15 +1263,17 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
         kp.cand_C = grid->C; kp.cand_U = grid->d_U; kp.cand_k = grid->d_k; kp.cand_D = grid->d_D;
         if (wants_order(g, opt, P)) {
             hipLaunchKernelGGL(fc_order_sinks_kernel, dim3(1), dim3(1024), 0, stream, g->N, g->n, g->d_compute_ids,
-                               grid->d_U, grid->d_k, g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, grid->d_D);
+                               grid->d_U, grid->d_k, g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, grid->d_D,
+                               reinterpret_cast<uint8_t *>(d_order + ws_keys_index(P)));
             HIP_TRY(hipGetLastError());
-            kp.order = d_order;
+            kp.order = d_order; kp.n_order = g->N;
         }
     } else if (wants_order(g, opt, P)) {
         hipLaunchKernelGGL(fc_order_kernel, dim3(1), dim3(1024), 0, stream, P, g->n, g->N, d_sink, d_U, d_k,
-                           g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, d_Uden);
+                           g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, d_Uden,
+                           reinterpret_cast<uint8_t *>(d_order + ws_keys_index(P)));
         HIP_TRY(hipGetLastError());
-        kp.order = d_order;
+        kp.order = d_order; kp.n_order = int32_t(P);
     }
     if (ev_solver_start) HIP_TRY(hipEventRecord(ev_solver_start, stream));    // after the ordering kernel
     // grid: one workgroup per problem; the candidate grid is padded to whole groups of eight sinks
@@ -1286,10 +1310,6 @@ int fill_stats(long long P, uint32_t *d_pp, unsigned long long *d_tot, hipStream
     return FC_OK;
 }
 
-// caller-provided scratch of a batch call: [per-problem counters][totals, 256 B][launch order]
-size_t ws_totals_off(long long P) { return align_up(size_t(P) * FC_NSTAT * 4, 256); }
-size_t ws_order_off(long long P) { return ws_totals_off(P) + 256; }
-size_t stats_bytes(long long P) { return ws_order_off(P) + align_up(size_t(P) * 4, 256); }
 
 }  // namespace
 

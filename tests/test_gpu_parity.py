@@ -575,3 +575,49 @@ def test_remove_switches_on_config1():
                        np.array([b for _, b in got["links"]], dtype=np.int32),
                        np.array(list(got["links"].values()), dtype=np.int32), D.is_compute)
     assert o.feasible(Dstar, 1, kk)[0] and o.is_eulerian(Dstar)
+
+
+# ------------------------------------------------------------------ launch shapes the other tests do not reach
+
+def test_large_batch_two_streams_and_degenerate_graphs():
+    # 300 000 problems on a small graph: several rounds of the ordering kernel, several waves of workgroups
+    topo = w.config_topology(2)
+    rng = np.random.default_rng(42)
+    P = 300_000
+    sink = rng.integers(0, topo.n_vertices, P).astype(np.int32)
+    U = rng.integers(1, 40, P).astype(np.int32)
+    k = rng.integers(1, 12, P).astype(np.int32)
+    want = o.aux_maxflow_batch(topo, sink, U, k, threads=16)
+    with _upload(topo) as g:
+        got, _ = _gpu_flows(g, sink, U, k)
+        assert (got == want).all()
+        # the same graph used from two streams at once, each call with its own workspace and outputs
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        half = P // 2
+        a = [_dev(x[:half]) for x in (sink, U, k)]; b = [_dev(x[half:]) for x in (sink, U, k)]
+        torch.cuda.synchronize()
+        outs = []
+        for rep in range(3):
+            with torch.cuda.stream(s1):
+                f1, _ = fc.fc_maxflow_batch(g, *a, stream=s1)
+            with torch.cuda.stream(s2):
+                f2, _ = fc.fc_maxflow_batch(g, *b, stream=s2)
+            outs.append((f1, f2))
+        torch.cuda.synchronize()
+        for f1, f2 in outs:
+            assert (f1.cpu().numpy() == want[:half]).all() and (f2.cpu().numpy() == want[half:]).all()
+    # two compute nodes and nothing else; two compute nodes and no arcs at all
+    pair = w.Topology("pair", 2, np.array([0, 1], dtype=np.int32), np.array([1, 0], dtype=np.int32),
+                      np.array([5, 3], dtype=np.int32), np.array([1, 1], dtype=np.uint8))
+    with _upload(pair) as g:
+        got, _ = _gpu_flows(g, [0, 1, 1], [1, 1, 7], [4, 4, 2])
+        assert got.tolist() == [4 + min(4, 3), 4 + min(4, 5), 2 + min(2, 35)]
+        assert fc.fc_opt_throughput_search(g, 4)["inv_xstar"] == Fraction(1, 3)
+    empty = w.Topology("noarcs", 3, np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.int32), np.zeros(0, dtype=np.int32),
+                       np.array([1, 0, 1], dtype=np.uint8))
+    with _upload(empty) as g:
+        got, _ = _gpu_flows(g, [0, 1, 2], [3, 3, 3], [5, 5, 5])
+        assert got.tolist() == [5, 0, 5]
+        with pytest.raises(fc.FcError) as ei:
+            fc.fc_opt_throughput_search(g, 4)
+        assert ei.value.code == fc.FC_EDISCONNECTED
