@@ -77,7 +77,8 @@ typedef struct {
                                       the last one and some vertex was relabeled                       */
     int32_t global_relabel_permille; /* ... or when relabels since then reach this fraction of |V|     */
     int32_t global_relabel_rises;  /* ... or when the working height level moved up this many times since
-                                      then (default and -1: off)                                        */
+                                      then (-1: off; default: off, except fc_split_gamma_batch and
+                                      fc_remove_switches on graphs of 256 vertices or more: 2)          */
     int32_t tight_sink_percent;    /* a problem whose sink cut U*B^-(t) (+k) is below this percentage of the
                                       demand N*k relabels from the sink the first time the working level
                                       moves up (default 200, -1: off)                                  */

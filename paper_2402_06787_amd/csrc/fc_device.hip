@@ -303,7 +303,7 @@ __device__ __forceinline__ int32_t rebuild_pending(const State<COMPACT> &st, int
                 const int32_t v = base + q * T + tid;
                 const int32_t vc = v < n ? v : n - 1;             // clamped: reads stay unconditional
                 const int32_t hv = int32_t(st.h[vc]);
-                act[q] = v < n && v != t && hv < n && st.excess(vc) > 0;
+                act[q] = v < n && v != t && hv >= 1 && hv < n && st.excess(vc) > 0;
                 if (act[q] && hv > best) best = hv;
                 ba[q] = __ballot(act[q]);
                 tot += __popcll(ba[q]);
@@ -344,11 +344,11 @@ __device__ __forceinline__ int32_t rebuild_pending(const State<COMPACT> &st, int
 // p.gr_sub records, sized on the host so that at most 2n entries exist at a time), a group of
 // p.gr_lanes lanes takes K entries at a time and has the K record loads in flight before it looks
 // at the first.  A record carries a flag when it is the last of its row, so no row bounds are needed.
-// `src`, `sa`, `sb` (each -1 when absent): a vertex that never gets a height (an explicit source)
-// and two vertices joined to the sink by an unbounded arc (distance 1).
+// `src`, `src2`, `sa`, `sb` (each -1 when absent): vertices that never get a height (explicit sources)
+// and two more vertices that count as the sink (distance 0).
 template <bool COMPACT, bool RAT>
 __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32_t t, const ArcCap<RAT> &arc_cap,
-                               uint32_t &gr_scans FC_GRDBG_PARAM, int32_t src = -1, int32_t sa = -1, int32_t sb = -1) {
+                               uint32_t &gr_scans FC_GRDBG_PARAM, int32_t src = -1, int32_t src2 = -1, int32_t sa = -1, int32_t sb = -1) {
     using W = typename State<COMPACT>::W;
 #ifdef FC_GRDETAIL
     long long gtick_ = clock64();
@@ -365,7 +365,7 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
     const int32_t last_rec = p.n_rec - 1;
     W *const work = st.list0;              // list0 and list1 are adjacent
     lds_barrier();                         // slower wavefronts may still be reading what is overwritten here
-    for (int32_t v = tid; v < n; v += T) st.h[v] = W(v == t ? 0 : ((v == sa || v == sb) && v != src ? 1 : n));
+    for (int32_t v = tid; v < n; v += T) st.h[v] = W(v == t || v == sa || v == sb ? 0 : n);
     for (int32_t i = tid; i < FC_LVLS; i += T) st.sh->lvl[i] = 0;
     if (tid == 0) { st.sh->cnt[0] = 0; st.sh->down[0] = 0; }
     lds_barrier();
@@ -433,7 +433,7 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
                     live[q] = live[q] && ends == 0ull;
                     const int32_t fv = int32_t(st.f[r.pair]);
                     const int32_t res = r.fwd ? fv : arc_cap(r.bw) - fv;                 // residual of r.w -> frontier vertex
-                    x[q] = valid && res > 0 && r.w != src ? r.w : t;
+                    x[q] = valid && res > 0 && r.w != src && r.w != src2 ? r.w : t;
                     if (valid) ++gr_scans;
                 }
                 int32_t hx[K];
@@ -484,7 +484,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     extern __shared__ __align__(16) unsigned char smem[];
     const int32_t tid = threadIdx.x, T = blockDim.x, n = p.n, m0 = p.m0;
     int32_t j, t, U, k, D = 1;
-    int32_t src = -1, supply = -1, sa = -1, sb = -1;     // edge-splitting problems only (see KParams)
+    int32_t src = -1, src2 = -1, sa = -1, sb = -1;       // edge-splitting problems only (see below)
     if (GEN) {
         const int32_t a = int32_t(blockIdx.x) % p.N, it = int32_t(blockIdx.x) / p.N;
         const int32_t i = it >> 1, v = p.compute_ids[a];
@@ -495,8 +495,12 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
             return;
         }
-        if ((it & 1) == 0) { src = pu; t = pw; supply = pt != pu ? pt : -1; sa = v; }
-        else { src = pw; t = pt; sa = pu != pt ? pu : -1; sb = v != pt ? v : -1; }
+        // An unbounded arc (x, y) makes y as good a source as x, and x as good a sink as y, so its two ends
+        // are merged: F(u, w) with the arcs (u, t) and (v, w) has the sources {u, t} and the sinks {w, v};
+        // F(w, t) with the arcs (u, t) and (v, t) has the source w and the sinks {t, u, v}.  The source's
+        // unbounded arc into s is what gives every compute node its k units.
+        if ((it & 1) == 0) { src = pu; t = pw; src2 = pt != pu ? pt : -1; sa = v != pw ? v : -1; }
+        else { src = pw; t = pt; sa = pu != pt ? pu : -1; sb = v != pt && v != pu ? v : -1; }
     } else if (p.cand_C) {
         // Workgroups go to the 8 XCDs (each with an L2 of its own) round-robin by index.  All candidates
         // of one sink read that sink's tables, so they are given indices that are equal modulo 8:
@@ -548,7 +552,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     // capacities are clamped at it and the run ends when the sink holds it
     const int32_t NK = GEN ? int32_t((long long)U * p.sum_bw + NKll + 1) : int32_t(NKll);
     const ArcCap<RAT> arc_cap(U, D, NK);
-    if (GEN && (sa == src || sb == src)) {               // an unbounded arc from the source straight into the sink
+    if (GEN && (sa == src || sb == src || (src2 >= 0 && sa == src2))) {   // a vertex is source and sink at once
         if (tid == 0) p.flow_out[j] = NK;
         if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
         return;
@@ -627,20 +631,23 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             }
         }
         if (GEN) {
-            // preflow of an explicit source: its unbounded arc into s is what gave every compute node k; its
-            // unbounded arc to `supply` and its own arcs are saturated here.  Nothing ever returns to it.
-            if (tid == 0 && supply >= 0) st.excess_add_noret(supply, NK);
-            for (int32_t a = int32_t(st.rp[src]) + tid; a < int32_t(st.rp[src + 1]); a += T) {
-                const ArcRec r = load_arc<COMPACT>(p, a);
-                const int32_t cap = r.fwd ? arc_cap(r.bw) : 0;
-                if (cap > 0) { st.f[r.pair] = W(cap); st.excess_add_noret(r.w, cap); }
+            // preflow of the explicit sources: all their arcs are saturated.  Nothing ever returns to them
+            // (they keep the height n), and what they hold themselves does not count.
+            for (int which = 0; which < 2; ++which) {
+                const int32_t x = which ? src2 : src;
+                if (x < 0) continue;
+                for (int32_t a = int32_t(st.rp[x]) + tid; a < int32_t(st.rp[x + 1]); a += T) {
+                    const ArcRec r = load_arc<COMPACT>(p, a);
+                    const int32_t cap = r.fwd ? arc_cap(r.bw) : 0;
+                    if (cap > 0) { st.f[r.pair] = W(cap); st.excess_add_noret(r.w, cap); }
+                }
             }
             lds_barrier();
-            if (tid == 0) st.e[src] = W(0);
+            if (tid == 0) { st.e[src] = W(0); if (src2 >= 0) st.e[src2] = W(0); }
             lds_barrier();
         }
         if (!have_labels) {
-            global_relabel<COMPACT, RAT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG, src, sa, sb);
+            global_relabel<COMPACT, RAT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG, src, src2, sa, sb);
             if (tid == 0) ++c_gr;
         }
     }
@@ -759,10 +766,6 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             int32_t rem = ex;
             int32_t minh = 0x7fffffff;
             if (lg == 0) ++c_dis;
-            if (GEN && (u == sa || u == sb)) {            // joined to the sink by an unbounded arc: everything goes there
-                if (lg == 0) { st.excess_add_noret(t, ex); st.excess_sub(u, ex); ++c_push; }
-                continue;
-            }
             for (int32_t base = beg; base < end && rem > 0; base += G) {
                 const int32_t a = base + lg;
                 int32_t ra = 0, hw = 0, fv = 0;
@@ -798,7 +801,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
                         if (fast) {                       // the level below is walked in table order anyway
                             st.excess_add_noret(r.w, delta);
                             if (r.w != t) st.sh->down[sp] = 1;
-                        } else if (r.w == t) {
+                        } else if (GEN ? d == 1 : r.w == t) {   // into the sink (an edge-splitting problem can have three)
                             st.excess_add_noret(r.w, delta);
                         } else if (st.excess_add(r.w, delta) == 0) {
                             st.pend(cur, r.w);            // first excess this vertex gets: it becomes pending
@@ -885,7 +888,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             cur ^= 1;
         }
         if (!fast && rel_since > 0 && (rel_since >= p.gr_relabels || steps_since >= p.gr_steps || rises >= rise_limit) && d >= 1) {
-            global_relabel<COMPACT, RAT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG, src, sa, sb);
+            global_relabel<COMPACT, RAT>(p, st, t, arc_cap, c_grscan FC_GRDBG_ARG, src, src2, sa, sb);
             if (tid == 0) ++c_gr;
             rel_since = 0; steps_since = 0; rises = 0;
             d = rebuild_pending(st, n, t, cur ^ 1);
@@ -898,8 +901,13 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
 
     lds_barrier();
     if (tid == 0) {
-        const int32_t et = st.excess(t);
-        p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : (GEN && et > NK ? NK : et);    // "unbounded" is reported as one value
+        int32_t et = st.excess(t);
+        if (GEN) {                         // what arrived at any of the sinks; "unbounded" is reported as one value
+            if (sa >= 0) et += st.excess(sa);
+            if (sb >= 0) et += st.excess(sb);
+            if (et > NK) et = NK;
+        }
+        p.flow_out[j] = failed ? FC_FLOW_NOCONVERGE : et;
         if (!GEN) p.sink_cost[t] = uint32_t(total_steps) + 6u * c_gr + 1u;
     }
     if (p.stats) {
@@ -1677,6 +1685,9 @@ extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int
     uint32_t *d_pp = reinterpret_cast<uint32_t *>(ws + slab);
     unsigned long long *d_tot = reinterpret_cast<unsigned long long *>(ws + slab + ws_totals_off(P));
 
+    // these problems strand much excess (a source's saturated arcs carry more than the sinks take): on the
+    // larger graphs exact heights after the second upward move of the working level save many steps
+    if (!(options_or_null && options_or_null->global_relabel_rises) && g->n >= 256) opt.gr_rises = 2;
     KParams kp;
     common_params(g, opt, &kp);                          // no per-sink tables, no launch order: every field left null
     kp.split_u = d_u; kp.split_w = d_w; kp.split_t = d_t; kp.split_U = U; kp.split_k = k;
