@@ -469,8 +469,8 @@ def fc_remove_switches(n_vertices, tail, head, capacity, is_compute, k: int, str
     tail = _np(tail, np.int32); head = _np(head, np.int32); capacity = _np(capacity, np.int32)
     is_compute = _np(is_compute, np.uint8)
     n_out, n_routes, batches = c.c_int64(0), c.c_int64(0), c.c_int64(0)
-    out_cap, route_cap = 0, 0
-    for _ in range(2):                                   # first call sizes the outputs when they do not fit
+    out_cap = route_cap = max(1024, 4 * int(tail.shape[0]))      # a guess that normally fits
+    for _ in range(2):                                   # the call reports the sizes it needs when they do not fit
         ot = np.zeros(max(out_cap, 1), np.int32); oh = np.zeros_like(ot); oc = np.zeros_like(ot)
         ru = np.zeros(max(route_cap, 1), np.int32); rt = np.zeros_like(ru); rw = np.zeros_like(ru); ra = np.zeros_like(ru)
         rc = lib.fc_remove_switches(int(n_vertices), int(tail.shape[0]), _host_ptr(tail), _host_ptr(head), _host_ptr(capacity),

@@ -1325,6 +1325,13 @@ int fill_stats(long long P, uint32_t *d_pp, unsigned long long *d_tot, hipStream
 
 namespace {
 // with_tables = false skips the per-sink tables (for graphs that are only used by calls that cannot use them)
+// 32-bit arc records {other end, topology arc, bandwidth, forward | last-of-row << 1} in row order
+void fill_wide_records(const fc_graph *g, int4 *dst) {
+    const size_t M = size_t(2 * g->m0);
+    for (size_t i = 0; i < M; ++i) dst[i] = make_int4(g->other[i], g->pair[i], g->bw[i], g->fwd[i]);
+    for (size_t v = 0; v < size_t(g->n); ++v) if (g->row_ptr[v + 1] > g->row_ptr[v]) dst[size_t(g->row_ptr[v + 1]) - 1].w |= 2;
+}
+
 int upload_impl(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
                 const int32_t *bandwidth, const uint8_t *is_compute, bool with_tables, fc_graph **out) {
     if (!out) return FC_EINVAL;
@@ -1347,7 +1354,7 @@ int upload_impl(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const i
         std::vector<int4> wide(M ? M : 1, make_int4(0, 0, 0, 0));
         std::vector<uint8_t> last(M ? M : 1, 0);                     // final record of a vertex's row
         for (size_t v = 0; v < n; ++v) if (g->row_ptr[v + 1] > g->row_ptr[v]) last[size_t(g->row_ptr[v + 1]) - 1] = 1;
-        for (size_t i = 0; i < M; ++i) wide[i] = make_int4(g->other[i], g->pair[i], g->bw[i], g->fwd[i] | (last[i] << 1));
+        fill_wide_records(g, wide.data());
         g->on_device = true;
         if (hipMalloc(&g->d_row_ptr, sizeof(int32_t) * (n + 1)) != hipSuccess) return fail(FC_EDEVICE);
         if (hipMalloc(&g->d_arc_wide, sizeof(int4) * (M ? M : 1)) != hipSuccess) return fail(FC_EDEVICE);
@@ -1750,6 +1757,58 @@ extern "C" int fc_fixed_k_search(const fc_graph *g, int32_t k, int32_t candidate
 // current graph in one launch; the first positive one (in ingress order) is applied -- the ones before it are
 // zero on this very graph, exactly what the one-at-a-time loop of the pseudocode would have found -- and the
 // rest is evaluated again on the new graph.
+namespace {
+// Memory that fc_remove_switches keeps over its batches.  Every accepted split changes the graph, so
+// every batch needs the residual CSR anew -- but no fresh allocation and only one copy: the host
+// fills a pinned image [row offsets | in-bandwidths | pair lists | arc records] and one transfer puts
+// it into a device block of the same layout, which also holds what does not change (compute flags
+// and ids), the gamma values and the batch call's workspace.
+struct SplitPool {
+    int32_t n = 0, N = 0;
+    size_t rec_cap = 0, pair_cap = 0;                     // arc records and pairs there is room for
+    size_t off_row = 0, off_inbw = 0, off_pairs = 0, off_wide = 0, off_is = 0, off_ids = 0, off_cost = 0, off_gamma = 0, off_ws = 0, ws_bytes = 0;
+    unsigned char *d_blob = nullptr, *h_blob = nullptr;   // h_blob: pinned, covers [0, off_ws)
+    SplitPool() = default;
+    SplitPool(const SplitPool &) = delete;
+    SplitPool &operator=(const SplitPool &) = delete;
+    ~SplitPool() { release(); }
+    void release() {
+        if (d_blob) (void)hipFree(d_blob);
+        if (h_blob) (void)hipHostFree(h_blob);
+        d_blob = nullptr; h_blob = nullptr; rec_cap = 0; pair_cap = 0;
+    }
+    // room for `recs` arc records and `pairs` pairs; growing re-creates both blocks (contents are rewritten by every batch)
+    int ensure(const fc_graph *h, size_t recs, size_t pairs, hipStream_t stream) {
+        if (d_blob && recs <= rec_cap && pairs <= pair_cap) return FC_OK;
+        const size_t want_rec = std::max<size_t>(recs + recs / 2 + 64, 2 * rec_cap);     // splits add links: leave headroom
+        const size_t want_pairs = std::max<size_t>(std::max<size_t>(pairs, 1), d_blob ? 2 * pair_cap : size_t(h->n));
+        if (d_blob && hipStreamSynchronize(stream) != hipSuccess) return FC_EDEVICE;
+        release();
+        n = h->n; N = h->N;
+        size_t o = 0;
+        off_row = o; o = align_up(o + sizeof(int32_t) * (size_t(n) + 1), 256);
+        off_inbw = o; o = align_up(o + sizeof(int32_t) * size_t(n), 256);
+        off_pairs = o; o = align_up(o + sizeof(int32_t) * 3 * want_pairs, 256);
+        off_wide = o; o = align_up(o + sizeof(int4) * want_rec, 256);
+        off_is = o; o = align_up(o + size_t(n), 256);
+        off_ids = o; o = align_up(o + sizeof(int32_t) * size_t(N), 256);
+        off_cost = o; o = align_up(o + sizeof(uint32_t) * size_t(n), 256);
+        off_gamma = o; o = align_up(o + sizeof(int32_t) * want_pairs, 256);
+        off_ws = o;
+        const long long P = (long long)want_pairs * 2 * N;
+        ws_bytes = align_up(size_t(P) * 4, 256) + stats_bytes(P);
+        if (hipMalloc(reinterpret_cast<void **>(&d_blob), off_ws + ws_bytes) != hipSuccess) { d_blob = nullptr; return FC_EDEVICE; }
+        if (hipHostMalloc(reinterpret_cast<void **>(&h_blob), off_ws, hipHostMallocDefault) != hipSuccess) { h_blob = nullptr; release(); return FC_EDEVICE; }
+        rec_cap = want_rec; pair_cap = want_pairs;
+        std::memset(h_blob, 0, off_ws);
+        std::memcpy(h_blob + off_is, h->is_compute.data(), size_t(n));
+        std::memcpy(h_blob + off_ids, h->compute_ids.data(), sizeof(int32_t) * size_t(N));
+        if (hipMemcpyAsync(d_blob + off_is, h_blob + off_is, off_gamma - off_is, hipMemcpyHostToDevice, stream) != hipSuccess) return FC_EDEVICE;
+        return FC_OK;
+    }
+};
+}  // namespace
+
 extern "C" int fc_remove_switches(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
                                   const int32_t *capacity, const uint8_t *is_compute, int32_t k,
                                   int64_t out_capacity, int64_t *n_out, int32_t *out_tail, int32_t *out_head, int32_t *out_cap,
@@ -1774,8 +1833,11 @@ extern "C" int fc_remove_switches(int32_t n_vertices, int64_t n_arcs, const int3
         std::map<Key, std::map<int32_t, long long>> table;
         int64_t batches = 0;
         std::vector<int32_t> at, ah, ab, pu, pw, pt, gam;
-        int32_t *d_pairs = nullptr, *d_gamma = nullptr; void *d_ws = nullptr; size_t ws_have = 0; int64_t pairs_have = 0;
-        auto cleanup = [&]() { if (d_pairs) (void)hipFree(d_pairs); if (d_gamma) (void)hipFree(d_gamma); if (d_ws) (void)hipFree(d_ws); };
+        SplitPool pool;
+        int dev = -1, lds_limit = 0, n_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return FC_EDEVICE;
+        auto cleanup = [&]() { (void)hipStreamSynchronize(stream); pool.release(); };
         for (int32_t w = 0; w < n_vertices; ++w) {
             if (is_compute[w]) continue;
             std::vector<int32_t> egress;
@@ -1795,35 +1857,44 @@ extern "C" int fc_remove_switches(int32_t n_vertices, int64_t n_arcs, const int3
                         if (kv.second >= (1ll << 31)) { cleanup(); return FC_EOVERFLOW; }
                         at.push_back(kv.first.first); ah.push_back(kv.first.second); ab.push_back(int32_t(kv.second));
                     }
-                    fc_graph *g = nullptr;
-                    int rc = upload_impl(n_vertices, int64_t(at.size()), at.data(), ah.data(), ab.data(), is_compute, false, &g);
+                    // the split graph of this batch: residual CSR on the host, then one transfer into the pool
+                    fc_graph *h = nullptr;
+                    int rc = fc_host_build(n_vertices, int64_t(at.size()), at.data(), ah.data(), ab.data(), is_compute, &h);
                     if (rc != FC_OK) { cleanup(); return rc; }
-                    const int64_t np = int64_t(pu.size());
-                    const size_t need = fc_split_gamma_workspace_bytes(g, np);
-                    if (np > pairs_have) {
-                        if (d_pairs) (void)hipFree(d_pairs); if (d_gamma) (void)hipFree(d_gamma);
-                        d_pairs = nullptr; d_gamma = nullptr; pairs_have = 0;
-                        if (hipMalloc(&d_pairs, sizeof(int32_t) * 3 * size_t(np)) != hipSuccess || hipMalloc(&d_gamma, sizeof(int32_t) * size_t(np)) != hipSuccess) { fc_graph_free(g); cleanup(); return FC_EDEVICE; }
-                        pairs_have = np;
-                    }
-                    if (need > ws_have) {
-                        if (d_ws) (void)hipFree(d_ws);
-                        d_ws = nullptr; ws_have = 0;
-                        if (hipMalloc(&d_ws, need) != hipSuccess) { fc_graph_free(g); cleanup(); return FC_EDEVICE; }
-                        ws_have = need;
-                    }
-                    bool ok = hipMemcpyAsync(d_pairs, pu.data(), sizeof(int32_t) * size_t(np), hipMemcpyHostToDevice, stream) == hipSuccess &&
-                              hipMemcpyAsync(d_pairs + np, pw.data(), sizeof(int32_t) * size_t(np), hipMemcpyHostToDevice, stream) == hipSuccess &&
-                              hipMemcpyAsync(d_pairs + 2 * np, pt.data(), sizeof(int32_t) * size_t(np), hipMemcpyHostToDevice, stream) == hipSuccess;
+                    const size_t np = pu.size(), M = size_t(2 * h->m0);
+                    rc = pool.ensure(h, M, np, stream);
+                    if (rc != FC_OK) { fc_graph_free(h); cleanup(); return rc; }
+                    std::memcpy(pool.h_blob + pool.off_row, h->row_ptr.data(), sizeof(int32_t) * (size_t(h->n) + 1));
+                    std::memcpy(pool.h_blob + pool.off_inbw, h->in_bw.data(), sizeof(int32_t) * size_t(h->n));
+                    int32_t *hp = reinterpret_cast<int32_t *>(pool.h_blob + pool.off_pairs);
+                    std::memcpy(hp, pu.data(), sizeof(int32_t) * np);
+                    std::memcpy(hp + pool.pair_cap, pw.data(), sizeof(int32_t) * np);
+                    std::memcpy(hp + 2 * pool.pair_cap, pt.data(), sizeof(int32_t) * np);
+                    fill_wide_records(h, reinterpret_cast<int4 *>(pool.h_blob + pool.off_wide));
+                    h->on_device = true; h->device = dev; h->lds_limit = lds_limit; h->n_cu = n_cu;
+                    h->d_row_ptr = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_row);
+                    h->d_in_bw = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_inbw);
+                    h->d_arc_wide = pool.d_blob + pool.off_wide;
+                    h->d_is_compute = pool.d_blob + pool.off_is;
+                    h->d_compute_ids = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_ids);
+                    h->d_sink_cost = reinterpret_cast<uint32_t *>(pool.d_blob + pool.off_cost);
+                    int32_t *d_pairs = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_pairs);
+                    int32_t *d_gamma = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_gamma);
+                    int32_t *h_gamma = reinterpret_cast<int32_t *>(pool.h_blob + pool.off_gamma);
+                    bool ok = hipMemcpyAsync(pool.d_blob, pool.h_blob, pool.off_wide + sizeof(int4) * M, hipMemcpyHostToDevice, stream) == hipSuccess;
                     if (ok) {
-                        rc = fc_split_gamma_batch(g, 1, k, np, d_pairs, d_pairs + np, d_pairs + 2 * np, d_gamma, nullptr, d_ws, ws_have, stream, options_or_null, nullptr);
-                        gam.assign(size_t(np), 0);
-                        ok = rc == FC_OK && hipMemcpyAsync(gam.data(), d_gamma, sizeof(int32_t) * size_t(np), hipMemcpyDeviceToHost, stream) == hipSuccess &&
+                        rc = fc_split_gamma_batch(h, 1, k, int64_t(np), d_pairs, d_pairs + pool.pair_cap, d_pairs + 2 * pool.pair_cap, d_gamma, nullptr,
+                                                  pool.d_blob + pool.off_ws, pool.ws_bytes, stream, options_or_null, nullptr);
+                        ok = rc == FC_OK && hipMemcpyAsync(h_gamma, d_gamma, sizeof(int32_t) * np, hipMemcpyDeviceToHost, stream) == hipSuccess &&
                              hipStreamSynchronize(stream) == hipSuccess;
                     }
-                    fc_graph_free(g);
+                    // the pool owns the device memory: detach it before the host graph goes
+                    h->on_device = false;
+                    h->d_row_ptr = nullptr; h->d_in_bw = nullptr; h->d_arc_wide = nullptr; h->d_is_compute = nullptr; h->d_compute_ids = nullptr; h->d_sink_cost = nullptr;
+                    fc_graph_free(h);
                     ++batches;
                     if (!ok) { cleanup(); return rc != FC_OK ? rc : FC_EDEVICE; }
+                    gam.assign(h_gamma, h_gamma + np);
                     size_t hit = which.size();
                     for (size_t q = 0; q < which.size(); ++q) {
                         if (gam[q] < 0) { cleanup(); return FC_ENOCONVERGE; }     // invalid, or min_v F(s, v) >= N k does not hold in D
