@@ -13,6 +13,8 @@ the paper (ForestColl, arXiv 2402.06787):
   (`optimality_binary_search`), or by enumerating every cut of the bound (star) of
   Section 4 (`brute_inv_xstar`).
 * (U, k) by the gcd rule of Section 5.2 "Determine k" / Proposition 3 (`smallest_U_k`).
+* the non-uniform variant (Section 5.7): source arcs of capacity m_c * k (`weighted_aux_network`,
+  `weighted_aux_maxflow_batch`, `weighted_feasible`).
 * edge splitting (Appendix E.2): the 2N max-flows and gamma of Theorem 10 (`split_flows`,
   `split_gamma`), gamma by its definition (`brute_split_gamma`), the split graph (`split_off`), and the loop of
   Algorithm 2 around them (`remove_switches`).
@@ -34,6 +36,10 @@ Readings of the paper taken here (each also listed in the design notes):
  - parallel arcs add up; self-loops and zero-bandwidth arcs carry nothing.
  - if some cut with compute nodes on both sides has no exiting bandwidth the bound
    is infinite (the paper assumes B^+(S) >= 1): `Disconnected` is raised.
+ - non-uniform allgather (Section 5.7, last sentence): compute node c sends a weight m_c >= 0 (an
+   integer) instead of one unit, the arc (s, c) gets capacity m_c * k, and the verdict is
+   F(s, v) >= k * sum_c m_c for every compute node v -- what s emits when all its arcs are full, as
+   N k is in the uniform case.  The paper says only that the source arcs are adjusted.
  - fixed k: "link e with bandwidth b_e" is one ordered vertex pair with the summed bandwidth of
    its parallel arcs (`links`); floor(U b_e) is taken per link; max_e b_e (termination width and
    denominator bound of Algorithm 3) is over links; the verdict is F >= N k as in Algorithm 1.
@@ -162,6 +168,52 @@ def aux_maxflow_batch(topo, sink, U, k, algo="dinic", threads=1):
     if rc != 0 or (out < 0).any():
         raise RuntimeError("oracle batch failed")
     return out
+
+
+# ------------------------------------------------------------------ non-uniform source capacities (Section 5.7)
+
+def _compute_weights(topo, weights):
+    """weights: one nonnegative integer per vertex (entries of switches are ignored)."""
+    wts = [int(x) for x in np.asarray(weights).tolist()]
+    if len(wts) != topo.n_vertices or any(x < 0 for x in wts):
+        raise ValueError("weights: one nonnegative integer per vertex")
+    return [wts[v] if topo.is_compute[v] else 0 for v in range(topo.n_vertices)]
+
+
+def weighted_aux_network(topo, U, k, weights, U_den=1):
+    """The auxiliary network when compute node c sends m_c = weights[c] units instead of one: arc e
+    with capacity floor(U * b_e / U_den), arc (s, c) with capacity m_c * k for every compute node c."""
+    wts = _compute_weights(topo, weights)
+    comp = np.flatnonzero(topo.is_compute).astype(np.int32)
+    s = topo.n_vertices
+    tail = np.concatenate([topo.tail.astype(np.int32), np.full(comp.shape[0], s, dtype=np.int32)])
+    head = np.concatenate([topo.head.astype(np.int32), comp])
+    cap = [int(U) * int(b) // int(U_den) for b in topo.bandwidth.tolist()] + [wts[int(c)] * int(k) for c in comp.tolist()]
+    return topo.n_vertices + 1, tail, head, cap, s
+
+
+def weighted_aux_maxflow_batch(topo, sink, U, k, weights, U_den=None, algo="dinic"):
+    """F(s, sink_j) in the weighted auxiliary network for every problem j = (sink_j, U_j [/ U_den_j], k_j).
+    With U_den the capacities are floor(U_j b_e / U_den_j) per arc (the caller passes merged links when the
+    floor is to be taken per link)."""
+    sink = np.asarray(sink).tolist(); U = np.asarray(U).tolist(); k = np.asarray(k).tolist()
+    den = [1] * len(sink) if U_den is None else np.asarray(U_den).tolist()
+    out = np.zeros(len(sink), dtype=np.int64)
+    for j in range(len(sink)):
+        n, tail, head, cap, s = weighted_aux_network(topo, U[j], k[j], weights, den[j])
+        out[j] = maxflow(n, tail, head, cap, s, int(sink[j]), algo)
+    return out
+
+
+def weighted_feasible(topo, U, k, weights, algo="dinic"):
+    """Verdict of the non-uniform variant: min over compute nodes v of F(s, v) >= k * sum_c m_c.
+    Returns (verdict, flows)."""
+    wts = _compute_weights(topo, weights)
+    comp = np.flatnonzero(topo.is_compute).astype(np.int32)
+    flows = weighted_aux_maxflow_batch(topo, comp, [int(U)] * len(comp), [int(k)] * len(comp), weights, None, algo)
+    need = int(k) * sum(wts)
+    assert (flows <= need).all(), "s cannot emit more than k * sum of the weights"
+    return bool((flows >= need).all()), flows
 
 
 # ------------------------------------------------------------------ verdict (Theorem 1 / Theorem 3)

@@ -488,3 +488,86 @@ def test_remove_switches_on_random_eulerian_graphs(seed):
     _check_switch_removal(D, k, Dstar, table)
     # the optimum cannot improve, and D itself was at its optimum 1/x* = 1/k (scaled by Proposition 3)
     assert o.optimality_binary_search(Dstar) == o.optimality_binary_search(D) == Fraction(1, k)
+
+
+# ---------------------------------------------------------------- non-uniform source capacities (Section 5.7)
+
+def _line(bws, n):
+    """compute nodes 0 .. n-1 on a directed line i -> i+1 with bandwidths bws"""
+    return w.Topology("line", n, np.arange(n - 1, dtype=np.int32), np.arange(1, n, dtype=np.int32),
+                      np.asarray(bws, dtype=np.int32), np.ones(n, dtype=np.uint8))
+
+
+def test_weighted_closed_forms_on_lines():
+    # a -> b: what reaches b is its own m_b k plus whatever of a's m_a k the link carries
+    for ma, mb, B, U, k in ((3, 1, 2, 1, 1), (3, 1, 2, 2, 1), (0, 2, 5, 1, 3), (4, 0, 1, 3, 2), (2, 5, 7, 1, 4)):
+        t = _line([B], 2)
+        f = o.weighted_aux_maxflow_batch(t, [0, 1], [U, U], [k, k], [ma, mb])
+        assert f.tolist() == [ma * k, mb * k + min(ma * k, U * B)]
+    # a -> b -> c, three different weights: a permuted or dropped weight changes the value
+    for (ma, mb, mc), (B1, B2), U, k in (((5, 1, 2), (3, 4), 1, 1), ((1, 7, 0), (9, 2), 2, 3), ((2, 3, 4), (1, 100), 3, 2)):
+        t = _line([B1, B2], 3)
+        f = o.weighted_aux_maxflow_batch(t, [2, 1], [U, U], [k, k], [ma, mb, mc])
+        assert f.tolist() == [mc * k + min(U * B2, mb * k + min(U * B1, ma * k)), mb * k + min(U * B1, ma * k)]
+
+
+def test_weighted_verdict_threshold_is_k_times_the_weight_sum():
+    # two nodes joined both ways with bandwidth B, weights (3, 1): b must receive 3k over the link, so the
+    # candidate is feasible iff U B >= 3 k -- although F(s, b) reaches N k = 2 k much earlier
+    t = w.Topology("pair", 2, np.array([0, 1], np.int32), np.array([1, 0], np.int32), np.array([2, 2], np.int32), np.ones(2, np.uint8))
+    for U, k, want in ((1, 1, False), (3, 2, True), (2, 2, False), (3, 3, False), (9, 6, True)):
+        ok, flows = o.weighted_feasible(t, U, k, [3, 1])
+        assert ok is want and flows.tolist() == [3 * k + min(k, 2 * U), k + min(3 * k, 2 * U)]
+    assert o.weighted_feasible(t, 1, 2, [1, 1])[0] == o.feasible(t, 1, 2)[0]
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_weighted_flows_equal_brute_min_cut_and_reduce_to_the_uniform_case(seed):
+    topo = w.random_tiny(2000 + seed)
+    rng = np.random.default_rng(3000 + seed)
+    U, k = int(rng.integers(1, 5)), int(rng.integers(1, 8))
+    wts = rng.integers(0, 4, topo.n_vertices)
+    comp = [int(v) for v in topo.compute_nodes]
+    n, tail, head, cap, s = o.weighted_aux_network(topo, U, k, wts)
+    got = o.weighted_aux_maxflow_batch(topo, comp, [U] * len(comp), [k] * len(comp), wts, algo=ALGOS[seed % 2])
+    for i, v in enumerate(comp):
+        assert got[i] == o.brute_min_cut(n, tail, head, cap, s, v)
+    # weight 1 everywhere is the network of Section 5.2
+    ones = np.ones(topo.n_vertices, dtype=np.int64)
+    assert (o.weighted_aux_maxflow_batch(topo, comp, [U] * len(comp), [k] * len(comp), ones) ==
+            o.aux_maxflow_batch(topo, comp, [U] * len(comp), [k] * len(comp))).all()
+    assert o.weighted_feasible(topo, U, k, ones)[0] == o.feasible(topo, U, k)[0]
+    # a common factor can sit in the weights or in k; scaling everything scales the flows
+    a = o.weighted_aux_maxflow_batch(topo, comp, [U] * len(comp), [3 * k] * len(comp), wts)
+    b = o.weighted_aux_maxflow_batch(topo, comp, [U] * len(comp), [k] * len(comp), 3 * wts)
+    c = o.weighted_aux_maxflow_batch(topo, comp, [3 * U] * len(comp), [3 * k] * len(comp), wts)
+    assert (a == b).all() and (c == 3 * got).all()
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_a_weight_is_that_many_unit_nodes_behind_wide_links(seed):
+    # a compute node of weight m >= 1 sends what it and m - 1 extra unit nodes, each joined to it by a link that
+    # carries its k units, would send: the flows into the original nodes agree with the uniform network's
+    topo = w.random_tiny(2500 + seed)
+    rng = np.random.default_rng(3500 + seed)
+    U, k = int(rng.integers(1, 4)), int(rng.integers(1, 6))
+    wts = np.where(np.asarray(topo.is_compute) != 0, rng.integers(1, 4, topo.n_vertices), 0)
+    tail, head, bw, isc = topo.tail.tolist(), topo.head.tolist(), topo.bandwidth.tolist(), list(np.asarray(topo.is_compute).tolist())
+    nv = topo.n_vertices
+    for c in [int(v) for v in topo.compute_nodes]:
+        for _ in range(int(wts[c]) - 1):
+            tail.append(nv); head.append(c); bw.append(k); isc.append(1); nv += 1      # U * k >= k
+    big = w.Topology("expanded", nv, np.asarray(tail, np.int32), np.asarray(head, np.int32), np.asarray(bw, np.int32), np.asarray(isc, np.uint8))
+    comp = [int(v) for v in topo.compute_nodes]
+    want = o.aux_maxflow_batch(big, comp, [U] * len(comp), [k] * len(comp))
+    got = o.weighted_aux_maxflow_batch(topo, comp, [U] * len(comp), [k] * len(comp), wts)
+    assert (got == want).all()
+
+
+def test_weighted_floor_capacities():
+    t = _line([3, 5], 3)
+    # multiplier 5/2: floor(7.5) = 7 and floor(12.5) = 12
+    f = o.weighted_aux_maxflow_batch(t, [2], [5], [1], [20, 1, 2], U_den=[2])
+    assert f.tolist() == [2 + min(12, 1 + min(7, 20))]
+    with pytest.raises(ValueError):
+        o.weighted_aux_network(t, 1, 1, [1, -1, 1])
