@@ -131,6 +131,22 @@ int fc_graph_free(fc_graph *g);
 int fc_graph_info(const fc_graph *g, int32_t *n_compute, int64_t *n_arcs_merged,
                   int64_t *min_in_bw_compute, int32_t *max_bw, int32_t *gcd_bw, int32_t *is_eulerian);
 
+/* Non-uniform allgather / reduce-scatter (Section 5.7, "Other Collective Operations"): when compute
+ * nodes send different amounts of data the capacities of s's arcs are adjusted.  Reading taken here:
+ * compute node c has an integer weight m_c >= 0, its arc (s, c) has capacity m_c * k_j instead of k_j,
+ * and N * k_j becomes k_j * (sum of the weights) wherever it appears -- the verdict's threshold, the
+ * clamp of the capacities, the validity bound (< 2^31) and the 16-bit limit (<= 65535).
+ *
+ * weight_per_vertex: host int32 [n_vertices] (entries of switch nodes are ignored), or null to return
+ * to unit weights.  The weights stay with the graph and apply to every later fc_maxflow_batch,
+ * fc_maxflow_batch_floor, fc_feasible and fc_feasible_floor call; the tree certificate is not used
+ * while they are set.  The searches and the edge-splitting calls, which the paper defines for unit
+ * weights only, return FC_EUNSUPPORTED while they are set.  Synchronous (one small copy); must not
+ * run concurrently with other calls on the same graph.
+ * Errors: FC_EINVAL (negative weight, all weights zero), FC_EOVERFLOW (sum >= 2^31), FC_EDEVICE
+ * (graph not uploaded, copy failed), FC_ENOMEM. */
+int fc_graph_set_source_weights(fc_graph *g, const int32_t *weight_per_vertex);
+
 /* Residual CSR as built on the host (for inspection and tests).  Vertex u owns records
  * row_ptr[u] .. row_ptr[u+1]-1; record r describes a residual arc u -> other[r] that belongs to
  * merged topology arc pair[r] of bandwidth bw[r]; forward[r] = 1 if the topology arc leaves u,

@@ -22,7 +22,7 @@ FC_EWORKSPACE, FC_EDEVICE, FC_ENOCONVERGE, FC_EUNSUPPORTED = -5, -6, -7, -8
 FC_FLOW_INVALID, FC_FLOW_NOCONVERGE, FC_FLOW_UNSUPPORTED = -1, -2, -3
 FC_GAMMA_INVALID = -2147483648
 
-EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_free", "fc_graph_info", "fc_graph_csr",
+EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_free", "fc_graph_info", "fc_graph_csr", "fc_graph_set_source_weights",
             "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_maxflow_batch_floor", "fc_feasible_workspace_bytes",
             "fc_feasible_floor", "fc_fixed_k_search", "fc_fixed_k_search_with_verdicts",
             "fc_split_gamma_workspace_bytes", "fc_split_gamma_batch", "fc_remove_switches",
@@ -83,6 +83,8 @@ def load_library():
     lib.fc_graph_info.restype = c.c_int
     lib.fc_graph_info.argtypes = [vp, c.POINTER(i32), c.POINTER(i64), c.POINTER(i64), c.POINTER(i32),
                                   c.POINTER(i32), c.POINTER(i32)]
+    lib.fc_graph_set_source_weights.restype = c.c_int
+    lib.fc_graph_set_source_weights.argtypes = [vp, vp]
     lib.fc_graph_csr.restype = c.c_int
     lib.fc_graph_csr.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.fc_maxflow_batch_workspace_bytes.restype = sz
@@ -215,6 +217,18 @@ def fc_graph_info(g: Graph) -> GraphInfo:
     _check(load_library().fc_graph_info(g.handle, c.byref(nc), c.byref(m), c.byref(mb), c.byref(mx),
                                         c.byref(gc), c.byref(eu)), "fc_graph_info")
     return GraphInfo(nc.value, m.value, mb.value, mx.value, gc.value, bool(eu.value))
+
+
+def fc_graph_set_source_weights(g: Graph, weights) -> None:
+    """weights: one nonnegative integer per vertex (host array), or None for unit weights."""
+    lib = load_library()
+    if weights is None:
+        _check(lib.fc_graph_set_source_weights(g.handle, None), "fc_graph_set_source_weights")
+        return
+    wts = _np(weights, np.int32)
+    if wts.shape[0] != g.n_vertices:
+        raise ValueError("weights: one entry per vertex")
+    _check(lib.fc_graph_set_source_weights(g.handle, _host_ptr(wts)), "fc_graph_set_source_weights")
 
 
 def fc_graph_csr(g: Graph):

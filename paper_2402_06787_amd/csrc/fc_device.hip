@@ -76,6 +76,8 @@ struct KParams {
     const int32_t *split_u, *split_w, *split_t;
     int32_t split_U, split_k;
     long long sum_bw;            // sum of all link bandwidths (bounds every finite cut)
+    const int32_t *src_w;        // [n] weight m_c of compute node c: arc (s, c) has capacity m_c * k (Section 5.7); null: all 1
+    long long sum_w;             // sum of the weights (N while they are all 1): s emits at most sum_w * k
     uint32_t *sink_cost;         // [n] what the last problem of each sink cost (feeds the next launch's order)
 };
 
@@ -521,7 +523,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     }
 
     // ---- problem and its validity (uniform over the workgroup)
-    const long long NKll = (long long)p.N * (long long)k;
+    const long long NKll = p.sum_w * (long long)k;       // all of s's arcs together: N * k, or k * (sum of the weights)
     const bool valid = t >= 0 && t < n && U >= 1 && k >= 1 && D >= 1 && NKll < (1ll << 31);
     if (!valid) {                       // both layouts write the same marker
         if (tid == 0) p.flow_out[j] = FC_FLOW_INVALID;
@@ -609,8 +611,8 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             if (have_labels) {
                 const uint32_t lc = p.labels[size_t(t) * size_t(n) + size_t(v)];
                 st.h[v] = W(lc & 0x7fffu);
-                st.e[v] = W((lc & 0x8000u) ? k : 0);
-            } else st.e[v] = W(p.is_compute[v] ? k : 0);
+                st.e[v] = W((lc & 0x8000u) ? (p.src_w ? k * p.src_w[v] : k) : 0);
+            } else st.e[v] = W(p.is_compute[v] ? (p.src_w ? k * p.src_w[v] : k) : 0);
         }
         if (tid == 0) {
             st.rp[n] = W(p.row_ptr[n]);
@@ -674,7 +676,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     // first pass: such problems get exact heights as soon as the working level first moves up
     int32_t rise_limit = p.gr_rises;
     if (p.tight_pct > 0 && !GEN) {
-        const long long have = (long long)U * (long long)p.in_bw[t] / D + (p.is_compute[t] ? k : 0);
+        const long long have = (long long)U * (long long)p.in_bw[t] / D + (p.is_compute[t] ? (p.src_w ? k * p.src_w[t] : k) : 0);
         if (have * 100ll < NKll * (long long)p.tight_pct) rise_limit = 1;
     }
     bool failed = false;
@@ -950,13 +952,13 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
 constexpr int FC_ORDER_BUCKETS = 256;
 
 // sort key of a problem: bucket 0 holds the most expensive ones
-__device__ __forceinline__ int32_t order_bucket(int32_t t, int32_t u, int32_t kk, int32_t n, int32_t N, const int32_t *in_bw,
+__device__ __forceinline__ int32_t order_bucket(int32_t t, int32_t u, int32_t kk, int32_t n, long long sum_w, const int32_t *in_bw,
                                                 const uint8_t *is_compute, const uint32_t *sink_cost) {
     constexpr int NB = FC_ORDER_BUCKETS;
     if (t < 0 || t >= n || u < 1 || kk < 1) return NB - 1;                  // nothing to solve
     int32_t cost = int32_t(sink_cost[t]);
     if (cost == 0) {
-        const long long need = (long long)N * kk;
+        const long long need = sum_w * kk;
         const long long have = (long long)u * in_bw[t] + (is_compute[t] ? kk : 0);
         // ratio have / need against 1, 1.25, 1.5, 2, 3, 4, 6
         cost = have < need ? 80 : have * 4 < need * 5 ? 60 : have * 2 < need * 3 ? 45 : have < need * 2 ? 35
@@ -996,7 +998,7 @@ __device__ __forceinline__ void order_bucket_bases(const int32_t *hist, int32_t 
     }
 }
 
-__global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, int32_t N, const int32_t *sink,
+__global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, long long sum_w, const int32_t *sink,
                                                         const int32_t *U, const int32_t *k, const int32_t *in_bw,
                                                         const uint8_t *is_compute, const uint32_t *sink_cost,
                                                         int32_t *order, const int32_t *Uden, uint8_t *keys) {
@@ -1013,7 +1015,7 @@ __global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, 
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const long long jj = j0 + (long long)r * T + tid;
-            b[r] = jj < P ? order_bucket(sink[jj], mult(jj), k[jj], n, N, in_bw, is_compute, sink_cost) : -1;
+            b[r] = jj < P ? order_bucket(sink[jj], mult(jj), k[jj], n, sum_w, in_bw, is_compute, sink_cost) : -1;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -1051,7 +1053,7 @@ __global__ void __launch_bounds__(1024) fc_order_sinks_kernel(int32_t N, int32_t
                                                               const uint8_t *__restrict__ is_compute,
                                                               const uint32_t *__restrict__ sink_cost,
                                                               int32_t *__restrict__ order, const int32_t *__restrict__ cD,
-                                                              uint8_t *__restrict__ keys) {
+                                                              uint8_t *__restrict__ keys, long long sum_w) {
     constexpr int NB = FC_ORDER_BUCKETS, R = 4;
     __shared__ int32_t hist[NB], base[NB];
     const int32_t tid = threadIdx.x, T = blockDim.x;
@@ -1064,7 +1066,7 @@ __global__ void __launch_bounds__(1024) fc_order_sinks_kernel(int32_t N, int32_t
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int32_t i = i0 + r * T + tid;
-            b[r] = i < N ? order_bucket(compute_ids[i], u0, k0, n, N, in_bw, is_compute, sink_cost) : -1;
+            b[r] = i < N ? order_bucket(compute_ids[i], u0, k0, n, sum_w, in_bw, is_compute, sink_cost) : -1;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -1090,8 +1092,9 @@ __global__ void __launch_bounds__(1024) fc_order_sinks_kernel(int32_t N, int32_t
     }
 }
 
-// feasible_c = AND over sinks of [F(s, v) >= N * k_c] (Theorem 1 / Theorem 3); one workgroup per candidate
-__global__ void __launch_bounds__(256) fc_verdict_kernel(int32_t N, const int32_t *compute_ids, const int32_t *ck,
+// feasible_c = AND over sinks of [F(s, v) >= N * k_c] (Theorem 1 / Theorem 3); one workgroup per candidate.
+// sum_w = N, or the sum of the compute nodes' weights when s's arcs have capacities m_c * k (Section 5.7).
+__global__ void __launch_bounds__(256) fc_verdict_kernel(int32_t N, long long sum_w, const int32_t *compute_ids, const int32_t *ck,
                                                          const int32_t *cU, const int32_t *cD, const int32_t *flows,
                                                          uint8_t *feasible, int32_t *witness) {
     __shared__ int32_t s_wit;
@@ -1099,7 +1102,7 @@ __global__ void __launch_bounds__(256) fc_verdict_kernel(int32_t N, const int32_
     if (tid == 0) s_wit = 0x7fffffff;
     __syncthreads();
     const int32_t k = ck[c], U = cU[c];
-    const long long need = (long long)N * (long long)k;
+    const long long need = sum_w * (long long)k;
     const bool ok_cand = U >= 1 && k >= 1 && (!cD || cD[c] >= 1) && need < (1ll << 31);
     int32_t best = 0x7fffffff;
     for (int32_t s = tid; s < N; s += blockDim.x) {
@@ -1241,6 +1244,7 @@ void common_params(const fc_graph *g, const Resolved &opt, KParams *kp) {
     kp->is_compute = g->d_is_compute;
     kp->compute_ids = g->d_compute_ids;
     kp->in_bw = g->d_in_bw; kp->sink_cost = g->d_sink_cost; kp->sum_bw = g->sum_bw;
+    kp->src_w = g->d_src_weight; kp->sum_w = g->sum_w;
     kp->gr_steps = opt.gr_steps; kp->gr_relabels = opt.gr_relabels; kp->gr_rises = opt.gr_rises;
     kp->tight_pct = opt.tight_pct; kp->use_gap = opt.use_gap; kp->max_steps = opt.max_steps;
 }
@@ -1258,13 +1262,13 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
     bool wide_possible = lds_bytes(g, false) <= size_t(g->lds_limit);
     if (!compact_possible && !wide_possible) return FC_EUNSUPPORTED;
     // the caller vouches that every N * k_j fits the 16-bit layout: skip the 32-bit launch
-    if (compact_possible && opt.src_cap_bound > 0 && (long long)g->N * opt.src_cap_bound <= 65535ll) wide_possible = false;
+    if (compact_possible && opt.src_cap_bound > 0 && (long long)g->sum_w * opt.src_cap_bound <= 65535ll) wide_possible = false;
     kp.arc_compact = compact_possible ? reinterpret_cast<const uint2 *>(g->d_arc_compact) : nullptr;
     kp.labels = opt.use_labels ? g->d_labels : nullptr;
     kp.label_hmax = g->d_label_hmax;
     kp.p1 = opt.use_labels ? reinterpret_cast<const uint4 *>(g->d_p1) : nullptr;
     kp.level_off = g->d_level_off;
-    kp.tree_ratio = opt.tree_certificate && opt.use_labels && !rational ? g->d_tree_ratio : nullptr;   // the certificate's ratio test needs exact capacities U * b
+    kp.tree_ratio = opt.tree_certificate && opt.use_labels && !rational && !g->d_src_weight ? g->d_tree_ratio : nullptr;   // the certificate's ratio test needs exact capacities U * b
     kp.sink = d_sink; kp.U = d_U; kp.k = d_k; kp.Uden = d_Uden; kp.flow_out = d_flow; kp.stats = d_stats_pp;
     kp.wide_available = wide_possible ? 1 : 0;
     if (grid) {
@@ -1272,12 +1276,12 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
         if (wants_order(g, opt, P)) {
             hipLaunchKernelGGL(fc_order_sinks_kernel, dim3(1), dim3(1024), 0, stream, g->N, g->n, g->d_compute_ids,
                                grid->d_U, grid->d_k, g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, grid->d_D,
-                               reinterpret_cast<uint8_t *>(d_order + ws_keys_index(P)));
+                               reinterpret_cast<uint8_t *>(d_order + ws_keys_index(P)), (long long)g->sum_w);
             HIP_TRY(hipGetLastError());
             kp.order = d_order; kp.n_order = g->N;
         }
     } else if (wants_order(g, opt, P)) {
-        hipLaunchKernelGGL(fc_order_kernel, dim3(1), dim3(1024), 0, stream, P, g->n, g->N, d_sink, d_U, d_k,
+        hipLaunchKernelGGL(fc_order_kernel, dim3(1), dim3(1024), 0, stream, P, g->n, (long long)g->sum_w, d_sink, d_U, d_k,
                            g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, d_Uden,
                            reinterpret_cast<uint8_t *>(d_order + ws_keys_index(P)));
         HIP_TRY(hipGetLastError());
@@ -1419,6 +1423,7 @@ extern "C" int fc_graph_free(fc_graph *g) {
         if (g->d_is_compute) (void)hipFree(g->d_is_compute);
         if (g->d_compute_ids) (void)hipFree(g->d_compute_ids);
         if (g->d_in_bw) (void)hipFree(g->d_in_bw);
+        if (g->d_src_weight) (void)hipFree(g->d_src_weight);
         if (g->d_sink_cost) (void)hipFree(g->d_sink_cost);
         if (g->d_tree_ratio) (void)hipFree(g->d_tree_ratio);
         if (g->d_labels) (void)hipFree(g->d_labels);
@@ -1427,6 +1432,33 @@ extern "C" int fc_graph_free(fc_graph *g) {
         if (g->d_level_off) (void)hipFree(g->d_level_off);
     }
     delete g;
+    return FC_OK;
+}
+
+extern "C" int fc_graph_set_source_weights(fc_graph *g, const int32_t *weight_per_vertex) {
+    if (!g) return FC_EINVAL;
+    if (!g->on_device) return FC_EDEVICE;
+    if (!weight_per_vertex) {                            // back to the uniform case
+        if (g->d_src_weight) { (void)hipFree(g->d_src_weight); g->d_src_weight = nullptr; }
+        g->src_weight.clear(); g->sum_w = g->N;
+        return FC_OK;
+    }
+    try {
+        std::vector<int32_t> wts(size_t(g->n), 0);
+        long long sum = 0;
+        for (int32_t v = 0; v < g->n; ++v) {
+            if (!g->is_compute[size_t(v)]) continue;     // entries of switches are ignored
+            if (weight_per_vertex[v] < 0) return FC_EINVAL;
+            wts[size_t(v)] = weight_per_vertex[v]; sum += weight_per_vertex[v];
+        }
+        if (sum < 1) return FC_EINVAL;
+        if (sum >= (1ll << 31)) return FC_EOVERFLOW;
+        if (!g->d_src_weight && hipMalloc(&g->d_src_weight, sizeof(int32_t) * size_t(g->n)) != hipSuccess) { g->d_src_weight = nullptr; return FC_EDEVICE; }
+        if (hipMemcpy(g->d_src_weight, wts.data(), sizeof(int32_t) * size_t(g->n), hipMemcpyHostToDevice) != hipSuccess) return FC_EDEVICE;
+        g->src_weight.swap(wts); g->sum_w = sum;
+    } catch (const std::bad_alloc &) {
+        return FC_ENOMEM;
+    }
     return FC_OK;
 }
 
@@ -1525,7 +1557,7 @@ int feasible_impl(const fc_graph *g, int32_t n_candidates, const int32_t *d_edge
     rc = run_batch(g, P, nullptr, nullptr, nullptr, d_flow, opt, stream, stats_or_null ? d_pp : nullptr, d_order, &grid, ev0);
     if (rc != FC_OK) return done(rc);
     if (stats_or_null && hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
-    hipLaunchKernelGGL(fc_verdict_kernel, dim3(unsigned(n_candidates)), dim3(256), 0, stream, g->N, g->d_compute_ids,
+    hipLaunchKernelGGL(fc_verdict_kernel, dim3(unsigned(n_candidates)), dim3(256), 0, stream, g->N, (long long)g->sum_w, g->d_compute_ids,
                        d_src_cap, d_edge_mult, d_mult_den, d_flow, d_feasible_out, d_witness_sink_or_null);
     if (hipGetLastError() != hipSuccess) return done(FC_EDEVICE);
     if (!stats_or_null) return done(FC_OK);
@@ -1602,6 +1634,7 @@ extern "C" int fc_opt_throughput_search(const fc_graph *g, int32_t candidates_pe
                                         uint8_t *trace_verdict, int32_t trace_capacity, int32_t *trace_len_or_null) {
     if (!g || !inv_xstar || !U || !k || candidates_per_round < 1 || candidates_per_round > 4096 || trace_capacity < 0) return FC_EINVAL;
     if (!g->on_device) return FC_EDEVICE;
+    if (g->d_src_weight) return FC_EUNSUPPORTED;         // the paper defines this only for unit weights
     Resolved opt;
     int rc = resolve_options(g, options_or_null, &opt);
     if (rc != FC_OK) return rc;
@@ -1675,6 +1708,7 @@ extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int
                                     void *hip_stream, const fc_options *options_or_null, fc_stats *stats_or_null) {
     if (!g || n_pairs < 0 || U < 1 || k < 1) return FC_EINVAL;
     if (!g->on_device) return FC_EDEVICE;
+    if (g->d_src_weight) return FC_EUNSUPPORTED;         // the paper defines this only for unit weights
     Resolved opt;
     int rc = resolve_options(g, options_or_null, &opt);
     if (rc != FC_OK) return rc;
@@ -1728,6 +1762,7 @@ extern "C" int fc_fixed_k_search(const fc_graph *g, int32_t k, int32_t candidate
                                  int32_t *trace_len_or_null) {
     if (!g || !U_star || k < 1 || candidates_per_round < 1 || candidates_per_round > 4096 || trace_capacity < 0) return FC_EINVAL;
     if (!g->on_device) return FC_EDEVICE;
+    if (g->d_src_weight) return FC_EUNSUPPORTED;         // the paper defines this only for unit weights
     Resolved opt;
     int rc = resolve_options(g, options_or_null, &opt);
     if (rc != FC_OK) return rc;

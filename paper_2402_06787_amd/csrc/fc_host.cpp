@@ -58,6 +58,7 @@ int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const
             if (is_compute[v]) g->compute_ids.push_back(v);
         }
         g->N = int32_t(g->compute_ids.size());
+        g->sum_w = g->N;
         if (g->N < 2) { delete g; return FC_EINVAL; }
 
         std::vector<int64_t> in_bw(size_t(n_vertices), 0), out_bw(size_t(n_vertices), 0);

@@ -20,6 +20,8 @@ struct fc_graph {
     std::vector<int32_t> compute_ids;  // [N] increasing
     std::vector<int32_t> in_bw;        // [n] in-bandwidth B^-(v) of every vertex
     int64_t sum_bw = 0;                // sum of all link bandwidths
+    std::vector<int32_t> src_weight;   // [n] m_c of the non-uniform variant (0 for switches); empty: every compute node 1
+    int64_t sum_w = 0;                 // sum of the weights; N while they are uniform
     int64_t min_in_bw = 0;         // min over compute nodes of B^-(v)
     int32_t max_bw = 0, gcd_bw = 0, eulerian = 0;
     int32_t max_row = 0;           // longest residual row
@@ -32,6 +34,7 @@ struct fc_graph {
     uint8_t *d_is_compute = nullptr;   // [n]
     int32_t *d_compute_ids = nullptr;  // [N]
     int32_t *d_in_bw = nullptr;        // [n]
+    int32_t *d_src_weight = nullptr;   // [n], or null while the weights are uniform
     uint32_t *d_sink_cost = nullptr;   // [n] cost of the last problem solved per sink (scheduling hint, updated by the solver)
     uint16_t *d_labels = nullptr;      // [n*n] exact initial labels per sink (row = sink), bit 15 = compute; or null
     uint16_t *d_label_hmax = nullptr;  // [n] highest finite label of a compute node, per sink

@@ -621,3 +621,108 @@ def test_large_batch_two_streams_and_degenerate_graphs():
         with pytest.raises(fc.FcError) as ei:
             fc.fc_opt_throughput_search(g, 4)
         assert ei.value.code == fc.FC_EDISCONNECTED
+
+
+# ------------------------------------------------------------------ non-uniform source capacities (Section 5.7)
+
+def _merged(topo):
+    tail, head, bw = o.links(topo)
+    return w.Topology(topo.name, topo.n_vertices, tail, head, bw, topo.is_compute)
+
+
+@pytest.mark.parametrize("cfg", [1, 3, 4, 5])
+def test_weighted_source_arcs_match_oracle(cfg):
+    topo = w.config_topology(cfg)
+    N, comp = topo.n_compute, topo.compute_nodes
+    rng = np.random.default_rng(700 + cfg)
+    wts = rng.integers(0, 4, topo.n_vertices).astype(np.int32)
+    wts[comp[0]] = 3                                       # not all zero
+    sum_w = int(wts[comp].sum())
+    inv = Fraction(*_optimum(cfg, topo))
+    # candidates around the unit-weight optimum scaled by the mean weight, plus one that needs the 32-bit state
+    mean = Fraction(sum_w, N)
+    cands = []
+    for kk in (1, 2, 5):
+        centre = inv * mean * kk
+        cands += [(max(1, int(centre * f)), kk) for f in (Fraction(1, 2), Fraction(9, 10), 1, Fraction(11, 10), 2)]
+    cands.append((max(1, int(inv * mean * 70000 // sum_w + 1)), 70000 // sum_w + 1))      # k * sum_w > 65535
+    U = np.array([c[0] for c in cands], np.int32); k = np.array([c[1] for c in cands], np.int32)
+    sinks = comp if cfg < 4 else np.sort(rng.choice(comp, 64 if cfg == 4 else 24, replace=False))
+    sink = np.tile(sinks, len(cands)); Uj = np.repeat(U, len(sinks)); kj = np.repeat(k, len(sinks))
+    want = o.weighted_aux_maxflow_batch(topo, sink, Uj, kj, wts)
+    with _upload(topo) as g:
+        before, _ = _gpu_flows(g, sink[: len(sinks)], Uj[: len(sinks)], kj[: len(sinks)])
+        fc.fc_graph_set_source_weights(g, wts)
+        got, stats = _gpu_flows(g, sink, Uj, kj, want_stats=True)
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, (cfg, bad[:8], got[bad[:8]], want[bad[:8]])
+        assert stats["not_converged"] == 0
+        assert (got <= kj.astype(np.int64) * sum_w).all()
+        # all launch modes agree
+        for opt in ({"use_label_table": 2}, {"force_wide": 1}, {"tree_certificate": 1}, {"schedule": 2, "use_gap": 2}):
+            alt, _ = _gpu_flows(g, sink, Uj, kj, options=opt)
+            assert (alt == want).all(), opt
+        # verdicts: F >= k * sum of the weights at every compute node
+        res = fc.fc_feasible(g, _dev(U), _dev(k), want_flows=True)
+        torch.cuda.synchronize()
+        feas = res["feasible"].cpu().numpy(); wit = res["witness"].cpu().numpy(); flows = res["flows"].cpu().numpy().astype(np.int64)
+        if cfg < 4:
+            assert (flows.reshape(-1) == want).all()
+            for c in range(len(cands)):
+                row = want[c * N:(c + 1) * N]
+                short = comp[row < int(k[c]) * sum_w]
+                assert bool(feas[c]) == (short.size == 0) and wit[c] == (-1 if short.size == 0 else short.min())
+        else:
+            pos = np.searchsorted(comp, sinks)
+            assert (flows[:, pos].reshape(-1) == want).all()
+        # floor capacities with weights (the floor is per link: the oracle gets merged links)
+        mt = _merged(topo)
+        num = np.repeat(U.astype(np.int64) * 3 + 1, len(sinks)); den = np.full(len(sink), 3, np.int64)
+        want_f = o.weighted_aux_maxflow_batch(mt, sink[: 6 * len(sinks)], num[: 6 * len(sinks)], kj[: 6 * len(sinks)], wts, U_den=den[: 6 * len(sinks)])
+        got_f, _ = _gpu_flows_floor(g, sink[: 6 * len(sinks)], num[: 6 * len(sinks)], den[: 6 * len(sinks)], kj[: 6 * len(sinks)])
+        assert (got_f == want_f).all()
+        # what the paper defines for unit weights only is refused, not answered wrongly
+        for call in (lambda: fc.fc_opt_throughput_search(g, 4), lambda: fc.fc_fixed_k_search(g, 2, 4)):
+            with pytest.raises(fc.FcError) as err:
+                call()
+            assert err.value.code == fc.FC_EUNSUPPORTED
+        # unit weights, given explicitly or by resetting, are the uniform case again
+        fc.fc_graph_set_source_weights(g, np.ones(topo.n_vertices, np.int32))
+        ones, _ = _gpu_flows(g, sink[: len(sinks)], Uj[: len(sinks)], kj[: len(sinks)])
+        fc.fc_graph_set_source_weights(g, None)
+        after, _ = _gpu_flows(g, sink[: len(sinks)], Uj[: len(sinks)], kj[: len(sinks)])
+        assert (ones == before).all() and (after == before).all()
+        assert fc.fc_opt_throughput_search(g, 8)["inv_xstar"] == inv
+
+
+def test_weighted_source_arcs_on_tiny_random_graphs_and_bad_weights():
+    for seed in range(40):
+        topo = w.random_tiny(4000 + seed)
+        rng = np.random.default_rng(4500 + seed)
+        comp = topo.compute_nodes
+        wts = rng.integers(0, 5, topo.n_vertices).astype(np.int32)
+        if wts[comp].sum() == 0:
+            wts[comp[-1]] = 1
+        P = 24
+        sink = rng.choice(comp, P).astype(np.int32); U = rng.integers(1, 6, P).astype(np.int32); k = rng.integers(1, 9, P).astype(np.int32)
+        want = o.weighted_aux_maxflow_batch(topo, sink, U, k, wts)
+        with _upload(topo) as g:
+            fc.fc_graph_set_source_weights(g, wts)
+            got, _ = _gpu_flows(g, sink, U, k)
+            assert (got == want).all(), seed
+            ok, flows = o.weighted_feasible(topo, int(U[0]), int(k[0]), wts)
+            res = fc.fc_feasible(g, _dev(U[:1]), _dev(k[:1]), want_flows=True)
+            torch.cuda.synchronize()
+            assert bool(res["feasible"].cpu().numpy()[0]) == ok and (res["flows"].cpu().numpy()[0] == flows).all()
+    topo = w.config_topology(1)
+    with _upload(topo) as g:
+        bad = np.ones(topo.n_vertices, np.int32); bad[topo.compute_nodes[1]] = -1
+        for arr, code in ((bad, fc.FC_EINVAL), (np.zeros(topo.n_vertices, np.int32), fc.FC_EINVAL),
+                          (np.full(topo.n_vertices, 2 ** 30, np.int32), fc.FC_EOVERFLOW)):
+            with pytest.raises(fc.FcError) as err:
+                fc.fc_graph_set_source_weights(g, arr)
+            assert err.value.code == code
+        # a k whose product with the weight sum leaves 31 bits is a malformed problem, as N k is without weights
+        fc.fc_graph_set_source_weights(g, np.full(topo.n_vertices, 2 ** 20, np.int32))
+        got, _ = _gpu_flows(g, topo.compute_nodes[:2], [1, 1], [1, 2 ** 11])
+        assert got[1] == fc.FC_FLOW_INVALID and got[0] == o.weighted_aux_maxflow_batch(topo, topo.compute_nodes[:1], [1], [1], np.full(topo.n_vertices, 2 ** 20))[0]
