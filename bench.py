@@ -118,6 +118,28 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     solves_per_s = P * args.steps / elapsed
 
+    # the same 16384 problems as an explicit (sink, U, k) list through fc_maxflow_batch: the same solver
+    # kernel behind a per-problem ordering kernel instead of the per-sink one; reported beside the headline
+    batch_leg = None
+    if not args.no_certificate_leg:
+        pl = w.all_sinks(topo, cU, ck)
+        d_sink, d_mult, d_cap = (torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev) for a in (pl.sink, pl.edge_mult, pl.src_cap))
+        ws_b = torch.empty(fc.fc_maxflow_batch_workspace_bytes(g, P), dtype=torch.uint8, device=dev)
+        d_out = torch.empty(P, dtype=torch.int32, device=dev)
+        for _ in range(args.warmup):
+            fc.fc_maxflow_batch(g, d_sink, d_mult, d_cap, d_flow_out=d_out, d_workspace=ws_b, options=opts)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fc.fc_maxflow_batch(g, d_sink, d_mult, d_cap, d_flow_out=d_out, d_workspace=ws_b, options=opts)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        batch_leg = {"value": P * args.steps / el, "unit": "solves/s", "ms_per_step": el / args.steps * 1e3,
+                     "note": "explicit problem list; not the headline"}
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+
     # the same step with the optional first-arc tree certificate (problems whose sink tree carries
     # all N*k units are answered without running the solver); reported beside the headline, never as it
     elapsed_cert = None
@@ -214,6 +236,12 @@ def main():
             ref = [oracle.split_gamma(D3, k3, pu[i], pw[i], pt[i]) for i in range(0, 256, 32)]
             gamma["parity_vs_oracle"] = {"checked_pairs": len(ref), "mismatches": int(sum(int(got[i * 32]) != ref[i] for i in range(len(ref))))}
         g3.close()
+        # Algorithm 2's loop around such batches on the same graph (capacities U * b_e): every switch split off
+        cap3 = (np.asarray(t3.bandwidth, dtype=np.int64) * U3).astype(np.int32)
+        t0 = time.perf_counter()
+        rs = fc.fc_remove_switches(t3.n_vertices, t3.tail, t3.head, cap3, t3.is_compute, k3)
+        gamma["remove_switches"] = {"wall_ms": (time.perf_counter() - t0) * 1e3, "batches": rs["batches"],
+                                    "links_out": len(rs["links"]), "table_entries": sum(len(v) for v in rs["table"].values())}
 
     # the dominant kernel alone: HIP events recorded by the library on the launch stream around
     # the solver kernel, same inputs, same launch configuration
@@ -251,6 +279,7 @@ def main():
         "with_tree_certificate": None if elapsed_cert is None else
             {"value": P * args.steps / elapsed_cert, "unit": "solves/s", "ms_per_step": elapsed_cert / args.steps * 1e3,
              "note": "option tree_certificate=1; not the headline"},
+        "fc_maxflow_batch": batch_leg,
         "fixed_k": fixed,
         "split_gamma": gamma,
         "search": {"inv_xstar": f"{inv[0]}/{inv[1]}", "U": str(search["U"]), "k": search["k"],

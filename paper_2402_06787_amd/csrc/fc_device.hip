@@ -44,6 +44,8 @@
 
 namespace {
 
+constexpr int FC_ORDER_CHUNK = 16;     // consecutive entries of a launch order that share an XCD
+
 struct KParams {
     int32_t n, N, m0;
     int32_t n_rec;               // residual arc records (at least 1: a zeroed dummy when the graph has no arcs)
@@ -66,6 +68,7 @@ struct KParams {
     int32_t wide_available;      // the 32-bit-state kernel is launched too
     const int32_t *order;        // workgroup -> problem (hardest first), or null for the identity
     int32_t n_order;             // entries of `order`: an entry outside [0, n_order) is never followed
+    int32_t order_chunked;       // problem-list launches: runs of FC_ORDER_CHUNK consecutive entries of `order` go to one XCD
     // candidate x sink launches (fc_feasible): workgroup b solves candidate b % cand_C for the sink that
     // has place b / cand_C in the order; the problem list is never written out
     int32_t cand_C;              // 0: plain problem list
@@ -516,7 +519,14 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
         j = c * p.N + i; t = p.compute_ids[i]; U = p.cand_U[c]; k = p.cand_k[c];
         if (RAT) D = p.cand_D[c];
     } else {
-        j = p.order ? p.order[blockIdx.x] : int32_t(blockIdx.x);
+        if (p.order_chunked) {
+            // the order lists the problems of one sink next to each other; workgroups go to the XCDs round-robin
+            // by index, so a run of consecutive entries is given indices that are equal modulo 8 (see above)
+            const int32_t xcd = int32_t(blockIdx.x) & 7, q = int32_t(blockIdx.x) >> 3;
+            const int32_t idx = ((q / FC_ORDER_CHUNK) * 8 + xcd) * FC_ORDER_CHUNK + q % FC_ORDER_CHUNK;
+            if (idx >= p.n_order) return;                 // the grid is padded to whole groups of eight runs
+            j = p.order[idx];
+        } else j = p.order ? p.order[blockIdx.x] : int32_t(blockIdx.x);
         if (p.order && (j < 0 || j >= p.n_order)) return;
         t = p.sink[j]; U = p.U[j]; k = p.k[j];
         if (RAT) D = p.Uden[j];
@@ -1043,6 +1053,81 @@ __global__ void __launch_bounds__(1024) fc_order_kernel(long long P, int32_t n, 
     }
 }
 
+// The same for graphs of at most FC_ORDER_BY_SINK_MAX vertices, where the per-vertex counters fit
+// on chip: the SINKS are sorted by cost and every sink's problems follow each other in the order, so
+// that they run at the same time on the same XCD and share the sink's tables in its L2 (the solver
+// maps runs of FC_ORDER_CHUNK entries to one XCD).  A sink's key comes from its history, else from
+// the guess for its first-listed problem.  Two passes over the problem list, one over the vertices.
+constexpr int FC_ORDER_BY_SINK_MAX = 4096;
+
+__global__ void __launch_bounds__(1024) fc_order_by_sink_kernel(long long P, int32_t n, long long sum_w,
+                                                                const int32_t *__restrict__ sink, const int32_t *__restrict__ U,
+                                                                const int32_t *__restrict__ k, const int32_t *__restrict__ in_bw,
+                                                                const uint8_t *__restrict__ is_compute,
+                                                                const uint32_t *__restrict__ sink_cost,
+                                                                int32_t *__restrict__ order, const int32_t *__restrict__ Uden) {
+    constexpr int NB = FC_ORDER_BUCKETS, NV = FC_ORDER_BY_SINK_MAX + 1, R = 8;
+    __shared__ int32_t cnt[NV], rep[NV], hist[NB], base[NB];   // slot n: problems whose sink is not a vertex (last)
+    const int32_t tid = threadIdx.x, T = blockDim.x;
+    for (int32_t v = tid; v <= n; v += T) { cnt[v] = 0; rep[v] = 0x7fffffff; }
+    for (int32_t b = tid; b < NB; b += T) hist[b] = 0;
+    __syncthreads();
+    for (long long j0 = 0; j0 < P; j0 += (long long)R * T) {
+        int32_t t[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const long long jj = j0 + (long long)r * T + tid;
+            t[r] = jj < P ? sink[jj] : -2;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (t[r] == -2) continue;
+            const int32_t v = t[r] >= 0 && t[r] < n ? t[r] : n;
+            atomicAdd(&cnt[v], 1);
+            atomicMin(&rep[v], int32_t(j0 + (long long)r * T + tid));
+        }
+    }
+    __syncthreads();
+    // every listed sink's bucket, weighted by the number of its problems; the bucket is kept in rep[]
+    for (int32_t v = tid; v <= n; v += T) {
+        const int32_t c = cnt[v];
+        int32_t b = NB - 1;
+        if (c > 0 && v < n) {
+            const int32_t jj = rep[v];
+            int32_t u = U[jj];
+            if (Uden) { const int32_t dd = Uden[jj]; u = dd >= 1 && u >= dd ? u / dd : (u >= 1 && dd >= 1 ? 1 : 0); }
+            b = order_bucket(v, u, k[jj], n, sum_w, in_bw, is_compute, sink_cost);
+        }
+        rep[v] = b;
+        if (c > 0) atomicAdd(&hist[b], c);
+    }
+    __syncthreads();
+    if (tid < 64) order_bucket_bases(hist, base, tid);
+    __syncthreads();
+    // a contiguous range per sink inside its bucket (the invalid ones after every real sink of the last bucket)
+    for (int32_t v = tid; v < n; v += T) {
+        const int32_t c = cnt[v];
+        if (c > 0) cnt[v] = atomicAdd(&base[rep[v]], c);
+    }
+    __syncthreads();
+    if (tid == 0 && cnt[n] > 0) cnt[n] = atomicAdd(&base[NB - 1], cnt[n]);
+    __syncthreads();
+    for (long long j0 = 0; j0 < P; j0 += (long long)R * T) {
+        int32_t t[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const long long jj = j0 + (long long)r * T + tid;
+            t[r] = jj < P ? sink[jj] : -2;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (t[r] == -2) continue;
+            const int32_t v = t[r] >= 0 && t[r] < n ? t[r] : n;
+            order[atomicAdd(&cnt[v], 1)] = int32_t(j0 + (long long)r * T + tid);
+        }
+    }
+}
+
 // fc_feasible's problems are C candidates x N sinks (problem c * N + i).  Only the N sinks are
 // sorted (by the cost of candidate 0): order[place] = i.  The solver derives each workgroup's
 // (candidate, sink) from its index, so the C problems of a sink sit next to each other in the
@@ -1281,15 +1366,22 @@ int run_batch(const fc_graph *g, long long P, const int32_t *d_sink, const int32
             kp.order = d_order; kp.n_order = g->N;
         }
     } else if (wants_order(g, opt, P)) {
-        hipLaunchKernelGGL(fc_order_kernel, dim3(1), dim3(1024), 0, stream, P, g->n, (long long)g->sum_w, d_sink, d_U, d_k,
-                           g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, d_Uden,
-                           reinterpret_cast<uint8_t *>(d_order + ws_keys_index(P)));
+        if (g->n <= FC_ORDER_BY_SINK_MAX) {
+            hipLaunchKernelGGL(fc_order_by_sink_kernel, dim3(1), dim3(1024), 0, stream, P, g->n, (long long)g->sum_w, d_sink, d_U, d_k,
+                               g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, d_Uden);
+            kp.order_chunked = 1;
+        } else {
+            hipLaunchKernelGGL(fc_order_kernel, dim3(1), dim3(1024), 0, stream, P, g->n, (long long)g->sum_w, d_sink, d_U, d_k,
+                               g->d_in_bw, g->d_is_compute, g->d_sink_cost, d_order, d_Uden,
+                               reinterpret_cast<uint8_t *>(d_order + ws_keys_index(P)));
+        }
         HIP_TRY(hipGetLastError());
         kp.order = d_order; kp.n_order = int32_t(P);
     }
     if (ev_solver_start) HIP_TRY(hipEventRecord(ev_solver_start, stream));    // after the ordering kernel
     // grid: one workgroup per problem; the candidate grid is padded to whole groups of eight sinks
-    const long long grid_wgs = grid ? (long long)((g->N + 7) / 8) * 8 * grid->C : P;
+    const long long grid_wgs = grid ? (long long)((g->N + 7) / 8) * 8 * grid->C
+                             : kp.order_chunked ? (P + 8 * FC_ORDER_CHUNK - 1) / (8 * FC_ORDER_CHUNK) * (8 * FC_ORDER_CHUNK) : P;
     if (compact_possible) {
         int rc = rational ? launch_g<true, true>(kp, grid_wgs, opt.T, opt.G, lds_bytes(g, true), stream)
                           : launch_g<true, false>(kp, grid_wgs, opt.T, opt.G, lds_bytes(g, true), stream);
