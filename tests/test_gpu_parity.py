@@ -623,6 +623,29 @@ def test_large_batch_two_streams_and_degenerate_graphs():
         assert ei.value.code == fc.FC_EDISCONNECTED
 
 
+def test_ordered_list_with_malformed_problems_and_a_ragged_length():
+    # an explicit list long enough to be reordered (sinks grouped, runs of 16 per XCD), its length no multiple of
+    # the run size, with sinks that are not vertices and non-positive multipliers scattered through it
+    topo = w.config_topology(3)
+    rng = np.random.default_rng(77)
+    for P in (5003, 1031, 128 * 9 + 1):
+        sink = rng.choice(topo.compute_nodes, P).astype(np.int32)
+        U = rng.integers(10, 70, P).astype(np.int32); k = rng.integers(1, 9, P).astype(np.int32)
+        bad = rng.random(P) < 0.06
+        kind = rng.integers(0, 5, P)
+        sink[bad & (kind == 0)] = -1; sink[bad & (kind == 1)] = topo.n_vertices; sink[bad & (kind == 2)] = topo.n_vertices + 1000
+        U[bad & (kind == 3)] = 0; k[bad & (kind == 4)] = -3
+        ok = ~bad
+        want = o.aux_maxflow_batch(topo, sink[ok], U[ok], k[ok], threads=16)
+        with _upload(topo) as g:
+            for rep in range(2):                           # the second call sorts by the first one's cost hints
+                got, stats = _gpu_flows(g, sink, U, k, want_stats=True)
+                assert (got[ok] == want).all() and (got[bad] == fc.FC_FLOW_INVALID).all(), (P, rep)
+                assert stats["not_converged"] == 0
+            plain, _ = _gpu_flows(g, sink, U, k, options={"schedule": 2})
+            assert (plain == got).all()
+
+
 # ------------------------------------------------------------------ non-uniform source capacities (Section 5.7)
 
 def _merged(topo):
