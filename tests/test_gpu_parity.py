@@ -419,10 +419,10 @@ def _switch_pairs(topo):
     return [(u, sw, t) for sw in switches for (u, x) in sorted(cap) if x == sw for (y, t) in sorted(cap) if y == sw]
 
 
-def _gamma_on_gpu(topo, U, k, pairs, want_flows=True):
+def _gamma_on_gpu(topo, U, k, pairs, want_flows=True, options=None):
     pu, pw, pt = (np.array([p[i] for p in pairs], dtype=np.int32) for i in range(3))
     with _upload(topo) as g:
-        res = fc.fc_split_gamma_batch(g, U, k, _dev(pu), _dev(pw), _dev(pt), want_flows=want_flows, want_stats=True)
+        res = fc.fc_split_gamma_batch(g, U, k, _dev(pu), _dev(pw), _dev(pt), want_flows=want_flows, want_stats=True, options=options)
         torch.cuda.synchronize()
     assert res["stats"]["not_converged"] == 0
     return res["gamma"].cpu().numpy().astype(np.int64), (res["flows"].cpu().numpy().astype(np.int64) if want_flows else None)
@@ -505,6 +505,12 @@ def test_split_gamma_on_configs(cfg):
         F1, F2 = o.split_flows(D, kk, u, sw, t)
         assert (flows[i, 0] == F1).all() and (flows[i, 1] == F2).all(), (cfg, u, sw, t)
         assert got[i] == o.split_gamma(D, kk, u, sw, t)
+    # initial heights from the distance tables (the default on the larger graphs) or from a search in the kernel;
+    # relabel policies; lanes per vertex
+    for opt in ({"use_label_table": 2}, {"global_relabel_rises": -1, "use_gap": 2}, {"global_relabel_rises": 1, "lanes_per_vertex": 4},
+                {"threads_per_problem": 256, "lanes_per_vertex": 32}):
+        alt, alt_flows = _gamma_on_gpu(topo, U, kk, pick, options=opt)
+        assert (alt == got).all() and (alt_flows == flows).all(), (cfg, opt)
 
 
 # ------------------------------------------------------------------ Algorithm 2: the switch-removal loop around the gamma batches
