@@ -281,9 +281,11 @@ int fc_fixed_k_search_with_verdicts(int32_t n_compute, int64_t min_in_bw, int32_
  * that is not two links through a switch node.  d_flows_or_null: device int32 [n_pairs][2][N], the two
  * families of flows in compute-node order; "unbounded" (a path of unbounded arcs exists) is reported as
  * the one value U * (sum of all b_e) + N k + 1, which exceeds every finite cut.  That value must stay
- * below 2^30 (FC_EOVERFLOW), and the 32-bit on-chip state must fit (FC_EUNSUPPORTED).  Workspace,
- * stream, options and stats as for fc_maxflow_batch (no per-sink tables, launch order or certificate
- * apply to these problems). */
+ * below 2^30 (FC_EOVERFLOW), and the 32-bit on-chip state must fit (FC_EUNSUPPORTED).  When the flows are
+ * not asked for, a max-flow ends as soon as N k + min{c(e), c(f)} units have arrived -- from there on it
+ * cannot be the term that decides gamma -- so gamma is the same and the work is much less; with
+ * d_flows every value is the exact maximum.  Workspace, stream, options and stats as for
+ * fc_maxflow_batch (no first-pass tables, launch order or certificate apply to these problems). */
 #define FC_GAMMA_INVALID (-2147483647 - 1)
 size_t fc_split_gamma_workspace_bytes(const fc_graph *g, int64_t n_pairs);
 int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int64_t n_pairs, const int32_t *d_u,

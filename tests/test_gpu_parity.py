@@ -484,6 +484,8 @@ def test_split_gamma_matches_oracle_on_random_eulerian_graphs():
             assert got[i] == o.split_gamma(D, kk, u, sw, t), (seed, u, sw, t)
             assert got[i] >= 0
         assert (got[len(pairs):] == fc.FC_GAMMA_INVALID).all()
+        early, _ = _gamma_on_gpu(sym, U, kk, pairs + bogus, want_flows=False)      # max-flows may stop early: same gamma
+        assert (early == got).all(), seed
         checked += len(pairs)
     assert checked > 200
 
@@ -511,6 +513,9 @@ def test_split_gamma_on_configs(cfg):
                 {"threads_per_problem": 256, "lanes_per_vertex": 32}):
         alt, alt_flows = _gamma_on_gpu(topo, U, kk, pick, options=opt)
         assert (alt == got).all() and (alt_flows == flows).all(), (cfg, opt)
+    # without the flows a max-flow may stop once N k + min{c(e), c(f)} units have arrived: gamma is the same
+    early, _ = _gamma_on_gpu(topo, U, kk, pick, want_flows=False)
+    assert (early == got).all()
 
 
 # ------------------------------------------------------------------ Algorithm 2: the switch-removal loop around the gamma batches
