@@ -724,7 +724,8 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
     bool failed = false;
 
     // ---- steps: one height level each
-    while (d >= 1 && arrived() < stop_at) {
+    if (arrived() >= stop_at) d = 0;       // nothing to do (inside the loop the same test follows every step)
+    while (d >= 1) {
         const int32_t sp = total_steps & 1;
         FC_TICK(t_other);
         int32_t cnt, lvltot = 0;
