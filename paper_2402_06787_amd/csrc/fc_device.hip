@@ -873,6 +873,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
         lds_barrier();
         FC_TICK(t_discharge);
         const int32_t nrel = st.sh->nrel[sp], down = st.sh->down[sp];
+        const int32_t arr = arrived();     // read with the step's other results; nothing below moves excess
         int32_t dn = st.sh->dnext[sp];
         const int32_t dcarry = st.sh->dcarry[sp];
         // level d lost its last vertex: nothing above it can reach the sink any more
@@ -909,7 +910,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
             }
         }
         FC_TICK(t_post);
-        if (arrived() >= stop_at) break;
+        if (arr >= stop_at) break;
         if (total_steps >= p.max_steps) { failed = true; break; }
 
         // ---- next level
