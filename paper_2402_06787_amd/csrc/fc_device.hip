@@ -620,7 +620,22 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) 
         uint4 *fz = reinterpret_cast<uint4 *>(smem + cv.f);
         const int32_t quads = int32_t((cv.h - cv.f) / 16);
         for (int32_t i = tid; i < quads; i += T) fz[i] = make_uint4(0u, 0u, 0u, 0u);
-        for (int32_t v = tid; v < n; v += T) {
+        // four vertices per lane when the 16-bit rows are 8-byte aligned (n a multiple of 4): the label row and the
+        // row offsets come as 8- and 16-byte loads, heights, excess and offsets go out as 8-byte LDS stores
+        const bool by_four = COMPACT && !GEN && have_labels && (n & 3) == 0 && p.src_w == nullptr;
+        if (by_four) {
+            const uint2 *lab4 = reinterpret_cast<const uint2 *>(p.labels + size_t(t) * size_t(n));
+            const int4 *rp4 = reinterpret_cast<const int4 *>(p.row_ptr);
+            uint2 *h2 = reinterpret_cast<uint2 *>(smem + cv.h), *e2 = reinterpret_cast<uint2 *>(smem + cv.e), *r2 = reinterpret_cast<uint2 *>(smem + cv.rp);
+            for (int32_t i = tid; i < (n >> 2); i += T) {
+                const uint2 l = lab4[i];
+                const int4 r = rp4[i];
+                h2[i] = make_uint2(l.x & 0x7fff7fffu, l.y & 0x7fff7fffu);
+                e2[i] = make_uint2(((l.x >> 15) & 0x00010001u) * uint32_t(k), ((l.y >> 15) & 0x00010001u) * uint32_t(k));   // k < 2^16 here
+                r2[i] = make_uint2(uint32_t(r.x) | (uint32_t(r.y) << 16), uint32_t(r.z) | (uint32_t(r.w) << 16));
+            }
+        }
+        for (int32_t v = tid; v < n && !by_four; v += T) {
             st.rp[v] = W(p.row_ptr[v]);
             if (have_labels) {
                 const uint32_t lc = p.labels[size_t(t) * size_t(n) + size_t(v)];
