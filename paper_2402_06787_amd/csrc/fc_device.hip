@@ -481,9 +481,13 @@ __device__ void global_relabel(const KParams &p, const State<COMPACT> &st, int32
 // collect the smallest residual-neighbour height for the relabel in the same scan.
 //
 // Template flags: COMPACT = 16-bit on-chip state, RAT = rational multipliers (floor capacities),
-// GEN = an edge-splitting problem (explicit source, "unbounded" arcs, no tables), G = lanes per vertex.
-template <bool COMPACT, bool RAT, bool GEN, int G>
-__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(5))) fc_push_relabel_kernel(KParams p) {
+// GEN = an edge-splitting problem (explicit source, "unbounded" arcs, no tables), G = lanes per vertex,
+// OCC = wavefronts per SIMD the register allocation leaves room for.  A problem's LDS footprint decides how
+// many wavefronts a CU can hold: large graphs stop at 5 per SIMD and get the build with the most
+// registers; small graphs fit 8 per SIMD and run faster with fewer registers (a few spilled) and
+// more wavefronts in flight.
+template <bool COMPACT, bool RAT, bool GEN, int G, int OCC>
+__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(OCC))) fc_push_relabel_kernel(KParams p) {
     static_assert(!GEN || (!COMPACT && !RAT), "the edge-splitting problems use the 32-bit state and integer multipliers");
     using W = typename State<COMPACT>::W;
     constexpr int32_t NEWH = State<COMPACT>::NEWH;
@@ -1311,9 +1315,9 @@ int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
     return FC_OK;
 }
 
-template <bool COMPACT, bool RAT, bool GEN, int G>
-int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_t stream) {
-    auto kern = fc_push_relabel_kernel<COMPACT, RAT, GEN, G>;
+template <bool COMPACT, bool RAT, bool GEN, int G, int OCC>
+int launch_occ(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_t stream) {
+    auto kern = fc_push_relabel_kernel<COMPACT, RAT, GEN, G, OCC>;
 #ifdef FC_TUNING_BUILD
     if (const char *pad = getenv("FC_LDS_PAD")) lds += size_t(atol(pad));     // occupancy experiments: request more LDS than needed
 #endif
@@ -1329,6 +1333,20 @@ int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_
     hipLaunchKernelGGL(kern, dim3(unsigned(P)), dim3(unsigned(T)), lds, stream, kp);
     HIP_TRY(hipGetLastError());
     return FC_OK;
+}
+
+// Which register budget: measured on MI355X, the edge-splitting kernels are fastest built for 6 wavefronts
+// per SIMD; the others for 8 when the LDS of a CU (160 KB) holds that many wavefronts, else for 5.
+template <bool COMPACT, bool RAT, bool GEN, int G>
+int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_t stream) {
+    if constexpr (GEN) {
+        return launch_occ<COMPACT, RAT, true, G, 6>(kp, P, T, lds, stream);
+    } else {
+        const size_t wgs_by_lds = std::min<size_t>(32, (160u * 1024u) / std::max<size_t>(lds, 1));
+        const size_t waves_per_simd = wgs_by_lds * size_t(T / 64) / 4;
+        if (waves_per_simd >= 8) return launch_occ<COMPACT, RAT, false, G, 8>(kp, P, T, lds, stream);
+        return launch_occ<COMPACT, RAT, false, G, 5>(kp, P, T, lds, stream);
+    }
 }
 
 template <bool COMPACT, bool RAT, bool GEN = false>
