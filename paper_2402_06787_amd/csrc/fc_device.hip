@@ -1285,7 +1285,12 @@ int resolve_options(const fc_graph *g, const fc_options *o, Resolved *r) {
     fc_options z; std::memset(&z, 0, sizeof z);
     if (!o) o = &z;
     int32_t T = o->threads_per_problem;
-    if (T == 0) T = g->n >= 512 ? 256 : (g->n >= 96 ? 128 : 64);
+    if (T == 0) {
+        // A problem that fills much of a CU's LDS leaves room for few workgroups: give it four wavefronts.  When many
+        // problems fit, one or two wavefronts each and more problems in flight are faster (measured on configs 3 to 5).
+        const size_t wgs_by_lds = (160u * 1024u) / std::max<size_t>(lds_bytes(g, compact_ids_fit(g)), 1);
+        T = wgs_by_lds < 8 ? 256 : (g->n >= 256 ? 128 : 64);
+    }
     if (T < 64 || T > 1024 || (T % 64) != 0) return FC_EINVAL;
     int32_t G = o->lanes_per_vertex;
     if (G == 0) {
@@ -1336,15 +1341,17 @@ int launch_occ(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_
 }
 
 // Which register budget: measured on MI355X, the edge-splitting kernels are fastest built for 6 wavefronts
-// per SIMD; the others for 8 when the LDS of a CU (160 KB) holds that many wavefronts, else for 5.
+// per SIMD; the others for as many as the LDS of a CU (160 KB) holds, between 5 and 8.
 template <bool COMPACT, bool RAT, bool GEN, int G>
 int launch_one(const KParams &kp, long long P, int32_t T, size_t lds, hipStream_t stream) {
     if constexpr (GEN) {
         return launch_occ<COMPACT, RAT, true, G, 6>(kp, P, T, lds, stream);
     } else {
         const size_t wgs_by_lds = std::min<size_t>(32, (160u * 1024u) / std::max<size_t>(lds, 1));
-        const size_t waves_per_simd = wgs_by_lds * size_t(T / 64) / 4;
+        const size_t waves_per_simd = wgs_by_lds * size_t(T / 64) / 4;      // what the LDS leaves room for
         if (waves_per_simd >= 8) return launch_occ<COMPACT, RAT, false, G, 8>(kp, P, T, lds, stream);
+        if (waves_per_simd == 7) return launch_occ<COMPACT, RAT, false, G, 7>(kp, P, T, lds, stream);
+        if (waves_per_simd == 6) return launch_occ<COMPACT, RAT, false, G, 6>(kp, P, T, lds, stream);
         return launch_occ<COMPACT, RAT, false, G, 5>(kp, P, T, lds, stream);
     }
 }
