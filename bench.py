@@ -90,6 +90,9 @@ def main():
     # candidates: configs 2 and 5 centre them on the optimum, found here by the library's own search
     t0 = time.perf_counter()
     search = fc.fc_opt_throughput_search(g, 16)
+    search_cold_ms = (time.perf_counter() - t0) * 1e3      # the process's first launches: code objects are loaded here
+    t0 = time.perf_counter()
+    search = fc.fc_opt_throughput_search(g, 16)
     search_ms = (time.perf_counter() - t0) * 1e3
     inv = (search["inv_xstar"].numerator, search["inv_xstar"].denominator)
     cU, ck = config_candidates(cfg, inv)
@@ -293,7 +296,8 @@ def main():
         "fixed_k": fixed,
         "split_gamma": gamma,
         "search": {"inv_xstar": f"{inv[0]}/{inv[1]}", "U": str(search["U"]), "k": search["k"],
-                   "rounds": search["rounds"], "candidates_tested": search["trace_len"], "wall_ms": search_ms},
+                   "rounds": search["rounds"], "candidates_tested": search["trace_len"], "wall_ms": search_ms,
+                   "first_call_wall_ms": search_cold_ms},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "fc_push_relabel_kernel", "algorithmic_bytes_per_launch": int(bytes_alg)},
