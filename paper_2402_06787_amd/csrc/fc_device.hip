@@ -1911,7 +1911,10 @@ extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int
     auto done = [&](int code) { if (ev0) (void)hipEventDestroy(ev0); if (ev1) (void)hipEventDestroy(ev1); return code; };
     if (stats_or_null && hipEventRecord(ev0, stream) != hipSuccess) return done(FC_EDEVICE);
     // these problems start without tables, in worklist mode: fewer wavefronts per problem pay off
-    const int32_t T_gen = (options_or_null && options_or_null->threads_per_problem) ? opt.T : (g->n >= 256 ? 128 : 64);
+    // (four when few problems fit a CU's LDS and the runs are short because they may stop early: config 4 +12 %)
+    const bool roomy = (160u * 1024u) / std::max<size_t>(lds_bytes(g, false), 1) >= 8;
+    const int32_t T_gen = (options_or_null && options_or_null->threads_per_problem) ? opt.T
+                        : (!roomy && kp.split_early) ? 256 : (g->n >= 256 ? 128 : 64);
     rc = launch_g<false, false, true>(kp, P, T_gen, opt.G, lds_bytes(g, false), stream);
     if (rc != FC_OK) return done(rc);
     if (stats_or_null && hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
