@@ -138,6 +138,36 @@ def test_option_matrix_same_values():
             assert stats["not_converged"] == 0
 
 
+def test_every_register_budget_gives_the_same_values():
+    # the solver exists in builds for 5, 6, 7 and 8 wavefronts per SIMD, picked from the LDS a problem needs and the
+    # workgroup size: reach each of them with both state widths, and with rational multipliers
+    cases = [(5, dict(threads_per_problem=256)), (5, dict(threads_per_problem=320)), (5, dict(threads_per_problem=384)),
+             (5, dict(threads_per_problem=512)), (4, dict()), (4, dict(force_wide=1, threads_per_problem=256)),
+             (4, dict(force_wide=1, threads_per_problem=128)), (3, dict()), (3, dict(force_wide=1, threads_per_problem=64)),
+             (3, dict(force_wide=1, threads_per_problem=128)), (3, dict(threads_per_problem=1024, lanes_per_vertex=4))]
+    rng = np.random.default_rng(9)
+    cache = {}
+    for cfg, opts in cases:
+        if cfg not in cache:
+            topo = w.config_topology(cfg)
+            inv = Fraction(*_optimum(cfg, topo))
+            P = 160
+            sink = rng.choice(topo.compute_nodes, P).astype(np.int32)
+            k = rng.integers(1, 6, P).astype(np.int32)
+            den = rng.integers(1, 5, P).astype(np.int32)
+            num = np.maximum(1, (inv * k.astype(object) * den.astype(object) * rng.choice([Fraction(1, 2), Fraction(9, 10), 1, Fraction(11, 10), 3], P))
+                             .astype(object)).astype(np.int64).astype(np.int32)
+            mt = _merged(topo)
+            cache[cfg] = (topo, sink, num, den, k, o.aux_maxflow_batch(topo, sink, num, k, threads=16),
+                          o.aux_maxflow_batch_floor(mt, sink, num, den, k, threads=16))
+        topo, sink, num, den, k, want_int, want_floor = cache[cfg]
+        with _upload(topo) as g:
+            got, stats = _gpu_flows(g, sink, num, k, options=opts, want_stats=True)
+            assert (got == want_int).all() and stats["not_converged"] == 0, (cfg, opts)
+            got, _ = _gpu_flows_floor(g, sink, num, den, k, options=opts)
+            assert (got == want_floor).all(), (cfg, opts)
+
+
 # ------------------------------------------------------------------ the first-arc tree certificate and the launch order
 
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
