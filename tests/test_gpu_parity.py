@@ -620,6 +620,37 @@ def test_remove_switches_on_config1():
 
 # ------------------------------------------------------------------ launch shapes the other tests do not reach
 
+def test_remove_switches_on_config4_keeps_the_optimum():
+    # too large for the oracle's loop: check what Theorem 9 promises instead.  D = G({U b_e}) at the optimum
+    # U / k = 63 / 4 has 1/x* = 1/k; D* must be a compute-only Eulerian digraph with the same optimum, every link
+    # that was routed through a switch must be covered by its table entries, and capacity is conserved per node.
+    topo = w.config_topology(4)
+    U, k = 63, 4
+    D = _scaled(topo, U)
+    res = _remove_on_gpu(D, k)
+    links, table = res["links"], res["table"]
+    comp = set(int(v) for v in topo.compute_nodes)
+    assert links and all(a in comp and b in comp and c > 0 for (a, b), c in links.items())
+    n = topo.n_vertices
+    out = np.zeros(n, np.int64); inn = np.zeros(n, np.int64)
+    for (a, b), c in links.items():
+        out[a] += c; inn[b] += c
+    assert (out == inn).all()
+    # a compute node keeps its total egress capacity: every unit that left it still leaves it
+    out0 = np.zeros(n, np.int64)
+    np.add.at(out0, D.tail, D.bandwidth.astype(np.int64))
+    assert all(out[v] <= out0[v] for v in comp)            # detours u -> w -> u disappear, nothing is added
+    direct = {}
+    for a, b, c in zip(D.tail.tolist(), D.head.tolist(), D.bandwidth.tolist()):
+        if a in comp and b in comp:
+            direct[(a, b)] = direct.get((a, b), 0) + int(c)
+    for key, c in links.items():
+        assert c == direct.get(key, 0) + sum(table.get(key, {}).values()), key
+    keys = sorted(links)
+    with fc.fc_graph_upload(n, [a for a, b in keys], [b for a, b in keys], [links[x] for x in keys], topo.is_compute) as g:
+        assert fc.fc_opt_throughput_search(g, 8)["inv_xstar"] == Fraction(1, k)
+
+
 def test_large_batch_two_streams_and_degenerate_graphs():
     # 300 000 problems on a small graph: several rounds of the ordering kernel, several waves of workgroups
     topo = w.config_topology(2)
