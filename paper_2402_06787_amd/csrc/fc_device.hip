@@ -78,7 +78,8 @@ struct KParams {
     // unbounded arcs (w, s), (u, t), (v, t) (type 1); multiplier split_U and source arcs split_k for all
     const int32_t *split_u, *split_w, *split_t;
     int32_t split_U, split_k;
-    int32_t split_early;         // 1: a problem may stop once N k + min{c(e), c(f)} units have arrived (only gamma is wanted)
+    int32_t split_early;         // 1: a problem may stop once N k + min{c(e), c(f)} units have arrived (only gamma is wanted);
+                                 // 2: once N k + min{c(e), c(f)} + c(f) have (the caller also wants that much of the slack)
     long long sum_bw;            // sum of all link bandwidths (bounds every finite cut)
     const int32_t *src_w;        // [n] weight m_c of compute node c: arc (s, c) has capacity m_c * k (Section 5.7); null: all 1
     long long sum_w;             // sum of the weights (N while they are all 1): s emits at most sum_w * k
@@ -699,7 +700,8 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(OCC))
             }
             lds_barrier();
             const uint32_t cf = st.sh->st[0], ce = st.sh->st[1];
-            stop_at = int32_t(NKll) + int32_t(ce < cf ? ce : cf);      // below the "unbounded" value NK
+            stop_at = int32_t(NKll) + int32_t(ce < cf ? ce : cf) + (p.split_early == 2 ? int32_t(cf) : 0);
+            if (stop_at > NK) stop_at = NK;                            // never above the "unbounded" value
             lds_barrier();
             if (tid == 0) { st.sh->st[0] = 0u; st.sh->st[1] = 0u; }
         }
@@ -1827,7 +1829,7 @@ namespace {
 __global__ void __launch_bounds__(256) fc_split_gamma_kernel(int32_t N, int32_t n, int32_t U, int32_t k,
                                                              const int32_t *pu, const int32_t *pw, const int32_t *pt,
                                                              const int32_t *flows, const int32_t *row_ptr, const int4 *arcs,
-                                                             const uint8_t *is_compute, int32_t *gamma) {
+                                                             const uint8_t *is_compute, int32_t *gamma, int32_t *slack_or_null) {
     __shared__ int32_t s_min, s_bad;
     const int32_t i = blockIdx.x, tid = threadIdx.x;
     if (tid == 0) { s_min = 0x7fffffff; s_bad = 0; }
@@ -1847,9 +1849,10 @@ __global__ void __launch_bounds__(256) fc_split_gamma_kernel(int32_t N, int32_t 
             for (int32_t a = row_ptr[u]; a < row_ptr[u + 1]; ++a) if ((arcs[a].w & 1) && arcs[a].x == w) ce = (long long)U * arcs[a].z;
             for (int32_t a = row_ptr[w]; a < row_ptr[w + 1]; ++a) if ((arcs[a].w & 1) && arcs[a].x == t) cf = (long long)U * arcs[a].z;
         }
-        if (ce < 1 || cf < 1) gamma[i] = FC_GAMMA_INVALID;           // not two links through a switch, or a failed flow
+        if (ce < 1 || cf < 1) { gamma[i] = FC_GAMMA_INVALID; if (slack_or_null) slack_or_null[i] = 0; }   // not two links through a switch, or a failed flow
         else {
             long long gm = (long long)s_min - (long long)N * k;
+            if (slack_or_null) slack_or_null[i] = int32_t(gm);       // min_v F - N k, or a lower bound of it where a flow stopped early
             if (ce < gm) gm = ce;
             if (cf < gm) gm = cf;
             gamma[i] = int32_t(gm);
@@ -1864,10 +1867,13 @@ extern "C" size_t fc_split_gamma_workspace_bytes(const fc_graph *g, int64_t n_pa
     return align_up(size_t(P) * 4, 256) + stats_bytes(P);
 }
 
-extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int64_t n_pairs, const int32_t *d_u,
-                                    const int32_t *d_w, const int32_t *d_t, int32_t *d_gamma_out,
-                                    int32_t *d_flows_or_null, void *d_workspace, size_t workspace_bytes,
-                                    void *hip_stream, const fc_options *options_or_null, fc_stats *stats_or_null) {
+namespace {
+// fc_split_gamma_batch, and for the switch-removal loop a variant that also returns every pair's slack
+// min_v F - N k (exact, or the lower bound N k + min{c(e), c(f)} + c(f) - N k at which its flows stopped)
+int split_gamma_impl(const fc_graph *g, int32_t U, int32_t k, int64_t n_pairs, const int32_t *d_u,
+                     const int32_t *d_w, const int32_t *d_t, int32_t *d_gamma_out,
+                     int32_t *d_flows_or_null, void *d_workspace, size_t workspace_bytes,
+                     void *hip_stream, const fc_options *options_or_null, fc_stats *stats_or_null, int32_t *d_slack_or_null) {
     if (!g || n_pairs < 0 || U < 1 || k < 1) return FC_EINVAL;
     if (!g->on_device) return FC_EDEVICE;
     if (g->d_src_weight) return FC_EUNSUPPORTED;         // the paper defines this only for unit weights
@@ -1899,7 +1905,7 @@ extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int
     kp.labels = opt.use_labels && g->n >= 256 ? g->d_labels : nullptr;
     kp.label_hmax = g->d_label_hmax;
     kp.split_u = d_u; kp.split_w = d_w; kp.split_t = d_t; kp.split_U = U; kp.split_k = k;
-    kp.split_early = d_flows_or_null ? 0 : 1;            // exact flow values only when the caller wants to see them
+    kp.split_early = d_flows_or_null ? 0 : (d_slack_or_null ? 2 : 1);   // exact flow values only when the caller wants to see them
     kp.flow_out = d_flow; kp.stats = stats_or_null ? d_pp : nullptr;
     kp.wide_available = 1;
 
@@ -1919,12 +1925,21 @@ extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int
     if (rc != FC_OK) return done(rc);
     if (stats_or_null && hipEventRecord(ev1, stream) != hipSuccess) return done(FC_EDEVICE);
     hipLaunchKernelGGL(fc_split_gamma_kernel, dim3(unsigned(n_pairs)), dim3(256), 0, stream, g->N, g->n, U, k, d_u, d_w, d_t,
-                       d_flow, g->d_row_ptr, reinterpret_cast<const int4 *>(g->d_arc_wide), g->d_is_compute, d_gamma_out);
+                       d_flow, g->d_row_ptr, reinterpret_cast<const int4 *>(g->d_arc_wide), g->d_is_compute, d_gamma_out, d_slack_or_null);
     if (hipGetLastError() != hipSuccess) return done(FC_EDEVICE);
     if (!stats_or_null) return done(FC_OK);
     rc = fill_stats(P, d_pp, d_tot, stream, ev0, ev1, stats_or_null);
     if (rc != FC_OK) return done(rc);
     return done(stats_or_null->not_converged ? FC_ENOCONVERGE : FC_OK);
+}
+}  // namespace
+
+extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int64_t n_pairs, const int32_t *d_u,
+                                    const int32_t *d_w, const int32_t *d_t, int32_t *d_gamma_out,
+                                    int32_t *d_flows_or_null, void *d_workspace, size_t workspace_bytes,
+                                    void *hip_stream, const fc_options *options_or_null, fc_stats *stats_or_null) {
+    return split_gamma_impl(g, U, k, n_pairs, d_u, d_w, d_t, d_gamma_out, d_flows_or_null, d_workspace, workspace_bytes,
+                            hip_stream, options_or_null, stats_or_null, nullptr);
 }
 
 extern "C" int fc_fixed_k_search(const fc_graph *g, int32_t k, int32_t candidates_per_round, fc_rational *U_star,
@@ -1999,7 +2014,7 @@ struct SplitPool {
         off_is = o; o = align_up(o + size_t(n), 256);
         off_ids = o; o = align_up(o + sizeof(int32_t) * size_t(N), 256);
         off_cost = o; o = align_up(o + sizeof(uint32_t) * size_t(n), 256);
-        off_gamma = o; o = align_up(o + sizeof(int32_t) * want_pairs, 256);
+        off_gamma = o; o = align_up(o + sizeof(int32_t) * 2 * want_pairs, 256);   // gamma values, then slacks
         off_ws = o;
         const long long P = (long long)want_pairs * 2 * N;
         ws_bytes = align_up(size_t(P) * 4, 256) + stats_bytes(P);
@@ -2089,9 +2104,9 @@ extern "C" int fc_remove_switches(int32_t n_vertices, int64_t n_arcs, const int3
                     int32_t *h_gamma = reinterpret_cast<int32_t *>(pool.h_blob + pool.off_gamma);
                     bool ok = hipMemcpyAsync(pool.d_blob, pool.h_blob, pool.off_wide + sizeof(int4) * M, hipMemcpyHostToDevice, stream) == hipSuccess;
                     if (ok) {
-                        rc = fc_split_gamma_batch(h, 1, k, int64_t(np), d_pairs, d_pairs + pool.pair_cap, d_pairs + 2 * pool.pair_cap, d_gamma, nullptr,
-                                                  pool.d_blob + pool.off_ws, pool.ws_bytes, stream, options_or_null, nullptr);
-                        ok = rc == FC_OK && hipMemcpyAsync(h_gamma, d_gamma, sizeof(int32_t) * np, hipMemcpyDeviceToHost, stream) == hipSuccess &&
+                        rc = split_gamma_impl(h, 1, k, int64_t(np), d_pairs, d_pairs + pool.pair_cap, d_pairs + 2 * pool.pair_cap, d_gamma, nullptr,
+                                              pool.d_blob + pool.off_ws, pool.ws_bytes, stream, options_or_null, nullptr, d_gamma + pool.pair_cap);
+                        ok = rc == FC_OK && hipMemcpyAsync(h_gamma, d_gamma, sizeof(int32_t) * (pool.pair_cap + np), hipMemcpyDeviceToHost, stream) == hipSuccess &&
                              hipStreamSynchronize(stream) == hipSuccess;
                     }
                     // the pool owns the device memory: detach it before the host graph goes
@@ -2101,17 +2116,34 @@ extern "C" int fc_remove_switches(int32_t n_vertices, int64_t n_arcs, const int3
                     ++batches;
                     if (!ok) { cleanup(); return rc != FC_OK ? rc : FC_EDEVICE; }
                     gam.assign(h_gamma, h_gamma + np);
-                    size_t hit = which.size();
-                    for (size_t q = 0; q < which.size(); ++q) {
-                        if (gam[q] < 0) { cleanup(); return FC_ENOCONVERGE; }     // invalid, or min_v F(s, v) >= N k does not hold in D
-                        if (gam[q] > 0) { hit = q; break; }
+                    const int32_t *slk = h_gamma + pool.pair_cap;
+                    // Walk the ingress links in order.  Until a split is applied every gamma is exact for the current graph
+                    // (zeros are skipped).  After splits of total amount `applied`, a later pair need not be evaluated again
+                    // when its flows cannot have become binding: no cut holds both e and f, so a split of gamma lowers any
+                    // max-flow by at most gamma, and if slack - applied >= min{c(e), c(f) now} that minimum is its gamma.
+                    long long applied = 0;
+                    size_t q = 0;
+                    for (; q < which.size(); ++q) {
+                        const auto f_it = cap.find(Key(w, t));
+                        if (f_it == cap.end()) break;                        // f is used up
+                        const int32_t u = pu[q];
+                        long long gmm;
+                        if (applied == 0) {
+                            if (gam[q] < 0) { cleanup(); return FC_ENOCONVERGE; }     // invalid, or min_v F(s, v) >= N k does not hold in D
+                            if (gam[q] == 0) continue;
+                            gmm = gam[q];
+                        } else {
+                            const long long m = std::min<long long>(cap.at(Key(u, w)), f_it->second);
+                            if (gam[q] > 0 && (long long)slk[q] - applied >= m) gmm = m;
+                            else break;                                      // this one has to be evaluated on the current graph
+                        }
+                        auto take = [&](Key key) { auto it = cap.find(key); it->second -= gmm; if (it->second == 0) cap.erase(it); };
+                        take(Key(u, w)); take(Key(w, t));
+                        if (u != t) { cap[Key(u, t)] += gmm; table[Key(u, t)][w] += gmm; }   // a detour u -> w -> u just disappears
+                        applied += gmm;
                     }
-                    if (hit == which.size()) break;                          // no ingress link can give anything to f
-                    const int32_t u = pu[hit]; const long long gmm = gam[hit];
-                    auto take = [&](Key key) { auto it = cap.find(key); it->second -= gmm; if (it->second == 0) cap.erase(it); };
-                    take(Key(u, w)); take(Key(w, t));
-                    if (u != t) { cap[Key(u, t)] += gmm; table[Key(u, t)][w] += gmm; }   // a detour u -> w -> u just disappears
-                    pos = which[hit] + 1;
+                    if (applied == 0) break;                                 // no ingress link can give anything to f
+                    pos = q < which.size() ? which[q] : ingress.size();
                 }
                 if (cap.count(Key(w, t))) { cleanup(); return FC_ENOCONVERGE; }   // Theorem 9 promises f can be used up: the input broke its conditions
             }
