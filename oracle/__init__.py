@@ -10,4 +10,5 @@ from .reference import (Disconnected, build_c, maxflow, aux_network, aux_maxflow
                         brute_min_cut, brute_cut_condition, aux_maxflow_batch_floor,
                         fixed_k_feasible, fixed_k_binary_search, brute_fixed_k, links, link_capacities, is_eulerian,
                         unbounded, split_flows, split_gamma, split_off, brute_split_gamma, remove_switches,
-                        weighted_aux_network, weighted_aux_maxflow_batch, weighted_feasible)
+                        weighted_aux_network, weighted_aux_maxflow_batch, weighted_feasible,
+                        tree_mu_network, tree_mu, brute_tree_mu, construct_trees)

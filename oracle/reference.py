@@ -18,6 +18,8 @@ the paper (ForestColl, arXiv 2402.06787):
 * edge splitting (Appendix E.2): the 2N max-flows and gamma of Theorem 10 (`split_flows`,
   `split_gamma`), gamma by its definition (`brute_split_gamma`), the split graph (`split_off`), and the loop of
   Algorithm 2 around them (`remove_switches`).
+* spanning tree construction (Appendix E.3): mu by one max-flow on the network D-bar (`tree_mu`), mu by its
+  definition over all cuts (`brute_tree_mu`), and the construction loop around it (`construct_trees`).
 * the fixed-k variant (Section 5.5, Appendix E.4): the verdict on the network with capacities
   floor(U b_e) for a rational U (`fixed_k_feasible`), U* by Algorithm 3 taken literally in
   exact rationals (`fixed_k_binary_search`), or by trying every fraction j / b_e
@@ -40,6 +42,9 @@ Readings of the paper taken here (each also listed in the design notes):
    integer) instead of one unit, the arc (s, c) gets capacity m_c * k, and the verdict is
    F(s, v) >= k * sum_c m_c for every compute node v -- what s emits when all its arcs are full, as
    N k is in the uniform case.  The paper says only that the source arcs are adjusted.
+ - spanning tree construction: the arcs (s_i, r) of D-bar are "unbounded"; they get the finite capacity
+   sum of all g(e) + sum of the other demands + 1, more than any finite cut.  "Pick an edge" is read as: the
+   first edge leaving the root-set in (x, y) order whose mu is positive; root-sets are grown in creation order.
  - fixed k: "link e with bandwidth b_e" is one ordered vertex pair with the summed bandwidth of
    its parallel arcs (`links`); floor(U b_e) is taken per link; max_e b_e (termination width and
    denominator bound of Algorithm 3) is over links; the verdict is F >= N k as in Algorithm 1.
@@ -519,6 +524,92 @@ def remove_switches(topo, k, algo="dinic"):
             if (w, t) in link_capacities(D):
                 raise AssertionError("an egress link of a switch could not be split off completely (Theorem 9)")
     return D, table
+
+
+# ------------------------------------------------------------------ spanning tree construction (Appendix E.3)
+
+def tree_mu_network(n, cap, sets, demand, grow, x):
+    """The flow network D-bar of Appendix E.3 for growing root-set `grow` from vertex x: the digraph with
+    capacities cap[(a, b)] = g(a, b), one extra vertex s_i per root-set i != grow, an arc (x, s_i) of capacity
+    m(R_i) and an arc (s_i, r) for every r in R_i that carries anything (capacity: more than every finite cut)."""
+    others = [i for i in range(len(sets)) if i != grow]
+    inf = sum(cap.values()) + sum(demand[i] for i in others) + 1
+    tail, head, c = [], [], []
+    for (a, b), g in sorted(cap.items()):
+        if g > 0 and a != b:
+            tail.append(a); head.append(b); c.append(int(g))
+    for j, i in enumerate(others):
+        tail.append(x); head.append(n + j); c.append(int(demand[i]))
+        for r in sorted(sets[i]):
+            tail.append(n + j); head.append(r); c.append(inf)
+    return n + len(others), np.array(tail, dtype=np.int32), np.array(head, dtype=np.int32), c
+
+
+def tree_mu(n, cap, sets, demand, grow, x, y, algo="dinic"):
+    """mu for the edge (x, y), x in R_grow, y outside it (Appendix E.3, the theorem that computes mu by one
+    max-flow): min{ g(x, y), m(R_grow), F(x, y; D-bar) - sum of m(R_i) over i != grow }."""
+    assert x in sets[grow] and y not in sets[grow] and cap.get((x, y), 0) > 0
+    nv, tail, head, c = tree_mu_network(n, cap, sets, demand, grow, x)
+    F = maxflow(nv, tail, head, c, int(x), int(y), algo)
+    return min(int(cap[(x, y)]), int(demand[grow]), F - sum(demand[i] for i in range(len(sets)) if i != grow))
+
+
+def brute_tree_mu(n, cap, sets, demand, grow, x, y):
+    """mu by its definition (Appendix E.3, the formula taken from Berczi and Frank): min of g(x, y), m(R_grow) and
+    c(S, V - S) - p(S) over all S with x in S, y not in S, R_grow not inside S, where p(S) adds up m(R_i)
+    over the root-sets R_i inside S."""
+    assert n <= 14
+    best = min(int(cap[(x, y)]), int(demand[grow]))
+    masks = [sum(1 << r for r in R) for R in sets]
+    for S in range(1 << n):
+        if not (S >> x) & 1 or (S >> y) & 1 or (masks[grow] & ~S) == 0:
+            continue
+        cut = sum(g for (a, b), g in cap.items() if (S >> a) & 1 and not (S >> b) & 1)
+        p = sum(demand[i] for i in range(len(sets)) if (masks[i] & ~S) == 0)
+        best = min(best, cut - p)
+    return best
+
+
+def construct_trees(n, links, k, algo="dinic", observe=None):
+    """Spanning Tree Construction (Appendix E.3) on the compute-only digraph D* = links {(a, b): capacity} over
+    vertices 0 .. n-1: every root u starts with R = {u} of multiplicity k; a root-set that does not span yet is
+    grown by the first edge (x, y) in (x, y) order that leaves it and has mu > 0; if mu is less than its
+    multiplicity a copy keeps the rest.  Root-sets are taken in creation order.  Returns a list of
+    (root, multiplicity, edges in the order they were added); the multiplicities of a root add up to k.
+    `observe(g, sets, demand, i, x, y, mu)`, if given, sees every mu that is computed."""
+    g = {key: int(c) for key, c in links.items() if c > 0 and key[0] != key[1]}
+    sets = [{u} for u in range(n)]
+    demand = [int(k)] * n
+    root = list(range(n))
+    edges = [[] for _ in range(n)]
+    full = set(range(n))
+    while True:
+        todo = [i for i in range(len(sets)) if sets[i] != full]
+        if not todo:
+            break
+        i = todo[0]
+        while sets[i] != full:
+            grown = False
+            for (x, y) in sorted(g):
+                if x in sets[i] and y not in sets[i]:
+                    mu = tree_mu(n, g, sets, demand, i, x, y, algo)
+                    if observe is not None:
+                        observe(g, sets, demand, i, x, y, mu)
+                    if mu == 0:
+                        continue
+                    assert mu > 0
+                    if mu < demand[i]:
+                        sets.append(set(sets[i])); demand.append(demand[i] - mu); root.append(root[i])
+                        edges.append(list(edges[i])); demand[i] = mu
+                    edges[i].append((x, y)); sets[i].add(y)
+                    g[(x, y)] -= mu
+                    if g[(x, y)] == 0:
+                        del g[(x, y)]
+                    grown = True
+                    break
+            if not grown:
+                raise AssertionError("no edge leaving the root-set can be added (the packing condition does not hold)")
+    return [(root[i], demand[i], edges[i]) for i in range(len(sets))]
 
 
 # ------------------------------------------------------------------ brute force (tiny graphs only)

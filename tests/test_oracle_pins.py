@@ -571,3 +571,95 @@ def test_weighted_floor_capacities():
     assert f.tolist() == [2 + min(12, 1 + min(7, 20))]
     with pytest.raises(ValueError):
         o.weighted_aux_network(t, 1, 1, [1, -1, 1])
+
+
+# ---------------------------------------------------------------- spanning tree construction (Appendix E.3)
+
+def _check_trees(n, links, k, trees):
+    """what the construction promises: every tree spans all vertices from its root, the multiplicities of a root
+    add up to k, and no link carries more trees than its capacity"""
+    use, per_root = {}, {}
+    for root, m, edges in trees:
+        assert m >= 1 and len(edges) == n - 1
+        seen = {root}
+        for x, y in edges:
+            assert x in seen and y not in seen
+            seen.add(y)
+            use[(x, y)] = use.get((x, y), 0) + m
+        assert seen == set(range(n))
+        per_root[root] = per_root.get(root, 0) + m
+    assert per_root == {u: k for u in range(n)}
+    assert all(c <= links[e] for e, c in use.items())
+    return use
+
+
+@pytest.mark.parametrize("b", [1, 2, 3])
+def test_trees_on_the_paper_example(b):
+    # the switch-free form of the worked example (Appendix E.2 figure): optimum 1/x* = 1/b, so U = 1, k = b
+    topo = w.paper_example_split(b)
+    links = o.link_capacities(topo)
+    assert o.feasible(topo, 1, b)[0]
+    trees = o.construct_trees(8, links, b)
+    use = _check_trees(8, links, b, trees)
+    # the inter-box links are the bottleneck cut: 4 b leave each box and 4 roots x b trees have to cross it
+    assert all(use.get((j, 4 + j), 0) == b and use.get((4 + j, j), 0) == b for j in range(4))
+
+
+def test_trees_on_complete_digraphs_use_every_link():
+    # K_n with capacity c on every ordered pair: c(S, V - S) = |S| (n - |S|) c >= |S| k exactly when c >= k, and
+    # with c = k the n k trees need n k (n - 1) link slots, which is all there are
+    for n, k in ((2, 1), (2, 5), (3, 2), (4, 3), (5, 1)):
+        links = {(a, b): k for a in range(n) for b in range(n) if a != b}
+        trees = o.construct_trees(n, links, k)
+        use = _check_trees(n, links, k, trees)
+        assert use == links
+    # two nodes: the only tree of root a is the link (a, b), k times
+    assert sorted(o.construct_trees(2, {(0, 1): 4, (1, 0): 4}, 4)) == [(0, 4, [(0, 1)]), (1, 4, [(1, 0)])]
+    # capacity short of k on one link: the packing condition fails and the construction says so
+    with pytest.raises(AssertionError):
+        o.construct_trees(3, {(0, 1): 1, (1, 0): 2, (1, 2): 2, (2, 1): 2, (0, 2): 2, (2, 0): 2}, 2)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_mu_by_max_flow_equals_its_definition(seed):
+    # random small compute-only digraphs that satisfy the packing condition (a complete digraph of capacity k
+    # plus random extra capacity); every mu the construction computes is checked against the cut formula
+    rng = np.random.default_rng(6000 + seed)
+    n = int(rng.integers(3, 6)); k = int(rng.integers(1, 4))
+    links = {(a, b): k + int(rng.integers(0, 3)) for a in range(n) for b in range(n) if a != b}
+    count = [0]
+
+    def observe(g, sets, demand, i, x, y, mu):
+        assert mu == o.brute_tree_mu(n, g, sets, demand, i, x, y)
+        assert 0 <= mu <= min(g[(x, y)], demand[i])
+        count[0] += 1
+
+    trees = o.construct_trees(n, links, k, algo=ALGOS[seed % 2], observe=observe)
+    _check_trees(n, links, k, trees)
+    assert count[0] >= n * (n - 1)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_trees_after_switch_removal(seed):
+    # the whole back end on a small random switch topology: optimum, scaling, switch removal, trees
+    base = w.random_tiny(7000 + seed, n_vertices=int(5 + seed % 3))
+    cap = {}
+    for t, h, b in zip(base.tail.tolist(), base.head.tolist(), base.bandwidth.tolist()):
+        if t != h and b > 0:
+            key = (min(t, h), max(t, h)); cap[key] = cap.get(key, 0) + int(b)
+    tail = [a for a, b in cap] + [b for a, b in cap]; head = [b for a, b in cap] + [a for a, b in cap]
+    sym = w.Topology(f"euler{seed}", base.n_vertices, np.array(tail, dtype=np.int32), np.array(head, dtype=np.int32),
+                     np.array(list(cap.values()) * 2, dtype=np.int32), base.is_compute.copy())
+    try:
+        inv = o.optimality_binary_search(sym)
+    except o.Disconnected:
+        pytest.skip("disconnected draw")
+    Uq, k = o.smallest_U_k(inv, sym.bandwidth)
+    U, kk = Uq.numerator, k * Uq.denominator
+    D = w.Topology(sym.name, sym.n_vertices, sym.tail, sym.head, (sym.bandwidth.astype(np.int64) * U).astype(np.int32), sym.is_compute)
+    Dstar, _ = o.remove_switches(D, kk)
+    comp = [int(v) for v in sym.compute_nodes]
+    idx = {v: i for i, v in enumerate(comp)}
+    links = {(idx[a], idx[b]): c for (a, b), c in o.link_capacities(Dstar).items()}
+    trees = o.construct_trees(len(comp), links, kk)
+    _check_trees(len(comp), links, kk, trees)
