@@ -313,6 +313,45 @@ int fc_remove_switches(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, 
 
 const char *fc_strerror(int code);
 
+/* ------------------------------------------------------------------------------------------
+ * Spanning tree construction (Appendix E.3) on the compute-only digraph D* that switch removal leaves.
+ * The state of the construction is: the remaining capacity g(e) of every link, and root-sets R_i with
+ * demands m(R_i) (R_i = the vertices the m(R_i) identical out-trees of some root span so far).  An edge
+ * (x, y) with x in R_grow and y outside it can be added to
+ *   mu = min{ g(x, y), m(R_grow), F(x, y; D-bar) - sum of m(R_i) over i != grow }
+ * of those trees, where D-bar adds a vertex s_i per other root-set with an arc (x, s_i) of capacity m(R_i)
+ * and unbounded arcs (s_i, r), r in R_i (the theorem of Appendix E.3 that computes mu by one max-flow).
+ *
+ * fc_tree_mu_batch evaluates mu for many candidate edges of one state in one launch.  All arrays are host
+ * arrays; the call is synchronous.  tail/head/capacity: the n_links links of D* over vertices
+ * 0..n_vertices-1 with their remaining capacities (parallel entries add up).  set_ptr [n_sets+1],
+ * set_members: the root-sets as lists; set_demand [n_sets] >= 1; grow_set: the one being grown.
+ * mu_out [n_edges]: mu, or FC_MU_INVALID for an entry that is no link from inside R_grow to outside it.
+ * flows_or_null [n_edges]: F(x, y; D-bar); without it a max-flow may stop as soon as it cannot decide mu.
+ * The graph with its n_sets extra vertices and one arc per (set, member) must fit the 32-bit on-chip state
+ * (FC_EUNSUPPORTED otherwise: a few hundred vertices), and the sum of all capacities and demands must stay
+ * below 2^30 (FC_EOVERFLOW).  Other errors: FC_EINVAL, FC_EDEVICE, FC_ENOMEM, FC_ENOCONVERGE.
+ *
+ * fc_construct_trees runs the whole construction around such launches: every vertex u starts as the
+ * root-set {u} with demand k; the first root-set (in creation order) that does not span yet is grown by the
+ * first link leaving it, in (x, y) order, whose mu is positive; when mu is below its demand a copy keeps
+ * the rest.  All candidate links of a state are evaluated in one launch (the ones before the first positive
+ * mu are zero on this very state, so the result is that of trying them one by one).  Output: n_trees
+ * root-sets; tree i has root tree_root[i], multiplicity tree_multiplicity[i] (they add up to k per root)
+ * and the n_vertices - 1 edges tree_edge_x/y[i * (n_vertices - 1) ..] in the order they were added.
+ * Needs min over v of F(s, v) >= N k to hold in D* (what switch removal preserves); FC_ENOCONVERGE if no
+ * edge can be added.  FC_EWORKSPACE with *n_trees set when tree_capacity is too small. */
+#define FC_MU_INVALID FC_GAMMA_INVALID
+int fc_tree_mu_batch(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head,
+                     const int32_t *capacity, int32_t n_sets, const int64_t *set_ptr, const int32_t *set_members,
+                     const int32_t *set_demand, int32_t grow_set, int64_t n_edges, const int32_t *edge_x,
+                     const int32_t *edge_y, int32_t *mu_out, int32_t *flows_or_null, void *hip_stream,
+                     const fc_options *options_or_null);
+int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head,
+                       const int32_t *capacity, int32_t k, int64_t tree_capacity, int64_t *n_trees,
+                       int32_t *tree_root, int32_t *tree_multiplicity, int32_t *tree_edge_x, int32_t *tree_edge_y,
+                       int64_t *n_batches_or_null, void *hip_stream, const fc_options *options_or_null);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,7 +10,7 @@ from .binding import (FcError, Graph, GraphInfo, fc_options, fc_stats, fc_ration
                       fc_feasible_workspace_bytes, fc_feasible, fc_opt_throughput_search,
                       fc_search_with_verdicts, fc_maxflow_batch_floor, fc_feasible_floor, fc_fixed_k_search,
                       fc_fixed_k_search_with_verdicts, fc_split_gamma_workspace_bytes, fc_split_gamma_batch, fc_remove_switches,
-                      LIB_PATH, EXPORTED)
+                      fc_tree_mu_batch, fc_construct_trees, LIB_PATH, EXPORTED)
 from .binding import (FC_OK, FC_EINVAL, FC_EOVERFLOW, FC_EDISCONNECTED, FC_ENOMEM, FC_EWORKSPACE, FC_EDEVICE,
                       FC_ENOCONVERGE, FC_EUNSUPPORTED, FC_FLOW_INVALID, FC_FLOW_NOCONVERGE, FC_FLOW_UNSUPPORTED,
-                      FC_GAMMA_INVALID)
+                      FC_GAMMA_INVALID, FC_MU_INVALID)

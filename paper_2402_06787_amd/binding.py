@@ -25,7 +25,7 @@ FC_GAMMA_INVALID = -2147483648
 EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_free", "fc_graph_info", "fc_graph_csr", "fc_graph_set_source_weights",
             "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_maxflow_batch_floor", "fc_feasible_workspace_bytes",
             "fc_feasible_floor", "fc_fixed_k_search", "fc_fixed_k_search_with_verdicts",
-            "fc_split_gamma_workspace_bytes", "fc_split_gamma_batch", "fc_remove_switches",
+            "fc_split_gamma_workspace_bytes", "fc_split_gamma_batch", "fc_remove_switches", "fc_tree_mu_batch", "fc_construct_trees",
             "fc_feasible", "fc_opt_throughput_search", "fc_search_with_verdicts", "fc_strerror"]
 
 
@@ -116,6 +116,10 @@ def load_library():
     lib.fc_split_gamma_workspace_bytes.argtypes = [vp, i64]
     lib.fc_split_gamma_batch.restype = c.c_int
     lib.fc_split_gamma_batch.argtypes = [vp, i32, i32, i64, vp, vp, vp, vp, vp, vp, sz, vp, c.POINTER(fc_options), c.POINTER(fc_stats)]
+    lib.fc_tree_mu_batch.restype = c.c_int
+    lib.fc_tree_mu_batch.argtypes = [i32, i64, vp, vp, vp, i32, vp, vp, vp, i32, i64, vp, vp, vp, vp, vp, c.POINTER(fc_options)]
+    lib.fc_construct_trees.restype = c.c_int
+    lib.fc_construct_trees.argtypes = [i32, i64, vp, vp, vp, i32, i64, c.POINTER(i64), vp, vp, vp, vp, c.POINTER(i64), vp, c.POINTER(fc_options)]
     lib.fc_remove_switches.restype = c.c_int
     lib.fc_remove_switches.argtypes = [i32, i64, vp, vp, vp, vp, i32, i64, c.POINTER(i64), vp, vp, vp,
                                        i64, c.POINTER(i64), vp, vp, vp, vp, c.POINTER(i64), vp, c.POINTER(fc_options)]
@@ -501,3 +505,59 @@ def fc_remove_switches(n_vertices, tail, head, capacity, is_compute, k: int, str
     for i in range(n_routes.value):
         table.setdefault((int(ru[i]), int(rt[i])), {})[int(rw[i])] = int(ra[i])
     return {"links": links, "table": table, "batches": int(batches.value)}
+
+
+FC_MU_INVALID = FC_GAMMA_INVALID
+
+
+def _links_arrays(links):
+    keys = sorted(links)
+    return (np.array([a for a, _ in keys], dtype=np.int32), np.array([b for _, b in keys], dtype=np.int32),
+            np.array([int(links[key]) for key in keys], dtype=np.int32))
+
+
+def fc_tree_mu_batch(n_vertices, links, sets, demand, grow_set, edges, want_flows=False, stream=None, options=None):
+    """mu (Appendix E.3) for the candidate edges [(x, y), ...] of root-set `grow_set` in the state (links =
+    {(a, b): remaining capacity}, sets = list of vertex collections, demand = list of multiplicities).
+    Returns dict(mu=int32 array, flows=int32 array or None)."""
+    tail, head, cap = _links_arrays(links)
+    ptr = np.zeros(len(sets) + 1, dtype=np.int64)
+    for i, R in enumerate(sets):
+        ptr[i + 1] = ptr[i] + len(R)
+    mem = np.array([int(r) for R in sets for r in sorted(R)], dtype=np.int32)
+    dem = _np(demand, np.int32)
+    ex = np.array([int(e[0]) for e in edges], dtype=np.int32); ey = np.array([int(e[1]) for e in edges], dtype=np.int32)
+    mu = np.zeros(max(len(edges), 1), dtype=np.int32)
+    flows = np.zeros(max(len(edges), 1), dtype=np.int32) if want_flows else None
+    rc = load_library().fc_tree_mu_batch(int(n_vertices), int(tail.shape[0]), _host_ptr(tail), _host_ptr(head), _host_ptr(cap),
+                                         len(sets), _host_ptr(ptr), _host_ptr(mem), _host_ptr(dem), int(grow_set), len(edges),
+                                         _host_ptr(ex), _host_ptr(ey), _host_ptr(mu), _host_ptr(flows) if flows is not None else None,
+                                         _stream_ptr(stream), _opts(options))
+    _check(rc, "fc_tree_mu_batch")
+    return {"mu": mu[: len(edges)], "flows": flows[: len(edges)] if flows is not None else None}
+
+
+def fc_construct_trees(n_vertices, links, k: int, stream=None, options=None):
+    """Spanning tree construction (Appendix E.3) on D* = links {(a, b): capacity} over vertices 0..n_vertices-1.
+    Returns dict(trees=[(root, multiplicity, [(x, y), ...]), ...], batches=int)."""
+    c = ctypes
+    tail, head, cap = _links_arrays(links)
+    n = int(n_vertices)
+    n_trees, batches = c.c_int64(0), c.c_int64(0)
+    room = max(4 * n, 64)
+    for _ in range(2):                                   # the call reports the size it needs when the guess was short
+        root = np.zeros(room, np.int32); mult = np.zeros(room, np.int32)
+        exs = np.zeros(room * max(n - 1, 1), np.int32); eys = np.zeros_like(exs)
+        rc = load_library().fc_construct_trees(n, int(tail.shape[0]), _host_ptr(tail), _host_ptr(head), _host_ptr(cap), int(k), room,
+                                               c.byref(n_trees), _host_ptr(root), _host_ptr(mult), _host_ptr(exs), _host_ptr(eys),
+                                               c.byref(batches), _stream_ptr(stream), _opts(options))
+        if rc == FC_EWORKSPACE and n_trees.value > room:
+            room = int(n_trees.value)
+            continue
+        break
+    _check(rc, "fc_construct_trees")
+    trees = []
+    for i in range(n_trees.value):
+        lo = i * (n - 1)
+        trees.append((int(root[i]), int(mult[i]), [(int(exs[lo + q]), int(eys[lo + q])) for q in range(n - 1)]))
+    return {"trees": trees, "batches": int(batches.value)}

@@ -80,6 +80,10 @@ struct KParams {
     int32_t split_U, split_k;
     int32_t split_early;         // 1: a problem may stop once N k + min{c(e), c(f)} units have arrived (only gamma is wanted);
                                  // 2: once N k + min{c(e), c(f)} + c(f) have (the caller also wants that much of the slack)
+    // explicit (source, sink) launches (the max-flows of spanning tree construction, Appendix E.3): workgroup b
+    // solves F(pair_src[b], pair_dst[b]) with the source's arcs saturated, the excess src_w[v] * split_k at every
+    // flagged vertex, multiplier split_U, and may stop once pair_stop[b] units have arrived
+    const int32_t *pair_src, *pair_dst, *pair_stop;
     long long sum_bw;            // sum of all link bandwidths (bounds every finite cut)
     const int32_t *src_w;        // [n] weight m_c of compute node c: arc (s, c) has capacity m_c * k (Section 5.7); null: all 1
     long long sum_w;             // sum of the weights (N while they are all 1): s emits at most sum_w * k
@@ -497,7 +501,15 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(OCC))
     int32_t j, t, U, k, D = 1;
     int32_t src = -1, src2 = -1, sa = -1, sb = -1;       // edge-splitting problems only (see below)
     int32_t gu = -1, gw = -1, gt = -1;                   // their pair e = (gu, gw), f = (gw, gt)
-    if (GEN) {
+    if (GEN && p.pair_src) {
+        j = int32_t(blockIdx.x); U = p.split_U; k = p.split_k;
+        src = p.pair_src[j]; t = p.pair_dst[j];
+        if (src < 0 || src >= n || t < 0 || t >= n || src == t) {
+            if (tid == 0) p.flow_out[j] = FC_FLOW_INVALID;
+            if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
+            return;
+        }
+    } else if (GEN) {
         const int32_t a = int32_t(blockIdx.x) % p.N, it = int32_t(blockIdx.x) / p.N;
         const int32_t i = it >> 1, v = p.compute_ids[a];
         const int32_t pu = p.split_u[i], pw = p.split_w[i], pt = p.split_t[i];
@@ -690,7 +702,11 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(OCC))
             if (tid == 0) { st.e[src] = W(0); if (src2 >= 0) st.e[src2] = W(0); }
             lds_barrier();
         }
-        if (GEN && p.split_early) {
+        if (GEN && p.pair_stop) {
+            const int32_t lim = p.pair_stop[j];
+            if (lim >= 0 && lim < NK) stop_at = lim;
+        }
+        if (GEN && p.split_early && !p.pair_src) {
             // gamma = min{c(e), c(f), min_v F - N k}: a flow of N k + min{c(e), c(f)} cannot be the binding term, so the
             // problem may stop when that much has arrived.  Both capacities are records of w's row.
             for (int32_t a = int32_t(st.rp[gw]) + tid; a < int32_t(st.rp[gw + 1]); a += T) {
@@ -1940,6 +1956,200 @@ extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int
                                     void *hip_stream, const fc_options *options_or_null, fc_stats *stats_or_null) {
     return split_gamma_impl(g, U, k, n_pairs, d_u, d_w, d_t, d_gamma_out, d_flows_or_null, d_workspace, workspace_bytes,
                             hip_stream, options_or_null, stats_or_null, nullptr);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Spanning tree construction (Appendix E.3).  mu for an edge (x, y) that leaves the root-set being
+// grown is  min{ g(x, y), m(R_grow), F(x, y; D-bar) - sum of the other demands },  where D-bar adds to
+// the digraph one vertex s_i per other root-set with an arc (x, s_i) of capacity m(R_i) and unbounded
+// arcs from s_i to the members of R_i.  Here every root-set gets its vertex s_i once (vertices
+// n .. n + n_sets - 1, unbounded arcs to its members); the arcs (x, s_i) never exist as arcs: they are
+// saturated by definition of the preflow, so s_i simply starts with the excess m(R_i) -- the same
+// device that gives the compute nodes their k units in the auxiliary network -- and the grown set's
+// s_i starts with nothing.  All candidate edges of one state form one launch of explicit
+// (source, sink) problems on that shared graph.
+namespace {
+struct TreeState {
+    int32_t n = 0;                                       // vertices of D*
+    std::map<std::pair<int32_t, int32_t>, long long> g;  // remaining capacities
+    std::vector<std::vector<int32_t>> members;           // root-sets, members in increasing order
+    std::vector<uint8_t> inside;                         // [set][vertex] membership
+    std::vector<long long> demand;
+};
+
+// mu for the candidate edges (xs[j], ys[j]) of root-set `grow`; flows_or_null receives F(x, y; D-bar)
+int tree_mu_launch(const TreeState &st, int32_t grow, const std::vector<int32_t> &xs, const std::vector<int32_t> &ys,
+                   std::vector<int32_t> &mu, int32_t *flows_or_null, hipStream_t stream, const fc_options *options_or_null) {
+    const int32_t n = st.n, H = int32_t(st.members.size());
+    const size_t E = xs.size();
+    mu.assign(E, FC_GAMMA_INVALID);
+    if (E == 0) return FC_OK;
+    long long sum_g = 0, others = 0;
+    for (const auto &kv : st.g) sum_g += kv.second;
+    for (int32_t i = 0; i < H; ++i) if (i != grow) others += st.demand[size_t(i)];
+    const long long unbounded = sum_g + others + 1;      // more than any finite cut of D-bar
+    if (unbounded >= (1ll << 30) || others < 1) return others < 1 ? FC_EINVAL : FC_EOVERFLOW;
+    std::vector<int32_t> at, ah, ab, wts(size_t(n + H), 0);
+    std::vector<uint8_t> flagged(size_t(n + H), 0);
+    for (const auto &kv : st.g) { at.push_back(kv.first.first); ah.push_back(kv.first.second); ab.push_back(int32_t(kv.second)); }
+    for (int32_t i = 0; i < H; ++i) {
+        flagged[size_t(n + i)] = 1;
+        wts[size_t(n + i)] = i == grow ? 0 : int32_t(st.demand[size_t(i)]);
+        for (int32_t r : st.members[size_t(i)]) { at.push_back(n + i); ah.push_back(r); ab.push_back(int32_t(unbounded)); }
+    }
+    fc_graph *h = nullptr;
+    int rc = upload_impl(n + H, int64_t(at.size()), at.data(), ah.data(), ab.data(), flagged.data(), false, &h);
+    if (rc != FC_OK) return rc;
+    h->sum_bw = sum_g;                                   // the finite arcs only: "unbounded" is measured against them
+    int32_t *d_pairs = nullptr, *d_flow = nullptr;
+    auto fail = [&](int code) { if (d_pairs) (void)hipFree(d_pairs); if (d_flow) (void)hipFree(d_flow); fc_graph_free(h); return code; };
+    rc = fc_graph_set_source_weights(h, wts.data());
+    if (rc != FC_OK) return fail(rc);
+    if (lds_bytes(h, false) > size_t(h->lds_limit)) return fail(FC_EUNSUPPORTED);
+    Resolved opt;
+    rc = resolve_options(h, options_or_null, &opt);
+    if (rc != FC_OK) return fail(rc);
+    // a max-flow may stop once it cannot decide mu any more: at the other demands + min{g(x, y), m(R_grow)}
+    std::vector<int32_t> stage(3 * E, 0);
+    for (size_t j = 0; j < E; ++j) {
+        stage[j] = xs[j]; stage[E + j] = ys[j];
+        const auto it = st.g.find(std::make_pair(xs[j], ys[j]));
+        const long long cap_xy = it == st.g.end() ? 0 : it->second;
+        stage[2 * E + j] = flows_or_null ? -1 : int32_t(others + std::min<long long>(cap_xy, st.demand[size_t(grow)]));
+    }
+    if (hipMalloc(&d_pairs, sizeof(int32_t) * 3 * E) != hipSuccess) { d_pairs = nullptr; return fail(FC_EDEVICE); }
+    if (hipMalloc(&d_flow, sizeof(int32_t) * E) != hipSuccess) { d_flow = nullptr; return fail(FC_EDEVICE); }
+    if (hipMemcpyAsync(d_pairs, stage.data(), sizeof(int32_t) * 3 * E, hipMemcpyHostToDevice, stream) != hipSuccess) return fail(FC_EDEVICE);
+    KParams kp;
+    common_params(h, opt, &kp);
+    kp.pair_src = d_pairs; kp.pair_dst = d_pairs + E; kp.pair_stop = d_pairs + 2 * E;
+    kp.split_U = 1; kp.split_k = 1;
+    kp.flow_out = d_flow; kp.wide_available = 1;
+    const int32_t T = (options_or_null && options_or_null->threads_per_problem) ? opt.T : (h->n >= 256 ? 128 : 64);
+    rc = launch_g<false, false, true>(kp, (long long)E, T, opt.G, lds_bytes(h, false), stream);
+    if (rc != FC_OK) return fail(rc);
+    std::vector<int32_t> flows(E, 0);
+    if (hipMemcpyAsync(flows.data(), d_flow, sizeof(int32_t) * E, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) return fail(FC_EDEVICE);
+    for (size_t j = 0; j < E; ++j) {
+        const int32_t x = xs[j], y = ys[j];
+        if (flows_or_null) flows_or_null[j] = flows[j];
+        const auto it = (x >= 0 && x < n && y >= 0 && y < n) ? st.g.find(std::make_pair(x, y)) : st.g.end();
+        if (it == st.g.end() || !st.inside[size_t(grow) * size_t(n) + size_t(x)] || st.inside[size_t(grow) * size_t(n) + size_t(y)] || flows[j] < 0) continue;
+        if (flows[j] == FC_FLOW_NOCONVERGE) return fail(FC_ENOCONVERGE);
+        long long m = std::min<long long>(it->second, st.demand[size_t(grow)]);
+        m = std::min<long long>(m, (long long)flows[j] - others);
+        mu[j] = int32_t(m);
+    }
+    return fail(FC_OK);                                  // frees what the launch used
+}
+
+int tree_state_from_arrays(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
+                           int32_t n_sets, const int64_t *set_ptr, const int32_t *set_members, const int32_t *set_demand, TreeState *st) {
+    if (n_vertices < 2 || n_links < 0 || n_sets < 2 || !set_ptr || !set_demand || (n_links > 0 && (!tail || !head || !capacity))) return FC_EINVAL;
+    st->n = n_vertices;
+    for (int64_t i = 0; i < n_links; ++i) {
+        if (tail[i] < 0 || tail[i] >= n_vertices || head[i] < 0 || head[i] >= n_vertices || capacity[i] < 0) return FC_EINVAL;
+        if (tail[i] != head[i] && capacity[i] > 0) st->g[std::make_pair(tail[i], head[i])] += capacity[i];
+    }
+    st->members.assign(size_t(n_sets), std::vector<int32_t>());
+    st->inside.assign(size_t(n_sets) * size_t(n_vertices), 0);
+    st->demand.assign(size_t(n_sets), 0);
+    for (int32_t i = 0; i < n_sets; ++i) {
+        if (set_ptr[i] > set_ptr[i + 1] || set_ptr[i] < 0 || set_demand[i] < 1) return FC_EINVAL;
+        st->demand[size_t(i)] = set_demand[i];
+        for (int64_t q = set_ptr[i]; q < set_ptr[i + 1]; ++q) {
+            const int32_t r = set_members[q];
+            if (r < 0 || r >= n_vertices) return FC_EINVAL;
+            if (!st->inside[size_t(i) * size_t(n_vertices) + size_t(r)]) { st->inside[size_t(i) * size_t(n_vertices) + size_t(r)] = 1; st->members[size_t(i)].push_back(r); }
+        }
+        std::sort(st->members[size_t(i)].begin(), st->members[size_t(i)].end());
+        if (st->members[size_t(i)].empty()) return FC_EINVAL;
+    }
+    return FC_OK;
+}
+}  // namespace
+
+extern "C" int fc_tree_mu_batch(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
+                                int32_t n_sets, const int64_t *set_ptr, const int32_t *set_members, const int32_t *set_demand,
+                                int32_t grow_set, int64_t n_edges, const int32_t *edge_x, const int32_t *edge_y,
+                                int32_t *mu_out, int32_t *flows_or_null, void *hip_stream, const fc_options *options_or_null) {
+    if (n_edges < 0 || grow_set < 0 || grow_set >= n_sets || (n_edges > 0 && (!edge_x || !edge_y || !mu_out))) return FC_EINVAL;
+    try {
+        TreeState st;
+        int rc = tree_state_from_arrays(n_vertices, n_links, tail, head, capacity, n_sets, set_ptr, set_members, set_demand, &st);
+        if (rc != FC_OK) return rc;
+        std::vector<int32_t> xs(edge_x, edge_x + n_edges), ys(edge_y, edge_y + n_edges), mu;
+        rc = tree_mu_launch(st, grow_set, xs, ys, mu, flows_or_null, reinterpret_cast<hipStream_t>(hip_stream), options_or_null);
+        if (rc != FC_OK) return rc;
+        for (int64_t j = 0; j < n_edges; ++j) mu_out[j] = mu[size_t(j)];
+        return FC_OK;
+    } catch (const std::bad_alloc &) {
+        return FC_ENOMEM;
+    }
+}
+
+extern "C" int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
+                                  int32_t k, int64_t tree_capacity, int64_t *n_trees, int32_t *tree_root, int32_t *tree_multiplicity,
+                                  int32_t *tree_edge_x, int32_t *tree_edge_y, int64_t *n_batches_or_null,
+                                  void *hip_stream, const fc_options *options_or_null) {
+    if (n_vertices < 2 || k < 1 || !n_trees || tree_capacity < 0) return FC_EINVAL;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    try {
+        TreeState st;
+        std::vector<int64_t> ptr(size_t(n_vertices) + 1, 0);
+        std::vector<int32_t> mem(size_t(n_vertices), 0), dem(size_t(n_vertices), k);
+        for (int32_t u = 0; u < n_vertices; ++u) { ptr[size_t(u) + 1] = u + 1; mem[size_t(u)] = u; }
+        int rc = tree_state_from_arrays(n_vertices, n_links, tail, head, capacity, n_vertices, ptr.data(), mem.data(), dem.data(), &st);
+        if (rc != FC_OK) return rc;
+        const int32_t n = n_vertices;
+        std::vector<int32_t> root(size_t(n), 0);
+        for (int32_t u = 0; u < n; ++u) root[size_t(u)] = u;
+        std::vector<std::vector<std::pair<int32_t, int32_t>>> edges((size_t(n)));
+        int64_t batches = 0;
+        std::vector<int32_t> xs, ys, mu;
+        for (size_t i = 0; i < st.members.size(); ++i) {               // copies are appended while this runs
+            while (int32_t(st.members[i].size()) < n) {
+                xs.clear(); ys.clear();
+                for (const auto &kv : st.g)                             // (x, y) order
+                    if (st.inside[i * size_t(n) + size_t(kv.first.first)] && !st.inside[i * size_t(n) + size_t(kv.first.second)]) { xs.push_back(kv.first.first); ys.push_back(kv.first.second); }
+                if (xs.empty()) return FC_ENOCONVERGE;
+                rc = tree_mu_launch(st, int32_t(i), xs, ys, mu, nullptr, stream, options_or_null);
+                ++batches;
+                if (rc != FC_OK) return rc;
+                size_t hit = xs.size();
+                for (size_t q = 0; q < xs.size(); ++q) {
+                    if (mu[q] < 0) return FC_ENOCONVERGE;               // the packing condition does not hold for this input
+                    if (mu[q] > 0) { hit = q; break; }
+                }
+                if (hit == xs.size()) return FC_ENOCONVERGE;
+                const int32_t x = xs[hit], y = ys[hit]; const long long m = mu[hit];
+                if (m < st.demand[i]) {                                 // a copy keeps the rest of the multiplicity
+                    st.members.push_back(st.members[i]); st.demand.push_back(st.demand[i] - m); root.push_back(root[i]);
+                    edges.push_back(edges[i]);
+                    st.inside.insert(st.inside.end(), st.inside.begin() + long(i * size_t(n)), st.inside.begin() + long((i + 1) * size_t(n)));
+                    st.demand[i] = m;
+                }
+                edges[i].push_back(std::make_pair(x, y));
+                st.inside[i * size_t(n) + size_t(y)] = 1;
+                st.members[i].insert(std::upper_bound(st.members[i].begin(), st.members[i].end(), y), y);
+                auto it = st.g.find(std::make_pair(x, y));
+                it->second -= m;
+                if (it->second == 0) st.g.erase(it);
+            }
+        }
+        *n_trees = int64_t(st.members.size());
+        if (n_batches_or_null) *n_batches_or_null = batches;
+        if (*n_trees > tree_capacity) return FC_EWORKSPACE;
+        if (!tree_root || !tree_multiplicity || !tree_edge_x || !tree_edge_y) return FC_EINVAL;
+        for (size_t i = 0; i < st.members.size(); ++i) {
+            tree_root[i] = root[i]; tree_multiplicity[i] = int32_t(st.demand[i]);
+            for (size_t q = 0; q < edges[i].size(); ++q) { tree_edge_x[i * size_t(n - 1) + q] = edges[i][q].first; tree_edge_y[i * size_t(n - 1) + q] = edges[i][q].second; }
+        }
+        return FC_OK;
+    } catch (const std::bad_alloc &) {
+        return FC_ENOMEM;
+    }
 }
 
 extern "C" int fc_fixed_k_search(const fc_graph *g, int32_t k, int32_t candidates_per_round, fc_rational *U_star,

@@ -821,3 +821,102 @@ def test_weighted_source_arcs_on_tiny_random_graphs_and_bad_weights():
         fc.fc_graph_set_source_weights(g, np.full(topo.n_vertices, 2 ** 20, np.int32))
         got, _ = _gpu_flows(g, topo.compute_nodes[:2], [1, 1], [1, 2 ** 11])
         assert got[1] == fc.FC_FLOW_INVALID and got[0] == o.weighted_aux_maxflow_batch(topo, topo.compute_nodes[:1], [1], [1], np.full(topo.n_vertices, 2 ** 20))[0]
+
+
+# ------------------------------------------------------------------ spanning tree construction (Appendix E.3)
+
+def _check_trees(n, links, k, trees):
+    use, per_root = {}, {}
+    for root, m, edges in trees:
+        assert m >= 1 and len(edges) == n - 1
+        seen = {root}
+        for x, y in edges:
+            assert x in seen and y not in seen
+            seen.add(y)
+            use[(x, y)] = use.get((x, y), 0) + m
+        assert seen == set(range(n))
+        per_root[root] = per_root.get(root, 0) + m
+    assert per_root == {u: k for u in range(n)}
+    assert all(c <= links[e] for e, c in use.items())
+    return use
+
+
+def _star_links(topo, U, k):
+    """D* of a switch topology at (U, k): switch removal by the oracle, compute nodes renumbered 0..N-1"""
+    D = _scaled(topo, U)
+    Dstar, _ = o.remove_switches(D, k)
+    comp = [int(v) for v in topo.compute_nodes]
+    idx = {v: i for i, v in enumerate(comp)}
+    return len(comp), {(idx[a], idx[b]): c for (a, b), c in o.link_capacities(Dstar).items()}
+
+
+def test_tree_mu_batches_match_oracle():
+    # every mu the oracle's construction computes, replayed state by state as batches on the GPU: all candidate
+    # edges of the state at once, with exact flows and with early stops
+    cases = [(8, o.link_capacities(w.paper_example_split(2)), 2)]
+    for n, k in ((3, 2), (5, 3)):
+        rng = np.random.default_rng(100 * n + k)
+        cases.append((n, {(a, b): k + int(rng.integers(0, 3)) for a in range(n) for b in range(n) if a != b}, k))
+    cases.append(_star_links(w.paper_example_switch(1), 1, 1) + (1,))
+    for n, links, k in cases:
+        states = []
+
+        def observe(g, sets, demand, i, x, y, mu):
+            if not states or states[-1][0] != (dict(g), [set(R) for R in sets], list(demand), i):
+                states.append(((dict(g), [set(R) for R in sets], list(demand), i), []))
+            states[-1][1].append((x, y, mu))
+
+        o.construct_trees(n, links, k, observe=observe)
+        assert states
+        for (g, sets, demand, i), seen in states[:: max(1, len(states) // 25)]:
+            cand = [(x, y) for (x, y) in sorted(g) if x in sets[i] and y not in sets[i]]
+            want = [o.tree_mu(n, g, sets, demand, i, x, y) for (x, y) in cand]
+            assert [m for (_, _, m) in seen] == want[: len(seen)]
+            others = sum(demand[l] for l in range(len(sets)) if l != i)
+            exact = fc.fc_tree_mu_batch(n, g, sets, demand, i, cand, want_flows=True)
+            assert exact["mu"].tolist() == want
+            nv, tail, head, c = o.tree_mu_network(n, g, sets, demand, i, cand[0][0])
+            assert exact["flows"][0] == o.maxflow(nv, tail, head, c, cand[0][0], cand[0][1])
+            assert (exact["flows"] >= others).all()
+            early = fc.fc_tree_mu_batch(n, g, sets, demand, i, cand)
+            assert early["mu"].tolist() == want
+            # entries that are no candidate: inside to inside, outside to inside, a missing link
+            inside = sorted(sets[i]); outside = [v for v in range(n) if v not in sets[i]]
+            bogus = [(inside[0], inside[0]), (outside[0], inside[0]), (-1, 0), (inside[0], n)]
+            res = fc.fc_tree_mu_batch(n, g, sets, demand, i, cand + bogus)
+            assert res["mu"].tolist() == want + [fc.FC_MU_INVALID] * 4
+
+
+def test_construct_trees_matches_oracle():
+    cases = [(8, o.link_capacities(w.paper_example_split(1)), 1), (8, o.link_capacities(w.paper_example_split(3)), 3),
+             (2, {(0, 1): 4, (1, 0): 4}, 4), (4, {(a, b): 3 for a in range(4) for b in range(4) if a != b}, 3),
+             _star_links(w.paper_example_switch(2), 1, 2) + (2,)]
+    rng = np.random.default_rng(5)
+    for n in (3, 5, 6):
+        k = int(rng.integers(1, 5))
+        cases.append((n, {(a, b): k + int(rng.integers(0, 4)) for a in range(n) for b in range(n) if a != b}, k))
+    for n, links, k in cases:
+        want = o.construct_trees(n, links, k)
+        got = fc.fc_construct_trees(n, links, k)
+        assert got["trees"] == want, (n, k)
+        _check_trees(n, links, k, got["trees"])
+        assert got["batches"] >= n - 1
+    # the packing condition fails: the construction reports it
+    with pytest.raises(fc.FcError) as err:
+        fc.fc_construct_trees(3, {(0, 1): 1, (1, 0): 2, (1, 2): 2, (2, 1): 2, (0, 2): 2, (2, 0): 2}, 2)
+    assert err.value.code == fc.FC_ENOCONVERGE
+
+
+def test_trees_on_config1_after_switch_removal_on_the_gpu():
+    # the back end on the GPU alone: optimum, switch removal, trees; then the oracle's trees for the same D*
+    topo = w.config_topology(1)
+    inv = Fraction(*_optimum(1, topo))
+    Uq, k = o.smallest_U_k(inv, topo.bandwidth)
+    U, kk = Uq.numerator, k * Uq.denominator
+    res = _remove_on_gpu(_scaled(topo, U), kk)
+    comp = [int(v) for v in topo.compute_nodes]
+    idx = {v: i for i, v in enumerate(comp)}
+    links = {(idx[a], idx[b]): c for (a, b), c in res["links"].items()}
+    got = fc.fc_construct_trees(len(comp), links, kk)
+    _check_trees(len(comp), links, kk, got["trees"])
+    assert got["trees"] == o.construct_trees(len(comp), links, kk)
