@@ -1958,200 +1958,6 @@ extern "C" int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int
                             hip_stream, options_or_null, stats_or_null, nullptr);
 }
 
-// ---------------------------------------------------------------------------------------------
-// Spanning tree construction (Appendix E.3).  mu for an edge (x, y) that leaves the root-set being
-// grown is  min{ g(x, y), m(R_grow), F(x, y; D-bar) - sum of the other demands },  where D-bar adds to
-// the digraph one vertex s_i per other root-set with an arc (x, s_i) of capacity m(R_i) and unbounded
-// arcs from s_i to the members of R_i.  Here every root-set gets its vertex s_i once (vertices
-// n .. n + n_sets - 1, unbounded arcs to its members); the arcs (x, s_i) never exist as arcs: they are
-// saturated by definition of the preflow, so s_i simply starts with the excess m(R_i) -- the same
-// device that gives the compute nodes their k units in the auxiliary network -- and the grown set's
-// s_i starts with nothing.  All candidate edges of one state form one launch of explicit
-// (source, sink) problems on that shared graph.
-namespace {
-struct TreeState {
-    int32_t n = 0;                                       // vertices of D*
-    std::map<std::pair<int32_t, int32_t>, long long> g;  // remaining capacities
-    std::vector<std::vector<int32_t>> members;           // root-sets, members in increasing order
-    std::vector<uint8_t> inside;                         // [set][vertex] membership
-    std::vector<long long> demand;
-};
-
-// mu for the candidate edges (xs[j], ys[j]) of root-set `grow`; flows_or_null receives F(x, y; D-bar)
-int tree_mu_launch(const TreeState &st, int32_t grow, const std::vector<int32_t> &xs, const std::vector<int32_t> &ys,
-                   std::vector<int32_t> &mu, int32_t *flows_or_null, hipStream_t stream, const fc_options *options_or_null) {
-    const int32_t n = st.n, H = int32_t(st.members.size());
-    const size_t E = xs.size();
-    mu.assign(E, FC_GAMMA_INVALID);
-    if (E == 0) return FC_OK;
-    long long sum_g = 0, others = 0;
-    for (const auto &kv : st.g) sum_g += kv.second;
-    for (int32_t i = 0; i < H; ++i) if (i != grow) others += st.demand[size_t(i)];
-    const long long unbounded = sum_g + others + 1;      // more than any finite cut of D-bar
-    if (unbounded >= (1ll << 30) || others < 1) return others < 1 ? FC_EINVAL : FC_EOVERFLOW;
-    std::vector<int32_t> at, ah, ab, wts(size_t(n + H), 0);
-    std::vector<uint8_t> flagged(size_t(n + H), 0);
-    for (const auto &kv : st.g) { at.push_back(kv.first.first); ah.push_back(kv.first.second); ab.push_back(int32_t(kv.second)); }
-    for (int32_t i = 0; i < H; ++i) {
-        flagged[size_t(n + i)] = 1;
-        wts[size_t(n + i)] = i == grow ? 0 : int32_t(st.demand[size_t(i)]);
-        for (int32_t r : st.members[size_t(i)]) { at.push_back(n + i); ah.push_back(r); ab.push_back(int32_t(unbounded)); }
-    }
-    fc_graph *h = nullptr;
-    int rc = upload_impl(n + H, int64_t(at.size()), at.data(), ah.data(), ab.data(), flagged.data(), false, &h);
-    if (rc != FC_OK) return rc;
-    h->sum_bw = sum_g;                                   // the finite arcs only: "unbounded" is measured against them
-    int32_t *d_pairs = nullptr, *d_flow = nullptr;
-    auto fail = [&](int code) { if (d_pairs) (void)hipFree(d_pairs); if (d_flow) (void)hipFree(d_flow); fc_graph_free(h); return code; };
-    rc = fc_graph_set_source_weights(h, wts.data());
-    if (rc != FC_OK) return fail(rc);
-    if (lds_bytes(h, false) > size_t(h->lds_limit)) return fail(FC_EUNSUPPORTED);
-    Resolved opt;
-    rc = resolve_options(h, options_or_null, &opt);
-    if (rc != FC_OK) return fail(rc);
-    // a max-flow may stop once it cannot decide mu any more: at the other demands + min{g(x, y), m(R_grow)}
-    std::vector<int32_t> stage(3 * E, 0);
-    for (size_t j = 0; j < E; ++j) {
-        stage[j] = xs[j]; stage[E + j] = ys[j];
-        const auto it = st.g.find(std::make_pair(xs[j], ys[j]));
-        const long long cap_xy = it == st.g.end() ? 0 : it->second;
-        stage[2 * E + j] = flows_or_null ? -1 : int32_t(others + std::min<long long>(cap_xy, st.demand[size_t(grow)]));
-    }
-    if (hipMalloc(&d_pairs, sizeof(int32_t) * 3 * E) != hipSuccess) { d_pairs = nullptr; return fail(FC_EDEVICE); }
-    if (hipMalloc(&d_flow, sizeof(int32_t) * E) != hipSuccess) { d_flow = nullptr; return fail(FC_EDEVICE); }
-    if (hipMemcpyAsync(d_pairs, stage.data(), sizeof(int32_t) * 3 * E, hipMemcpyHostToDevice, stream) != hipSuccess) return fail(FC_EDEVICE);
-    KParams kp;
-    common_params(h, opt, &kp);
-    kp.pair_src = d_pairs; kp.pair_dst = d_pairs + E; kp.pair_stop = d_pairs + 2 * E;
-    kp.split_U = 1; kp.split_k = 1;
-    kp.flow_out = d_flow; kp.wide_available = 1;
-    const int32_t T = (options_or_null && options_or_null->threads_per_problem) ? opt.T : (h->n >= 256 ? 128 : 64);
-    rc = launch_g<false, false, true>(kp, (long long)E, T, opt.G, lds_bytes(h, false), stream);
-    if (rc != FC_OK) return fail(rc);
-    std::vector<int32_t> flows(E, 0);
-    if (hipMemcpyAsync(flows.data(), d_flow, sizeof(int32_t) * E, hipMemcpyDeviceToHost, stream) != hipSuccess ||
-        hipStreamSynchronize(stream) != hipSuccess) return fail(FC_EDEVICE);
-    for (size_t j = 0; j < E; ++j) {
-        const int32_t x = xs[j], y = ys[j];
-        if (flows_or_null) flows_or_null[j] = flows[j];
-        const auto it = (x >= 0 && x < n && y >= 0 && y < n) ? st.g.find(std::make_pair(x, y)) : st.g.end();
-        if (it == st.g.end() || !st.inside[size_t(grow) * size_t(n) + size_t(x)] || st.inside[size_t(grow) * size_t(n) + size_t(y)] || flows[j] < 0) continue;
-        if (flows[j] == FC_FLOW_NOCONVERGE) return fail(FC_ENOCONVERGE);
-        long long m = std::min<long long>(it->second, st.demand[size_t(grow)]);
-        m = std::min<long long>(m, (long long)flows[j] - others);
-        mu[j] = int32_t(m);
-    }
-    return fail(FC_OK);                                  // frees what the launch used
-}
-
-int tree_state_from_arrays(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
-                           int32_t n_sets, const int64_t *set_ptr, const int32_t *set_members, const int32_t *set_demand, TreeState *st) {
-    if (n_vertices < 2 || n_links < 0 || n_sets < 2 || !set_ptr || !set_demand || (n_links > 0 && (!tail || !head || !capacity))) return FC_EINVAL;
-    st->n = n_vertices;
-    for (int64_t i = 0; i < n_links; ++i) {
-        if (tail[i] < 0 || tail[i] >= n_vertices || head[i] < 0 || head[i] >= n_vertices || capacity[i] < 0) return FC_EINVAL;
-        if (tail[i] != head[i] && capacity[i] > 0) st->g[std::make_pair(tail[i], head[i])] += capacity[i];
-    }
-    st->members.assign(size_t(n_sets), std::vector<int32_t>());
-    st->inside.assign(size_t(n_sets) * size_t(n_vertices), 0);
-    st->demand.assign(size_t(n_sets), 0);
-    for (int32_t i = 0; i < n_sets; ++i) {
-        if (set_ptr[i] > set_ptr[i + 1] || set_ptr[i] < 0 || set_demand[i] < 1) return FC_EINVAL;
-        st->demand[size_t(i)] = set_demand[i];
-        for (int64_t q = set_ptr[i]; q < set_ptr[i + 1]; ++q) {
-            const int32_t r = set_members[q];
-            if (r < 0 || r >= n_vertices) return FC_EINVAL;
-            if (!st->inside[size_t(i) * size_t(n_vertices) + size_t(r)]) { st->inside[size_t(i) * size_t(n_vertices) + size_t(r)] = 1; st->members[size_t(i)].push_back(r); }
-        }
-        std::sort(st->members[size_t(i)].begin(), st->members[size_t(i)].end());
-        if (st->members[size_t(i)].empty()) return FC_EINVAL;
-    }
-    return FC_OK;
-}
-}  // namespace
-
-extern "C" int fc_tree_mu_batch(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
-                                int32_t n_sets, const int64_t *set_ptr, const int32_t *set_members, const int32_t *set_demand,
-                                int32_t grow_set, int64_t n_edges, const int32_t *edge_x, const int32_t *edge_y,
-                                int32_t *mu_out, int32_t *flows_or_null, void *hip_stream, const fc_options *options_or_null) {
-    if (n_edges < 0 || grow_set < 0 || grow_set >= n_sets || (n_edges > 0 && (!edge_x || !edge_y || !mu_out))) return FC_EINVAL;
-    try {
-        TreeState st;
-        int rc = tree_state_from_arrays(n_vertices, n_links, tail, head, capacity, n_sets, set_ptr, set_members, set_demand, &st);
-        if (rc != FC_OK) return rc;
-        std::vector<int32_t> xs(edge_x, edge_x + n_edges), ys(edge_y, edge_y + n_edges), mu;
-        rc = tree_mu_launch(st, grow_set, xs, ys, mu, flows_or_null, reinterpret_cast<hipStream_t>(hip_stream), options_or_null);
-        if (rc != FC_OK) return rc;
-        for (int64_t j = 0; j < n_edges; ++j) mu_out[j] = mu[size_t(j)];
-        return FC_OK;
-    } catch (const std::bad_alloc &) {
-        return FC_ENOMEM;
-    }
-}
-
-extern "C" int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
-                                  int32_t k, int64_t tree_capacity, int64_t *n_trees, int32_t *tree_root, int32_t *tree_multiplicity,
-                                  int32_t *tree_edge_x, int32_t *tree_edge_y, int64_t *n_batches_or_null,
-                                  void *hip_stream, const fc_options *options_or_null) {
-    if (n_vertices < 2 || k < 1 || !n_trees || tree_capacity < 0) return FC_EINVAL;
-    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-    try {
-        TreeState st;
-        std::vector<int64_t> ptr(size_t(n_vertices) + 1, 0);
-        std::vector<int32_t> mem(size_t(n_vertices), 0), dem(size_t(n_vertices), k);
-        for (int32_t u = 0; u < n_vertices; ++u) { ptr[size_t(u) + 1] = u + 1; mem[size_t(u)] = u; }
-        int rc = tree_state_from_arrays(n_vertices, n_links, tail, head, capacity, n_vertices, ptr.data(), mem.data(), dem.data(), &st);
-        if (rc != FC_OK) return rc;
-        const int32_t n = n_vertices;
-        std::vector<int32_t> root(size_t(n), 0);
-        for (int32_t u = 0; u < n; ++u) root[size_t(u)] = u;
-        std::vector<std::vector<std::pair<int32_t, int32_t>>> edges((size_t(n)));
-        int64_t batches = 0;
-        std::vector<int32_t> xs, ys, mu;
-        for (size_t i = 0; i < st.members.size(); ++i) {               // copies are appended while this runs
-            while (int32_t(st.members[i].size()) < n) {
-                xs.clear(); ys.clear();
-                for (const auto &kv : st.g)                             // (x, y) order
-                    if (st.inside[i * size_t(n) + size_t(kv.first.first)] && !st.inside[i * size_t(n) + size_t(kv.first.second)]) { xs.push_back(kv.first.first); ys.push_back(kv.first.second); }
-                if (xs.empty()) return FC_ENOCONVERGE;
-                rc = tree_mu_launch(st, int32_t(i), xs, ys, mu, nullptr, stream, options_or_null);
-                ++batches;
-                if (rc != FC_OK) return rc;
-                size_t hit = xs.size();
-                for (size_t q = 0; q < xs.size(); ++q) {
-                    if (mu[q] < 0) return FC_ENOCONVERGE;               // the packing condition does not hold for this input
-                    if (mu[q] > 0) { hit = q; break; }
-                }
-                if (hit == xs.size()) return FC_ENOCONVERGE;
-                const int32_t x = xs[hit], y = ys[hit]; const long long m = mu[hit];
-                if (m < st.demand[i]) {                                 // a copy keeps the rest of the multiplicity
-                    st.members.push_back(st.members[i]); st.demand.push_back(st.demand[i] - m); root.push_back(root[i]);
-                    edges.push_back(edges[i]);
-                    st.inside.insert(st.inside.end(), st.inside.begin() + long(i * size_t(n)), st.inside.begin() + long((i + 1) * size_t(n)));
-                    st.demand[i] = m;
-                }
-                edges[i].push_back(std::make_pair(x, y));
-                st.inside[i * size_t(n) + size_t(y)] = 1;
-                st.members[i].insert(std::upper_bound(st.members[i].begin(), st.members[i].end(), y), y);
-                auto it = st.g.find(std::make_pair(x, y));
-                it->second -= m;
-                if (it->second == 0) st.g.erase(it);
-            }
-        }
-        *n_trees = int64_t(st.members.size());
-        if (n_batches_or_null) *n_batches_or_null = batches;
-        if (*n_trees > tree_capacity) return FC_EWORKSPACE;
-        if (!tree_root || !tree_multiplicity || !tree_edge_x || !tree_edge_y) return FC_EINVAL;
-        for (size_t i = 0; i < st.members.size(); ++i) {
-            tree_root[i] = root[i]; tree_multiplicity[i] = int32_t(st.demand[i]);
-            for (size_t q = 0; q < edges[i].size(); ++q) { tree_edge_x[i * size_t(n - 1) + q] = edges[i][q].first; tree_edge_y[i * size_t(n - 1) + q] = edges[i][q].second; }
-        }
-        return FC_OK;
-    } catch (const std::bad_alloc &) {
-        return FC_ENOMEM;
-    }
-}
-
 extern "C" int fc_fixed_k_search(const fc_graph *g, int32_t k, int32_t candidates_per_round, fc_rational *U_star,
                                  int32_t *rounds_or_null, void *hip_stream, const fc_options *options_or_null,
                                  int32_t *trace_num, int32_t *trace_den, uint8_t *trace_verdict, int32_t trace_capacity,
@@ -2197,7 +2003,7 @@ namespace {
 struct SplitPool {
     int32_t n = 0, N = 0;
     size_t rec_cap = 0, pair_cap = 0;                     // arc records and pairs there is room for
-    size_t off_row = 0, off_inbw = 0, off_pairs = 0, off_wide = 0, off_is = 0, off_ids = 0, off_cost = 0, off_gamma = 0, off_ws = 0, ws_bytes = 0;
+    size_t off_row = 0, off_inbw = 0, off_wts = 0, off_pairs = 0, off_wide = 0, off_is = 0, off_ids = 0, off_cost = 0, off_gamma = 0, off_ws = 0, ws_bytes = 0;
     unsigned char *d_blob = nullptr, *h_blob = nullptr;   // h_blob: pinned, covers [0, off_ws)
     SplitPool() = default;
     SplitPool(const SplitPool &) = delete;
@@ -2209,16 +2015,19 @@ struct SplitPool {
         d_blob = nullptr; h_blob = nullptr; rec_cap = 0; pair_cap = 0;
     }
     // room for `recs` arc records and `pairs` pairs; growing re-creates both blocks (contents are rewritten by every batch)
-    int ensure(const fc_graph *h, size_t recs, size_t pairs, hipStream_t stream) {
-        if (d_blob && recs <= rec_cap && pairs <= pair_cap) return FC_OK;
-        const size_t want_rec = std::max<size_t>(recs + recs / 2 + 64, 2 * rec_cap);     // splits add links: leave headroom
-        const size_t want_pairs = std::max<size_t>(std::max<size_t>(pairs, 1), d_blob ? 2 * pair_cap : size_t(h->n));
+    // (with_workspace: room for the counters and flows of pairs * 2N edge-splitting max-flows behind the block)
+    int ensure(const fc_graph *h, size_t recs, size_t pairs, hipStream_t stream, bool with_workspace = true) {
+        if (d_blob && n == h->n && N == h->N && recs <= rec_cap && pairs <= pair_cap) return FC_OK;
+        // more room only where it ran out (the block is also rebuilt when the vertex set changes)
+        const size_t want_rec = recs > rec_cap ? std::max<size_t>(recs + recs / 2 + 64, 2 * rec_cap) : rec_cap;    // splits add links: leave headroom
+        const size_t want_pairs = pairs > pair_cap ? std::max<size_t>(std::max<size_t>(pairs, 1), d_blob ? 2 * pair_cap : size_t(h->n)) : pair_cap;
         if (d_blob && hipStreamSynchronize(stream) != hipSuccess) return FC_EDEVICE;
         release();
         n = h->n; N = h->N;
         size_t o = 0;
         off_row = o; o = align_up(o + sizeof(int32_t) * (size_t(n) + 1), 256);
         off_inbw = o; o = align_up(o + sizeof(int32_t) * size_t(n), 256);
+        off_wts = o; o = align_up(o + sizeof(int32_t) * size_t(n), 256);     // source weights (tree construction)
         off_pairs = o; o = align_up(o + sizeof(int32_t) * 3 * want_pairs, 256);
         off_wide = o; o = align_up(o + sizeof(int4) * want_rec, 256);
         off_is = o; o = align_up(o + size_t(n), 256);
@@ -2227,7 +2036,7 @@ struct SplitPool {
         off_gamma = o; o = align_up(o + sizeof(int32_t) * 2 * want_pairs, 256);   // gamma values, then slacks
         off_ws = o;
         const long long P = (long long)want_pairs * 2 * N;
-        ws_bytes = align_up(size_t(P) * 4, 256) + stats_bytes(P);
+        ws_bytes = with_workspace ? align_up(size_t(P) * 4, 256) + stats_bytes(P) : 0;
         if (hipMalloc(reinterpret_cast<void **>(&d_blob), off_ws + ws_bytes) != hipSuccess) { d_blob = nullptr; return FC_EDEVICE; }
         if (hipHostMalloc(reinterpret_cast<void **>(&h_blob), off_ws, hipHostMallocDefault) != hipSuccess) { h_blob = nullptr; release(); return FC_EDEVICE; }
         rec_cap = want_rec; pair_cap = want_pairs;
@@ -2239,6 +2048,229 @@ struct SplitPool {
     }
 };
 }  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// Spanning tree construction (Appendix E.3).  mu for an edge (x, y) that leaves the root-set being
+// grown is  min{ g(x, y), m(R_grow), F(x, y; D-bar) - sum of the other demands },  where D-bar adds to
+// the digraph one vertex s_i per other root-set with an arc (x, s_i) of capacity m(R_i) and unbounded
+// arcs from s_i to the members of R_i.  Here every root-set gets its vertex s_i once (vertices
+// n .. n + n_sets - 1, unbounded arcs to its members); the arcs (x, s_i) never exist as arcs: they are
+// saturated by definition of the preflow, so s_i simply starts with the excess m(R_i) -- the same
+// device that gives the compute nodes their k units in the auxiliary network -- and the grown set's
+// s_i starts with nothing.  All candidate edges of one state form one launch of explicit
+// (source, sink) problems on that shared graph.
+namespace {
+struct TreeState {
+    int32_t n = 0;                                       // vertices of D*
+    std::map<std::pair<int32_t, int32_t>, long long> g;  // remaining capacities
+    std::vector<std::vector<int32_t>> members;           // root-sets, members in increasing order
+    std::vector<uint8_t> inside;                         // [set][vertex] membership
+    std::vector<long long> demand;
+};
+
+// mu for the candidate edges (xs[j], ys[j]) of root-set `grow`; flows_or_null receives F(x, y; D-bar).
+// The graph of the state goes to the device in one transfer through `pool`, as in the switch-removal loop.
+int tree_mu_launch(const TreeState &st, int32_t grow, const std::vector<int32_t> &xs, const std::vector<int32_t> &ys,
+                   std::vector<int32_t> &mu, int32_t *flows_or_null, hipStream_t stream, const fc_options *options_or_null,
+                   SplitPool &pool) {
+    const int32_t n = st.n, H = int32_t(st.members.size());
+    const size_t E = xs.size();
+    mu.assign(E, FC_GAMMA_INVALID);
+    if (E == 0) return FC_OK;
+    long long sum_g = 0, others = 0;
+    for (const auto &kv : st.g) sum_g += kv.second;
+    for (int32_t i = 0; i < H; ++i) if (i != grow) others += st.demand[size_t(i)];
+    const long long unbounded = sum_g + others + 1;      // more than any finite cut of D-bar
+    if (unbounded >= (1ll << 30) || others < 1) return others < 1 ? FC_EINVAL : FC_EOVERFLOW;
+    std::vector<int32_t> at, ah, ab;
+    std::vector<uint8_t> flagged(size_t(n + H), 0);
+    for (const auto &kv : st.g) { at.push_back(kv.first.first); ah.push_back(kv.first.second); ab.push_back(int32_t(kv.second)); }
+    for (int32_t i = 0; i < H; ++i) {
+        flagged[size_t(n + i)] = 1;
+        for (int32_t r : st.members[size_t(i)]) { at.push_back(n + i); ah.push_back(r); ab.push_back(int32_t(unbounded)); }
+    }
+    fc_graph *h = nullptr;
+    int rc = fc_host_build(n + H, int64_t(at.size()), at.data(), ah.data(), ab.data(), flagged.data(), &h);
+    if (rc != FC_OK) return rc;
+    int dev = -1, lds_limit = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) { fc_graph_free(h); return FC_EDEVICE; }
+    h->device = dev; h->lds_limit = lds_limit; h->n_cu = n_cu;
+    auto done = [&](int code) {                          // the pool owns the device memory: detach it before the host graph goes
+        h->on_device = false;
+        h->d_row_ptr = nullptr; h->d_in_bw = nullptr; h->d_arc_wide = nullptr; h->d_is_compute = nullptr; h->d_compute_ids = nullptr;
+        h->d_sink_cost = nullptr; h->d_src_weight = nullptr;
+        fc_graph_free(h);
+        return code;
+    };
+    if (lds_bytes(h, false) > size_t(lds_limit)) return done(FC_EUNSUPPORTED);
+    const size_t M = size_t(2 * h->m0);
+    rc = pool.ensure(h, M, E, stream, false);
+    if (rc != FC_OK) return done(rc);
+    std::memcpy(pool.h_blob + pool.off_row, h->row_ptr.data(), sizeof(int32_t) * (size_t(h->n) + 1));
+    std::memcpy(pool.h_blob + pool.off_inbw, h->in_bw.data(), sizeof(int32_t) * size_t(h->n));
+    int32_t *hw = reinterpret_cast<int32_t *>(pool.h_blob + pool.off_wts);
+    std::memset(hw, 0, sizeof(int32_t) * size_t(h->n));
+    for (int32_t i = 0; i < H; ++i) hw[n + i] = i == grow ? 0 : int32_t(st.demand[size_t(i)]);   // the excess the root-set vertices start with
+    // a max-flow may stop once it cannot decide mu any more: at the other demands + min{g(x, y), m(R_grow)}
+    int32_t *hp = reinterpret_cast<int32_t *>(pool.h_blob + pool.off_pairs);
+    for (size_t j = 0; j < E; ++j) {
+        hp[j] = xs[j]; hp[pool.pair_cap + j] = ys[j];
+        const auto it = st.g.find(std::make_pair(xs[j], ys[j]));
+        const long long cap_xy = it == st.g.end() ? 0 : it->second;
+        hp[2 * pool.pair_cap + j] = flows_or_null ? -1 : int32_t(others + std::min<long long>(cap_xy, st.demand[size_t(grow)]));
+    }
+    fill_wide_records(h, reinterpret_cast<int4 *>(pool.h_blob + pool.off_wide));
+    h->on_device = true;
+    h->d_row_ptr = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_row);
+    h->d_in_bw = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_inbw);
+    h->d_src_weight = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_wts);
+    h->d_arc_wide = pool.d_blob + pool.off_wide;
+    h->d_is_compute = pool.d_blob + pool.off_is;
+    h->d_compute_ids = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_ids);
+    h->d_sink_cost = reinterpret_cast<uint32_t *>(pool.d_blob + pool.off_cost);
+    h->sum_bw = sum_g;                                   // the finite arcs only: "unbounded" is measured against them
+    h->sum_w = others;
+    int32_t *d_pairs = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_pairs);
+    int32_t *d_flow = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_gamma);
+    int32_t *h_flow = reinterpret_cast<int32_t *>(pool.h_blob + pool.off_gamma);
+    if (hipMemcpyAsync(pool.d_blob, pool.h_blob, pool.off_wide + sizeof(int4) * M, hipMemcpyHostToDevice, stream) != hipSuccess) return done(FC_EDEVICE);
+    Resolved opt;
+    rc = resolve_options(h, options_or_null, &opt);
+    if (rc != FC_OK) return done(rc);
+    KParams kp;
+    common_params(h, opt, &kp);
+    kp.pair_src = d_pairs; kp.pair_dst = d_pairs + pool.pair_cap; kp.pair_stop = d_pairs + 2 * pool.pair_cap;
+    kp.split_U = 1; kp.split_k = 1;
+    kp.flow_out = d_flow; kp.wide_available = 1;
+    const int32_t T = (options_or_null && options_or_null->threads_per_problem) ? opt.T : (h->n >= 256 ? 128 : 64);
+    rc = launch_g<false, false, true>(kp, (long long)E, T, opt.G, lds_bytes(h, false), stream);
+    if (rc != FC_OK) return done(rc);
+    if (hipMemcpyAsync(h_flow, d_flow, sizeof(int32_t) * E, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) return done(FC_EDEVICE);
+    for (size_t j = 0; j < E; ++j) {
+        const int32_t x = xs[j], y = ys[j], fl = h_flow[j];
+        if (flows_or_null) flows_or_null[j] = fl;
+        const auto it = (x >= 0 && x < n && y >= 0 && y < n) ? st.g.find(std::make_pair(x, y)) : st.g.end();
+        if (it == st.g.end() || !st.inside[size_t(grow) * size_t(n) + size_t(x)] || st.inside[size_t(grow) * size_t(n) + size_t(y)]) continue;
+        if (fl == FC_FLOW_NOCONVERGE) return done(FC_ENOCONVERGE);
+        if (fl < 0) continue;
+        long long m = std::min<long long>(it->second, st.demand[size_t(grow)]);
+        m = std::min<long long>(m, (long long)fl - others);
+        mu[j] = int32_t(m);
+    }
+    return done(FC_OK);
+}
+
+int tree_state_from_arrays(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
+                           int32_t n_sets, const int64_t *set_ptr, const int32_t *set_members, const int32_t *set_demand, TreeState *st) {
+    if (n_vertices < 2 || n_links < 0 || n_sets < 2 || !set_ptr || !set_demand || (n_links > 0 && (!tail || !head || !capacity))) return FC_EINVAL;
+    st->n = n_vertices;
+    for (int64_t i = 0; i < n_links; ++i) {
+        if (tail[i] < 0 || tail[i] >= n_vertices || head[i] < 0 || head[i] >= n_vertices || capacity[i] < 0) return FC_EINVAL;
+        if (tail[i] != head[i] && capacity[i] > 0) st->g[std::make_pair(tail[i], head[i])] += capacity[i];
+    }
+    st->members.assign(size_t(n_sets), std::vector<int32_t>());
+    st->inside.assign(size_t(n_sets) * size_t(n_vertices), 0);
+    st->demand.assign(size_t(n_sets), 0);
+    for (int32_t i = 0; i < n_sets; ++i) {
+        if (set_ptr[i] > set_ptr[i + 1] || set_ptr[i] < 0 || set_demand[i] < 1) return FC_EINVAL;
+        st->demand[size_t(i)] = set_demand[i];
+        for (int64_t q = set_ptr[i]; q < set_ptr[i + 1]; ++q) {
+            const int32_t r = set_members[q];
+            if (r < 0 || r >= n_vertices) return FC_EINVAL;
+            if (!st->inside[size_t(i) * size_t(n_vertices) + size_t(r)]) { st->inside[size_t(i) * size_t(n_vertices) + size_t(r)] = 1; st->members[size_t(i)].push_back(r); }
+        }
+        std::sort(st->members[size_t(i)].begin(), st->members[size_t(i)].end());
+        if (st->members[size_t(i)].empty()) return FC_EINVAL;
+    }
+    return FC_OK;
+}
+}  // namespace
+
+extern "C" int fc_tree_mu_batch(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
+                                int32_t n_sets, const int64_t *set_ptr, const int32_t *set_members, const int32_t *set_demand,
+                                int32_t grow_set, int64_t n_edges, const int32_t *edge_x, const int32_t *edge_y,
+                                int32_t *mu_out, int32_t *flows_or_null, void *hip_stream, const fc_options *options_or_null) {
+    if (n_edges < 0 || grow_set < 0 || grow_set >= n_sets || (n_edges > 0 && (!edge_x || !edge_y || !mu_out))) return FC_EINVAL;
+    try {
+        TreeState st;
+        int rc = tree_state_from_arrays(n_vertices, n_links, tail, head, capacity, n_sets, set_ptr, set_members, set_demand, &st);
+        if (rc != FC_OK) return rc;
+        std::vector<int32_t> xs(edge_x, edge_x + n_edges), ys(edge_y, edge_y + n_edges), mu;
+        SplitPool pool;
+        rc = tree_mu_launch(st, grow_set, xs, ys, mu, flows_or_null, reinterpret_cast<hipStream_t>(hip_stream), options_or_null, pool);
+        if (rc != FC_OK) return rc;
+        for (int64_t j = 0; j < n_edges; ++j) mu_out[j] = mu[size_t(j)];
+        return FC_OK;
+    } catch (const std::bad_alloc &) {
+        return FC_ENOMEM;
+    }
+}
+
+extern "C" int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
+                                  int32_t k, int64_t tree_capacity, int64_t *n_trees, int32_t *tree_root, int32_t *tree_multiplicity,
+                                  int32_t *tree_edge_x, int32_t *tree_edge_y, int64_t *n_batches_or_null,
+                                  void *hip_stream, const fc_options *options_or_null) {
+    if (n_vertices < 2 || k < 1 || !n_trees || tree_capacity < 0) return FC_EINVAL;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    try {
+        TreeState st;
+        std::vector<int64_t> ptr(size_t(n_vertices) + 1, 0);
+        std::vector<int32_t> mem(size_t(n_vertices), 0), dem(size_t(n_vertices), k);
+        for (int32_t u = 0; u < n_vertices; ++u) { ptr[size_t(u) + 1] = u + 1; mem[size_t(u)] = u; }
+        int rc = tree_state_from_arrays(n_vertices, n_links, tail, head, capacity, n_vertices, ptr.data(), mem.data(), dem.data(), &st);
+        if (rc != FC_OK) return rc;
+        const int32_t n = n_vertices;
+        std::vector<int32_t> root(size_t(n), 0);
+        for (int32_t u = 0; u < n; ++u) root[size_t(u)] = u;
+        std::vector<std::vector<std::pair<int32_t, int32_t>>> edges((size_t(n)));
+        int64_t batches = 0;
+        std::vector<int32_t> xs, ys, mu;
+        SplitPool pool;
+        for (size_t i = 0; i < st.members.size(); ++i) {               // copies are appended while this runs
+            while (int32_t(st.members[i].size()) < n) {
+                xs.clear(); ys.clear();
+                for (const auto &kv : st.g)                             // (x, y) order
+                    if (st.inside[i * size_t(n) + size_t(kv.first.first)] && !st.inside[i * size_t(n) + size_t(kv.first.second)]) { xs.push_back(kv.first.first); ys.push_back(kv.first.second); }
+                if (xs.empty()) return FC_ENOCONVERGE;
+                rc = tree_mu_launch(st, int32_t(i), xs, ys, mu, nullptr, stream, options_or_null, pool);
+                ++batches;
+                if (rc != FC_OK) return rc;
+                size_t hit = xs.size();
+                for (size_t q = 0; q < xs.size(); ++q) {
+                    if (mu[q] < 0) return FC_ENOCONVERGE;               // the packing condition does not hold for this input
+                    if (mu[q] > 0) { hit = q; break; }
+                }
+                if (hit == xs.size()) return FC_ENOCONVERGE;
+                const int32_t x = xs[hit], y = ys[hit]; const long long m = mu[hit];
+                if (m < st.demand[i]) {                                 // a copy keeps the rest of the multiplicity
+                    st.members.push_back(st.members[i]); st.demand.push_back(st.demand[i] - m); root.push_back(root[i]);
+                    edges.push_back(edges[i]);
+                    st.inside.insert(st.inside.end(), st.inside.begin() + long(i * size_t(n)), st.inside.begin() + long((i + 1) * size_t(n)));
+                    st.demand[i] = m;
+                }
+                edges[i].push_back(std::make_pair(x, y));
+                st.inside[i * size_t(n) + size_t(y)] = 1;
+                st.members[i].insert(std::upper_bound(st.members[i].begin(), st.members[i].end(), y), y);
+                auto it = st.g.find(std::make_pair(x, y));
+                it->second -= m;
+                if (it->second == 0) st.g.erase(it);
+            }
+        }
+        *n_trees = int64_t(st.members.size());
+        if (n_batches_or_null) *n_batches_or_null = batches;
+        if (*n_trees > tree_capacity) return FC_EWORKSPACE;
+        if (!tree_root || !tree_multiplicity || !tree_edge_x || !tree_edge_y) return FC_EINVAL;
+        for (size_t i = 0; i < st.members.size(); ++i) {
+            tree_root[i] = root[i]; tree_multiplicity[i] = int32_t(st.demand[i]);
+            for (size_t q = 0; q < edges[i].size(); ++q) { tree_edge_x[i * size_t(n - 1) + q] = edges[i][q].first; tree_edge_y[i * size_t(n - 1) + q] = edges[i][q].second; }
+        }
+        return FC_OK;
+    } catch (const std::bad_alloc &) {
+        return FC_ENOMEM;
+    }
+}
 
 extern "C" int fc_remove_switches(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
                                   const int32_t *capacity, const uint8_t *is_compute, int32_t k,
