@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-certificate-leg", action="store_true",
                     help="skip the side measurement with tree_certificate=1 (keeps profiler traces to one kind of launch)")
+    ap.add_argument("--tree-leg-config", type=int, default=1, choices=[1, 3],
+                    help="config whose switch-free digraph the spanning-tree side leg runs on (3 takes about 20 s)")
     ap.add_argument("--threads-per-problem", type=int, default=0)
     ap.add_argument("--lanes-per-vertex", type=int, default=0)
     ap.add_argument("--copy-probe", action="store_true",
@@ -255,6 +257,23 @@ def main():
         rs = fc.fc_remove_switches(t3.n_vertices, t3.tail, t3.head, cap3, t3.is_compute, k3)
         gamma["remove_switches"] = {"wall_ms": (time.perf_counter() - t0) * 1e3, "batches": rs["batches"],
                                     "links_out": len(rs["links"]), "table_entries": sum(len(v) for v in rs["table"].values())}
+        # spanning tree construction (Appendix E.3) on a switch-free digraph: mu for all candidate edges of a state per launch
+        if args.tree_leg_config == 3:
+            tt, Ut, kt, rt = t3, U3, k3, rs
+        else:
+            tt = w.config_topology(1)
+            gt = fc.fc_graph_upload(tt.n_vertices, tt.tail, tt.head, tt.bandwidth, tt.is_compute)
+            st_ = fc.fc_opt_throughput_search(gt, 16)
+            Ut, kt = st_["U"].numerator, st_["k"] * st_["U"].denominator
+            gt.close()
+            rt = fc.fc_remove_switches(tt.n_vertices, tt.tail, tt.head, (np.asarray(tt.bandwidth, dtype=np.int64) * Ut).astype(np.int32), tt.is_compute, kt)
+        comp_t = np.flatnonzero(np.asarray(tt.is_compute)).tolist()
+        idx_t = {v: i for i, v in enumerate(comp_t)}
+        links_t = {(idx_t[a], idx_t[b]): c for (a, b), c in rt["links"].items()}
+        t0 = time.perf_counter()
+        tr = fc.fc_construct_trees(len(comp_t), links_t, kt)
+        gamma["construct_trees"] = {"workload": f"{tt.name} after switch removal: {len(comp_t)} nodes, {len(links_t)} links, k={kt}",
+                                    "wall_ms": (time.perf_counter() - t0) * 1e3, "launches": tr["batches"], "root_sets": len(tr["trees"])}
 
     # the dominant kernel alone: HIP events recorded by the library on the launch stream around
     # the solver kernel, same inputs, same launch configuration
