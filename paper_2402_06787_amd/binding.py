@@ -263,6 +263,16 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
+def _stream_ptr_for_host_call(stream):
+    """For the entry points that take host arrays and validate them before any device call: without a GPU the
+    default stream is passed as null, so that what they reject is still reported as such (and everything else
+    fails in the library with FC_EDEVICE)."""
+    import torch
+    if stream is None and not torch.cuda.is_available():
+        return ctypes.c_void_p(0)
+    return _stream_ptr(stream)
+
+
 def fc_maxflow_batch_workspace_bytes(g: Graph, n_problems: int) -> int:
     return int(load_library().fc_maxflow_batch_workspace_bytes(g.handle, int(n_problems)))
 
@@ -494,7 +504,7 @@ def fc_remove_switches(n_vertices, tail, head, capacity, is_compute, k: int, str
         rc = lib.fc_remove_switches(int(n_vertices), int(tail.shape[0]), _host_ptr(tail), _host_ptr(head), _host_ptr(capacity),
                                     _host_ptr(is_compute), int(k), out_cap, c.byref(n_out), _host_ptr(ot), _host_ptr(oh),
                                     _host_ptr(oc), route_cap, c.byref(n_routes), _host_ptr(ru), _host_ptr(rt), _host_ptr(rw),
-                                    _host_ptr(ra), c.byref(batches), _stream_ptr(stream), _opts(options))
+                                    _host_ptr(ra), c.byref(batches), _stream_ptr_for_host_call(stream), _opts(options))
         if rc == FC_EWORKSPACE and (n_out.value > out_cap or n_routes.value > route_cap):
             out_cap, route_cap = int(n_out.value), int(n_routes.value)
             continue
@@ -532,7 +542,7 @@ def fc_tree_mu_batch(n_vertices, links, sets, demand, grow_set, edges, want_flow
     rc = load_library().fc_tree_mu_batch(int(n_vertices), int(tail.shape[0]), _host_ptr(tail), _host_ptr(head), _host_ptr(cap),
                                          len(sets), _host_ptr(ptr), _host_ptr(mem), _host_ptr(dem), int(grow_set), len(edges),
                                          _host_ptr(ex), _host_ptr(ey), _host_ptr(mu), _host_ptr(flows) if flows is not None else None,
-                                         _stream_ptr(stream), _opts(options))
+                                         _stream_ptr_for_host_call(stream), _opts(options))
     _check(rc, "fc_tree_mu_batch")
     return {"mu": mu[: len(edges)], "flows": flows[: len(edges)] if flows is not None else None}
 
@@ -550,7 +560,7 @@ def fc_construct_trees(n_vertices, links, k: int, stream=None, options=None):
         exs = np.zeros(room * max(n - 1, 1), np.int32); eys = np.zeros_like(exs)
         rc = load_library().fc_construct_trees(n, int(tail.shape[0]), _host_ptr(tail), _host_ptr(head), _host_ptr(cap), int(k), room,
                                                c.byref(n_trees), _host_ptr(root), _host_ptr(mult), _host_ptr(exs), _host_ptr(eys),
-                                               c.byref(batches), _stream_ptr(stream), _opts(options))
+                                               c.byref(batches), _stream_ptr_for_host_call(stream), _opts(options))
         if rc == FC_EWORKSPACE and n_trees.value > room:
             room = int(n_trees.value)
             continue

@@ -101,6 +101,30 @@ def test_device_calls_fail_loudly_without_device_graph():
     assert lib.fc_maxflow_batch(None, 1, None, None, None, None, None, 0, None, None, None) == fc.FC_EINVAL
 
 
+def test_host_side_validation_of_the_graph_surgery_entry_points():
+    # what these calls reject, they reject before touching a device
+    links = {(0, 1): 2, (1, 0): 2, (1, 2): 2, (2, 1): 2, (0, 2): 2, (2, 0): 2}
+    sets, demand = [{0}, {1}, {2}], [2, 2, 2]
+    for kwargs in (dict(sets=[{0}], demand=[2], grow_set=0),                 # a single root-set: nothing to weigh against
+                   dict(sets=sets, demand=demand, grow_set=3),              # no such root-set
+                   dict(sets=sets, demand=[2, 0, 2], grow_set=0),           # demands are positive
+                   dict(sets=[{0}, {1}, {7}], demand=demand, grow_set=0),   # a member that is no vertex
+                   dict(sets=[{0}, set(), {2}], demand=demand, grow_set=0)):
+        with pytest.raises(fc.FcError) as ei:
+            fc.fc_tree_mu_batch(3, links, edges=[(0, 1)], **kwargs)
+        assert ei.value.code == fc.FC_EINVAL, kwargs
+    with pytest.raises(fc.FcError) as ei:
+        fc.fc_construct_trees(1, {}, 2)
+    assert ei.value.code == fc.FC_EINVAL
+    with pytest.raises(fc.FcError) as ei:
+        fc.fc_construct_trees(3, links, 0)
+    assert ei.value.code == fc.FC_EINVAL
+    # Algorithm 2 needs an Eulerian digraph
+    with pytest.raises(fc.FcError) as ei:
+        fc.fc_remove_switches(3, [0, 1], [1, 2], [1, 1], [1, 1, 0], 1)
+    assert ei.value.code == fc.FC_EINVAL
+
+
 def _search_with_oracle(topo, cpr):
     g = fc.fc_graph_build(topo.n_vertices, topo.tail, topo.head, topo.bandwidth, topo.is_compute)
     info = fc.fc_graph_info(g)
