@@ -920,3 +920,43 @@ def test_trees_on_config1_after_switch_removal_on_the_gpu():
     got = fc.fc_construct_trees(len(comp), links, kk)
     _check_trees(len(comp), links, kk, got["trees"])
     assert got["trees"] == o.construct_trees(len(comp), links, kk)
+
+
+def test_tree_mu_on_config3_sized_states():
+    # 128 nodes and as many root-sets: the state with its root-set vertices and arcs needs most of a CU's LDS.
+    # States are made up (every root-set a breadth-first ball of random size around its root), which the formula
+    # does not mind; mu and the flows are compared with the oracle for every candidate edge of a few root-sets.
+    topo = w.config_topology(3)
+    U, k = 15, 2
+    res = _remove_on_gpu(_scaled(topo, U), k)
+    comp = [int(v) for v in topo.compute_nodes]
+    idx = {v: i for i, v in enumerate(comp)}
+    links = {(idx[a], idx[b]): c for (a, b), c in res["links"].items()}
+    n = len(comp)
+    out = {}
+    for (a, b) in sorted(links):
+        out.setdefault(a, []).append(b)
+    rng = np.random.default_rng(33)
+    sets = []
+    for u in range(n):
+        size = int(rng.integers(1, 65))
+        ball, queue = [u], [u]
+        while queue and len(ball) < size:
+            x = queue.pop(0)
+            for y in out.get(x, []):
+                if y not in ball and len(ball) < size:
+                    ball.append(y); queue.append(y)
+        sets.append(set(ball))
+    demand = [int(rng.integers(1, k + 1)) for _ in range(n)]
+    g = {e: c - int(rng.integers(0, min(c, 3))) for e, c in links.items()}
+    g = {e: c for e, c in g.items() if c > 0}
+    for i in (0, 17, 64, 127):
+        cand = [(x, y) for (x, y) in sorted(g) if x in sets[i] and y not in sets[i]][:24]
+        assert cand
+        want = [o.tree_mu(n, g, sets, demand, i, x, y) for (x, y) in cand]
+        exact = fc.fc_tree_mu_batch(n, g, sets, demand, i, cand, want_flows=True)
+        assert exact["mu"].tolist() == want, i
+        for j in (0, len(cand) - 1):
+            nv, tail, head, c = o.tree_mu_network(n, g, sets, demand, i, cand[j][0])
+            assert exact["flows"][j] == o.maxflow(nv, tail, head, c, cand[j][0], cand[j][1])
+        assert fc.fc_tree_mu_batch(n, g, sets, demand, i, cand)["mu"].tolist() == want
