@@ -26,6 +26,7 @@
 #include <mutex>
 #include <new>
 #include <map>
+#include <set>
 #include <vector>
 
 #include "fc_internal.h"
@@ -45,6 +46,10 @@
 namespace {
 
 constexpr int FC_ORDER_CHUNK = 16;     // consecutive entries of a launch order that share an XCD
+
+// One of several graphs of a launch (explicit (source, sink) problems only): where its row offsets and arc
+// records start relative to the launch's arrays, how many records it has, and the sum of its finite capacities.
+struct GraphDesc { int32_t row_off, arc_off, n_rec, pad; long long sum_bw; };
 
 struct KParams {
     int32_t n, N, m0;
@@ -84,6 +89,8 @@ struct KParams {
     // solves F(pair_src[b], pair_dst[b]) with the source's arcs saturated, the excess src_w[v] * split_k at every
     // flagged vertex, multiplier split_U, and may stop once pair_stop[b] units have arrived
     const int32_t *pair_src, *pair_dst, *pair_stop;
+    const int32_t *pair_graph;   // null, or per problem the index of its graph in `graphs` (same vertex set, different arcs)
+    const GraphDesc *graphs;
     long long sum_bw;            // sum of all link bandwidths (bounds every finite cut)
     const int32_t *src_w;        // [n] weight m_c of compute node c: arc (s, c) has capacity m_c * k (Section 5.7); null: all 1
     long long sum_w;             // sum of the weights (N while they are all 1): s emits at most sum_w * k
@@ -504,6 +511,10 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(OCC))
     if (GEN && p.pair_src) {
         j = int32_t(blockIdx.x); U = p.split_U; k = p.split_k;
         src = p.pair_src[j]; t = p.pair_dst[j];
+        if (p.pair_graph) {                              // this problem's graph among the launch's
+            const GraphDesc gd = p.graphs[p.pair_graph[j]];
+            p.row_ptr += gd.row_off; p.arc_wide += gd.arc_off; p.n_rec = gd.n_rec; p.sum_bw = gd.sum_bw;
+        }
         if (src < 0 || src >= n || t < 0 || t >= n || src == t) {
             if (tid == 0) p.flow_out[j] = FC_FLOW_INVALID;
             if (p.stats && tid < FC_NSTAT) p.stats[size_t(j) * FC_NSTAT + tid] = 0u;
@@ -2208,12 +2219,185 @@ extern "C" int fc_tree_mu_batch(int32_t n_vertices, int64_t n_links, const int32
     }
 }
 
+namespace {
+// The residual CSR of D-bar for the construction's current state, kept on the host and edited in place: an
+// accepted edge (x, y) of amount m adds one arc (s_i, y) and lowers g(x, y) by m (an arc that reaches 0 stays
+// as a record of capacity 0, which carries nothing).  Copies of it with further edits are the graphs of the
+// states a launch speculates on.
+struct TreeCsr {
+    int32_t nv = 0, m0 = 0;
+    long long sum_g = 0;                                 // finite capacities only
+    std::vector<int32_t> row_ptr;                        // [nv + 1]
+    std::vector<int4> rec;                               // {other, pair, capacity, forward | last-of-row << 1}
+
+    int build(const TreeState &st, int32_t unbounded) {
+        const int32_t n = st.n, H = int32_t(st.members.size());
+        std::vector<int32_t> at, ah, ab;
+        std::vector<uint8_t> flagged(size_t(n + H), 0);
+        sum_g = 0;
+        for (const auto &kv : st.g) { at.push_back(kv.first.first); ah.push_back(kv.first.second); ab.push_back(int32_t(kv.second)); sum_g += kv.second; }
+        for (int32_t i = 0; i < H; ++i) {
+            flagged[size_t(n + i)] = 1;
+            for (int32_t r : st.members[size_t(i)]) { at.push_back(n + i); ah.push_back(r); ab.push_back(unbounded); }
+        }
+        fc_graph *h = nullptr;
+        const int rc = fc_host_build(n + H, int64_t(at.size()), at.data(), ah.data(), ab.data(), flagged.data(), &h);
+        if (rc != FC_OK) return rc;
+        nv = h->n; m0 = int32_t(h->m0);
+        row_ptr = h->row_ptr;
+        rec.assign(size_t(2 * h->m0), make_int4(0, 0, 0, 0));
+        fill_wide_records(h, rec.data());
+        fc_graph_free(h);
+        return FC_OK;
+    }
+    // one more record at the end of row v
+    void append(int32_t v, int4 r) {
+        const int32_t pos = row_ptr[size_t(v) + 1];
+        if (pos > row_ptr[size_t(v)]) rec[size_t(pos) - 1].w &= ~2;      // the row's last record is this one from now on
+        r.w |= 2;
+        rec.insert(rec.begin() + pos, r);
+        for (size_t q = size_t(v) + 1; q < row_ptr.size(); ++q) ++row_ptr[q];
+    }
+    void add_arc(int32_t a, int32_t b, int32_t capacity) {
+        const int32_t pair = m0++;
+        append(a, make_int4(b, pair, capacity, 1));
+        append(b, make_int4(a, pair, capacity, 0));
+    }
+    void lower(int32_t a, int32_t b, long long by) {       // the arc exists
+        for (int32_t q = row_ptr[size_t(a)]; q < row_ptr[size_t(a) + 1]; ++q)
+            if ((rec[size_t(q)].w & 1) && rec[size_t(q)].x == b) rec[size_t(q)].z -= int32_t(by);
+        for (int32_t q = row_ptr[size_t(b)]; q < row_ptr[size_t(b) + 1]; ++q)
+            if (!(rec[size_t(q)].w & 1) && rec[size_t(q)].x == a) rec[size_t(q)].z -= int32_t(by);
+        sum_g -= by;
+    }
+};
+
+// device block + pinned image for launches on several graphs of one vertex set
+struct TreePool {
+    unsigned char *d = nullptr, *h = nullptr;
+    size_t cap = 0;
+    ~TreePool() { release(); }
+    TreePool() = default;
+    TreePool(const TreePool &) = delete;
+    TreePool &operator=(const TreePool &) = delete;
+    void release() { if (d) (void)hipFree(d); if (h) (void)hipHostFree(h); d = nullptr; h = nullptr; cap = 0; }
+    int ensure(size_t bytes, hipStream_t stream) {
+        if (bytes <= cap) return FC_OK;
+        if (d && hipStreamSynchronize(stream) != hipSuccess) return FC_EDEVICE;
+        release();
+        const size_t want = bytes + bytes / 2;
+        if (hipMalloc(reinterpret_cast<void **>(&d), want) != hipSuccess) { d = nullptr; return FC_EDEVICE; }
+        if (hipHostMalloc(reinterpret_cast<void **>(&h), want, hipHostMallocDefault) != hipSuccess) { h = nullptr; release(); return FC_EDEVICE; }
+        cap = want;
+        return FC_OK;
+    }
+};
+
+struct ChainState {                                       // one speculated state: its graph and candidate edges
+    TreeCsr csr;
+    std::vector<int32_t> xs, ys;
+    std::vector<long long> cap_xy;                        // g(x, y) in this state
+    int32_t guess = -1;                                   // index of the candidate expected to be accepted in full, or -1
+};
+
+// One launch for a chain of states of root-set `grow`: chain[0] is the current state, chain[j + 1] is chain[j]
+// after its guessed edge.  flows[j][q] receives F for candidate q of state j.
+int tree_chain_launch(const TreeState &st, int32_t grow, long long others, const std::vector<ChainState> &chain,
+                      std::vector<std::vector<int32_t>> &flows, hipStream_t stream, const fc_options *options_or_null, TreePool &pool) {
+    const int32_t nv = chain[0].csr.nv, H = int32_t(st.members.size()), n = st.n;
+    const size_t J = chain.size();
+    size_t E = 0, recs = 0; int32_t m0max = 0;
+    for (const ChainState &c : chain) { E += c.xs.size(); recs += c.csr.rec.size(); m0max = std::max(m0max, c.csr.m0); }
+    // layout (256-byte aligned sections)
+    size_t o = 0;
+    const size_t off_desc = o; o = align_up(o + sizeof(GraphDesc) * J, 256);
+    const size_t off_rows = o; o = align_up(o + sizeof(int32_t) * J * (size_t(nv) + 1), 256);
+    const size_t off_pairs = o; o = align_up(o + sizeof(int32_t) * 4 * E, 256);
+    const size_t off_wts = o; o = align_up(o + sizeof(int32_t) * size_t(nv), 256);
+    const size_t off_is = o; o = align_up(o + size_t(nv), 256);
+    const size_t off_ids = o; o = align_up(o + sizeof(int32_t) * size_t(H), 256);
+    const size_t off_cost = o; o = align_up(o + sizeof(uint32_t) * size_t(nv), 256);
+    const size_t off_rec = o; o = align_up(o + sizeof(int4) * std::max<size_t>(recs, 1), 256);
+    const size_t upload = o;
+    const size_t off_flow = o; o = align_up(o + sizeof(int32_t) * E, 256);
+    int rc = pool.ensure(o, stream);
+    if (rc != FC_OK) return rc;
+    GraphDesc *desc = reinterpret_cast<GraphDesc *>(pool.h + off_desc);
+    int32_t *rows = reinterpret_cast<int32_t *>(pool.h + off_rows), *pairs = reinterpret_cast<int32_t *>(pool.h + off_pairs);
+    int32_t *wts = reinterpret_cast<int32_t *>(pool.h + off_wts), *ids = reinterpret_cast<int32_t *>(pool.h + off_ids);
+    int4 *rec = reinterpret_cast<int4 *>(pool.h + off_rec);
+    std::memset(pool.h + off_wts, 0, off_rec - off_wts);
+    for (int32_t i = 0; i < H; ++i) {
+        wts[n + i] = i == grow ? 0 : int32_t(st.demand[size_t(i)]);      // the excess the root-set vertices start with
+        pool.h[off_is + size_t(n + i)] = 1; ids[i] = n + i;
+    }
+    size_t e = 0, r = 0;
+    for (size_t j = 0; j < J; ++j) {
+        const ChainState &c = chain[j];
+        desc[j].row_off = int32_t(j * (size_t(nv) + 1)); desc[j].arc_off = int32_t(r); desc[j].n_rec = std::max<int32_t>(1, int32_t(c.csr.rec.size()));
+        desc[j].pad = 0; desc[j].sum_bw = c.csr.sum_g;
+        std::memcpy(rows + j * (size_t(nv) + 1), c.csr.row_ptr.data(), sizeof(int32_t) * (size_t(nv) + 1));
+        if (!c.csr.rec.empty()) std::memcpy(rec + r, c.csr.rec.data(), sizeof(int4) * c.csr.rec.size());
+        r += c.csr.rec.size();
+        for (size_t q = 0; q < c.xs.size(); ++q, ++e) {
+            pairs[e] = c.xs[q]; pairs[E + e] = c.ys[q];
+            // a max-flow may stop once it cannot decide mu any more: at the other demands + min{g(x, y), m(R_grow)}
+            pairs[2 * E + e] = int32_t(others + std::min<long long>(c.cap_xy[q], st.demand[size_t(grow)]));
+            pairs[3 * E + e] = int32_t(j);
+        }
+    }
+    // a host-side stand-in for the graph object: the launch helpers read sizes and device pointers from it
+    fc_graph hg;
+    hg.n = nv; hg.N = H; hg.m0 = m0max; hg.sum_w = others; hg.sum_bw = chain[0].csr.sum_g;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&hg.lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&hg.n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return FC_EDEVICE;
+    hg.device = dev; hg.on_device = true;
+    hg.d_row_ptr = reinterpret_cast<int32_t *>(pool.d + off_rows);
+    hg.d_arc_wide = pool.d + off_rec;
+    hg.d_is_compute = pool.d + off_is;
+    hg.d_compute_ids = reinterpret_cast<int32_t *>(pool.d + off_ids);
+    hg.d_in_bw = reinterpret_cast<int32_t *>(pool.d + off_cost);       // unused by these launches; any [nv] array will do
+    hg.d_sink_cost = reinterpret_cast<uint32_t *>(pool.d + off_cost);
+    hg.d_src_weight = reinterpret_cast<int32_t *>(pool.d + off_wts);
+    auto done = [&](int code) {                          // the pool owns the device memory
+        hg.on_device = false;
+        hg.d_row_ptr = nullptr; hg.d_arc_wide = nullptr; hg.d_is_compute = nullptr; hg.d_compute_ids = nullptr; hg.d_in_bw = nullptr;
+        hg.d_sink_cost = nullptr; hg.d_src_weight = nullptr;
+        return code;
+    };
+    if (lds_bytes(&hg, false) > size_t(hg.lds_limit)) return done(FC_EUNSUPPORTED);
+    if (hipMemcpyAsync(pool.d, pool.h, upload, hipMemcpyHostToDevice, stream) != hipSuccess) return done(FC_EDEVICE);
+    Resolved opt;
+    rc = resolve_options(&hg, options_or_null, &opt);
+    if (rc != FC_OK) return done(rc);
+    KParams kp;
+    common_params(&hg, opt, &kp);
+    int32_t *d_pairs = reinterpret_cast<int32_t *>(pool.d + off_pairs);
+    kp.pair_src = d_pairs; kp.pair_dst = d_pairs + E; kp.pair_stop = d_pairs + 2 * E; kp.pair_graph = d_pairs + 3 * E;
+    kp.graphs = reinterpret_cast<const GraphDesc *>(pool.d + off_desc);
+    kp.split_U = 1; kp.split_k = 1;
+    kp.flow_out = reinterpret_cast<int32_t *>(pool.d + off_flow); kp.wide_available = 1;
+    const int32_t T = (options_or_null && options_or_null->threads_per_problem) ? opt.T : (nv >= 256 ? 128 : 64);
+    rc = launch_g<false, false, true>(kp, (long long)E, T, opt.G, lds_bytes(&hg, false), stream);
+    if (rc != FC_OK) return done(rc);
+    const int32_t *h_flow = reinterpret_cast<const int32_t *>(pool.h + off_flow);
+    if (hipMemcpyAsync(pool.h + off_flow, pool.d + off_flow, sizeof(int32_t) * E, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) return done(FC_EDEVICE);
+    flows.assign(J, std::vector<int32_t>());
+    e = 0;
+    for (size_t j = 0; j < J; ++j) { flows[j].assign(h_flow + e, h_flow + e + chain[j].xs.size()); e += chain[j].xs.size(); }
+    return done(FC_OK);
+}
+}  // namespace
+
 extern "C" int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
                                   int32_t k, int64_t tree_capacity, int64_t *n_trees, int32_t *tree_root, int32_t *tree_multiplicity,
                                   int32_t *tree_edge_x, int32_t *tree_edge_y, int64_t *n_batches_or_null,
                                   void *hip_stream, const fc_options *options_or_null) {
     if (n_vertices < 2 || k < 1 || !n_trees || tree_capacity < 0) return FC_EINVAL;
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    constexpr size_t FC_TREE_CHAIN = 8;                  // states a launch looks ahead
     try {
         TreeState st;
         std::vector<int64_t> ptr(size_t(n_vertices) + 1, 0);
@@ -2222,40 +2406,90 @@ extern "C" int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int
         int rc = tree_state_from_arrays(n_vertices, n_links, tail, head, capacity, n_vertices, ptr.data(), mem.data(), dem.data(), &st);
         if (rc != FC_OK) return rc;
         const int32_t n = n_vertices;
+        long long sum_g0 = 0;
+        for (const auto &kv : st.g) sum_g0 += kv.second;
+        const long long unbounded = sum_g0 + (long long)n * k + 1;      // above every finite cut of every state (capacities only shrink)
+        if (unbounded >= (1ll << 30)) return FC_EOVERFLOW;
         std::vector<int32_t> root(size_t(n), 0);
         for (int32_t u = 0; u < n; ++u) root[size_t(u)] = u;
         std::vector<std::vector<std::pair<int32_t, int32_t>>> edges((size_t(n)));
         int64_t batches = 0;
-        std::vector<int32_t> xs, ys, mu;
-        SplitPool pool;
+        TreePool pool;
+        TreeCsr cur;
+        bool cur_valid = false;
+        std::vector<ChainState> chain;
+        std::vector<std::vector<int32_t>> flows;
         for (size_t i = 0; i < st.members.size(); ++i) {               // copies are appended while this runs
+            std::set<std::pair<int32_t, int32_t>> rejected;            // edges that had mu = 0 for this root-set: guessed to stay so
             while (int32_t(st.members[i].size()) < n) {
-                xs.clear(); ys.clear();
-                for (const auto &kv : st.g)                             // (x, y) order
-                    if (st.inside[i * size_t(n) + size_t(kv.first.first)] && !st.inside[i * size_t(n) + size_t(kv.first.second)]) { xs.push_back(kv.first.first); ys.push_back(kv.first.second); }
-                if (xs.empty()) return FC_ENOCONVERGE;
-                rc = tree_mu_launch(st, int32_t(i), xs, ys, mu, nullptr, stream, options_or_null, pool);
+                if (!cur_valid) { rc = cur.build(st, int32_t(unbounded)); if (rc != FC_OK) return rc; cur_valid = true; }
+                long long others = 0;
+                for (size_t l = 0; l < st.members.size(); ++l) if (l != i) others += st.demand[l];
+                if (others < 1) return FC_EINVAL;
+                // the chain: every state's candidates in (x, y) order; its guess is the first one not rejected before,
+                // taken in full; the next state is this one after that edge
+                chain.clear();
+                std::vector<uint8_t> in_set(st.inside.begin() + long(i * size_t(n)), st.inside.begin() + long((i + 1) * size_t(n)));
+                std::map<std::pair<int32_t, int32_t>, long long> used;  // capacity the chain's guesses have taken
+                int32_t inside_count = int32_t(st.members[i].size());
+                for (size_t j = 0; j < FC_TREE_CHAIN && inside_count < n; ++j) {
+                    chain.emplace_back();
+                    ChainState &c = chain.back();
+                    c.csr = j == 0 ? cur : chain[j - 1].csr;
+                    if (j > 0) {
+                        const ChainState &pc = chain[j - 1];
+                        const int32_t gx = pc.xs[size_t(pc.guess)], gy = pc.ys[size_t(pc.guess)];
+                        c.csr.add_arc(n + int32_t(i), gy, int32_t(unbounded));
+                        c.csr.lower(gx, gy, st.demand[i]);
+                    }
+                    for (const auto &kv : st.g) {
+                        const auto u_it = used.find(kv.first);
+                        const long long left = kv.second - (u_it == used.end() ? 0 : u_it->second);
+                        if (left > 0 && in_set[size_t(kv.first.first)] && !in_set[size_t(kv.first.second)]) { c.xs.push_back(kv.first.first); c.ys.push_back(kv.first.second); c.cap_xy.push_back(left); }
+                    }
+                    if (c.xs.empty()) { if (j == 0) return FC_ENOCONVERGE; chain.pop_back(); break; }
+                    for (size_t q = 0; q < c.xs.size(); ++q)
+                        if (!rejected.count(std::make_pair(c.xs[q], c.ys[q]))) { c.guess = int32_t(q); break; }
+                    if (c.guess < 0 || c.cap_xy[size_t(c.guess)] < st.demand[i]) { c.guess = -1; break; }   // no guess, or it would need a copy
+                    used[std::make_pair(c.xs[size_t(c.guess)], c.ys[size_t(c.guess)])] += st.demand[i];
+                    in_set[size_t(c.ys[size_t(c.guess)])] = 1; ++inside_count;
+                }
+                rc = tree_chain_launch(st, int32_t(i), others, chain, flows, stream, options_or_null, pool);
                 ++batches;
                 if (rc != FC_OK) return rc;
-                size_t hit = xs.size();
-                for (size_t q = 0; q < xs.size(); ++q) {
-                    if (mu[q] < 0) return FC_ENOCONVERGE;               // the packing condition does not hold for this input
-                    if (mu[q] > 0) { hit = q; break; }
+                // walk the chain: a state's result counts only while every guess before it was right
+                for (size_t j = 0; j < chain.size() && int32_t(st.members[i].size()) < n; ++j) {
+                    const ChainState &c = chain[j];
+                    size_t hit = c.xs.size(); long long m = 0;
+                    for (size_t q = 0; q < c.xs.size(); ++q) {
+                        const int32_t fl = flows[j][q];
+                        if (fl == FC_FLOW_NOCONVERGE || fl < 0) return FC_ENOCONVERGE;
+                        const long long mu = std::min<long long>(std::min<long long>(c.cap_xy[q], st.demand[i]), (long long)fl - others);
+                        if (mu < 0) return FC_ENOCONVERGE;              // the packing condition does not hold for this input
+                        if (mu > 0) { hit = q; m = mu; break; }
+                        rejected.insert(std::make_pair(c.xs[q], c.ys[q]));
+                    }
+                    if (hit == c.xs.size()) return FC_ENOCONVERGE;
+                    const int32_t x = c.xs[hit], y = c.ys[hit];
+                    const bool as_guessed = int32_t(hit) == c.guess && m == st.demand[i] && j + 1 < chain.size();
+                    if (m < st.demand[i]) {                             // a copy keeps the rest of the multiplicity
+                        st.members.push_back(st.members[i]); st.demand.push_back(st.demand[i] - m); root.push_back(root[i]);
+                        edges.push_back(edges[i]);
+                        st.inside.insert(st.inside.end(), st.inside.begin() + long(i * size_t(n)), st.inside.begin() + long((i + 1) * size_t(n)));
+                        st.demand[i] = m;
+                        cur_valid = false;                              // one more root-set vertex: the graph is built anew
+                    }
+                    edges[i].push_back(std::make_pair(x, y));
+                    st.inside[i * size_t(n) + size_t(y)] = 1;
+                    st.members[i].insert(std::upper_bound(st.members[i].begin(), st.members[i].end(), y), y);
+                    auto it = st.g.find(std::make_pair(x, y));
+                    it->second -= m;
+                    if (it->second == 0) st.g.erase(it);
+                    if (as_guessed) continue;                           // the next state of the chain is the true one
+                    // the chain ends here: the current graph is this state's plus the edge that was really taken
+                    if (cur_valid) { cur = c.csr; cur.add_arc(n + int32_t(i), y, int32_t(unbounded)); cur.lower(x, y, m); }
+                    break;
                 }
-                if (hit == xs.size()) return FC_ENOCONVERGE;
-                const int32_t x = xs[hit], y = ys[hit]; const long long m = mu[hit];
-                if (m < st.demand[i]) {                                 // a copy keeps the rest of the multiplicity
-                    st.members.push_back(st.members[i]); st.demand.push_back(st.demand[i] - m); root.push_back(root[i]);
-                    edges.push_back(edges[i]);
-                    st.inside.insert(st.inside.end(), st.inside.begin() + long(i * size_t(n)), st.inside.begin() + long((i + 1) * size_t(n)));
-                    st.demand[i] = m;
-                }
-                edges[i].push_back(std::make_pair(x, y));
-                st.inside[i * size_t(n) + size_t(y)] = 1;
-                st.members[i].insert(std::upper_bound(st.members[i].begin(), st.members[i].end(), y), y);
-                auto it = st.g.find(std::make_pair(x, y));
-                it->second -= m;
-                if (it->second == 0) st.g.erase(it);
             }
         }
         *n_trees = int64_t(st.members.size());
