@@ -336,7 +336,9 @@ const char *fc_strerror(int code);
  * root-set {u} with demand k; the first root-set (in creation order) that does not span yet is grown by the
  * first link leaving it, in (x, y) order, whose mu is positive; when mu is below its demand a copy keeps
  * the rest.  All candidate links of a state are evaluated in one launch (the ones before the first positive
- * mu are zero on this very state, so the result is that of trying them one by one).  Output: n_trees
+ * mu are zero on this very state, so the result is that of trying them one by one), and the launch looks
+ * ahead: it also evaluates the states that follow if, each time, the first link not rejected before is
+ * accepted in full; those results are used as far as the guesses turn out right.  Output: n_trees
  * root-sets; tree i has root tree_root[i], multiplicity tree_multiplicity[i] (they add up to k per root)
  * and the n_vertices - 1 edges tree_edge_x/y[i * (n_vertices - 1) ..] in the order they were added.
  * Needs min over v of F(s, v) >= N k to hold in D* (what switch removal preserves); FC_ENOCONVERGE if no
