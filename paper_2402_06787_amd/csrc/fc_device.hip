@@ -2064,12 +2064,10 @@ struct SplitPool {
 // Spanning tree construction (Appendix E.3).  mu for an edge (x, y) that leaves the root-set being
 // grown is  min{ g(x, y), m(R_grow), F(x, y; D-bar) - sum of the other demands },  where D-bar adds to
 // the digraph one vertex s_i per other root-set with an arc (x, s_i) of capacity m(R_i) and unbounded
-// arcs from s_i to the members of R_i.  Here every root-set gets its vertex s_i once (vertices
-// n .. n + n_sets - 1, unbounded arcs to its members); the arcs (x, s_i) never exist as arcs: they are
-// saturated by definition of the preflow, so s_i simply starts with the excess m(R_i) -- the same
-// device that gives the compute nodes their k units in the auxiliary network -- and the grown set's
-// s_i starts with nothing.  All candidate edges of one state form one launch of explicit
-// (source, sink) problems on that shared graph.
+// arcs from s_i to the members of R_i.  The arcs (x, s_i) never exist as arcs here: they are saturated
+// by definition of the preflow, so s_i simply starts with the excess m(R_i) -- the same device that
+// gives the compute nodes their k units in the auxiliary network.  Most s_i are not needed either (see
+// TreeCsr::build).  All candidate edges of a state are explicit (source, sink) problems of one launch.
 namespace {
 struct TreeState {
     int32_t n = 0;                                       // vertices of D*
@@ -2078,100 +2076,6 @@ struct TreeState {
     std::vector<uint8_t> inside;                         // [set][vertex] membership
     std::vector<long long> demand;
 };
-
-// mu for the candidate edges (xs[j], ys[j]) of root-set `grow`; flows_or_null receives F(x, y; D-bar).
-// The graph of the state goes to the device in one transfer through `pool`, as in the switch-removal loop.
-int tree_mu_launch(const TreeState &st, int32_t grow, const std::vector<int32_t> &xs, const std::vector<int32_t> &ys,
-                   std::vector<int32_t> &mu, int32_t *flows_or_null, hipStream_t stream, const fc_options *options_or_null,
-                   SplitPool &pool) {
-    const int32_t n = st.n, H = int32_t(st.members.size());
-    const size_t E = xs.size();
-    mu.assign(E, FC_GAMMA_INVALID);
-    if (E == 0) return FC_OK;
-    long long sum_g = 0, others = 0;
-    for (const auto &kv : st.g) sum_g += kv.second;
-    for (int32_t i = 0; i < H; ++i) if (i != grow) others += st.demand[size_t(i)];
-    const long long unbounded = sum_g + others + 1;      // more than any finite cut of D-bar
-    if (unbounded >= (1ll << 30) || others < 1) return others < 1 ? FC_EINVAL : FC_EOVERFLOW;
-    std::vector<int32_t> at, ah, ab;
-    std::vector<uint8_t> flagged(size_t(n + H), 0);
-    for (const auto &kv : st.g) { at.push_back(kv.first.first); ah.push_back(kv.first.second); ab.push_back(int32_t(kv.second)); }
-    for (int32_t i = 0; i < H; ++i) {
-        flagged[size_t(n + i)] = 1;
-        for (int32_t r : st.members[size_t(i)]) { at.push_back(n + i); ah.push_back(r); ab.push_back(int32_t(unbounded)); }
-    }
-    fc_graph *h = nullptr;
-    int rc = fc_host_build(n + H, int64_t(at.size()), at.data(), ah.data(), ab.data(), flagged.data(), &h);
-    if (rc != FC_OK) return rc;
-    int dev = -1, lds_limit = 0, n_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) { fc_graph_free(h); return FC_EDEVICE; }
-    h->device = dev; h->lds_limit = lds_limit; h->n_cu = n_cu;
-    auto done = [&](int code) {                          // the pool owns the device memory: detach it before the host graph goes
-        h->on_device = false;
-        h->d_row_ptr = nullptr; h->d_in_bw = nullptr; h->d_arc_wide = nullptr; h->d_is_compute = nullptr; h->d_compute_ids = nullptr;
-        h->d_sink_cost = nullptr; h->d_src_weight = nullptr;
-        fc_graph_free(h);
-        return code;
-    };
-    if (lds_bytes(h, false) > size_t(lds_limit)) return done(FC_EUNSUPPORTED);
-    const size_t M = size_t(2 * h->m0);
-    rc = pool.ensure(h, M, E, stream, false);
-    if (rc != FC_OK) return done(rc);
-    std::memcpy(pool.h_blob + pool.off_row, h->row_ptr.data(), sizeof(int32_t) * (size_t(h->n) + 1));
-    std::memcpy(pool.h_blob + pool.off_inbw, h->in_bw.data(), sizeof(int32_t) * size_t(h->n));
-    int32_t *hw = reinterpret_cast<int32_t *>(pool.h_blob + pool.off_wts);
-    std::memset(hw, 0, sizeof(int32_t) * size_t(h->n));
-    for (int32_t i = 0; i < H; ++i) hw[n + i] = i == grow ? 0 : int32_t(st.demand[size_t(i)]);   // the excess the root-set vertices start with
-    // a max-flow may stop once it cannot decide mu any more: at the other demands + min{g(x, y), m(R_grow)}
-    int32_t *hp = reinterpret_cast<int32_t *>(pool.h_blob + pool.off_pairs);
-    for (size_t j = 0; j < E; ++j) {
-        hp[j] = xs[j]; hp[pool.pair_cap + j] = ys[j];
-        const auto it = st.g.find(std::make_pair(xs[j], ys[j]));
-        const long long cap_xy = it == st.g.end() ? 0 : it->second;
-        hp[2 * pool.pair_cap + j] = flows_or_null ? -1 : int32_t(others + std::min<long long>(cap_xy, st.demand[size_t(grow)]));
-    }
-    fill_wide_records(h, reinterpret_cast<int4 *>(pool.h_blob + pool.off_wide));
-    h->on_device = true;
-    h->d_row_ptr = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_row);
-    h->d_in_bw = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_inbw);
-    h->d_src_weight = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_wts);
-    h->d_arc_wide = pool.d_blob + pool.off_wide;
-    h->d_is_compute = pool.d_blob + pool.off_is;
-    h->d_compute_ids = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_ids);
-    h->d_sink_cost = reinterpret_cast<uint32_t *>(pool.d_blob + pool.off_cost);
-    h->sum_bw = sum_g;                                   // the finite arcs only: "unbounded" is measured against them
-    h->sum_w = others;
-    int32_t *d_pairs = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_pairs);
-    int32_t *d_flow = reinterpret_cast<int32_t *>(pool.d_blob + pool.off_gamma);
-    int32_t *h_flow = reinterpret_cast<int32_t *>(pool.h_blob + pool.off_gamma);
-    if (hipMemcpyAsync(pool.d_blob, pool.h_blob, pool.off_wide + sizeof(int4) * M, hipMemcpyHostToDevice, stream) != hipSuccess) return done(FC_EDEVICE);
-    Resolved opt;
-    rc = resolve_options(h, options_or_null, &opt);
-    if (rc != FC_OK) return done(rc);
-    KParams kp;
-    common_params(h, opt, &kp);
-    kp.pair_src = d_pairs; kp.pair_dst = d_pairs + pool.pair_cap; kp.pair_stop = d_pairs + 2 * pool.pair_cap;
-    kp.split_U = 1; kp.split_k = 1;
-    kp.flow_out = d_flow; kp.wide_available = 1;
-    const int32_t T = (options_or_null && options_or_null->threads_per_problem) ? opt.T : (h->n >= 256 ? 128 : 64);
-    rc = launch_g<false, false, true>(kp, (long long)E, T, opt.G, lds_bytes(h, false), stream);
-    if (rc != FC_OK) return done(rc);
-    if (hipMemcpyAsync(h_flow, d_flow, sizeof(int32_t) * E, hipMemcpyDeviceToHost, stream) != hipSuccess ||
-        hipStreamSynchronize(stream) != hipSuccess) return done(FC_EDEVICE);
-    for (size_t j = 0; j < E; ++j) {
-        const int32_t x = xs[j], y = ys[j], fl = h_flow[j];
-        if (flows_or_null) flows_or_null[j] = fl;
-        const auto it = (x >= 0 && x < n && y >= 0 && y < n) ? st.g.find(std::make_pair(x, y)) : st.g.end();
-        if (it == st.g.end() || !st.inside[size_t(grow) * size_t(n) + size_t(x)] || st.inside[size_t(grow) * size_t(n) + size_t(y)]) continue;
-        if (fl == FC_FLOW_NOCONVERGE) return done(FC_ENOCONVERGE);
-        if (fl < 0) continue;
-        long long m = std::min<long long>(it->second, st.demand[size_t(grow)]);
-        m = std::min<long long>(m, (long long)fl - others);
-        mu[j] = int32_t(m);
-    }
-    return done(FC_OK);
-}
 
 int tree_state_from_arrays(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
                            int32_t n_sets, const int64_t *set_ptr, const int32_t *set_members, const int32_t *set_demand, TreeState *st) {
@@ -2199,49 +2103,45 @@ int tree_state_from_arrays(int32_t n_vertices, int64_t n_links, const int32_t *t
 }
 }  // namespace
 
-extern "C" int fc_tree_mu_batch(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
-                                int32_t n_sets, const int64_t *set_ptr, const int32_t *set_members, const int32_t *set_demand,
-                                int32_t grow_set, int64_t n_edges, const int32_t *edge_x, const int32_t *edge_y,
-                                int32_t *mu_out, int32_t *flows_or_null, void *hip_stream, const fc_options *options_or_null) {
-    if (n_edges < 0 || grow_set < 0 || grow_set >= n_sets || (n_edges > 0 && (!edge_x || !edge_y || !mu_out))) return FC_EINVAL;
-    try {
-        TreeState st;
-        int rc = tree_state_from_arrays(n_vertices, n_links, tail, head, capacity, n_sets, set_ptr, set_members, set_demand, &st);
-        if (rc != FC_OK) return rc;
-        std::vector<int32_t> xs(edge_x, edge_x + n_edges), ys(edge_y, edge_y + n_edges), mu;
-        SplitPool pool;
-        rc = tree_mu_launch(st, grow_set, xs, ys, mu, flows_or_null, reinterpret_cast<hipStream_t>(hip_stream), options_or_null, pool);
-        if (rc != FC_OK) return rc;
-        for (int64_t j = 0; j < n_edges; ++j) mu_out[j] = mu[size_t(j)];
-        return FC_OK;
-    } catch (const std::bad_alloc &) {
-        return FC_ENOMEM;
-    }
-}
-
 namespace {
 // The residual CSR of D-bar for the construction's current state, kept on the host and edited in place: an
-// accepted edge (x, y) of amount m adds one arc (s_i, y) and lowers g(x, y) by m (an arc that reaches 0 stays
-// as a record of capacity 0, which carries nothing).  Copies of it with further edits are the graphs of the
-// states a launch speculates on.
+// accepted edge (x, y) of amount m lowers g(x, y) by m (an arc that reaches 0 stays as a record of capacity 0,
+// which carries nothing); the grown root-set itself has no vertex in the network.  Copies with further edits
+// are the graphs of the states a launch speculates on.
 struct TreeCsr {
     int32_t nv = 0, m0 = 0;
     long long sum_g = 0;                                 // finite capacities only
+    long long others = 0;                                // demands of the root-sets that are in the graph: F is measured against them
+    long long spanning = 0;                              // demands of the root-sets left out because they span already
     std::vector<int32_t> row_ptr;                        // [nv + 1]
     std::vector<int4> rec;                               // {other, pair, capacity, forward | last-of-row << 1}
+    std::vector<int32_t> weight;                         // [nv] excess a vertex starts with
 
-    int build(const TreeState &st, int32_t unbounded) {
+    // D-bar for growing root-set `grow`, without the vertices it does not need.  A root-set that spans already has
+    // an unbounded arc into y: its demand always arrives, so it is left out and its demand is not counted.  The
+    // vertex s_l of a one-member root-set {u} only hands its m to u: u starts with that excess instead.  What
+    // remains are the partly grown copies, each with its vertex and unbounded arcs to its members.
+    int build(const TreeState &st, int32_t grow, int32_t unbounded) {
         const int32_t n = st.n, H = int32_t(st.members.size());
         std::vector<int32_t> at, ah, ab;
-        std::vector<uint8_t> flagged(size_t(n + H), 0);
-        sum_g = 0;
+        sum_g = 0; others = 0; spanning = 0;
         for (const auto &kv : st.g) { at.push_back(kv.first.first); ah.push_back(kv.first.second); ab.push_back(int32_t(kv.second)); sum_g += kv.second; }
-        for (int32_t i = 0; i < H; ++i) {
-            flagged[size_t(n + i)] = 1;
-            for (int32_t r : st.members[size_t(i)]) { at.push_back(n + i); ah.push_back(r); ab.push_back(unbounded); }
+        std::vector<int32_t> wts(size_t(n), 0);
+        int32_t extra = 0;
+        for (int32_t l = 0; l < H; ++l) {
+            if (l == grow) continue;
+            const auto &R = st.members[size_t(l)];
+            if (int32_t(R.size()) == n) { spanning += st.demand[size_t(l)]; continue; }
+            others += st.demand[size_t(l)];
+            if (R.size() == 1) { wts[size_t(R[0])] += int32_t(st.demand[size_t(l)]); continue; }
+            for (int32_t r : R) { at.push_back(n + extra); ah.push_back(r); ab.push_back(unbounded); }
+            wts.push_back(int32_t(st.demand[size_t(l)]));
+            ++extra;
         }
+        weight = wts;
+        std::vector<uint8_t> flagged(size_t(n + extra), 1);    // every vertex may start with excess (most weights are 0)
         fc_graph *h = nullptr;
-        const int rc = fc_host_build(n + H, int64_t(at.size()), at.data(), ah.data(), ab.data(), flagged.data(), &h);
+        const int rc = fc_host_build(n + extra, int64_t(at.size()), at.data(), ah.data(), ab.data(), flagged.data(), &h);
         if (rc != FC_OK) return rc;
         nv = h->n; m0 = int32_t(h->m0);
         row_ptr = h->row_ptr;
@@ -2249,19 +2149,6 @@ struct TreeCsr {
         fill_wide_records(h, rec.data());
         fc_graph_free(h);
         return FC_OK;
-    }
-    // one more record at the end of row v
-    void append(int32_t v, int4 r) {
-        const int32_t pos = row_ptr[size_t(v) + 1];
-        if (pos > row_ptr[size_t(v)]) rec[size_t(pos) - 1].w &= ~2;      // the row's last record is this one from now on
-        r.w |= 2;
-        rec.insert(rec.begin() + pos, r);
-        for (size_t q = size_t(v) + 1; q < row_ptr.size(); ++q) ++row_ptr[q];
-    }
-    void add_arc(int32_t a, int32_t b, int32_t capacity) {
-        const int32_t pair = m0++;
-        append(a, make_int4(b, pair, capacity, 1));
-        append(b, make_int4(a, pair, capacity, 0));
     }
     void lower(int32_t a, int32_t b, long long by) {       // the arc exists
         for (int32_t q = row_ptr[size_t(a)]; q < row_ptr[size_t(a) + 1]; ++q)
@@ -2302,9 +2189,10 @@ struct ChainState {                                       // one speculated stat
 
 // One launch for a chain of states of root-set `grow`: chain[0] is the current state, chain[j + 1] is chain[j]
 // after its guessed edge.  flows[j][q] receives F for candidate q of state j.
-int tree_chain_launch(const TreeState &st, int32_t grow, long long others, const std::vector<ChainState> &chain,
+int tree_chain_launch(const TreeState &st, int32_t grow, const std::vector<ChainState> &chain, bool exact_flows,
                       std::vector<std::vector<int32_t>> &flows, hipStream_t stream, const fc_options *options_or_null, TreePool &pool) {
-    const int32_t nv = chain[0].csr.nv, H = int32_t(st.members.size()), n = st.n;
+    const int32_t nv = chain[0].csr.nv, H = nv;          // every vertex is flagged as one that may start with excess
+    const long long others = chain[0].csr.others;
     const size_t J = chain.size();
     size_t E = 0, recs = 0; int32_t m0max = 0;
     for (const ChainState &c : chain) { E += c.xs.size(); recs += c.csr.rec.size(); m0max = std::max(m0max, c.csr.m0); }
@@ -2327,10 +2215,7 @@ int tree_chain_launch(const TreeState &st, int32_t grow, long long others, const
     int32_t *wts = reinterpret_cast<int32_t *>(pool.h + off_wts), *ids = reinterpret_cast<int32_t *>(pool.h + off_ids);
     int4 *rec = reinterpret_cast<int4 *>(pool.h + off_rec);
     std::memset(pool.h + off_wts, 0, off_rec - off_wts);
-    for (int32_t i = 0; i < H; ++i) {
-        wts[n + i] = i == grow ? 0 : int32_t(st.demand[size_t(i)]);      // the excess the root-set vertices start with
-        pool.h[off_is + size_t(n + i)] = 1; ids[i] = n + i;
-    }
+    for (int32_t v = 0; v < nv; ++v) { wts[v] = chain[0].csr.weight[size_t(v)]; pool.h[off_is + size_t(v)] = 1; ids[v] = v; }
     size_t e = 0, r = 0;
     for (size_t j = 0; j < J; ++j) {
         const ChainState &c = chain[j];
@@ -2342,7 +2227,7 @@ int tree_chain_launch(const TreeState &st, int32_t grow, long long others, const
         for (size_t q = 0; q < c.xs.size(); ++q, ++e) {
             pairs[e] = c.xs[q]; pairs[E + e] = c.ys[q];
             // a max-flow may stop once it cannot decide mu any more: at the other demands + min{g(x, y), m(R_grow)}
-            pairs[2 * E + e] = int32_t(others + std::min<long long>(c.cap_xy[q], st.demand[size_t(grow)]));
+            pairs[2 * E + e] = exact_flows ? -1 : int32_t(others + std::min<long long>(c.cap_xy[q], st.demand[size_t(grow)]));
             pairs[3 * E + e] = int32_t(j);
         }
     }
@@ -2391,6 +2276,59 @@ int tree_chain_launch(const TreeState &st, int32_t grow, long long others, const
 }
 }  // namespace
 
+extern "C" int fc_tree_mu_batch(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
+                                int32_t n_sets, const int64_t *set_ptr, const int32_t *set_members, const int32_t *set_demand,
+                                int32_t grow_set, int64_t n_edges, const int32_t *edge_x, const int32_t *edge_y,
+                                int32_t *mu_out, int32_t *flows_or_null, void *hip_stream, const fc_options *options_or_null) {
+    if (n_edges < 0 || grow_set < 0 || grow_set >= n_sets || (n_edges > 0 && (!edge_x || !edge_y || !mu_out))) return FC_EINVAL;
+    try {
+        TreeState st;
+        int rc = tree_state_from_arrays(n_vertices, n_links, tail, head, capacity, n_sets, set_ptr, set_members, set_demand, &st);
+        if (rc != FC_OK) return rc;
+        if (n_edges == 0) return FC_OK;
+        const int32_t n = st.n;
+        long long sum_g = 0, all = 0;
+        for (const auto &kv : st.g) sum_g += kv.second;
+        for (long long m : st.demand) all += m;
+        const long long unbounded = sum_g + all + 1;
+        if (unbounded >= (1ll << 30)) return FC_EOVERFLOW;
+        std::vector<ChainState> chain(1);
+        ChainState &c = chain[0];
+        rc = c.csr.build(st, grow_set, int32_t(unbounded));
+        if (rc != FC_OK) return rc;
+        // entries that are no link from inside the root-set to outside it are not sent at all
+        std::vector<int64_t> slot(size_t(n_edges), -1);
+        for (int64_t j = 0; j < n_edges; ++j) {
+            const int32_t x = edge_x[j], y = edge_y[j];
+            mu_out[j] = FC_GAMMA_INVALID;
+            if (flows_or_null) flows_or_null[j] = FC_FLOW_INVALID;
+            if (x < 0 || x >= n || y < 0 || y >= n) continue;
+            const auto it = st.g.find(std::make_pair(x, y));
+            if (it == st.g.end() || !st.inside[size_t(grow_set) * size_t(n) + size_t(x)] || st.inside[size_t(grow_set) * size_t(n) + size_t(y)]) continue;
+            slot[size_t(j)] = int64_t(c.xs.size());
+            c.xs.push_back(x); c.ys.push_back(y); c.cap_xy.push_back(it->second);
+        }
+        if (c.xs.empty()) return FC_OK;
+        TreePool pool;
+        std::vector<std::vector<int32_t>> flows;
+        rc = tree_chain_launch(st, grow_set, chain, flows_or_null != nullptr, flows, reinterpret_cast<hipStream_t>(hip_stream), options_or_null, pool);
+        if (rc != FC_OK) return rc;
+        for (int64_t j = 0; j < n_edges; ++j) {
+            if (slot[size_t(j)] < 0) continue;
+            const size_t q = size_t(slot[size_t(j)]);
+            const int32_t fl = flows[0][q];
+            if (fl == FC_FLOW_NOCONVERGE) return FC_ENOCONVERGE;
+            if (fl < 0) continue;
+            // the root-sets that span already were left out of the network: their demands always arrive
+            if (flows_or_null) flows_or_null[j] = int32_t(std::min<long long>((long long)fl + c.csr.spanning, (1ll << 31) - 1));
+            mu_out[j] = int32_t(std::min<long long>(std::min<long long>(c.cap_xy[q], st.demand[size_t(grow_set)]), (long long)fl - c.csr.others));
+        }
+        return FC_OK;
+    } catch (const std::bad_alloc &) {
+        return FC_ENOMEM;
+    }
+}
+
 extern "C" int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int32_t *tail, const int32_t *head, const int32_t *capacity,
                                   int32_t k, int64_t tree_capacity, int64_t *n_trees, int32_t *tree_root, int32_t *tree_multiplicity,
                                   int32_t *tree_edge_x, int32_t *tree_edge_y, int64_t *n_batches_or_null,
@@ -2421,11 +2359,10 @@ extern "C" int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int
         std::vector<std::vector<int32_t>> flows;
         for (size_t i = 0; i < st.members.size(); ++i) {               // copies are appended while this runs
             std::set<std::pair<int32_t, int32_t>> rejected;            // edges that had mu = 0 for this root-set: guessed to stay so
+            cur_valid = false;                                          // another root-set grows: another network
             while (int32_t(st.members[i].size()) < n) {
-                if (!cur_valid) { rc = cur.build(st, int32_t(unbounded)); if (rc != FC_OK) return rc; cur_valid = true; }
-                long long others = 0;
-                for (size_t l = 0; l < st.members.size(); ++l) if (l != i) others += st.demand[l];
-                if (others < 1) return FC_EINVAL;
+                if (!cur_valid) { rc = cur.build(st, int32_t(i), int32_t(unbounded)); if (rc != FC_OK) return rc; cur_valid = true; }
+                const long long others = cur.others;
                 // the chain: every state's candidates in (x, y) order; its guess is the first one not rejected before,
                 // taken in full; the next state is this one after that edge
                 chain.clear();
@@ -2436,11 +2373,9 @@ extern "C" int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int
                     chain.emplace_back();
                     ChainState &c = chain.back();
                     c.csr = j == 0 ? cur : chain[j - 1].csr;
-                    if (j > 0) {
+                    if (j > 0) {                                        // the grown set has no vertex in the network: only g changes
                         const ChainState &pc = chain[j - 1];
-                        const int32_t gx = pc.xs[size_t(pc.guess)], gy = pc.ys[size_t(pc.guess)];
-                        c.csr.add_arc(n + int32_t(i), gy, int32_t(unbounded));
-                        c.csr.lower(gx, gy, st.demand[i]);
+                        c.csr.lower(pc.xs[size_t(pc.guess)], pc.ys[size_t(pc.guess)], st.demand[i]);
                     }
                     for (const auto &kv : st.g) {
                         const auto u_it = used.find(kv.first);
@@ -2454,7 +2389,7 @@ extern "C" int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int
                     used[std::make_pair(c.xs[size_t(c.guess)], c.ys[size_t(c.guess)])] += st.demand[i];
                     in_set[size_t(c.ys[size_t(c.guess)])] = 1; ++inside_count;
                 }
-                rc = tree_chain_launch(st, int32_t(i), others, chain, flows, stream, options_or_null, pool);
+                rc = tree_chain_launch(st, int32_t(i), chain, false, flows, stream, options_or_null, pool);
                 ++batches;
                 if (rc != FC_OK) return rc;
                 // walk the chain: a state's result counts only while every guess before it was right
@@ -2487,7 +2422,7 @@ extern "C" int fc_construct_trees(int32_t n_vertices, int64_t n_links, const int
                     if (it->second == 0) st.g.erase(it);
                     if (as_guessed) continue;                           // the next state of the chain is the true one
                     // the chain ends here: the current graph is this state's plus the edge that was really taken
-                    if (cur_valid) { cur = c.csr; cur.add_arc(n + int32_t(i), y, int32_t(unbounded)); cur.lower(x, y, m); }
+                    if (cur_valid) { cur = c.csr; cur.lower(x, y, m); }
                     break;
                 }
             }
