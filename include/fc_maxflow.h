@@ -328,9 +328,9 @@ const char *fc_strerror(int code);
  * set_members: the root-sets as lists; set_demand [n_sets] >= 1; grow_set: the one being grown.
  * mu_out [n_edges]: mu, or FC_MU_INVALID for an entry that is no link from inside R_grow to outside it.
  * flows_or_null [n_edges]: F(x, y; D-bar); without it a max-flow may stop as soon as it cannot decide mu.
- * The graph with its n_sets extra vertices and one arc per (set, member) must fit the 32-bit on-chip state
- * (FC_EUNSUPPORTED otherwise: a few hundred vertices), and the sum of all capacities and demands must stay
- * below 2^30 (FC_EOVERFLOW).  Other errors: FC_EINVAL, FC_EDEVICE, FC_ENOMEM, FC_ENOCONVERGE.
+ * The digraph, plus one vertex and its member arcs per root-set that has more than one member but does not
+ * span yet (other than grow_set), must fit the 32-bit on-chip state (FC_EUNSUPPORTED otherwise), and the sum
+ * of all capacities and demands must stay below 2^30 (FC_EOVERFLOW).  Other errors: FC_EINVAL, FC_EDEVICE, FC_ENOMEM, FC_ENOCONVERGE.
  *
  * fc_construct_trees runs the whole construction around such launches: every vertex u starts as the
  * root-set {u} with demand k; the first root-set (in creation order) that does not span yet is grown by the

@@ -960,3 +960,33 @@ def test_tree_mu_on_config3_sized_states():
             nv, tail, head, c = o.tree_mu_network(n, g, sets, demand, i, cand[j][0])
             assert exact["flows"][j] == o.maxflow(nv, tail, head, c, cand[j][0], cand[j][1])
         assert fc.fc_tree_mu_batch(n, g, sets, demand, i, cand)["mu"].tolist() == want
+
+
+def test_trees_on_config3_after_switch_removal_are_valid():
+    # 128 roots x 127 edges: too many max-flows for the oracle's loop, so the promises of the construction are
+    # checked instead -- spanning trees, k per root, no link used beyond its capacity -- and, as a spot check,
+    # the first root's tree against the oracle's construction restricted to that root-set
+    topo = w.config_topology(3)
+    U, k = 15, 2
+    res = _remove_on_gpu(_scaled(topo, U), k)
+    comp = [int(v) for v in topo.compute_nodes]
+    idx = {v: i for i, v in enumerate(comp)}
+    links = {(idx[a], idx[b]): c for (a, b), c in res["links"].items()}
+    got = fc.fc_construct_trees(len(comp), links, k)
+    use = _check_trees(len(comp), links, k, got["trees"])
+    # config 3 is symmetric and tight: every unit of every link is used by some tree
+    assert sum(use.values()) == len(comp) * k * (len(comp) - 1)
+    assert got["batches"] < len(comp) * (len(comp) - 1)                # the look-ahead saves launches
+    # first steps of root 0 by the oracle: same edges in the same order
+    n = len(comp)
+    g = dict(links); sets = [{u} for u in range(n)]; demand = [k] * n
+    for step in range(6):
+        x, y = got["trees"][0][2][step]
+        cand = [(a, b) for (a, b) in sorted(g) if a in sets[0] and b not in sets[0]]
+        first = next((a, b) for (a, b) in cand if o.tree_mu(n, g, sets, demand, 0, a, b) > 0)
+        assert first == (x, y), step
+        mu = o.tree_mu(n, g, sets, demand, 0, x, y)
+        assert mu == got["trees"][0][1]
+        sets[0].add(y); g[(x, y)] -= mu
+        if g[(x, y)] == 0:
+            del g[(x, y)]
