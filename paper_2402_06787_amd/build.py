@@ -9,7 +9,9 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libfcmaxflow.so")
 SOURCES = [os.path.join(CSRC, "fc_host.cpp"), os.path.join(CSRC, "fc_device.hip")]
-HEADERS = [os.path.join(CSRC, "fc_internal.h"), os.path.join(ROOT, "include", "fc_maxflow.h")]
+# fc_device.hip is one translation unit made of the .inc parts it includes
+HEADERS = [os.path.join(CSRC, "fc_internal.h"), os.path.join(ROOT, "include", "fc_maxflow.h")] + \
+          [os.path.join(CSRC, f) for f in ("fc_solver_kernels.inc", "fc_launch.inc", "fc_api.inc", "fc_surgery.inc")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 code generation is switched off for all device code of this project
