@@ -663,3 +663,28 @@ def test_trees_after_switch_removal(seed):
     links = {(idx[a], idx[b]): c for (a, b), c in o.link_capacities(Dstar).items()}
     trees = o.construct_trees(len(comp), links, kk)
     _check_trees(len(comp), links, kk, trees)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_mu_of_an_edge_never_rises_while_its_root_set_grows(seed):
+    # what lets a construction skip an edge once it had mu = 0: growing R admits more cuts, used capacity lowers
+    # them, copies raise p(S), m(R) only shrinks
+    rng = np.random.default_rng(8000 + seed)
+    n = int(rng.integers(3, 7)); k = int(rng.integers(1, 5))
+    # a complete digraph of capacity >= k satisfies the packing condition; odd seeds thin it out and may not
+    links = {(a, b): k + int(rng.integers(0, 3)) for a in range(n) for b in range(n) if a != b and (seed % 2 == 0 or rng.random() < 0.85)}
+    for a in range(n):                                     # keep a ring so that the digraph stays connected
+        links.setdefault((a, (a + 1) % n), k)
+    last = {}
+
+    def observe(g, sets, demand, i, x, y, mu):
+        key = (i, x, y)
+        if key in last:
+            assert mu <= last[key], key
+        last[key] = mu
+
+    try:
+        trees = o.construct_trees(n, links, k, observe=observe)
+    except AssertionError:
+        pytest.skip("the packing condition does not hold for this draw")
+    _check_trees(n, links, k, trees)
