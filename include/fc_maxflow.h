@@ -99,6 +99,11 @@ typedef struct {
                                       counters stay 0).  Exact; it only skips work.                      */
     int32_t schedule;              /* 1 = on (default), 2 = off: start the problems that look hardest (least
                                       slack in the sink's own cut) first, so the launch has no long tail */
+    int32_t tree_warm_start;       /* fc_construct_trees: 1 = on (default), 2 = off.  On: while a root-set grows, the
+                                      flow that delivers the other root-sets' demands to a vertex y is kept on the
+                                      device from launch to launch, repaired for the capacities that were used up
+                                      since, and only the few units that decide mu are routed anew.  Off: every
+                                      max-flow starts from nothing.  Same trees either way.                  */
 } fc_options;
 
 /* ------------------------------------------------------------------------------------------

@@ -55,7 +55,8 @@ class fc_options(ctypes.Structure):
                 ("global_relabel_rises", ctypes.c_int32), ("tight_sink_percent", ctypes.c_int32),
                 ("use_gap", ctypes.c_int32), ("use_label_table", ctypes.c_int32),
                 ("force_wide", ctypes.c_int32), ("max_level_steps", ctypes.c_int32),
-                ("src_cap_bound", ctypes.c_int32), ("tree_certificate", ctypes.c_int32), ("schedule", ctypes.c_int32)]
+                ("src_cap_bound", ctypes.c_int32), ("tree_certificate", ctypes.c_int32), ("schedule", ctypes.c_int32),
+                ("tree_warm_start", ctypes.c_int32)]
 
 
 VERDICT_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32),
