@@ -901,6 +901,12 @@ def test_construct_trees_matches_oracle():
         assert got["trees"] == want, (n, k)
         _check_trees(n, links, k, got["trees"])
         assert got["batches"] >= n - 1
+        # every max-flow from nothing instead of from the flows kept between launches: the same trees
+        cold = fc.fc_construct_trees(n, links, k, options={"tree_warm_start": 2})
+        assert cold["trees"] == want and cold["batches"] == got["batches"], (n, k)
+    with pytest.raises(fc.FcError) as err:
+        fc.fc_construct_trees(2, {(0, 1): 4, (1, 0): 4}, 4, options={"tree_warm_start": 3})
+    assert err.value.code == fc.FC_EINVAL
     # the packing condition fails: the construction reports it
     with pytest.raises(fc.FcError) as err:
         fc.fc_construct_trees(3, {(0, 1): 1, (1, 0): 2, (1, 2): 2, (2, 1): 2, (0, 2): 2, (2, 0): 2}, 2)
@@ -977,6 +983,9 @@ def test_trees_on_config3_after_switch_removal_are_valid():
     # config 3 is symmetric and tight: every unit of every link is used by some tree
     assert sum(use.values()) == len(comp) * k * (len(comp) - 1)
     assert got["batches"] < len(comp) * (len(comp) - 1)                # the look-ahead saves launches
+    # the flows kept between launches change nothing: same trees as with every max-flow started from nothing
+    cold = fc.fc_construct_trees(len(comp), links, k, options={"tree_warm_start": 2})
+    assert cold["trees"] == got["trees"] and cold["batches"] == got["batches"]
     # first steps of root 0 by the oracle: same edges in the same order
     n = len(comp)
     g = dict(links); sets = [{u} for u in range(n)]; demand = [k] * n
