@@ -343,7 +343,12 @@ const char *fc_strerror(int code);
  * the rest.  All candidate links of a state are evaluated in one launch (the ones before the first positive
  * mu are zero on this very state, so the result is that of trying them one by one), and the launch looks
  * ahead: it also evaluates the states that follow if, each time, the first link not rejected before is
- * accepted in full; those results are used as far as the guesses turn out right.  Output: n_trees
+ * accepted in full; those results are used as far as the guesses turn out right.  A link whose mu was 0 is
+ * not tried again while the same root-set grows (its mu cannot rise).  Unless options->tree_warm_start is 2
+ * the launches do not start from nothing: the flow that brings the other root-sets' demands to a vertex y
+ * is kept in device memory (n_vertices rows of one value per link, and as many again per state a launch looks
+ * ahead: the option is ignored when that exceeds 2 GiB), a max-flow into y repairs it for the capacities used
+ * up since and then only routes the units that decide mu.  The trees are the same either way.  Output: n_trees
  * root-sets; tree i has root tree_root[i], multiplicity tree_multiplicity[i] (they add up to k per root)
  * and the n_vertices - 1 edges tree_edge_x/y[i * (n_vertices - 1) ..] in the order they were added.
  * Needs min over v of F(s, v) >= N k to hold in D* (what switch removal preserves); FC_ENOCONVERGE if no
