@@ -44,8 +44,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-certificate-leg", action="store_true",
                     help="skip the side measurement with tree_certificate=1 (keeps profiler traces to one kind of launch)")
-    ap.add_argument("--tree-leg-config", type=int, default=1, choices=[1, 3],
-                    help="config whose switch-free digraph the spanning-tree side leg runs on (3 takes about 20 s)")
+    ap.add_argument("--tree-leg-config", type=int, default=3, choices=[1, 3],
+                    help="config whose switch-free digraph the spanning-tree side leg runs on")
     ap.add_argument("--threads-per-problem", type=int, default=0)
     ap.add_argument("--lanes-per-vertex", type=int, default=0)
     ap.add_argument("--copy-probe", action="store_true",
@@ -274,6 +274,18 @@ def main():
         tr = fc.fc_construct_trees(len(comp_t), links_t, kt)
         gamma["construct_trees"] = {"workload": f"{tt.name} after switch removal: {len(comp_t)} nodes, {len(links_t)} links, k={kt}",
                                     "wall_ms": (time.perf_counter() - t0) * 1e3, "launches": tr["batches"], "root_sets": len(tr["trees"])}
+        # what the construction promises: out-trees that span, k per root, no link used beyond its capacity
+        use_t, per_t, ok_t = {}, {}, True
+        for root_t, mult_t, edges_t in tr["trees"]:
+            seen_t = {root_t}
+            for x_t, y_t in edges_t:
+                ok_t = ok_t and x_t in seen_t and y_t not in seen_t
+                seen_t.add(y_t)
+                use_t[(x_t, y_t)] = use_t.get((x_t, y_t), 0) + mult_t
+            ok_t = ok_t and len(seen_t) == len(comp_t)
+            per_t[root_t] = per_t.get(root_t, 0) + mult_t
+        ok_t = ok_t and per_t == {u: kt for u in range(len(comp_t))} and all(c <= links_t[e] for e, c in use_t.items())
+        gamma["construct_trees"]["valid"] = bool(ok_t)
 
     # the dominant kernel alone: HIP events recorded by the library on the launch stream around
     # the solver kernel, same inputs, same launch configuration

@@ -913,6 +913,19 @@ def test_construct_trees_matches_oracle():
     assert err.value.code == fc.FC_ENOCONVERGE
 
 
+@pytest.mark.parametrize("n,k,seed", [(5, 1, 0), (9, 2, 2), (12, 3, 3), (16, 2, 4)])
+def test_trees_on_superposed_random_out_trees_match_oracle(n, k, seed):
+    # capacities that differ from link to link: most accepted edges come with a partial mu, so copies with a vertex
+    # of their own enter the network all the time, the graph is built anew and the kept flows start over
+    links = w.superposed_out_trees(n, k, seed)
+    want = o.construct_trees(n, links, k)
+    got = fc.fc_construct_trees(n, links, k)
+    assert got["trees"] == want
+    assert _check_trees(n, links, k, got["trees"]) == links            # every unit of every link is used
+    cold = fc.fc_construct_trees(n, links, k, options={"tree_warm_start": 2})
+    assert cold["trees"] == want and cold["batches"] == got["batches"]
+
+
 def test_trees_on_config1_after_switch_removal_on_the_gpu():
     # the back end on the GPU alone: optimum, switch removal, trees; then the oracle's trees for the same D*
     topo = w.config_topology(1)

@@ -620,6 +620,19 @@ def test_trees_on_complete_digraphs_use_every_link():
         o.construct_trees(3, {(0, 1): 1, (1, 0): 2, (1, 2): 2, (2, 1): 2, (0, 2): 2, (2, 0): 2}, 2)
 
 
+@pytest.mark.parametrize("n,k,seed", [(5, 1, 0), (7, 2, 1), (9, 2, 2), (12, 3, 3)])
+def test_trees_on_superposed_random_out_trees_use_every_unit(n, k, seed):
+    # a digraph laid down as k random spanning out-trees per root, one unit per tree edge: a packing exists, and any
+    # packing of n k spanning out-trees uses n k (n - 1) units, which is all there are.  Capacities differ from
+    # link to link, so partial mu (copies) occur all the time.
+    links = w.superposed_out_trees(n, k, seed)
+    assert sum(links.values()) == n * k * (n - 1)
+    trees = o.construct_trees(n, links, k, algo=ALGOS[seed % 2])
+    use = _check_trees(n, links, k, trees)
+    assert use == links
+    assert len(trees) > n or k == 1 or n <= 2       # some root needed more than one kind of tree
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_mu_by_max_flow_equals_its_definition(seed):
     # random small compute-only digraphs that satisfy the packing condition (a complete digraph of capacity k

@@ -185,6 +185,22 @@ def random_tiny(seed: int, n_vertices: int | None = None, max_cap: int = 9,
     return g.done()
 
 
+def superposed_out_trees(n: int, k: int, seed: int) -> dict:
+    """Link capacities {(x, y): c} of a switch-free digraph over vertices 0..n-1 laid down as k random spanning
+    out-trees per root, one unit of capacity per tree edge: a packing of k out-trees per root exists by
+    construction and uses every unit, so spanning tree construction (Appendix E.3) must find one that does too.
+    Capacities vary from link to link and most trees end up with a multiplicity of their own."""
+    rng = np.random.default_rng(seed)
+    links: dict = {}
+    for root in range(n):
+        for _ in range(k):
+            order = [root] + [int(v) for v in rng.permutation([v for v in range(n) if v != root])]
+            for i in range(1, n):
+                x, y = order[int(rng.integers(0, i))], order[i]
+                links[(x, y)] = links.get((x, y), 0) + 1
+    return links
+
+
 # --------------------------------------------------------------------------- the five benchmark configs
 
 def _config1() -> Topology:
