@@ -104,6 +104,13 @@ typedef struct {
                                       device from launch to launch, repaired for the capacities that were used up
                                       since, and only the few units that decide mu are routed anew.  Off: every
                                       max-flow starts from nothing.  Same trees either way.                  */
+    int32_t split_two_launches;    /* edge splitting: 1 = on, 2 = off.  On: the 2N max-flows of a pair are solved in two
+                                      launches -- first the two problems without the compute node v, whose final
+                                      preflows are kept; then the 2N with v, each of which is answered at once where
+                                      the problem without v reached the value that settles gamma (one more sink never
+                                      lowers a flow) and otherwise goes on from the kept preflow.  Same values.
+                                      Default: off in fc_split_gamma_batch; fc_remove_switches switches it on for
+                                      a batch when the one before it was slow for its size                   */
 } fc_options;
 
 /* ------------------------------------------------------------------------------------------
