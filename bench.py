@@ -233,7 +233,7 @@ def main():
         P3 = 256 * 2 * t3.n_compute
         gamma = {"workload": f"{w.CONFIG_NAMES[3]} scaled by U={U3}, k={k3}: 256 pairs x 2N = {P3} max-flows per step",
                  "value": P3 / el, "unit": "solves/s", "ms_per_step": el * 1e3,
-                 "note": "gamma only: a max-flow may stop once it cannot decide gamma any more"}
+                 "note": "gamma only: a max-flow may stop once it cannot decide gamma any more, and is answered from the problem without its compute node v where that one already got there (two launches)"}
         for _ in range(3):
             fc.fc_split_gamma_batch(g3, U3, k3, *d3, want_flows=True, d_workspace=ws3)
         torch.cuda.synchronize()

@@ -109,8 +109,9 @@ typedef struct {
                                       preflows are kept; then the 2N with v, each of which is answered at once where
                                       the problem without v reached the value that settles gamma (one more sink never
                                       lowers a flow) and otherwise goes on from the kept preflow.  Same values.
-                                      Default: off in fc_split_gamma_batch; fc_remove_switches switches it on for
-                                      a batch when the one before it was slow for its size                   */
+                                      Default: on for a batch with at least twice as many max-flows as the device
+                                      holds workgroups at a time (a smaller batch lasts as long as its slowest
+                                      problem either way, and a second launch only adds to that)               */
 } fc_options;
 
 /* ------------------------------------------------------------------------------------------

@@ -516,6 +516,11 @@ def test_split_gamma_matches_oracle_on_random_eulerian_graphs():
         assert (got[len(pairs):] == fc.FC_GAMMA_INVALID).all()
         early, _ = _gamma_on_gpu(sym, U, kk, pairs + bogus, want_flows=False)      # max-flows may stop early: same gamma
         assert (early == got).all(), seed
+        # in two launches (first without the compute node v, then from the kept preflows): same flows, same gamma
+        two, two_flows = _gamma_on_gpu(sym, U, kk, pairs + bogus, options={"split_two_launches": 1})
+        assert (two == got).all() and (two_flows == flows).all(), seed
+        two_early, _ = _gamma_on_gpu(sym, U, kk, pairs + bogus, want_flows=False, options={"split_two_launches": 1})
+        assert (two_early == got).all(), seed
         checked += len(pairs)
     assert checked > 200
 
@@ -540,18 +545,22 @@ def test_split_gamma_on_configs(cfg):
     # initial heights from the distance tables (the default on the larger graphs) or from a search in the kernel;
     # relabel policies; lanes per vertex
     for opt in ({"use_label_table": 2}, {"global_relabel_rises": -1, "use_gap": 2}, {"global_relabel_rises": 1, "lanes_per_vertex": 4},
-                {"threads_per_problem": 256, "lanes_per_vertex": 32}):
+                {"threads_per_problem": 256, "lanes_per_vertex": 32}, {"split_two_launches": 1}, {"split_two_launches": 2},
+                {"split_two_launches": 1, "threads_per_problem": 64, "global_relabel_rises": -1}):
         alt, alt_flows = _gamma_on_gpu(topo, U, kk, pick, options=opt)
         assert (alt == got).all() and (alt_flows == flows).all(), (cfg, opt)
     # without the flows a max-flow may stop once N k + min{c(e), c(f)} units have arrived: gamma is the same
     early, _ = _gamma_on_gpu(topo, U, kk, pick, want_flows=False)
     assert (early == got).all()
+    for two in (1, 2):
+        early, _ = _gamma_on_gpu(topo, U, kk, pick, want_flows=False, options={"split_two_launches": two})
+        assert (early == got).all(), two
 
 
 # ------------------------------------------------------------------ Algorithm 2: the switch-removal loop around the gamma batches
 
-def _remove_on_gpu(D, k):
-    return fc.fc_remove_switches(D.n_vertices, D.tail, D.head, D.bandwidth, D.is_compute, k)
+def _remove_on_gpu(D, k, options=None):
+    return fc.fc_remove_switches(D.n_vertices, D.tail, D.head, D.bandwidth, D.is_compute, k, options=options)
 
 
 def test_remove_switches_matches_oracle_on_the_paper_example():
@@ -588,6 +597,8 @@ def test_remove_switches_matches_oracle_on_random_eulerian_graphs():
         got = _remove_on_gpu(D, kk)
         assert got["links"] == o.link_capacities(want), seed
         assert got["table"] == table, seed
+        two = _remove_on_gpu(D, kk, options={"split_two_launches": 1})      # every batch in two launches
+        assert two["links"] == got["links"] and two["table"] == got["table"], seed
         done += 1
     assert done >= 15
     # not Eulerian: refused; Eulerian but the condition min F >= N k fails: reported
@@ -616,6 +627,15 @@ def test_remove_switches_on_config1():
                        np.array([b for _, b in got["links"]], dtype=np.int32),
                        np.array(list(got["links"].values()), dtype=np.int32), D.is_compute)
     assert o.feasible(Dstar, 1, kk)[0] and o.is_eulerian(Dstar)
+
+
+def test_remove_switches_on_config3_in_one_and_in_two_launches_per_batch():
+    # the same links and the same table whether a batch's max-flows are solved in one launch, in two, or as the library chooses
+    topo = w.config_topology(3)
+    D = _scaled(topo, 15)
+    res = [_remove_on_gpu(D, 2, options=opt) for opt in (None, {"split_two_launches": 1}, {"split_two_launches": 2})]
+    assert len(res[0]["links"]) == 504
+    assert all(r["links"] == res[0]["links"] and r["table"] == res[0]["table"] for r in res[1:])
 
 
 # ------------------------------------------------------------------ launch shapes the other tests do not reach
