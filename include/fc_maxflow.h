@@ -299,7 +299,9 @@ int fc_fixed_k_search_with_verdicts(int32_t n_compute, int64_t min_in_bw, int32_
  * not asked for, a max-flow ends as soon as N k + min{c(e), c(f)} units have arrived -- from there on it
  * cannot be the term that decides gamma -- so gamma is the same and the work is much less; with
  * d_flows every value is the exact maximum.  Workspace, stream, options and stats as for
- * fc_maxflow_batch (no first-pass tables, launch order or certificate apply to these problems). */
+ * fc_maxflow_batch (no first-pass tables, launch order or certificate apply to these problems).  A large
+ * batch is solved in two launches (options->split_two_launches): then the counters and the device time in
+ * stats are those of the second launch, and a problem that the first launch settled counts no work at all. */
 #define FC_GAMMA_INVALID (-2147483647 - 1)
 size_t fc_split_gamma_workspace_bytes(const fc_graph *g, int64_t n_pairs);
 int fc_split_gamma_batch(const fc_graph *g, int32_t U, int32_t k, int64_t n_pairs, const int32_t *d_u,
