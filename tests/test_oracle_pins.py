@@ -701,3 +701,73 @@ def test_mu_of_an_edge_never_rises_while_its_root_set_grows(seed):
     except AssertionError:
         pytest.skip("the packing condition does not hold for this draw")
     _check_trees(n, links, k, trees)
+
+
+# ------------------------------------------------------------------ two facts the device path leans on, shown on the oracle
+
+@pytest.mark.parametrize("seed", range(6))
+def test_mu_is_what_a_small_supply_at_x_adds_to_the_other_demands(seed):
+    # mu = min{g, m(R), F(x, y; D-bar) - sum of the other demands}.  A maximum flow can be reached from any feasible
+    # flow, and only min{g, m(R)} more units matter, so mu is also what a supply of min{g(x, y), m(R)} at x -- an
+    # ordinary vertex, nothing saturated -- adds to the flow that delivers the other root-sets' demands to y; and
+    # those demands alone always arrive in full.  (The HIP path evaluates mu in these two parts.)
+    n, k = (6, 2) if seed % 2 else (5, 3)
+    links = w.superposed_out_trees(n, k, 40 + seed)
+    count = [0]
+
+    def observe(g, sets, demand, i, x, y, mu):
+        others = [l for l in range(len(sets)) if l != i]
+        inf = sum(g.values()) + sum(demand) + 1
+        sigma = n + len(others)                       # a source of its own: demands into the root-sets' vertices, the rest into x
+        arcs = [(a, b, c) for (a, b), c in sorted(g.items()) if c > 0]
+        for j, l in enumerate(others):
+            arcs.append((sigma, n + j, int(demand[l])))
+            arcs += [(n + j, r, inf) for r in sorted(sets[l])]
+        def flow(extra):
+            a = arcs + extra
+            return o.maxflow(sigma + 1, [t for t, _, _ in a], [h for _, h, _ in a], [c for _, _, c in a], sigma, y, ALGOS[seed % 2])
+        total = sum(int(demand[l]) for l in others)
+        assert flow([]) == total
+        supply = min(int(g[(x, y)]), int(demand[i]))
+        assert flow([(sigma, x, supply)]) - total == mu
+        count[0] += 1
+
+    o.construct_trees(n, links, k, observe=observe)
+    assert count[0] >= n * (n - 1)
+
+
+def test_one_more_sink_never_lowers_a_split_flow():
+    # Theorem 10's 2N max-flows of a pair differ in one sink, the compute node v (its unbounded arc into w or t makes it
+    # one).  Without that arc the flow cannot be larger: what the problem without v reaches, every problem with v
+    # reaches too.  (The HIP path answers from the problem without v where that already settles gamma.)
+    checked = 0
+    for seed in range(12):
+        base = w.random_tiny(6000 + seed, n_vertices=6 + seed % 3, max_cap=5, density=0.4)
+        if base.is_compute.all():
+            continue
+        cap = {}
+        for t, h, b in zip(base.tail.tolist(), base.head.tolist(), base.bandwidth.tolist()):
+            if t != h and b > 0:
+                key = (min(t, h), max(t, h)); cap[key] = cap.get(key, 0) + int(b)
+        tail = [a for a, b in cap] + [b for a, b in cap]; head = [b for a, b in cap] + [a for a, b in cap]
+        sym = w.Topology(f"euler{seed}", base.n_vertices, np.array(tail, dtype=np.int32), np.array(head, dtype=np.int32),
+                         np.array(list(cap.values()) * 2, dtype=np.int32), base.is_compute.copy())
+        k = 2
+        links = o.link_capacities(sym)
+        comp = [v for v in range(sym.n_vertices) if sym.is_compute[v]]
+        s = sym.n_vertices
+        inf = o.unbounded(sym, k)
+        common = [(a, b, c) for (a, b), c in sorted(links.items())] + [(s, c, k) for c in comp]
+        def flow(extra, src, dst):
+            a = common + [(x, y, inf) for x, y in extra if x != y]
+            return min(inf, o.maxflow(s + 1, [t for t, _, _ in a], [h for _, h, _ in a], [c for _, _, c in a], src, dst))
+        for sw in (v for v in range(sym.n_vertices) if not sym.is_compute[v]):
+            ins = sorted(a for (a, b) in links if b == sw); outs = sorted(b for (a, b) in links if a == sw)
+            for u in ins[:2]:
+                for t in outs[:2]:
+                    F1, F2 = o.split_flows(sym, k, u, sw, t)
+                    without1 = flow([(u, s), (u, t)], u, sw)
+                    without2 = flow([(sw, s), (u, t)], sw, t)
+                    assert (F1 >= without1).all() and (F2 >= without2).all(), (seed, u, sw, t)
+                    checked += 1
+    assert checked >= 20
