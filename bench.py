@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-certificate-leg", action="store_true",
                     help="skip the side measurement with tree_certificate=1 (keeps profiler traces to one kind of launch)")
+    ap.add_argument("--config4-back-end", action="store_true",
+                    help="also time switch removal and tree construction on config 4 (about 10 s more)")
     ap.add_argument("--tree-leg-config", type=int, default=3, choices=[1, 3],
                     help="config whose switch-free digraph the spanning-tree side leg runs on")
     ap.add_argument("--threads-per-problem", type=int, default=0)
@@ -286,6 +288,28 @@ def main():
             per_t[root_t] = per_t.get(root_t, 0) + mult_t
         ok_t = ok_t and per_t == {u: kt for u in range(len(comp_t))} and all(c <= links_t[e] for e, c in use_t.items())
         gamma["construct_trees"]["valid"] = bool(ok_t)
+        if args.config4_back_end:
+            # the same two stages on the largest switch topology (512 compute nodes, 84 switches), at its optimum from the library's search
+            t4 = w.config_topology(4)
+            g4 = fc.fc_graph_upload(t4.n_vertices, t4.tail, t4.head, t4.bandwidth, t4.is_compute)
+            s4 = fc.fc_opt_throughput_search(g4, 16)
+            U4, k4 = s4["U"].numerator, s4["k"] * s4["U"].denominator
+            g4.close()
+            t0 = time.perf_counter()
+            r4 = fc.fc_remove_switches(t4.n_vertices, t4.tail, t4.head, (np.asarray(t4.bandwidth, dtype=np.int64) * U4).astype(np.int32), t4.is_compute, k4)
+            el_r4 = time.perf_counter() - t0
+            comp4 = np.flatnonzero(np.asarray(t4.is_compute)).tolist()
+            idx4 = {v: i for i, v in enumerate(comp4)}
+            links4 = {(idx4[a], idx4[b]): c for (a, b), c in r4["links"].items()}
+            t0 = time.perf_counter()
+            tr4 = fc.fc_construct_trees(len(comp4), links4, k4)
+            el_t4 = time.perf_counter() - t0
+            edges4 = sum(m * len(e) for _, m, e in tr4["trees"])
+            gamma["config4_back_end"] = {"workload": f"{t4.name} at U = {U4}, k = {k4}: {len(comp4)} compute nodes, {t4.n_vertices - len(comp4)} switches",
+                                         "remove_switches": {"wall_ms": el_r4 * 1e3, "batches": r4["batches"], "links_out": len(r4["links"])},
+                                         "construct_trees": {"wall_ms": el_t4 * 1e3, "launches": tr4["batches"], "root_sets": len(tr4["trees"]),
+                                                             "tree_edges_with_multiplicity": int(edges4),
+                                                             "complete": bool(edges4 == len(comp4) * k4 * (len(comp4) - 1))}}
 
     # the dominant kernel alone: HIP events recorded by the library on the launch stream around
     # the solver kernel, same inputs, same launch configuration
