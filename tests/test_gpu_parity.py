@@ -946,6 +946,17 @@ def test_trees_on_superposed_random_out_trees_match_oracle(n, k, seed):
     assert cold["trees"] == want and cold["batches"] == got["batches"]
 
 
+@pytest.mark.parametrize("n,k,seed", [(48, 3, 11), (96, 1, 12)])
+def test_trees_on_larger_superposed_out_trees_use_every_unit(n, k, seed):
+    # beyond what the oracle's loop does in seconds: the construction's promises (which pin the packing down to "uses
+    # every unit of every link") and the same trees with and without kept flows; copies with a vertex of their own all the time
+    links = w.superposed_out_trees(n, k, seed)
+    got = fc.fc_construct_trees(n, links, k)
+    assert _check_trees(n, links, k, got["trees"]) == links
+    cold = fc.fc_construct_trees(n, links, k, options={"tree_warm_start": 2})
+    assert cold["trees"] == got["trees"]
+
+
 def test_trees_on_config1_after_switch_removal_on_the_gpu():
     # the back end on the GPU alone: optimum, switch removal, trees; then the oracle's trees for the same D*
     topo = w.config_topology(1)
