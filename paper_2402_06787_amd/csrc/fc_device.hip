@@ -34,15 +34,6 @@
 #define FC_LVLS 128  // heights below this have a population count (gap detection)
 #define FC_NSTAT 8   // per-problem counters: pushes, relabels, arc_scans, grs, gr_arc_scans, level_steps, discharges, not_converged
 
-// Optional per-phase cycle accounting for tuning builds (-DFC_PHASE_TIMING): the per-problem
-// counters relabels/global_relabels/gr_arc_scans/discharges are then replaced by the cycles
-// thread 0 spent in level compaction / discharge / initialisation / everything else.
-#ifdef FC_PHASE_TIMING
-#define FC_TICK(var) do { long long now_ = clock64(); var += uint32_t(now_ - tick_); tick_ = now_; } while (0)
-#else
-#define FC_TICK(var) do { } while (0)
-#endif
-
 #include "fc_solver_kernels.inc"   // device code
 #include "fc_launch.inc"           // option defaults, kernel build selection, launches
 #include "fc_api.inc"              // C ABI: graphs, batches, verdicts, searches, edge-splitting batches

@@ -113,6 +113,56 @@ def test_tiny_random_graphs_match_oracle(block):
                 assert (got2 == want).all(), seed
 
 
+def _funnel(n_feed, arcs_out):
+    """Compute nodes 0..n_feed-1 feed one switch u, which has the arcs `arcs_out` (bandwidths) to switches w_i, each of
+    which feeds the compute node t: all excess meets at u and has to be split over several admissible arcs."""
+    u, t = n_feed, n_feed + 1
+    tail, head, bw = [], [], []
+    for c in range(n_feed):
+        tail.append(c); head.append(u); bw.append(8)
+    for i, cap in enumerate(arcs_out):
+        wi = n_feed + 2 + i
+        tail.append(u); head.append(wi); bw.append(cap)
+        tail.append(wi); head.append(t); bw.append(8)
+    n = n_feed + 2 + len(arcs_out)
+    is_c = np.zeros(n, np.uint8); is_c[:n_feed] = 1; is_c[t] = 1
+    return w.Topology("funnel", n, np.asarray(tail, np.int32), np.asarray(head, np.int32), np.asarray(bw, np.int32), is_c)
+
+
+def test_residuals_near_two_to_the_31_are_split_without_wrapping():
+    # N * k just below 2^31 and capacities U * b of 2^28 .. N * k: the admissible residuals of one row add up to far more
+    # than 32 bits hold, while every single one, the excess and the flow value fit
+    topo = _funnel(7, [1, 1, 3, 3, 3, 3])
+    N = topo.n_compute
+    k = (1 << 28) - 1
+    assert N * k < (1 << 31) <= N * (k + 1)
+    cases = [(1 << 28, k), ((1 << 28) + 12345, k), (1 << 27, k), (3 << 26, k - 77), (1 << 28, k // 3), (1 << 30, k)]
+    sink = np.array([8, 0, 3] * len(cases), np.int32)                         # t, and two of the feeders
+    U = np.repeat([c[0] for c in cases], 3).astype(np.int32)
+    kk = np.repeat([c[1] for c in cases], 3).astype(np.int32)
+    want = o.aux_maxflow_batch(topo, sink, U, kk)
+    assert want.max() > (1 << 30)
+    with _upload(topo) as g:
+        for opts in [None, dict(lanes_per_vertex=4), dict(lanes_per_vertex=64), dict(lanes_per_vertex=16, use_label_table=2),
+                     dict(lanes_per_vertex=32, threads_per_problem=128)]:
+            got, _ = _gpu_flows(g, sink, U, kk, options=opts)
+            assert (got == want).all(), (opts, got.tolist(), want.tolist())
+    # random small graphs in the same range
+    for seed in range(40):
+        topo = w.random_tiny(500 + seed, n_vertices=10 + seed % 5, strongly_connected=True)
+        rng = np.random.default_rng(900 + seed)
+        N = topo.n_compute
+        P = 48
+        sink = rng.integers(0, topo.n_vertices, P).astype(np.int32)
+        kk = (((1 << 31) - 1) // N - rng.integers(0, 1000, P)).astype(np.int32)
+        U = rng.integers(1 << 24, 1 << 29, P).astype(np.int32)
+        want = o.aux_maxflow_batch(topo, sink, U, kk)
+        with _upload(topo) as g:
+            for opts in [dict(lanes_per_vertex=4), dict(lanes_per_vertex=64)]:
+                got, _ = _gpu_flows(g, sink, U, kk, options=opts)
+                assert (got == want).all(), (seed, opts, np.flatnonzero(got != want)[:5])
+
+
 # ------------------------------------------------------------------ every launch shape gives the same values
 
 def test_option_matrix_same_values():
