@@ -192,6 +192,24 @@ int fc_maxflow_batch(const fc_graph *g, int64_t n_problems, const int32_t *d_sin
                      void *d_workspace, size_t workspace_bytes, void *hip_stream,
                      const fc_options *options_or_null, fc_stats *stats_or_null);
 
+/* fc_maxflow_batch_static -- fc_maxflow_batch for callers that cannot allocate device memory: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same problems, same values;
+ * the scratch the batch needs (the launch order that starts the expensive problems first, and its sort keys)
+ * lives in a static array in the library's device image, 5 bytes per problem for at most
+ * FC_MAXFLOW_BATCH_STATIC_MAX_PROBLEMS problems (1.25 MiB, held on every GPU the library runs on until the
+ * process ends).  The call allocates and frees nothing, on the host side of the device or on the device, and
+ * takes no workspace and no stats (counters need per-problem scratch and a synchronisation).
+ * Arguments as for fc_maxflow_batch; asynchronous on `hip_stream`.  The graph must live on the current device.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different streams,
+ * different host threads) race on it and may run their problems in a poor order or skip some -- serialise them,
+ * or use fc_maxflow_batch with a workspace per call.  Nothing in the array has to be cleared between calls.
+ * Errors: FC_EWORKSPACE (n_problems above the maximum), FC_EINVAL, FC_EDEVICE (also: the graph is on another
+ * GPU than the current one), FC_EUNSUPPORTED. */
+#define FC_MAXFLOW_BATCH_STATIC_MAX_PROBLEMS 262144
+int fc_maxflow_batch_static(const fc_graph *g, int64_t n_problems, const int32_t *d_sink,
+                            const int32_t *d_edge_mult, const int32_t *d_src_cap, int32_t *d_flow_out,
+                            void *hip_stream, const fc_options *options_or_null);
+
 /* ------------------------------------------------------------------------------------------
  * fc_feasible -- the verdict of Theorem 1 in its integer form (Theorem 3 / Appendix E.1) for
  * each candidate j = (U_j, k_j):   feasible_j  <=>  min over v in V_c of F(s, v) >= N * k_j.

@@ -6,7 +6,8 @@ this package is its thin Python binding.  Build it with `python -m paper_2402_06
 """
 from .binding import (FcError, Graph, GraphInfo, fc_options, fc_stats, fc_rational, load_library, strerror,
                       fc_graph_build, fc_graph_upload, fc_graph_info, fc_graph_csr, fc_graph_set_source_weights,
-                      fc_maxflow_batch_workspace_bytes, fc_maxflow_batch,
+                      fc_maxflow_batch_workspace_bytes, fc_maxflow_batch, fc_maxflow_batch_static,
+                      FC_MAXFLOW_BATCH_STATIC_MAX_PROBLEMS,
                       fc_feasible_workspace_bytes, fc_feasible, fc_opt_throughput_search,
                       fc_search_with_verdicts, fc_maxflow_batch_floor, fc_feasible_floor, fc_fixed_k_search,
                       fc_fixed_k_search_with_verdicts, fc_split_gamma_workspace_bytes, fc_split_gamma_batch, fc_remove_switches,

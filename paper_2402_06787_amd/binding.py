@@ -23,7 +23,7 @@ FC_FLOW_INVALID, FC_FLOW_NOCONVERGE, FC_FLOW_UNSUPPORTED = -1, -2, -3
 FC_GAMMA_INVALID = -2147483648
 
 EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_free", "fc_graph_info", "fc_graph_csr", "fc_graph_set_source_weights",
-            "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_maxflow_batch_floor", "fc_feasible_workspace_bytes",
+            "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_maxflow_batch_static", "fc_maxflow_batch_floor", "fc_feasible_workspace_bytes",
             "fc_feasible_floor", "fc_fixed_k_search", "fc_fixed_k_search_with_verdicts",
             "fc_split_gamma_workspace_bytes", "fc_split_gamma_batch", "fc_remove_switches", "fc_tree_mu_batch", "fc_construct_trees",
             "fc_feasible", "fc_opt_throughput_search", "fc_search_with_verdicts", "fc_strerror"]
@@ -92,6 +92,8 @@ def load_library():
     lib.fc_maxflow_batch_workspace_bytes.argtypes = [vp, i64]
     lib.fc_maxflow_batch.restype = c.c_int
     lib.fc_maxflow_batch.argtypes = [vp, i64, vp, vp, vp, vp, vp, sz, vp, c.POINTER(fc_options), c.POINTER(fc_stats)]
+    lib.fc_maxflow_batch_static.restype = c.c_int
+    lib.fc_maxflow_batch_static.argtypes = [vp, i64, vp, vp, vp, vp, vp, c.POINTER(fc_options)]
     lib.fc_feasible_workspace_bytes.restype = sz
     lib.fc_feasible_workspace_bytes.argtypes = [vp, i32]
     lib.fc_feasible.restype = c.c_int
@@ -296,6 +298,22 @@ def fc_maxflow_batch(g: Graph, d_sink, d_edge_mult, d_src_cap, d_flow_out=None, 
         ctypes.byref(st) if st is not None else None)
     _check(rc, "fc_maxflow_batch")
     return d_flow_out, (st.as_dict() if st is not None else None)
+
+
+FC_MAXFLOW_BATCH_STATIC_MAX_PROBLEMS = 262144
+
+
+def fc_maxflow_batch_static(g: Graph, d_sink, d_edge_mult, d_src_cap, d_flow_out, stream=None, options=None):
+    """fc_maxflow_batch without a workspace: the library's static device array holds the scratch.  The caller
+    passes every buffer; nothing is allocated here or in the library.  Returns d_flow_out."""
+    import torch
+    P = int(d_sink.numel())
+    rc = load_library().fc_maxflow_batch_static(
+        g.handle, P, _dev_ptr(d_sink, torch.int32, P, "d_sink"), _dev_ptr(d_edge_mult, torch.int32, P, "d_edge_mult"),
+        _dev_ptr(d_src_cap, torch.int32, P, "d_src_cap"), _dev_ptr(d_flow_out, torch.int32, P, "d_flow_out"),
+        _stream_ptr(stream), _opts(options))
+    _check(rc, "fc_maxflow_batch_static")
+    return d_flow_out
 
 
 def fc_feasible_workspace_bytes(g: Graph, n_candidates: int) -> int:
