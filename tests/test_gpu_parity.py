@@ -189,15 +189,19 @@ def test_option_matrix_same_values():
 
 
 def test_every_register_budget_gives_the_same_values():
-    # the solver exists in builds for 5, 6, 7 and 8 wavefronts per SIMD, picked from the LDS a problem needs and the
-    # workgroup size: reach each of them with both state widths, and with rational multipliers
-    cases = [(5, dict(threads_per_problem=256)), (5, dict(threads_per_problem=320)), (5, dict(threads_per_problem=384)),
-             (5, dict(threads_per_problem=512)), (4, dict()), (4, dict(force_wide=1, threads_per_problem=256)),
-             (4, dict(force_wide=1, threads_per_problem=128)), (3, dict()), (3, dict(force_wide=1, threads_per_problem=64)),
-             (3, dict(force_wide=1, threads_per_problem=128)), (3, dict(threads_per_problem=1024, lanes_per_vertex=4))]
+    # the solver exists in builds for 5, 6 and 7 wavefronts per SIMD; a launch gets the one for min(what the LDS of a CU
+    # leaves room for, what the launch itself puts on a SIMD of the 256 CUs).  Reach each of them with both state widths
+    # and with rational multipliers: 160 distinct problems, repeated to make the launch as large as the case needs.
+    cases = [(5, 8, dict(threads_per_problem=256)), (5, 1, dict(threads_per_problem=320)), (5, 8, dict(threads_per_problem=384)),
+             (5, 1, dict(threads_per_problem=512)),
+             (4, 1, dict()), (4, 24, dict()), (4, 19, dict()), (4, 24, dict(force_wide=1, threads_per_problem=256)),
+             (4, 24, dict(force_wide=1, threads_per_problem=128)),
+             (3, 1, dict()), (3, 38, dict()), (3, 48, dict()), (3, 38, dict(force_wide=1, threads_per_problem=64)),
+             (3, 48, dict(force_wide=1, threads_per_problem=64)), (3, 24, dict(force_wide=1, threads_per_problem=128)),
+             (3, 2, dict(threads_per_problem=1024, lanes_per_vertex=4))]
     rng = np.random.default_rng(9)
     cache = {}
-    for cfg, opts in cases:
+    for cfg, rep, opts in cases:
         if cfg not in cache:
             topo = w.config_topology(cfg)
             inv = Fraction(*_optimum(cfg, topo))
@@ -211,11 +215,12 @@ def test_every_register_budget_gives_the_same_values():
             cache[cfg] = (topo, sink, num, den, k, o.aux_maxflow_batch(topo, sink, num, k, threads=16),
                           o.aux_maxflow_batch_floor(mt, sink, num, den, k, threads=16))
         topo, sink, num, den, k, want_int, want_floor = cache[cfg]
+        tile = lambda a: np.tile(a, rep)
         with _upload(topo) as g:
-            got, stats = _gpu_flows(g, sink, num, k, options=opts, want_stats=True)
-            assert (got == want_int).all() and stats["not_converged"] == 0, (cfg, opts)
-            got, _ = _gpu_flows_floor(g, sink, num, den, k, options=opts)
-            assert (got == want_floor).all(), (cfg, opts)
+            got, stats = _gpu_flows(g, tile(sink), tile(num), tile(k), options=opts, want_stats=True)
+            assert (got == tile(want_int)).all() and stats["not_converged"] == 0, (cfg, rep, opts)
+            got, _ = _gpu_flows_floor(g, tile(sink), tile(num), tile(den), tile(k), options=opts)
+            assert (got == tile(want_floor)).all(), (cfg, rep, opts)
 
 
 # ------------------------------------------------------------------ the first-arc tree certificate and the launch order
