@@ -1,14 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the batched max-flow feasibility path on one MI355X.
 
-One "step" is one pass of the hot path over one batch: `fc_feasible` on the 16 candidate
-throughputs of the largest benchmark configuration (1024 compute + 128 switch nodes, random
-out-degree-8 fabric) = 16 384 independent max-flows F(s, v) on the auxiliary network of the
-paper's Section 5.2 (preflow initialisation, discharge sweeps, relabeling, termination) plus
-the per-candidate verdict reduction of Theorem 1.  The topology is uploaded once, outside the
-timed region; candidate arrays are resident in HBM when the clock starts.
+One "step" is one pass of the hot path over one batch: `fc_maxflow_batch` on the 16 384 problems
+(1024 sinks x 16 candidate throughputs) of the largest benchmark configuration (1024 compute +
+128 switch nodes, random out-degree-8 fabric) -- launch ordering, preflow initialisation, discharge
+steps, relabeling, termination, one flow value per problem -- on the auxiliary network of the paper's
+Section 5.2.  The topology is uploaded once, outside the timed region (its cost is reported as
+`graph_upload_ms`); the problem arrays are resident in HBM when the clock starts.  The same problems
+through `fc_feasible` (candidate x sink grid + the verdict reduction of Theorem 1) are timed beside it,
+and so are the four smaller configurations.
 
-Prints ONE JSON line: metric, value (max-flow solves per second), roofline, cpu_baseline and side measurements.
+Prints ONE JSON line.  Every figure quoted in README.md can be re-derived from it:
+  value, ms_per_step            whole-step wall time over the timed region
+  roofline                      the dominant kernel against the vector-issue roof that binds it, with the
+                                algorithmic-bytes rate (with and without the per-problem init term) and the
+                                HBM traffic the hardware counters measured beside it
+  configs                       configs 1-4: solves/s for both entry points, counters, kernel time
+  graph_upload_ms, search       ingest + per-sink tables, and the optimality search on top of it
+  cpu_baseline, parity_vs_oracle
 """
 import argparse
 import json
@@ -21,18 +30,58 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# vector-issue roof: 256 CUs x 4 SIMDs, one wave64 instruction per 4 cycles (16 lanes per SIMD), 2.4 GHz
+VALU_PEAK_GINSTR = 256 * 4 * 2.4 / 4
 
 
 def algorithmic_bytes(stats, n_problems, n_with_source, m_with_source):
-    """Bytes the method itself must move for the work one launch did, in the plain 32-bit
-    layout: per arc scan a residual (4) and a height (4); per push two residuals and two
-    excesses (16); per relabel a height (4); per global relabel all residuals read and all
-    heights written; per problem the private state (2m residuals, n heights + excesses)
-    written once."""
+    """Bytes the method itself must move for the work one launch did, in the plain 32-bit layout that keeps all
+    state in memory: per arc scan a residual (4) and a height (4); per push two residuals and two excesses (16);
+    per relabel a height (4); per global relabel all residuals read and all heights written; per problem the
+    private state (2m residuals, n heights + excesses) written once -- the init term, returned separately."""
     n, m = n_with_source, m_with_source
     init = n_problems * (2 * m * 4 + n * 8)
-    return (8 * stats["arc_scans"] + 16 * stats["pushes"] + 4 * stats["relabels"] +
-            8 * stats["gr_arc_scans"] + stats["global_relabels"] * 4 * n + init)
+    dynamic = (8 * stats["arc_scans"] + 16 * stats["pushes"] + 4 * stats["relabels"] +
+               8 * stats["gr_arc_scans"] + stats["global_relabels"] * 4 * n)
+    return dynamic + init, init
+
+
+def load_counters():
+    """Per-launch hardware counters of the solver kernel from the committed rocprofv3 summaries."""
+    path = os.path.join(ROOT, "profiles", "counters.json")
+    try:
+        return json.load(open(path))
+    except Exception:
+        return {}
+
+
+def roofline_block(stats, kernel_ms, n_problems, n_src, m_src, hw):
+    """`hw`: {"valu_wave_instructions": .., "hbm_bytes": ..} per launch from profiles/counters.json, or {}."""
+    total, init = algorithmic_bytes(stats, n_problems, n_src, m_src)
+    sec = kernel_ms * 1e-3
+    valu = hw.get("valu_wave_instructions")
+    hbm = hw.get("hbm_bytes")
+    achieved = None if valu is None else valu / sec / 1e9
+    return {
+        # what binds the kernel (counters in profiles/): instruction issue, not memory -- all per-problem state is in LDS
+        "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_GINSTR, "unit": "G wave-instructions/s (vector ALU)",
+        "frac": None if achieved is None else achieved / VALU_PEAK_GINSTR,
+        "traffic": hbm,
+        "kernel": "fc_push_relabel_kernel", "kernel_ms": kernel_ms,
+        "kernel_ms_is": "mean HIP-event time of the solver kernel over launches that write no counters (stats_time_only)",
+        "valu_wave_instructions_per_launch": valu,
+        "hbm": {
+            "note": "algorithmic bytes = what a plain 32-bit in-memory layout would move for the counted work; the kernel "
+                    "keeps that state in LDS, so measured HBM traffic is a small fraction of it",
+            "algorithmic_bytes_per_launch": int(total), "algorithmic_init_bytes": int(init),
+            "algorithmic_gbs": total / sec / 1e9, "algorithmic_frac_of_peak": total / sec / 1e9 / HBM_PEAK_GBS,
+            "algorithmic_frac_without_init": (total - init) / sec / 1e9 / HBM_PEAK_GBS,
+            "measured_bytes_per_launch": hbm,
+            "measured_gbs": None if hbm is None else hbm / sec / 1e9,
+            "measured_frac_of_peak": None if hbm is None else hbm / sec / 1e9 / HBM_PEAK_GBS,
+            "peak_gbs": HBM_PEAK_GBS,
+        },
+    }
 
 
 def main():
@@ -42,12 +91,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-certificate-leg", action="store_true",
-                    help="skip the side measurement with tree_certificate=1 (keeps profiler traces to one kind of launch)")
-    ap.add_argument("--config4-back-end", action="store_true",
-                    help="also time switch removal and tree construction on config 4 (about 10 s more)")
-    ap.add_argument("--tree-leg-config", type=int, default=3, choices=[1, 3],
-                    help="config whose switch-free digraph the spanning-tree side leg runs on")
+    ap.add_argument("--quick", action="store_true",
+                    help="headline and fc_feasible legs only (keeps profiler traces to the two kinds of launch)")
+    ap.add_argument("--only", choices=["batch", "feasible"], default=None,
+                    help="with --quick: time only this entry point (one kind of solver launch in a profile)")
+    ap.add_argument("--back-end", type=int, default=3, choices=[0, 3, 4, 6],
+                    help="topology for the switch-removal + tree-construction leg: config 3 (default), config 4, "
+                         "6 = the 1024-compute Eulerian switch fabric (tens of seconds), 0 = skip")
     ap.add_argument("--threads-per-problem", type=int, default=0)
     ap.add_argument("--lanes-per-vertex", type=int, default=0)
     ap.add_argument("--copy-probe", action="store_true",
@@ -85,89 +135,136 @@ def main():
                           "copies": 5}), flush=True)
         return
 
-    cfg = args.config
-    topo = w.config_topology(cfg)
-    g = fc.fc_graph_upload(topo.n_vertices, topo.tail, topo.head, topo.bandwidth, topo.is_compute)
-    info = fc.fc_graph_info(g)
-    N = info.n_compute
+    hw_all = load_counters()
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
 
-    # candidates: configs 2 and 5 centre them on the optimum, found here by the library's own search
-    t0 = time.perf_counter()
-    search = fc.fc_opt_throughput_search(g, 16)
-    search_cold_ms = (time.perf_counter() - t0) * 1e3      # the process's first launches: code objects are loaded here
-    t0 = time.perf_counter()
-    search = fc.fc_opt_throughput_search(g, 16)
-    search_ms = (time.perf_counter() - t0) * 1e3
-    inv = (search["inv_xstar"].numerator, search["inv_xstar"].denominator)
-    cU, ck = config_candidates(cfg, inv)
-    C = len(cU)
-    P = C * N
-    d_U = torch.from_numpy(cU).to(dev); d_k = torch.from_numpy(ck).to(dev)
-    opts = {"src_cap_bound": int(ck.max())}
-    if args.threads_per_problem:
-        opts["threads_per_problem"] = args.threads_per_problem
-    if args.lanes_per_vertex:
-        opts["lanes_per_vertex"] = args.lanes_per_vertex
-    ws = torch.empty(fc.fc_feasible_workspace_bytes(g, C), dtype=torch.uint8, device=dev)
+    def timed(fn, warmup, steps):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
 
-    def step(want_stats=False, want_flows=False):
-        return fc.fc_feasible(g, d_U, d_k, want_flows=want_flows, want_witness=True, d_workspace=ws,
-                              options=opts, want_stats=want_stats)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-    solves_per_s = P * args.steps / elapsed
-
-    # the same 16384 problems as an explicit (sink, U, k) list through fc_maxflow_batch: the same solver
-    # kernel behind a per-problem ordering kernel instead of the per-sink one; reported beside the headline
-    batch_leg = None
-    if not args.no_certificate_leg:
+    def measure_config(cfg, steps, warmup, want=("batch", "feasible")):
+        """Upload, search, and time both entry points on one configuration's problem list."""
+        topo = w.config_topology(cfg)
+        t0 = time.perf_counter()
+        g = fc.fc_graph_upload(topo.n_vertices, topo.tail, topo.head, topo.bandwidth, topo.is_compute)
+        upload_ms = (time.perf_counter() - t0) * 1e3
+        info = fc.fc_graph_info(g)
+        N = info.n_compute
+        t0 = time.perf_counter()
+        search = fc.fc_opt_throughput_search(g, 16)
+        search_first_ms = (time.perf_counter() - t0) * 1e3     # may include loading code objects (first launches of the process)
+        t0 = time.perf_counter()
+        search = fc.fc_opt_throughput_search(g, 16)
+        search_ms = (time.perf_counter() - t0) * 1e3
+        inv = (search["inv_xstar"].numerator, search["inv_xstar"].denominator)
+        cU, ck = config_candidates(cfg, inv)               # configs 2 and 5 centre their candidates on the optimum
+        C = len(cU); P = C * N
         pl = w.all_sinks(topo, cU, ck)
-        d_sink, d_mult, d_cap = (torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev) for a in (pl.sink, pl.edge_mult, pl.src_cap))
-        ws_b = torch.empty(fc.fc_maxflow_batch_workspace_bytes(g, P), dtype=torch.uint8, device=dev)
+        opts = {"src_cap_bound": int(ck.max())}
+        if args.threads_per_problem:
+            opts["threads_per_problem"] = args.threads_per_problem
+        if args.lanes_per_vertex:
+            opts["lanes_per_vertex"] = args.lanes_per_vertex
+        n_src, m_src = topo.n_vertices + 1, info.n_arcs_merged + N
+        d_sink, d_mult, d_cap = to_dev(pl.sink), to_dev(pl.edge_mult), to_dev(pl.src_cap)
+        d_U, d_k = to_dev(cU), to_dev(ck)
+        ws_b = torch.empty(max(256, fc.fc_maxflow_batch_workspace_bytes(g, P)), dtype=torch.uint8, device=dev)
+        ws_f = torch.empty(max(256, fc.fc_feasible_workspace_bytes(g, C)), dtype=torch.uint8, device=dev)
         d_out = torch.empty(P, dtype=torch.int32, device=dev)
-        for _ in range(args.warmup):
-            fc.fc_maxflow_batch(g, d_sink, d_mult, d_cap, d_flow_out=d_out, d_workspace=ws_b, options=opts)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            fc.fc_maxflow_batch(g, d_sink, d_mult, d_cap, d_flow_out=d_out, d_workspace=ws_b, options=opts)
-        torch.cuda.synchronize()
-        el = time.perf_counter() - t0
-        batch_leg = {"value": P * args.steps / el, "unit": "solves/s", "ms_per_step": el / args.steps * 1e3,
-                     "note": "explicit problem list; not the headline"}
-        for _ in range(3):
-            step()
-        torch.cuda.synchronize()
+        batch = lambda **kw: fc.fc_maxflow_batch(g, d_sink, d_mult, d_cap, d_flow_out=d_out, d_workspace=ws_b,
+                                                 options=dict(opts, **kw.pop("o", {})), **kw)
+        feas = lambda **kw: fc.fc_feasible(g, d_U, d_k, want_witness=True, d_workspace=ws_f,
+                                           options=dict(opts, **kw.pop("o", {})), **kw)
+        res = {"config": cfg, "workload": f"{w.CONFIG_NAMES[cfg]}: {N} sinks x {C} candidates = {P} max-flows per step "
+                                          f"(|V|={topo.n_vertices}, merged arcs={info.n_arcs_merged}, k={int(ck[0])}, "
+                                          f"U={int(cU[0])}..{int(cU[-1])}, 1/x*={inv[0]}/{inv[1]})",
+               "problems_per_step": P, "graph_upload_ms": upload_ms,
+               "search": {"inv_xstar": f"{inv[0]}/{inv[1]}", "U": str(search["U"]), "k": search["k"], "rounds": search["rounds"],
+                          "candidates_tested": search["trace_len"], "wall_ms": search_ms, "first_call_wall_ms": search_first_ms,
+                          "incl_upload_ms": upload_ms + search_ms}}
+        for name, fn in (("batch", batch), ("feasible", feas)):
+            if name not in want:
+                continue
+            per_step = timed(lambda: fn(), warmup, steps)
+            kms = []
+            for _ in range(min(steps, 20)):                  # solver kernel alone, launches that write no counters
+                r = fn(want_stats=True, o={"stats_time_only": 1})
+                kms.append((r[1] if name == "batch" else r["stats"])["device_ms"])
+            r = fn(want_stats=True)                          # one launch that counts its work
+            st = r[1] if name == "batch" else r["stats"]
+            for _ in range(3):
+                fn()                                         # the cost hints as the plain path leaves them
+            kernel_ms = float(np.mean(kms))
+            entry = "fc_maxflow_batch" if name == "batch" else "fc_feasible"
+            hw = hw_all.get(f"cfg{cfg}", {}).get(entry, {})
+            res[entry] = {"value": P / per_step, "unit": "solves/s", "ms_per_step": per_step * 1e3,
+                          "kernel_ms": kernel_ms, "kernel_ms_counting_launch": st["device_ms"],
+                          "residual_edge_updates_per_sec": st["pushes"] / (kernel_ms * 1e-3),
+                          "arc_scans_per_sec": st["arc_scans"] / (kernel_ms * 1e-3),
+                          "per_launch": {k: int(v) for k, v in st.items() if k != "device_ms"},
+                          "roofline": roofline_block(st, kernel_ms, P, n_src, m_src, hw)}
+        handles = dict(g=g, topo=topo, info=info, N=N, P=P, C=C, cU=cU, ck=ck, pl=pl, opts=opts, d_U=d_U, d_k=d_k, ws_f=ws_f,
+                       feas=feas, batch=batch, d_out=d_out)
+        return res, handles
 
-    # the same step with the optional first-arc tree certificate (problems whose sink tree carries
-    # all N*k units are answered without running the solver); reported beside the headline, never as it
-    elapsed_cert = None
-    if not args.no_certificate_leg:
-        opts_cert = dict(opts, tree_certificate=1)
-        for _ in range(args.warmup):
-            fc.fc_feasible(g, d_U, d_k, want_witness=True, d_workspace=ws, options=opts_cert)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            fc.fc_feasible(g, d_U, d_k, want_witness=True, d_workspace=ws, options=opts_cert)
-        torch.cuda.synchronize()
-        elapsed_cert = time.perf_counter() - t0
+    # a first tiny upload + launch so that HIP initialisation and code-object loading are not billed to the ingest figure
+    tw = w.config_topology(1)
+    with fc.fc_graph_upload(tw.n_vertices, tw.tail, tw.head, tw.bandwidth, tw.is_compute) as g0:
+        fc.fc_opt_throughput_search(g0, 4)
+    torch.cuda.synchronize()
+
+    cfg = args.config
+    want = ("batch", "feasible") if not args.only else (args.only,)
+    head, H = measure_config(cfg, args.steps, args.warmup, want)
+    g, topo, N, P, C = H["g"], H["topo"], H["N"], H["P"], H["C"]
+    cU, ck, opts, d_U, d_k, ws = H["cU"], H["ck"], H["opts"], H["d_U"], H["d_k"], H["ws_f"]
+    main_leg = head["fc_maxflow_batch"] if "fc_maxflow_batch" in head else head["fc_feasible"]
+    entry_point = "fc_maxflow_batch" if "fc_maxflow_batch" in head else "fc_feasible"
+
+    out = {
+        "metric": "max-flow solves/sec", "value": main_leg["value"], "unit": "solves/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_leg["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": head["workload"], "entry_point": entry_point, "problems_per_step": P},
+        "residual_edge_updates_per_sec": main_leg["residual_edge_updates_per_sec"],
+        "arc_scans_per_sec": main_leg["arc_scans_per_sec"],
+        "kernel_ms": main_leg["kernel_ms"],
+        "per_launch": main_leg["per_launch"],
+        "roofline": main_leg["roofline"],
+        "fc_feasible": head.get("fc_feasible") if entry_point != "fc_feasible" else None,
+        "graph_upload_ms": head["graph_upload_ms"],
+        "graph_upload_is": "fc_graph_upload: validation, merging, residual CSR, per-sink label / first-arc tables on host threads, copies",
+        "search": head["search"],
+    }
+
+    if not args.quick:
+        # ---- the four smaller configurations, both entry points (a few ms each)
+        out["configs"] = []
+        for c in (1, 2, 3, 4):
+            if c == cfg:
+                continue
+            r, h = measure_config(c, max(10, args.steps), max(3, args.warmup // 2))
+            h["g"].close()
+            out["configs"].append(r)
+
+        # ---- the same step with the optional first-arc tree certificate (problems whose sink tree carries all
+        # N*k units are answered without running the solver); reported beside the headline, never as it
+        el = timed(lambda: H["feas"](o={"tree_certificate": 1}), args.warmup, args.steps)
+        out["with_tree_certificate"] = {"value": P / el, "unit": "solves/s", "ms_per_step": el * 1e3,
+                                        "note": "fc_feasible with option tree_certificate=1; not the headline"}
         for _ in range(3):                               # restore the cost hints the plain path leaves
-            step()
+            H["feas"]()
         torch.cuda.synchronize()
 
-    # the fixed-k variant (Section 5.5, Algorithm 3) on the same topology: k = 2, 16 rational multipliers
-    # around U*, capacities floor(U b_e); a side measurement, not the headline
-    fixed = None
-    if not args.no_certificate_leg:
+        # ---- the fixed-k variant (Section 5.5, Algorithm 3) on the same topology: k = 2, 16 rational multipliers
+        # around U*, capacities floor(U b_e)
         kfix = 2
         t0 = time.perf_counter()
         fk = fc.fc_fixed_k_search(g, kfix, 16)
@@ -178,17 +275,10 @@ def main():
         f_k = np.full(16, kfix, dtype=np.int32)
         dn, dd, dk2 = (torch.from_numpy(a).to(dev) for a in (f_num, f_den, f_k))
         fopts = {"src_cap_bound": kfix}
-        for _ in range(args.warmup):
-            fc.fc_feasible_floor(g, dn, dd, dk2, d_workspace=ws, options=fopts)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            fc.fc_feasible_floor(g, dn, dd, dk2, d_workspace=ws, options=fopts)
-        torch.cuda.synchronize()
-        el = time.perf_counter() - t0
+        el = timed(lambda: fc.fc_feasible_floor(g, dn, dd, dk2, d_workspace=ws, options=fopts), args.warmup, args.steps)
         fixed = {"k": kfix, "U_star": f"{Us.numerator}/{Us.denominator}", "search_wall_ms": fk_ms,
-                 "search_rounds": fk["rounds"], "value": 16 * N * args.steps / el, "unit": "solves/s",
-                 "ms_per_step": el / args.steps * 1e3, "candidates": "16 multipliers (num - 8 + j) / den around U*"}
+                 "search_rounds": fk["rounds"], "value": 16 * N / el, "unit": "solves/s",
+                 "ms_per_step": el * 1e3, "candidates": "16 multipliers (num - 8 + j) / den around U*"}
         if not args.no_cpu_baseline:
             import oracle
             fl = fc.fc_feasible_floor(g, dn, dd, dk2, want_flows=True, options=fopts)["flows"].cpu().numpy().astype(np.int64)
@@ -198,14 +288,13 @@ def main():
                                                  np.repeat(f_den[pick], N), np.repeat(f_k[pick], N),
                                                  threads=max(1, min(16, os.cpu_count() or 1)))
             fixed["parity_vs_oracle"] = {"checked": int(ref.size), "mismatches": int((fl[pick].reshape(-1) != ref).sum())}
+        out["fixed_k"] = fixed
         for _ in range(3):                               # restore the cost hints of the headline workload
-            step()
+            H["feas"]()
         torch.cuda.synchronize()
 
-    # edge-splitting gamma batches (Appendix E.2, Theorem 10) on the DGX-A100-shaped config, which is Eulerian:
-    # 256 (ingress, egress) pairs x 2N max-flows with explicit sources and unbounded arcs; side measurement
-    gamma = None
-    if not args.no_certificate_leg:
+        # ---- edge-splitting gamma batches (Appendix E.2) on the DGX-A100-shaped config, which is Eulerian:
+        # 256 (ingress, egress) pairs x 2N max-flows with explicit sources and unbounded arcs
         t3 = w.config_topology(3)
         g3 = fc.fc_graph_upload(t3.n_vertices, t3.tail, t3.head, t3.bandwidth, t3.is_compute)
         s3 = fc.fc_opt_throughput_search(g3, 16)
@@ -221,29 +310,16 @@ def main():
                 continue
             outs = np.flatnonzero(tl == hd[e])
             pu.append(int(tl[e])); pw.append(int(hd[e])); pt.append(int(hd[outs[int(rng.integers(0, len(outs)))]]))
-        d3 = [torch.from_numpy(np.array(a, dtype=np.int32)).to(dev) for a in (pu, pw, pt)]
+        d3 = [to_dev(np.array(a, dtype=np.int32)) for a in (pu, pw, pt)]
         ws3 = torch.empty(fc.fc_split_gamma_workspace_bytes(g3, 256), dtype=torch.uint8, device=dev)
-        for _ in range(3):
-            fc.fc_split_gamma_batch(g3, U3, k3, *d3, d_workspace=ws3)
-        torch.cuda.synchronize()
         reps = max(1, args.steps // 10)
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            fc.fc_split_gamma_batch(g3, U3, k3, *d3, d_workspace=ws3)
-        torch.cuda.synchronize()
-        el = (time.perf_counter() - t0) / reps
+        el = timed(lambda: fc.fc_split_gamma_batch(g3, U3, k3, *d3, d_workspace=ws3), 3, reps)
         P3 = 256 * 2 * t3.n_compute
         gamma = {"workload": f"{w.CONFIG_NAMES[3]} scaled by U={U3}, k={k3}: 256 pairs x 2N = {P3} max-flows per step",
                  "value": P3 / el, "unit": "solves/s", "ms_per_step": el * 1e3,
-                 "note": "gamma only: a max-flow may stop once it cannot decide gamma any more, and is answered from the problem without its compute node v where that one already got there (two launches)"}
-        for _ in range(3):
-            fc.fc_split_gamma_batch(g3, U3, k3, *d3, want_flows=True, d_workspace=ws3)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            fc.fc_split_gamma_batch(g3, U3, k3, *d3, want_flows=True, d_workspace=ws3)
-        torch.cuda.synchronize()
-        el = (time.perf_counter() - t0) / reps
+                 "note": "gamma only: a max-flow may stop once it cannot decide gamma any more, and is answered from the problem "
+                         "without its compute node v where that one already got there (two launches)"}
+        el = timed(lambda: fc.fc_split_gamma_batch(g3, U3, k3, *d3, want_flows=True, d_workspace=ws3), 3, reps)
         gamma["with_exact_flows"] = {"value": P3 / el, "unit": "solves/s", "ms_per_step": el * 1e3}
         if not args.no_cpu_baseline:
             import oracle
@@ -253,117 +329,60 @@ def main():
             ref = [oracle.split_gamma(D3, k3, pu[i], pw[i], pt[i]) for i in range(0, 256, 32)]
             gamma["parity_vs_oracle"] = {"checked_pairs": len(ref), "mismatches": int(sum(int(got[i * 32]) != ref[i] for i in range(len(ref))))}
         g3.close()
-        # Algorithm 2's loop around such batches on the same graph (capacities U * b_e): every switch split off
-        cap3 = (np.asarray(t3.bandwidth, dtype=np.int64) * U3).astype(np.int32)
-        t0 = time.perf_counter()
-        rs = fc.fc_remove_switches(t3.n_vertices, t3.tail, t3.head, cap3, t3.is_compute, k3)
-        gamma["remove_switches"] = {"wall_ms": (time.perf_counter() - t0) * 1e3, "batches": rs["batches"],
-                                    "links_out": len(rs["links"]), "table_entries": sum(len(v) for v in rs["table"].values())}
-        # spanning tree construction (Appendix E.3) on a switch-free digraph: mu for all candidate edges of a state per launch
-        if args.tree_leg_config == 3:
-            tt, Ut, kt, rt = t3, U3, k3, rs
-        else:
-            tt = w.config_topology(1)
-            gt = fc.fc_graph_upload(tt.n_vertices, tt.tail, tt.head, tt.bandwidth, tt.is_compute)
-            st_ = fc.fc_opt_throughput_search(gt, 16)
-            Ut, kt = st_["U"].numerator, st_["k"] * st_["U"].denominator
-            gt.close()
-            rt = fc.fc_remove_switches(tt.n_vertices, tt.tail, tt.head, (np.asarray(tt.bandwidth, dtype=np.int64) * Ut).astype(np.int32), tt.is_compute, kt)
-        comp_t = np.flatnonzero(np.asarray(tt.is_compute)).tolist()
-        idx_t = {v: i for i, v in enumerate(comp_t)}
-        links_t = {(idx_t[a], idx_t[b]): c for (a, b), c in rt["links"].items()}
-        t0 = time.perf_counter()
-        tr = fc.fc_construct_trees(len(comp_t), links_t, kt)
-        gamma["construct_trees"] = {"workload": f"{tt.name} after switch removal: {len(comp_t)} nodes, {len(links_t)} links, k={kt}",
-                                    "wall_ms": (time.perf_counter() - t0) * 1e3, "launches": tr["batches"], "root_sets": len(tr["trees"])}
-        # what the construction promises: out-trees that span, k per root, no link used beyond its capacity
-        use_t, per_t, ok_t = {}, {}, True
-        for root_t, mult_t, edges_t in tr["trees"]:
-            seen_t = {root_t}
-            for x_t, y_t in edges_t:
-                ok_t = ok_t and x_t in seen_t and y_t not in seen_t
-                seen_t.add(y_t)
-                use_t[(x_t, y_t)] = use_t.get((x_t, y_t), 0) + mult_t
-            ok_t = ok_t and len(seen_t) == len(comp_t)
-            per_t[root_t] = per_t.get(root_t, 0) + mult_t
-        ok_t = ok_t and per_t == {u: kt for u in range(len(comp_t))} and all(c <= links_t[e] for e, c in use_t.items())
-        gamma["construct_trees"]["valid"] = bool(ok_t)
-        if args.config4_back_end:
-            # the same two stages on the largest switch topology (512 compute nodes, 84 switches), at its optimum from the library's search
-            t4 = w.config_topology(4)
-            g4 = fc.fc_graph_upload(t4.n_vertices, t4.tail, t4.head, t4.bandwidth, t4.is_compute)
-            s4 = fc.fc_opt_throughput_search(g4, 16)
-            U4, k4 = s4["U"].numerator, s4["k"] * s4["U"].denominator
-            g4.close()
+        out["split_gamma"] = gamma
+
+        # ---- the generator's back end on a whole topology: Algorithm 2's loop around gamma batches (every switch split
+        # off), then spanning tree construction (Appendix E.3) on the switch-free digraph it leaves
+        if args.back_end:
+            if args.back_end == 6:
+                tb = w.eulerian_fabric_1024()
+            else:
+                tb = w.config_topology(args.back_end)
+            gb = fc.fc_graph_upload(tb.n_vertices, tb.tail, tb.head, tb.bandwidth, tb.is_compute)
             t0 = time.perf_counter()
-            r4 = fc.fc_remove_switches(t4.n_vertices, t4.tail, t4.head, (np.asarray(t4.bandwidth, dtype=np.int64) * U4).astype(np.int32), t4.is_compute, k4)
-            el_r4 = time.perf_counter() - t0
-            comp4 = np.flatnonzero(np.asarray(t4.is_compute)).tolist()
-            idx4 = {v: i for i, v in enumerate(comp4)}
-            links4 = {(idx4[a], idx4[b]): c for (a, b), c in r4["links"].items()}
+            sb = fc.fc_opt_throughput_search(gb, 16)
+            search_b_ms = (time.perf_counter() - t0) * 1e3
+            Ub, kb = sb["U"].numerator, sb["k"] * sb["U"].denominator
+            gb.close()
+            capb = (np.asarray(tb.bandwidth, dtype=np.int64) * Ub).astype(np.int32)
             t0 = time.perf_counter()
-            tr4 = fc.fc_construct_trees(len(comp4), links4, k4)
-            el_t4 = time.perf_counter() - t0
-            edges4 = sum(m * len(e) for _, m, e in tr4["trees"])
-            gamma["config4_back_end"] = {"workload": f"{t4.name} at U = {U4}, k = {k4}: {len(comp4)} compute nodes, {t4.n_vertices - len(comp4)} switches",
-                                         "remove_switches": {"wall_ms": el_r4 * 1e3, "batches": r4["batches"], "links_out": len(r4["links"])},
-                                         "construct_trees": {"wall_ms": el_t4 * 1e3, "launches": tr4["batches"], "root_sets": len(tr4["trees"]),
-                                                             "tree_edges_with_multiplicity": int(edges4),
-                                                             "complete": bool(edges4 == len(comp4) * k4 * (len(comp4) - 1))}}
-
-    # the dominant kernel alone: HIP events recorded by the library on the launch stream around
-    # the solver kernel, same inputs, same launch configuration
-    kms, last = [], None
-    for _ in range(min(args.steps, 50)):
-        last = step(want_stats=True)
-        kms.append(last["stats"]["device_ms"])
-    st = last["stats"]
-    kernel_ms = float(np.mean(kms))
-    n_src, m_src = topo.n_vertices + 1, info.n_arcs_merged + N
-    bytes_alg = algorithmic_bytes(st, P, n_src, m_src)
-    achieved = bytes_alg / (kernel_ms * 1e-3) / 1e9
-
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(f"cfg{cfg}", {}).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
-
-    out = {
-        "metric": "max-flow solves/sec", "value": solves_per_s, "unit": "solves/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
-        "data": "synthetic",
-        "config": {"workload": f"{w.CONFIG_NAMES[cfg]}: {N} sinks x {C} candidates = {P} max-flows per step "
-                               f"(|V|={topo.n_vertices}, merged arcs={info.n_arcs_merged}, k={int(ck[0])}, "
-                               f"U={int(cU[0])}..{int(cU[-1])}, 1/x*={inv[0]}/{inv[1]})",
-                   "entry_point": "fc_feasible", "problems_per_step": P},
-        "residual_edge_updates_per_sec": st["pushes"] / (kernel_ms * 1e-3),
-        "arc_scans_per_sec": st["arc_scans"] / (kernel_ms * 1e-3),
-        "kernel_ms": kernel_ms,
-        "per_launch": {k: int(v) for k, v in st.items() if k != "device_ms"},
-        "with_tree_certificate": None if elapsed_cert is None else
-            {"value": P * args.steps / elapsed_cert, "unit": "solves/s", "ms_per_step": elapsed_cert / args.steps * 1e3,
-             "note": "option tree_certificate=1; not the headline"},
-        "fc_maxflow_batch": batch_leg,
-        "fixed_k": fixed,
-        "split_gamma": gamma,
-        "search": {"inv_xstar": f"{inv[0]}/{inv[1]}", "U": str(search["U"]), "k": search["k"],
-                   "rounds": search["rounds"], "candidates_tested": search["trace_len"], "wall_ms": search_ms,
-                   "first_call_wall_ms": search_cold_ms},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "fc_push_relabel_kernel", "algorithmic_bytes_per_launch": int(bytes_alg)},
-    }
+            rs = fc.fc_remove_switches(tb.n_vertices, tb.tail, tb.head, capb, tb.is_compute, kb)
+            el_r = time.perf_counter() - t0
+            comp_t = np.flatnonzero(np.asarray(tb.is_compute)).tolist()
+            idx_t = {v: i for i, v in enumerate(comp_t)}
+            links_t = {(idx_t[a], idx_t[b]): c for (a, b), c in rs["links"].items()}
+            t0 = time.perf_counter()
+            tr = fc.fc_construct_trees(len(comp_t), links_t, kb)
+            el_t = time.perf_counter() - t0
+            # what the construction promises: out-trees that span, k per root, no link used beyond its capacity
+            use_t, per_t, ok_t = {}, {}, True
+            for root_t, mult_t, edges_t in tr["trees"]:
+                seen_t = {root_t}
+                for x_t, y_t in edges_t:
+                    ok_t = ok_t and x_t in seen_t and y_t not in seen_t
+                    seen_t.add(y_t)
+                    use_t[(x_t, y_t)] = use_t.get((x_t, y_t), 0) + mult_t
+                ok_t = ok_t and len(seen_t) == len(comp_t)
+                per_t[root_t] = per_t.get(root_t, 0) + mult_t
+            ok_t = ok_t and per_t == {u: kb for u in range(len(comp_t))} and all(c <= links_t[e] for e, c in use_t.items())
+            out["back_end"] = {
+                "workload": f"{tb.name} at U = {Ub}, k = {kb}: {len(comp_t)} compute nodes, {tb.n_vertices - len(comp_t)} switches",
+                "search_wall_ms": search_b_ms,
+                "remove_switches": {"wall_ms": el_r * 1e3, "batches": rs["batches"], "links_out": len(rs["links"]),
+                                    "table_entries": sum(len(v) for v in rs["table"].values())},
+                "construct_trees": {"wall_ms": el_t * 1e3, "launches": tr["batches"], "root_sets": len(tr["trees"]),
+                                    "tree_edges_with_multiplicity": int(sum(m * len(e) for _, m, e in tr["trees"])),
+                                    "valid": bool(ok_t)}}
+        for _ in range(3):
+            H["feas"]()
+        torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
         import oracle
-        flows = step(want_flows=True)["flows"]
+        flows = H["feas"](want_flows=True)["flows"]
         torch.cuda.synchronize()
         gpu_flows = flows.cpu().numpy().astype(np.int64).reshape(-1)
-        pl = w.all_sinks(topo, cU, ck)
+        pl = H["pl"]
         cores = max(1, min(16, os.cpu_count() or 1))
         # bounded sample: about 20 s of single-core work at ~1.2 ms per solve on the largest config
         stride = max(1, P // 16384)
@@ -379,7 +398,9 @@ def main():
                                "sample": f"{len(idx)} of the step's {P} problems (Dinic, gcc -O2, problems split "
                                          f"statically over {cores} threads)",
                                "single_thread_value": len(idx1) / t_one, "single_thread_sample": len(idx1)}
-        out["parity_vs_oracle"] = {"checked": int(len(idx)), "mismatches": int((gpu_flows[idx] != ref).sum())}
+        batch_flows = H["d_out"].cpu().numpy().astype(np.int64) if entry_point == "fc_maxflow_batch" else gpu_flows
+        out["parity_vs_oracle"] = {"checked": int(len(idx)), "mismatches": int((gpu_flows[idx] != ref).sum()),
+                                   "mismatches_fc_maxflow_batch": int((batch_flows[idx] != ref).sum())}
     g.close()
     print(json.dumps(out), flush=True)
 

@@ -112,6 +112,9 @@ typedef struct {
                                       Default: on for a batch with at least twice as many max-flows as the device
                                       holds workgroups at a time (a smaller batch lasts as long as its slowest
                                       problem either way, and a second launch only adds to that)               */
+    int32_t stats_time_only;       /* fc_maxflow_batch(_floor), fc_feasible(_floor) with stats: 1 = fill device_ms only.  The
+                                      kernels then run exactly as without stats (counting costs a few per cent: every
+                                      problem adds its counters up on chip and writes 32 bytes); the counters read 0  */
 } fc_options;
 
 /* ------------------------------------------------------------------------------------------
