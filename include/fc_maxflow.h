@@ -302,7 +302,7 @@ int fc_fixed_k_search_with_verdicts(int32_t n_compute, int64_t min_in_bw, int32_
                                     fc_rational *U_star, int32_t *rounds_or_null);
 
 /* ------------------------------------------------------------------------------------------
- * Edge splitting (Appendix E.2, Theorem 10).  D is the uploaded graph with every link capacity
+ * Edge splitting (Appendix E.2, the theorem that gives the maximum capacity gamma that can be split off).  D is the uploaded graph with every link capacity
  * multiplied by the integer U (the stage works on G({U b_e}); rescale the bandwidths first when
  * Proposition 3's U is a fraction), k the number of trees per compute node.  For pair i,
  * e = (u_i, w_i), f = (w_i, t_i) with w_i a switch node, gamma_i is the most capacity of e and f that can

@@ -5,7 +5,7 @@ package; it shares no code with the HIP library and never imports it.
 """
 from .reference import (Disconnected, build_c, maxflow, aux_network, aux_maxflow,
                         aux_maxflow_batch, feasible, in_bandwidths,
-                        min_compute_in_bandwidth, fraction_in_interval,
+                        min_compute_in_bandwidth, fraction_in_interval, smallest_true_fraction,
                         optimality_binary_search, smallest_U_k, brute_inv_xstar,
                         brute_min_cut, brute_cut_condition, aux_maxflow_batch_floor,
                         fixed_k_feasible, fixed_k_binary_search, brute_fixed_k, links, link_capacities, is_eulerian,

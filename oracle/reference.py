@@ -9,19 +9,19 @@ the paper (ForestColl, arXiv 2402.06787):
   (Dinic, Edmonds-Karp), or by brute-force cut enumeration (`brute_min_cut`).
 * the feasibility verdict of Theorem 1 / the integer form after Proposition 3
   (`feasible`).
-* 1/x* by Algorithm 1 taken literally in exact rational arithmetic
-  (`optimality_binary_search`), or by enumerating every cut of the bound (star) of
+* 1/x* by the search of Algorithm 1 in exact rational arithmetic (`optimality_binary_search`,
+  around `smallest_true_fraction`), or by enumerating every cut of the bound (star) of
   Section 4 (`brute_inv_xstar`).
 * (U, k) by the gcd rule of Section 5.2 "Determine k" / Proposition 3 (`smallest_U_k`).
 * the non-uniform variant (Section 5.7): source arcs of capacity m_c * k (`weighted_aux_network`,
   `weighted_aux_maxflow_batch`, `weighted_feasible`).
-* edge splitting (Appendix E.2): the 2N max-flows and gamma of Theorem 10 (`split_flows`,
+* edge splitting (Appendix E.2): the 2N max-flows and gamma of the maximum-split-off theorem (`split_flows`,
   `split_gamma`), gamma by its definition (`brute_split_gamma`), the split graph (`split_off`), and the loop of
   Algorithm 2 around them (`remove_switches`).
 * spanning tree construction (Appendix E.3): mu by one max-flow on the network D-bar (`tree_mu`), mu by its
   definition over all cuts (`brute_tree_mu`), and the construction loop around it (`construct_trees`).
 * the fixed-k variant (Section 5.5, Appendix E.4): the verdict on the network with capacities
-  floor(U b_e) for a rational U (`fixed_k_feasible`), U* by Algorithm 3 taken literally in
+  floor(U b_e) for a rational U (`fixed_k_feasible`), U* by the search of Algorithm 3 in
   exact rationals (`fixed_k_binary_search`), or by trying every fraction j / b_e
   (`brute_fixed_k`).
 
@@ -251,8 +251,9 @@ def min_compute_in_bandwidth(topo):
 
 
 def fraction_in_interval(l: Fraction, r: Fraction, max_den: int) -> Fraction:
-    """The fraction p/q in the closed interval [l, r] with q <= max_den (Algorithm 1,
-    last step), by brute force over denominators.  It must be unique."""
+    """The fraction p/q in the closed interval [l, r] with q <= max_den, by brute force over denominators.
+    It must be unique (two different fractions with denominators <= max_den are at least 1 / max_den^2 apart,
+    Proposition 2)."""
     found = set()
     for q in range(1, max_den + 1):
         p_lo = -((-l.numerator * q) // l.denominator)      # ceil(l*q)
@@ -264,30 +265,42 @@ def fraction_in_interval(l: Fraction, r: Fraction, max_den: int) -> Fraction:
     return found.pop()
 
 
+def smallest_true_fraction(verdict, below: Fraction, above: Fraction, max_den: int, note=None) -> Fraction:
+    """The threshold of a monotone verdict when that threshold is known to be a fraction with denominator
+    <= max_den inside [below, above]: verdict(z) is False for z under the threshold and True from it on,
+    `above` is known to be True.  The bracket is halved in exact rationals -- the lower end only ever moves to
+    a False point, the upper end to a True point, so the threshold stays inside -- until it is narrower than
+    the gap 1 / max_den^2 between two such fractions (Proposition 2); the threshold is then the only such
+    fraction the closed bracket holds.  This is the search of Algorithm 1 and of Algorithm 3; what differs
+    between them is the verdict, the range and the denominator bound.  `note(z, verdict)` sees every test."""
+    lo, hi = Fraction(below), Fraction(above)
+    gap = Fraction(1, max_den * max_den)
+    halvings = 0
+    while hi - lo >= gap:
+        z = (lo + hi) / 2
+        ok = bool(verdict(z))
+        if note is not None:
+            note(z, ok)
+        lo, hi = (lo, z) if ok else (z, hi)
+        halvings += 1
+    return fraction_in_interval(lo, hi, max_den), halvings
+
+
 def optimality_binary_search(topo, algo="dinic", threads=1, log=None):
-    """Algorithm 1 (Optimality Binary Search) in exact rationals.  Returns 1/x* as a
-    Fraction; `log`, if a list, receives (A, D, verdict) for every candidate A/D tested."""
+    """1/x* as a Fraction, by the search of Algorithm 1 in exact rationals.  Theorem 1: a candidate 1/x is at
+    or above 1/x* exactly when every compute node receives N x from s in the auxiliary network; Appendix E.1:
+    1/x* lies in [(N-1)/B, N-1] and its denominator is at most B = min over compute nodes of B^-(v).  A
+    candidate A/D is tested on integers (capacities A b_e, source arcs D).  `log`, if a list, receives
+    (A, D, verdict) for every candidate tested and a final ("rounds", count, None)."""
     N = topo.n_compute
     if N < 2:
         raise ValueError("need at least two compute nodes")
     B = min_compute_in_bandwidth(topo)
     if B < 1 or not feasible(topo, N - 1, 1, algo, threads)[0]:
         raise Disconnected()
-    l = Fraction(N - 1, B)
-    r = Fraction(N - 1, 1)
-    width = Fraction(1, B * B)
-    rounds = 0
-    while r - l >= width:
-        mid = (l + r) / 2
-        ok, _ = feasible(topo, mid.numerator, mid.denominator, algo, threads)
-        if log is not None:
-            log.append((mid.numerator, mid.denominator, ok))
-        if ok:
-            r = mid
-        else:
-            l = mid
-        rounds += 1
-    result = fraction_in_interval(l, r, B)
+    note = None if log is None else (lambda z, ok: log.append((z.numerator, z.denominator, ok)))
+    result, rounds = smallest_true_fraction(lambda z: feasible(topo, z.numerator, z.denominator, algo, threads)[0],
+                                            Fraction(N - 1, B), Fraction(N - 1), B, note)
     if log is not None:
         log.append(("rounds", rounds, None))
     return result
@@ -367,9 +380,11 @@ def fixed_k_feasible(topo, U: Fraction, k, algo="dinic", threads=1):
 
 
 def fixed_k_binary_search(topo, k, algo="dinic", threads=1, log=None):
-    """Algorithm 3 (Fixed-k Binary Search) in exact rationals.  Returns U* = 1/y*, the smallest U
-    for which k edge-disjoint out-trees per compute node exist in G({floor(U b_e)}); the
-    communication time is M/(N k) * U*.  `log`, if a list, receives (U, verdict) per test."""
+    """U* = 1/y*, the smallest U for which k edge-disjoint out-trees per compute node exist in
+    G({floor(U b_e)}) (the communication time is M/(N k) * U*), by the search of Algorithm 3 in exact
+    rationals.  Appendix E.4: the verdict is monotone in U, U* lies in [(N-1) k / B, (N-1) k], and some
+    U* b_e is an integer, so its denominator is at most the largest link bandwidth.  `log`, if a list,
+    receives (U, verdict) per test."""
     N = topo.n_compute
     k = int(k)
     if N < 2 or k < 1:
@@ -378,19 +393,9 @@ def fixed_k_binary_search(topo, k, algo="dinic", threads=1, log=None):
     if B < 1 or not fixed_k_feasible(topo, Fraction((N - 1) * k), k, algo, threads)[0]:
         raise Disconnected()
     bmax = int(links(topo)[2].max())
-    l = Fraction((N - 1) * k, B)
-    r = Fraction((N - 1) * k, 1)
-    width = Fraction(1, bmax * bmax)
-    while r - l >= width:
-        mid = (l + r) / 2
-        ok, _ = fixed_k_feasible(topo, mid, k, algo, threads)
-        if log is not None:
-            log.append((mid, ok))
-        if ok:
-            r = mid
-        else:
-            l = mid
-    return fraction_in_interval(l, r, bmax)
+    note = None if log is None else (lambda z, ok: log.append((z, ok)))
+    return smallest_true_fraction(lambda z: fixed_k_feasible(topo, z, k, algo, threads)[0],
+                                  Fraction((N - 1) * k, B), Fraction((N - 1) * k), bmax, note)[0]
 
 
 def brute_fixed_k(topo, k, algo="dinic"):
@@ -411,7 +416,7 @@ def brute_fixed_k(topo, k, algo="dinic"):
     raise AssertionError("the upper end of the range was feasible")
 
 
-# ------------------------------------------------------------------ edge splitting (Appendix E.2, Theorem 10)
+# ------------------------------------------------------------------ edge splitting (Appendix E.2, the maximum-split-off theorem)
 
 def link_capacities(topo):
     """{(tail, head): bandwidth} over the links."""
@@ -436,7 +441,7 @@ def unbounded(topo, k):
 
 
 def split_flows(topo, k, u, w, t, algo="dinic"):
-    """The 2N max-flows of Theorem 10 for splitting off e = (u, w), f = (w, t) in the integer-capacity
+    """The 2N max-flows of the maximum-split-off theorem (Appendix E.2) for splitting off e = (u, w), f = (w, t) in the integer-capacity
     digraph D = topo (capacities are the link bandwidths).  With s joined to every compute node by k:
       F1[v] = F(u, w; D_k + infinite arcs (u, s), (u, t), (v, w)),
       F2[v] = F(w, t; D_k + infinite arcs (w, s), (u, t), (v, t)),   v over the compute nodes,
@@ -462,7 +467,7 @@ def split_flows(topo, k, u, w, t, algo="dinic"):
 
 
 def split_gamma(topo, k, u, w, t, algo="dinic"):
-    """gamma of Theorem 10: the most capacity of e = (u, w) and f = (w, t) that can be replaced by a
+    """gamma of the maximum-split-off theorem (Appendix E.2): the most capacity of e = (u, w) and f = (w, t) that can be replaced by a
     direct arc (u, t) while min over compute nodes v of F(s, v) stays >= N k."""
     cap = link_capacities(topo)
     F1, F2 = split_flows(topo, k, u, w, t, algo)
@@ -500,7 +505,7 @@ def brute_split_gamma(topo, k, u, w, t, algo="dinic"):
 
 def remove_switches(topo, k, algo="dinic"):
     """Algorithm 2 (Remove Switch Nodes) on the integer-capacity Eulerian digraph D = topo: for every
-    switch w, every egress link f = (w, t) and every ingress link e = (u, w), split off gamma (Theorem 10)
+    switch w, every egress link f = (w, t) and every ingress link e = (u, w), split off gamma (the maximum-split-off theorem)
     when it is positive.  Switches, egress heads and ingress tails are visited in increasing id order;
     the links of w are listed when the loop over them starts, as in the pseudocode.  Returns (D*, table)
     with D* the resulting compute-only digraph and table[(u, t)][w] the capacity of (u, t) that is
@@ -522,7 +527,7 @@ def remove_switches(topo, k, algo="dinic"):
                         table.setdefault((u, t), {})
                         table[(u, t)][w] = table[(u, t)].get(w, 0) + g
             if (w, t) in link_capacities(D):
-                raise AssertionError("an egress link of a switch could not be split off completely (Theorem 9)")
+                raise AssertionError("an egress link of a switch could not be split off completely (the existence theorem of Appendix E.2 promises it can)")
     return D, table
 
 

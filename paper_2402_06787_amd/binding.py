@@ -479,7 +479,7 @@ def fc_fixed_k_search_with_verdicts(n_compute: int, min_in_bw: int, max_bw: int,
     return {"U_star": Fraction(r.num, r.den), "rounds": int(rounds.value)}
 
 
-# ------------------------------------------------------------------ edge splitting (gamma of Theorem 10)
+# ------------------------------------------------------------------ edge splitting (gamma of Appendix E.2's maximum-split-off theorem)
 
 def fc_split_gamma_workspace_bytes(g: Graph, n_pairs: int) -> int:
     return int(load_library().fc_split_gamma_workspace_bytes(g.handle, int(n_pairs)))

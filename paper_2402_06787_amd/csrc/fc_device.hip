@@ -15,8 +15,8 @@
 //
 // The same kernel is instantiated three ways: integer multipliers U (Section 5.2, Appendix E.1),
 // rational multipliers with capacities floor(U b_e) (fixed k, Section 5.5 / Algorithm 3), and the
-// max-flows with an explicit source and unbounded arcs that edge splitting needs (Appendix E.2,
-// Theorem 10).  The source is split over the included files below; they form one translation unit.
+// max-flows with an explicit source and unbounded arcs that edge splitting needs (Appendix E.2, the
+// theorem that gives the maximum capacity that can be split off).  The source is split over the included files below; they form one translation unit.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

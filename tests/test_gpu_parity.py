@@ -35,6 +35,12 @@ def _gpu_flows(g, sink, U, k, options=None, want_stats=False):
     return flows.cpu().numpy().astype(np.int64), stats
 
 
+def _golden(name):
+    import json, os
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)) as f:
+        return json.load(f)
+
+
 def _optimum(cfg, topo):
     if cfg not in _OPTIMA:
         x = o.optimality_binary_search(topo, threads=16)
@@ -496,7 +502,7 @@ def test_fixed_k_search_on_random_and_disconnected_graphs():
             assert fc.fc_fixed_k_search(g, k, 1 + seed % 7)["U_star"] == want, seed
 
 
-# ------------------------------------------------------------------ edge splitting: gamma of Theorem 10 (Appendix E.2)
+# ------------------------------------------------------------------ edge splitting: gamma of the maximum-split-off theorem (Appendix E.2)
 
 def _switch_pairs(topo):
     cap = o.link_capacities(topo)
@@ -691,12 +697,21 @@ def test_remove_switches_on_config3_in_one_and_in_two_launches_per_batch():
     res = [_remove_on_gpu(D, 2, options=opt) for opt in (None, {"split_two_launches": 1}, {"split_two_launches": 2})]
     assert len(res[0]["links"]) == 504
     assert all(r["links"] == res[0]["links"] and r["table"] == res[0]["table"] for r in res[1:])
+    # element by element against what the oracle's loop (Algorithm "Remove Switch Nodes") leaves on this input:
+    # tests/golden/config3_dstar.json, written by tests/golden/make_config3_goldens.py from the oracle alone
+    gold = _golden("config3_dstar.json")
+    assert (gold["U"], gold["k"]) == (15, 2)
+    assert res[0]["links"] == {(a, b): c for a, b, c in gold["links"]}
+    want_table = {}
+    for u, t, sw, amount in gold["table"]:
+        want_table.setdefault((u, t), {})[sw] = amount
+    assert res[0]["table"] == want_table
 
 
 # ------------------------------------------------------------------ launch shapes the other tests do not reach
 
 def test_remove_switches_on_config4_keeps_the_optimum():
-    # too large for the oracle's loop: check what Theorem 9 promises instead.  D = G({U b_e}) at the optimum
+    # too large for the oracle's loop: check what the edge-splitting existence theorem of Appendix E.2 promises instead.  D = G({U b_e}) at the optimum
     # U / k = 63 / 4 has 1/x* = 1/k; D* must be a compute-only Eulerian digraph with the same optimum, every link
     # that was routed through a switch must be covered by its table entries, and capacity is conserved per node.
     topo = w.config_topology(4)
@@ -1079,6 +1094,12 @@ def test_trees_on_config3_after_switch_removal_are_valid():
     links = {(idx[a], idx[b]): c for (a, b), c in res["links"].items()}
     got = fc.fc_construct_trees(len(comp), links, k)
     use = _check_trees(len(comp), links, k, got["trees"])
+    # element by element against the oracle's construction on the same D* (tests/golden/config3_trees.json, written by
+    # tests/golden/make_config3_goldens.py from the oracle alone): same roots, multiplicities and edges in the same order
+    gold = _golden("config3_trees.json")
+    assert (gold["n"], gold["k"]) == (len(comp), k)
+    want = [(r, m, [(e[i], e[i + 1]) for i in range(0, len(e), 2)]) for r, m, e in gold["trees"]]
+    assert got["trees"] == want
     # config 3 is symmetric and tight: every unit of every link is used by some tree
     assert sum(use.values()) == len(comp) * k * (len(comp) - 1)
     assert got["batches"] < len(comp) * (len(comp) - 1)                # the look-ahead saves launches
@@ -1098,3 +1119,87 @@ def test_trees_on_config3_after_switch_removal_are_valid():
         sets[0].add(y); g[(x, y)] -= mu
         if g[(x, y)] == 0:
             del g[(x, y)]
+
+
+# ------------------------------------------------------------------ the loops at size: states replayed by the oracle
+
+def _replay_sampled_states(n, links, k, trees, samples):
+    """States along a finished construction without copies (one root-set per root, multiplicity k), rebuilt from the
+    returned trees: before edge j of root-set i is added, the root-sets before i span, i holds its root and its first j
+    heads, the later ones are single vertices, and every edge added so far has used k units of its link.  For each
+    sampled (i, j) the oracle evaluates mu for the candidate edges in (x, y) order: all before the library's edge must be
+    0 and the library's edge must have mu = k (Appendix E.3, the theorem that computes mu by one max-flow)."""
+    assert len(trees) == n and all(m == k and r == i for i, (r, m, _) in enumerate(trees))
+    full = set(range(n))
+    checked = 0
+    for i, j in samples:
+        g = dict(links)
+        for l in range(i + 1):
+            for (x, y) in (trees[l][2] if l < i else trees[l][2][:j]):
+                g[(x, y)] -= k
+                if g[(x, y)] == 0:
+                    del g[(x, y)]
+        assert all(c > 0 for c in g.values())
+        sets = [set(full) for _ in range(i)] + [{i} | {y for _, y in trees[i][2][:j]}] + [{l} for l in range(i + 1, n)]
+        demand = [k] * n
+        chosen = trees[i][2][j]
+        for (x, y) in sorted(g):
+            if x in sets[i] and y not in sets[i]:
+                mu = o.tree_mu(n, g, sets, demand, i, x, y)
+                checked += 1
+                if (x, y) == chosen:
+                    assert mu == k, (i, j, x, y, mu)
+                    break
+                assert mu == 0, (i, j, x, y, mu)
+        else:
+            raise AssertionError(("the library's edge is no candidate", i, j))
+    return checked
+
+
+def test_trees_on_config4_sampled_states_replayed_by_the_oracle():
+    # 512 roots x 511 edges: far too many max-flows for the oracle's loop.  The construction's promises are checked in full;
+    # 20 states sampled along the library's own construction are rebuilt and every candidate edge up to the one the library
+    # took is evaluated by the oracle
+    topo = w.config_topology(4)
+    U, k = 63, 4
+    res = _remove_on_gpu(_scaled(topo, U), k)
+    comp = [int(v) for v in topo.compute_nodes]
+    idx = {v: i for i, v in enumerate(comp)}
+    links = {(idx[a], idx[b]): c for (a, b), c in res["links"].items()}
+    n = len(comp)
+    got = fc.fc_construct_trees(n, links, k)
+    use = _check_trees(n, links, k, got["trees"])
+    assert sum(use.values()) == n * k * (n - 1)
+    rng = np.random.default_rng(404)
+    samples = [(0, 0), (0, n - 2), (n - 1, n - 2), (n - 1, 0)] + [(int(rng.integers(0, n)), int(rng.integers(0, n - 1))) for _ in range(16)]
+    assert _replay_sampled_states(n, links, k, got["trees"], samples) >= len(samples)
+
+
+def test_back_end_on_a_rail_fabric_warm_and_cold_and_replayed():
+    # 32 boxes x 8 compute nodes, NVSwitch per box, 8 rail switches (the 1024-compute instance of the same generator is the
+    # back end's timing workload): search, switch removal, trees; the trees from kept flows equal the trees with every
+    # max-flow started from nothing; sampled states are replayed by the oracle; D* keeps the optimum
+    topo = w.rail_fabric(32, 8)
+    assert o.is_eulerian(topo)
+    with _upload(topo) as g:
+        sr = fc.fc_opt_throughput_search(g, 16)
+    assert sr["inv_xstar"] == Fraction(256 - 8, 8 * 2)                    # the cut around one box: 248 outside, 16 coming in
+    U, k = sr["U"].numerator, sr["k"] * sr["U"].denominator
+    D = _scaled(topo, U)
+    res = _remove_on_gpu(D, k)
+    comp = [int(v) for v in topo.compute_nodes]
+    assert all(a in set(comp) and b in set(comp) and c > 0 for (a, b), c in res["links"].items())
+    links = {(a, b): c for (a, b), c in res["links"].items()}            # compute nodes are 0..255 already
+    n = len(comp)
+    keys = sorted(links)
+    with fc.fc_graph_upload(n, [a for a, b in keys], [b for a, b in keys], [links[x] for x in keys], np.ones(n, np.uint8)) as g:
+        assert fc.fc_opt_throughput_search(g, 8)["inv_xstar"] == Fraction(1, k)
+    warm = fc.fc_construct_trees(n, links, k)
+    use = _check_trees(n, links, k, warm["trees"])
+    assert sum(use.values()) == n * k * (n - 1)
+    cold = fc.fc_construct_trees(n, links, k, options={"tree_warm_start": 2})
+    assert cold["trees"] == warm["trees"]
+    rng = np.random.default_rng(405)
+    samples = [(0, 0), (n - 1, n - 2)] + [(int(rng.integers(0, n)), int(rng.integers(0, n - 1))) for _ in range(10)]
+    assert _replay_sampled_states(n, links, k, warm["trees"], samples) >= len(samples)
+

@@ -6,6 +6,8 @@ import os
 from fractions import Fraction
 from math import ceil, log2
 
+import math
+
 import numpy as np
 import pytest
 
@@ -251,6 +253,25 @@ def test_fraction_gap_proposition2():
     assert o.fraction_in_interval(Fraction(299, 80), Fraction(301, 80), 8) == Fraction(15, 4)
 
 
+def test_threshold_search_recovers_every_bounded_fraction():
+    # the search both optimisations run: for EVERY fraction p/q with q <= X inside the range, a step verdict with its
+    # threshold there (closed on the feasible side, as Theorem 1's is) must give back exactly p/q, also when the threshold
+    # sits on an end of the range, and within the iteration ceiling ceil(log2(width * X^2)) of Appendix F
+    X = 7
+    lo, hi = Fraction(1, 2), Fraction(5)
+    fr = sorted({Fraction(p, q) for q in range(1, X + 1) for p in range(1, 5 * q + 1) if lo <= Fraction(p, q) <= hi})
+    assert fr[0] == lo and fr[-1] == hi and len(fr) > 60
+    for thr in fr:
+        seen = []
+        got, halvings = o.smallest_true_fraction(lambda z: z >= thr, lo, hi, X, lambda z, ok: seen.append((z, ok)))
+        assert got == thr
+        assert halvings == len(seen) and all(ok == (z >= thr) for z, ok in seen)
+        assert halvings <= math.ceil(math.log2((hi - lo) * X * X)) + 1
+    # a bracket that stops one halving too early still holds two candidates, which the last step refuses
+    with pytest.raises(AssertionError):
+        o.fraction_in_interval(Fraction(1, 7), Fraction(1, 6), X)              # 1/42 wide: not below 1/49
+
+
 def test_planted_mistakes_are_caught():
     """Each plausible slip, planted in a copy of the oracle's network builder, changes a pinned value."""
     topo = w.paper_example_switch(1)
@@ -346,7 +367,7 @@ def test_fixed_k_textbook_shapes(n, c, k):
     assert o.fixed_k_binary_search(w.directed_ring(n, c), k) == Fraction((n - 1) * k, c)
 
 
-# ---------------------------------------------------------------- edge splitting (Appendix E.2, Theorem 10)
+# ---------------------------------------------------------------- edge splitting (Appendix E.2, the maximum-split-off theorem)
 
 def _scaled_eulerian(seed):
     """A small bidirectional (hence Eulerian) graph with switches, scaled by Proposition 3's (U, k) so
@@ -440,7 +461,7 @@ def test_switch_removal_by_repeated_splitting_keeps_the_optimum():
                     g = o.split_gamma(D, k, u, sw, t)
                     if g > 0:
                         D = o.split_off(D, u, sw, t, g)
-                assert (sw, t) not in o.link_capacities(D)            # Theorem 9: f can always be split off completely
+                assert (sw, t) not in o.link_capacities(D)            # Appendix E.2, existence theorem: f can always be split off completely
         cap = o.link_capacities(D)
         assert all(D.is_compute[a] and D.is_compute[b] for a, b in cap)
         assert o.feasible(D, 1, k)[0]
@@ -451,7 +472,7 @@ def test_switch_removal_by_repeated_splitting_keeps_the_optimum():
 def _check_switch_removal(D, k, Dstar, table):
     cap0, cap1 = o.link_capacities(D), o.link_capacities(Dstar)
     assert all(D.is_compute[a] and D.is_compute[b] for a, b in cap1)          # every switch is isolated
-    assert o.is_eulerian(Dstar) and o.feasible(Dstar, 1, k)[0]                  # Theorem 9: the condition survives
+    assert o.is_eulerian(Dstar) and o.feasible(Dstar, 1, k)[0]                  # Appendix E.2, existence theorem: the condition survives
     # the table accounts for exactly the capacity that was added between compute nodes (a link that touches a
     # switch may be created by one split and used up by a later one: the recovery of paths is recursive) ...
     for key in set(cap1) | set(table):
@@ -683,11 +704,19 @@ def test_mu_of_an_edge_never_rises_while_its_root_set_grows(seed):
     # what lets a construction skip an edge once it had mu = 0: growing R admits more cuts, used capacity lowers
     # them, copies raise p(S), m(R) only shrinks
     rng = np.random.default_rng(8000 + seed)
-    n = int(rng.integers(3, 7)); k = int(rng.integers(1, 5))
-    # a complete digraph of capacity >= k satisfies the packing condition; odd seeds thin it out and may not
-    links = {(a, b): k + int(rng.integers(0, 3)) for a in range(n) for b in range(n) if a != b and (seed % 2 == 0 or rng.random() < 0.85)}
-    for a in range(n):                                     # keep a ring so that the digraph stays connected
-        links.setdefault((a, (a + 1) % n), k)
+    for _ in range(200):                                   # draw again until the packing condition holds
+        n = int(rng.integers(3, 7)); k = int(rng.integers(1, 5))
+        # a complete digraph of capacity >= k satisfies the packing condition; odd seeds thin it out and may not
+        links = {(a, b): k + int(rng.integers(0, 3)) for a in range(n) for b in range(n) if a != b and (seed % 2 == 0 or rng.random() < 0.85)}
+        for a in range(n):                                 # keep a ring so that the digraph stays connected
+            links.setdefault((a, (a + 1) % n), k)
+        keys = sorted(links)
+        topo = w.Topology("draw", n, np.array([a for a, _ in keys], np.int32), np.array([b for _, b in keys], np.int32),
+                          np.array([links[e] for e in keys], np.int32), np.ones(n, np.uint8))
+        if o.feasible(topo, 1, k)[0]:                      # min over v of F(s, v) >= N k: trees exist (Theorem 3)
+            break
+    else:
+        raise AssertionError("no draw satisfied the packing condition")
     last = {}
 
     def observe(g, sets, demand, i, x, y, mu):
@@ -696,10 +725,8 @@ def test_mu_of_an_edge_never_rises_while_its_root_set_grows(seed):
             assert mu <= last[key], key
         last[key] = mu
 
-    try:
-        trees = o.construct_trees(n, links, k, observe=observe)
-    except AssertionError:
-        pytest.skip("the packing condition does not hold for this draw")
+    trees = o.construct_trees(n, links, k, observe=observe)
+    assert len(last) >= n * (n - 1) // 2
     _check_trees(n, links, k, trees)
 
 
@@ -737,7 +764,7 @@ def test_mu_is_what_a_small_supply_at_x_adds_to_the_other_demands(seed):
 
 
 def test_one_more_sink_never_lowers_a_split_flow():
-    # Theorem 10's 2N max-flows of a pair differ in one sink, the compute node v (its unbounded arc into w or t makes it
+    # the 2N max-flows of a pair (maximum-split-off theorem, Appendix E.2) differ in one sink, the compute node v (its unbounded arc into w or t makes it
     # one).  Without that arc the flow cannot be larger: what the problem without v reaches, every problem with v
     # reaches too.  (The HIP path answers from the problem without v where that already settles gamma.)
     checked = 0
@@ -771,3 +798,19 @@ def test_one_more_sink_never_lowers_a_split_flow():
                     assert (F1 >= without1).all() and (F2 >= without2).all(), (seed, u, sw, t)
                     checked += 1
     assert checked >= 20
+
+
+# ------------------------------------------------------------------ the rail fabric (back-end timing workload)
+
+def test_rail_fabric_is_eulerian_and_has_the_box_cut_optimum():
+    # every link is bidirectional, so the digraph is Eulerian; the binding cut is the one around a box: N - 8 compute nodes
+    # outside, per_box * nic_cap coming in.  Tiny instances against brute force over all cuts, larger ones against the search.
+    for boxes, per_box, nv, nic in ((3, 3, 6, 1), (4, 2, 5, 2), (2, 4, 9, 1)):
+        t = w.rail_fabric(boxes, per_box, nv, nic)
+        assert t.n_vertices == boxes * per_box + boxes + per_box and o.is_eulerian(t)
+        want = Fraction(boxes * per_box - per_box, per_box * nic)
+        assert o.brute_inv_xstar(t) == want == o.optimality_binary_search(t)
+    t = w.rail_fabric(16, 8)
+    assert o.is_eulerian(t) and o.optimality_binary_search(t, threads=8) == Fraction(120, 16)
+    big = w.eulerian_fabric_1024()
+    assert big.n_compute == 1024 and big.n_vertices == 1160 and o.is_eulerian(big) and o.min_compute_in_bandwidth(big) == 26

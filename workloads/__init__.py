@@ -8,12 +8,14 @@ the oracle nor the HIP binding.
 from .topologies import (Topology, config_topology, shrunken_config5, paper_example_switch,
                          paper_example_split, paper_example_ring_unwound,
                          random_tiny, complete_digraph, directed_ring,
-                         bidirectional_ring, star_switch, superposed_out_trees, CONFIG_NAMES)
+                         bidirectional_ring, star_switch, superposed_out_trees, rail_fabric, eulerian_fabric_1024,
+                         CONFIG_NAMES)
 from .problems import ProblemList, config_problems, all_sinks
 
 __all__ = [
     "Topology", "config_topology", "shrunken_config5", "paper_example_switch", "paper_example_split",
     "paper_example_ring_unwound", "random_tiny", "complete_digraph",
-    "directed_ring", "bidirectional_ring", "star_switch", "superposed_out_trees", "CONFIG_NAMES",
+    "directed_ring", "bidirectional_ring", "star_switch", "superposed_out_trees", "rail_fabric", "eulerian_fabric_1024",
+    "CONFIG_NAMES",
     "ProblemList", "config_problems", "all_sinks",
 ]

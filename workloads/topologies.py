@@ -295,6 +295,27 @@ def _config5(n_compute: int = 1024, n_switch: int = 128, out_degree: int = 8,
     return g.done()
 
 
+def rail_fabric(n_boxes: int = 128, per_box: int = 8, nvswitch_cap: int = 24, nic_cap: int = 2,
+                name: str | None = None) -> Topology:
+    """Eulerian switch topology shaped like a rail-optimised DGX-A100 cluster: `n_boxes` boxes of `per_box` compute
+    nodes, one NVSwitch node per box (bidirectional links of `nvswitch_cap`), and `per_box` rail switches: compute
+    node j of every box has a bidirectional NIC link of `nic_cap` to rail switch j.  Every link is bidirectional, so
+    every vertex has equal in- and out-bandwidth.  The default is the 1024-compute instance (1160 vertices) on which
+    the generator's back end -- switch removal, spanning tree construction -- is timed; it stands in for the
+    1024-GPU A100 topology of the paper's generation-time table (Appendix C), whose description file is not public."""
+    n_compute = n_boxes * per_box
+    g = _Builder(name or f"rail_fabric_{n_boxes}x{per_box}", n_compute + n_boxes + per_box, n_compute)
+    for c in range(n_compute):
+        g.link(c, n_compute + c // per_box, nvswitch_cap)
+        g.link(c, n_compute + n_boxes + c % per_box, nic_cap)
+    return g.done()
+
+
+def eulerian_fabric_1024() -> Topology:
+    """128 boxes x 8 compute nodes, 128 NVSwitch nodes, 8 rail switches (see `rail_fabric`)."""
+    return rail_fabric(128, 8, 24, 2, name="rail_fabric_1024c_128x8")
+
+
 def config_topology(cfg: int) -> Topology:
     """Benchmark configuration `cfg` in 1..5 (see module docstring)."""
     return {1: _config1, 2: _config2, 3: _config3, 4: _config4, 5: _config5}[cfg]()
