@@ -115,6 +115,7 @@ typedef struct {
     int32_t stats_time_only;       /* fc_maxflow_batch(_floor), fc_feasible(_floor) with stats: 1 = fill device_ms only.  The
                                       kernels then run exactly as without stats (counting costs a few per cent: every
                                       problem adds its counters up on chip and writes 32 bytes); the counters read 0  */
+    int32_t tree_chain_states;     /* fc_construct_trees: states one launch looks ahead, 1 to 64 (default 32, see there)   */
 } fc_options;
 
 /* ------------------------------------------------------------------------------------------
@@ -373,12 +374,13 @@ const char *fc_strerror(int code);
  * first link leaving it, in (x, y) order, whose mu is positive; when mu is below its demand a copy keeps
  * the rest.  All candidate links of a state are evaluated in one launch (the ones before the first positive
  * mu are zero on this very state, so the result is that of trying them one by one), and the launch looks
- * ahead: it also evaluates the states that follow if, each time, the first link not rejected before is
- * accepted in full; those results are used as far as the guesses turn out right.  A link whose mu was 0 is
+ * ahead: it also evaluates the states that follow (options->tree_chain_states of them in all) if, each time,
+ * the first link that was neither rejected before nor zero the last time any root-set tried it is accepted in
+ * full; those results are used as far as the guesses turn out right.  A link whose mu was 0 is
  * not tried again while the same root-set grows (its mu cannot rise).  Unless options->tree_warm_start is 2
  * the launches do not start from nothing: the flow that brings the other root-sets' demands to a vertex y
  * is kept in device memory (n_vertices rows of one value per link, and as many again per state a launch looks
- * ahead: the option is ignored when that exceeds 2 GiB), a max-flow into y repairs it for the capacities used
+ * ahead: fewer states are looked ahead when that would exceed 2 GiB), a max-flow into y repairs it for the capacities used
  * up since and then only routes the units that decide mu.  The trees are the same either way.  Output: n_trees
  * root-sets; tree i has root tree_root[i], multiplicity tree_multiplicity[i] (they add up to k per root)
  * and the n_vertices - 1 edges tree_edge_x/y[i * (n_vertices - 1) ..] in the order they were added.
