@@ -115,6 +115,10 @@ typedef struct {
     int32_t stats_time_only;       /* fc_maxflow_batch(_floor), fc_feasible(_floor) with stats: 1 = fill device_ms only.  The
                                       kernels then run exactly as without stats (counting costs a few per cent: every
                                       problem adds its counters up on chip and writes 32 bytes); the counters read 0  */
+    int32_t split_carry;           /* fc_remove_switches: 1 = on (default), 2 = off.  On: while one switch is split, the preflow
+                                      each (ingress link, type) problem without v ended with is kept on the device and the
+                                      next batch's problem goes on from it, cut down to the new capacities and repaired,
+                                      instead of starting from nothing.  Same D* and table either way.                  */
     int32_t tree_chain_states;     /* fc_construct_trees: states one launch looks ahead, 1 to 64 (default 32, see there)   */
 } fc_options;
 
