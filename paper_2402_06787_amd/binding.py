@@ -57,7 +57,7 @@ class fc_options(ctypes.Structure):
                 ("force_wide", ctypes.c_int32), ("max_level_steps", ctypes.c_int32),
                 ("src_cap_bound", ctypes.c_int32), ("tree_certificate", ctypes.c_int32), ("schedule", ctypes.c_int32),
                 ("tree_warm_start", ctypes.c_int32), ("split_two_launches", ctypes.c_int32),
-                ("stats_time_only", ctypes.c_int32), ("split_carry", ctypes.c_int32), ("tree_chain_states", ctypes.c_int32)]
+                ("stats_time_only", ctypes.c_int32), ("split_carry", ctypes.c_int32), ("split_reverse", ctypes.c_int32), ("tree_chain_states", ctypes.c_int32)]
 
 
 VERDICT_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32),
