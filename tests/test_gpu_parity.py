@@ -582,6 +582,9 @@ def test_split_gamma_matches_oracle_on_random_eulerian_graphs():
         assert (two == got).all() and (two_flows == flows).all(), seed
         two_early, _ = _gamma_on_gpu(sym, U, kk, pairs + bogus, want_flows=False, options={"split_two_launches": 1})
         assert (two_early == got).all(), seed
+        # the second launch's problems solved forwards (all stranded excess towards v) instead of backwards from v
+        fwd, fwd_flows = _gamma_on_gpu(sym, U, kk, pairs + bogus, options={"split_two_launches": 1, "split_reverse": 2})
+        assert (fwd == got).all() and (fwd_flows == flows).all(), seed
         checked += len(pairs)
     assert checked > 200
 
@@ -607,7 +610,8 @@ def test_split_gamma_on_configs(cfg):
     # relabel policies; lanes per vertex
     for opt in ({"use_label_table": 2}, {"global_relabel_rises": -1, "use_gap": 2}, {"global_relabel_rises": 1, "lanes_per_vertex": 4},
                 {"threads_per_problem": 256, "lanes_per_vertex": 32}, {"split_two_launches": 1}, {"split_two_launches": 2},
-                {"split_two_launches": 1, "threads_per_problem": 64, "global_relabel_rises": -1}):
+                {"split_two_launches": 1, "threads_per_problem": 64, "global_relabel_rises": -1},
+                {"split_two_launches": 1, "split_reverse": 2}, {"split_two_launches": 1, "lanes_per_vertex": 64, "use_gap": 2}):
         alt, alt_flows = _gamma_on_gpu(topo, U, kk, pick, options=opt)
         assert (alt == got).all() and (alt_flows == flows).all(), (cfg, opt)
     # without the flows a max-flow may stop once N k + min{c(e), c(f)} units have arrived: gamma is the same
@@ -660,6 +664,10 @@ def test_remove_switches_matches_oracle_on_random_eulerian_graphs():
         assert got["table"] == table, seed
         two = _remove_on_gpu(D, kk, options={"split_two_launches": 1})      # every batch in two launches
         assert two["links"] == got["links"] and two["table"] == got["table"], seed
+        # without the preflows kept from batch to batch, without the backward second launch, without both
+        for opt in ({"split_carry": 2}, {"split_reverse": 2}, {"split_carry": 2, "split_reverse": 2, "split_two_launches": 1}):
+            alt = _remove_on_gpu(D, kk, options=opt)
+            assert alt["links"] == got["links"] and alt["table"] == got["table"], (seed, opt)
         done += 1
     assert done >= 15
     # not Eulerian: refused; Eulerian but the condition min F >= N k fails: reported
@@ -694,7 +702,8 @@ def test_remove_switches_on_config3_in_one_and_in_two_launches_per_batch():
     # the same links and the same table whether a batch's max-flows are solved in one launch, in two, or as the library chooses
     topo = w.config_topology(3)
     D = _scaled(topo, 15)
-    res = [_remove_on_gpu(D, 2, options=opt) for opt in (None, {"split_two_launches": 1}, {"split_two_launches": 2})]
+    res = [_remove_on_gpu(D, 2, options=opt) for opt in (None, {"split_two_launches": 1}, {"split_two_launches": 2},
+                                                         {"split_carry": 2}, {"split_reverse": 2}, {"split_carry": 2, "split_reverse": 2})]
     assert len(res[0]["links"]) == 504
     assert all(r["links"] == res[0]["links"] and r["table"] == res[0]["table"] for r in res[1:])
     # element by element against what the oracle's loop (Algorithm "Remove Switch Nodes") leaves on this input:
@@ -1106,6 +1115,11 @@ def test_trees_on_config3_after_switch_removal_are_valid():
     # the flows kept between launches change nothing: same trees as with every max-flow started from nothing
     cold = fc.fc_construct_trees(len(comp), links, k, options={"tree_warm_start": 2})
     assert cold["trees"] == got["trees"] and cold["batches"] == got["batches"]
+    # how far a launch looks ahead changes the number of launches, never a tree (1: no speculation at all)
+    for chain in (1, 5, 64):
+        alt = fc.fc_construct_trees(len(comp), links, k, options={"tree_chain_states": chain})
+        assert alt["trees"] == got["trees"], chain
+        assert (alt["batches"] > got["batches"]) == (chain < 32), (chain, alt["batches"], got["batches"])
     # first steps of root 0 by the oracle: same edges in the same order
     n = len(comp)
     g = dict(links); sets = [{u} for u in range(n)]; demand = [k] * n

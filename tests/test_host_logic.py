@@ -120,7 +120,8 @@ def test_host_side_validation_of_the_graph_surgery_entry_points():
         fc.fc_construct_trees(3, links, 0)
     assert ei.value.code == fc.FC_EINVAL
     # options out of range are refused before any launch
-    for bad in ({"tree_warm_start": 3}, {"tree_warm_start": -1}, {"split_two_launches": 3}, {"threads_per_problem": 100}):
+    for bad in ({"tree_warm_start": 3}, {"tree_warm_start": -1}, {"split_two_launches": 3}, {"threads_per_problem": 100},
+                {"tree_chain_states": 65}, {"tree_chain_states": -1}, {"split_carry": 3}, {"split_reverse": -1}):
         with pytest.raises(fc.FcError) as ei:
             fc.fc_construct_trees(3, links, 2, options=bad)
         assert ei.value.code == fc.FC_EINVAL, bad
