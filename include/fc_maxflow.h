@@ -119,10 +119,10 @@ typedef struct {
                                       each (ingress link, type) problem without v ended with is kept on the device and the
                                       next batch's problem goes on from it, cut down to the new capacities and repaired,
                                       instead of starting from nothing.  Same D* and table either way.                  */
-    int32_t split_reverse;         /* edge splitting in two launches: 1 = on (default), 2 = off.  On: a problem of the second
-                                      launch gives the new sink v the units that still matter and pushes them backwards
-                                      along the residual arcs to the excess the first launch left stranded, instead of
-                                      moving all that excess towards v.  Same values.                                  */
+    int32_t split_reverse;         /* edge splitting in two launches: 1 = on, 2 = off (default: on unless the flow values are
+                                      asked for).  On: a problem of the second launch gives the new sink v the units that
+                                      still matter and pushes them backwards along the residual arcs to the excess the
+                                      first launch left stranded, instead of moving all that excess towards v.  Same values. */
     int32_t tree_chain_states;     /* fc_construct_trees: states one launch looks ahead, 1 to 64 (default 32, see there)   */
 } fc_options;
 

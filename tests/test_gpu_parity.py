@@ -583,8 +583,11 @@ def test_split_gamma_matches_oracle_on_random_eulerian_graphs():
         two_early, _ = _gamma_on_gpu(sym, U, kk, pairs + bogus, want_flows=False, options={"split_two_launches": 1})
         assert (two_early == got).all(), seed
         # the second launch's problems solved forwards (all stranded excess towards v) instead of backwards from v
-        fwd, fwd_flows = _gamma_on_gpu(sym, U, kk, pairs + bogus, options={"split_two_launches": 1, "split_reverse": 2})
-        assert (fwd == got).all() and (fwd_flows == flows).all(), seed
+        for rev in (1, 2):
+            alt, alt_flows = _gamma_on_gpu(sym, U, kk, pairs + bogus, options={"split_two_launches": 1, "split_reverse": rev})
+            assert (alt == got).all() and (alt_flows == flows).all(), (seed, rev)
+        alt, _ = _gamma_on_gpu(sym, U, kk, pairs + bogus, want_flows=False, options={"split_two_launches": 1, "split_reverse": 2})
+        assert (alt == got).all(), seed
         checked += len(pairs)
     assert checked > 200
 
@@ -611,7 +614,7 @@ def test_split_gamma_on_configs(cfg):
     for opt in ({"use_label_table": 2}, {"global_relabel_rises": -1, "use_gap": 2}, {"global_relabel_rises": 1, "lanes_per_vertex": 4},
                 {"threads_per_problem": 256, "lanes_per_vertex": 32}, {"split_two_launches": 1}, {"split_two_launches": 2},
                 {"split_two_launches": 1, "threads_per_problem": 64, "global_relabel_rises": -1},
-                {"split_two_launches": 1, "split_reverse": 2}, {"split_two_launches": 1, "lanes_per_vertex": 64, "use_gap": 2}):
+                {"split_two_launches": 1, "split_reverse": 1}, {"split_two_launches": 1, "split_reverse": 1, "lanes_per_vertex": 64, "use_gap": 2}):
         alt, alt_flows = _gamma_on_gpu(topo, U, kk, pick, options=opt)
         assert (alt == got).all() and (alt_flows == flows).all(), (cfg, opt)
     # without the flows a max-flow may stop once N k + min{c(e), c(f)} units have arrived: gamma is the same
@@ -620,6 +623,8 @@ def test_split_gamma_on_configs(cfg):
     for two in (1, 2):
         early, _ = _gamma_on_gpu(topo, U, kk, pick, want_flows=False, options={"split_two_launches": two})
         assert (early == got).all(), two
+    early, _ = _gamma_on_gpu(topo, U, kk, pick, want_flows=False, options={"split_two_launches": 1, "split_reverse": 2})
+    assert (early == got).all()
 
 
 # ------------------------------------------------------------------ Algorithm 2: the switch-removal loop around the gamma batches
