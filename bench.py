@@ -95,9 +95,9 @@ def main():
                     help="headline and fc_feasible legs only (keeps profiler traces to the two kinds of launch)")
     ap.add_argument("--only", choices=["batch", "feasible"], default=None,
                     help="with --quick: time only this entry point (one kind of solver launch in a profile)")
-    ap.add_argument("--back-end", type=int, default=3, choices=[0, 3, 4, 6],
-                    help="topology for the switch-removal + tree-construction leg: config 3 (default), config 4, "
-                         "6 = the 1024-compute Eulerian switch fabric (tens of seconds), 0 = skip")
+    ap.add_argument("--back-end", type=str, default="3,4",
+                    help="topologies for the switch-removal + tree-construction leg, comma-separated: config 3 and config 4 "
+                         "(default, about 4 s together), 6 = the 1024-compute Eulerian switch fabric (about 30 s), 0 = skip")
     ap.add_argument("--threads-per-problem", type=int, default=0)
     ap.add_argument("--lanes-per-vertex", type=int, default=0)
     ap.add_argument("--copy-probe", action="store_true",
@@ -333,11 +333,12 @@ def main():
 
         # ---- the generator's back end on a whole topology: Algorithm 2's loop around gamma batches (every switch split
         # off), then spanning tree construction (Appendix E.3) on the switch-free digraph it leaves
-        if args.back_end:
-            if args.back_end == 6:
-                tb = w.eulerian_fabric_1024()
-            else:
-                tb = w.config_topology(args.back_end)
+        legs = [int(x) for x in args.back_end.split(",") if x.strip() and int(x) != 0]
+        if any(x not in (3, 4, 6) for x in legs):
+            raise SystemExit("bench.py: --back-end takes 3, 4, 6 (comma-separated) or 0")
+        out["back_end"] = []
+        for leg in legs:
+            tb = w.eulerian_fabric_1024() if leg == 6 else w.config_topology(leg)
             gb = fc.fc_graph_upload(tb.n_vertices, tb.tail, tb.head, tb.bandwidth, tb.is_compute)
             t0 = time.perf_counter()
             sb = fc.fc_opt_throughput_search(gb, 16)
@@ -365,14 +366,14 @@ def main():
                 ok_t = ok_t and len(seen_t) == len(comp_t)
                 per_t[root_t] = per_t.get(root_t, 0) + mult_t
             ok_t = ok_t and per_t == {u: kb for u in range(len(comp_t))} and all(c <= links_t[e] for e, c in use_t.items())
-            out["back_end"] = {
+            out["back_end"].append({
                 "workload": f"{tb.name} at U = {Ub}, k = {kb}: {len(comp_t)} compute nodes, {tb.n_vertices - len(comp_t)} switches",
                 "search_wall_ms": search_b_ms,
                 "remove_switches": {"wall_ms": el_r * 1e3, "batches": rs["batches"], "links_out": len(rs["links"]),
                                     "table_entries": sum(len(v) for v in rs["table"].values())},
                 "construct_trees": {"wall_ms": el_t * 1e3, "launches": tr["batches"], "root_sets": len(tr["trees"]),
                                     "tree_edges_with_multiplicity": int(sum(m * len(e) for _, m, e in tr["trees"])),
-                                    "valid": bool(ok_t)}}
+                                    "valid": bool(ok_t)}})
         for _ in range(3):
             H["feas"]()
         torch.cuda.synchronize()
