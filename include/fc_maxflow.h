@@ -150,6 +150,40 @@ int fc_graph_upload(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, con
                     const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out);
 int fc_graph_free(fc_graph *g);
 
+/* In-place bandwidth update of a graph that is already built or uploaded.  The edge-splitting loop (Appendix E.2,
+ * the algorithm that removes the switch nodes) changes three capacities per split -- c(u, w) and c(w, t) go down by
+ * gamma, c(u, t) goes up by gamma -- and asks for max-flows on the changed graph right away; what-if questions about a
+ * degraded or upgraded link are of the same kind.  This call rewrites the bandwidth of existing links where they
+ * lie: the residual CSR keeps its shape, its record numbering (fc_graph_csr) and its device addresses, and nothing
+ * is allocated beyond a staging list of 8 bytes per changed record that the graph keeps for later calls.
+ *
+ * tail, head, bandwidth: host int32 [n_updates].  Link (tail[i], head[i]) -- one ordered vertex pair, as after the
+ * merging of parallel arcs -- gets the bandwidth bandwidth[i] >= 0 (the new value, not a difference; when a link is
+ * listed twice the later entry wins).  A link lowered to 0 stays in the CSR as a pair of records that carry nothing
+ * and can be raised again.  A link that the graph does not have cannot be given bandwidth, because that would move
+ * records: build the graph with fc_graph_upload_with_spares, which is fc_graph_upload except that an arc of
+ * bandwidth 0 becomes such a link instead of being ignored (parallel arcs still add; self-loops are still ignored).
+ * For the edge-splitting loop the spares are the links (u, t) over the ingress tails u and egress heads t of a switch.
+ *
+ * The facts fc_graph_info reports (min B^-, max b_e, gcd, Eulerian flag) follow the update.  The per-sink tables of
+ * the uploaded graph (initial heights, first-arc trees: functions of the bandwidths) are
+ *   refresh_tables = 1: rebuilt on host threads and copied again, as in fc_graph_upload; every later call then
+ *                       behaves exactly as on a fresh upload of the updated arc list;
+ *   refresh_tables = 0: marked unusable until a later call with refresh_tables = 1: the solver kernels then start
+ *                       each problem with a search for exact heights on the device instead.  Same values, slower
+ *                       batches, a much cheaper update: the choice for loops that change the graph between launches.
+ * Synchronous: waits for `hip_stream` first (launches that still read the records), returns when the device copy
+ * is up to date.  Must not run concurrently with other calls on the same graph.  A graph from fc_graph_build gets
+ * the host part only.
+ * Errors: FC_EINVAL (null pointers, ids out of range, negative bandwidth, a link the graph does not have,
+ * refresh_tables not 0 or 1), FC_EOVERFLOW (an in-bandwidth sum reaches 2^31) -- in both cases nothing was changed;
+ * FC_ENOMEM; FC_EDEVICE (also: the graph lives on another GPU than the current one) -- after a device error during
+ * the update the graph must only be freed. */
+int fc_graph_upload_with_spares(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
+                                const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out);
+int fc_graph_update_arcs(fc_graph *g, int64_t n_updates, const int32_t *tail, const int32_t *head,
+                         const int32_t *bandwidth, int32_t refresh_tables, void *hip_stream);
+
 /* Facts Algorithm 1 and Proposition 3 need: N = |V_c|; number of arcs after merging;
  * min over compute nodes of the in-bandwidth B^-_G(v); max_e b_e; gcd of all b_e; whether
  * every vertex has equal in- and out-bandwidth (the paper's Eulerian assumption, needed only

@@ -22,7 +22,7 @@ FC_EWORKSPACE, FC_EDEVICE, FC_ENOCONVERGE, FC_EUNSUPPORTED = -5, -6, -7, -8
 FC_FLOW_INVALID, FC_FLOW_NOCONVERGE, FC_FLOW_UNSUPPORTED = -1, -2, -3
 FC_GAMMA_INVALID = -2147483648
 
-EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_free", "fc_graph_info", "fc_graph_csr", "fc_graph_set_source_weights",
+EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_upload_with_spares", "fc_graph_update_arcs", "fc_graph_free", "fc_graph_info", "fc_graph_csr", "fc_graph_set_source_weights",
             "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_maxflow_batch_static", "fc_maxflow_batch_floor", "fc_feasible_workspace_bytes",
             "fc_feasible_floor", "fc_fixed_k_search", "fc_fixed_k_search_with_verdicts",
             "fc_split_gamma_workspace_bytes", "fc_split_gamma_batch", "fc_remove_switches", "fc_tree_mu_batch", "fc_construct_trees",
@@ -80,6 +80,10 @@ def load_library():
     lib.fc_graph_build.argtypes = [i32, i64, vp, vp, vp, vp, c.POINTER(vp)]
     lib.fc_graph_upload.restype = c.c_int
     lib.fc_graph_upload.argtypes = [i32, i64, vp, vp, vp, vp, c.POINTER(vp)]
+    lib.fc_graph_upload_with_spares.restype = c.c_int
+    lib.fc_graph_upload_with_spares.argtypes = [i32, i64, vp, vp, vp, vp, c.POINTER(vp)]
+    lib.fc_graph_update_arcs.restype = c.c_int
+    lib.fc_graph_update_arcs.argtypes = [vp, i64, vp, vp, vp, i32, vp]
     lib.fc_graph_free.restype = c.c_int
     lib.fc_graph_free.argtypes = [vp]
     lib.fc_graph_info.restype = c.c_int
@@ -217,6 +221,21 @@ def fc_graph_build(n_vertices, tail, head, bandwidth, is_compute) -> Graph:
 
 def fc_graph_upload(n_vertices, tail, head, bandwidth, is_compute) -> Graph:
     return _graph_call("fc_graph_upload", n_vertices, tail, head, bandwidth, is_compute)
+
+
+def fc_graph_upload_with_spares(n_vertices, tail, head, bandwidth, is_compute) -> Graph:
+    """fc_graph_upload, except that an arc of bandwidth 0 becomes a link that carries nothing yet."""
+    return _graph_call("fc_graph_upload_with_spares", n_vertices, tail, head, bandwidth, is_compute)
+
+
+def fc_graph_update_arcs(g: Graph, tail, head, bandwidth, refresh_tables: bool = True, stream=None) -> None:
+    """Give the existing links (tail[i], head[i]) the bandwidths bandwidth[i], in place (host arrays)."""
+    tail = _np(tail, np.int32); head = _np(head, np.int32); bandwidth = _np(bandwidth, np.int32)
+    if not (tail.shape == head.shape == bandwidth.shape) or tail.ndim != 1:
+        raise ValueError("tail, head, bandwidth must be 1-d arrays of equal length")
+    _check(load_library().fc_graph_update_arcs(g.handle, int(tail.shape[0]), _host_ptr(tail), _host_ptr(head), _host_ptr(bandwidth),
+                                               1 if refresh_tables else 0, _stream_ptr_for_host_call(stream)),
+           "fc_graph_update_arcs")
 
 
 def fc_graph_info(g: Graph) -> GraphInfo:

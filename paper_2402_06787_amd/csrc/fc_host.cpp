@@ -26,7 +26,7 @@ struct Arc { int32_t t, h; int64_t b; };
 // Graph ingest.  The topology is the digraph G of the paper's problem definition (Section 5);
 // parallel arcs add (Appendix E.1: integer capacity = number of multi-edges).
 int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
-                  const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out) {
+                  const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out, bool keep_zero_links) {
     if (!out || n_vertices < 2 || n_arcs < 0 || !is_compute) return FC_EINVAL;
     if (n_arcs > 0 && (!tail || !head || !bandwidth)) return FC_EINVAL;
     if (n_vertices > (1 << 24) || n_arcs > (int64_t(1) << 28)) return FC_EUNSUPPORTED;
@@ -36,7 +36,7 @@ int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const
         for (int64_t i = 0; i < n_arcs; ++i) {
             if (tail[i] < 0 || tail[i] >= n_vertices || head[i] < 0 || head[i] >= n_vertices) return FC_EINVAL;
             if (bandwidth[i] < 0) return FC_EINVAL;
-            if (tail[i] == head[i] || bandwidth[i] == 0) continue;       // carry nothing
+            if (tail[i] == head[i] || (bandwidth[i] == 0 && !keep_zero_links)) continue;   // carry nothing
             arcs.push_back({tail[i], head[i], bandwidth[i]});
         }
         std::sort(arcs.begin(), arcs.end(), [](const Arc &x, const Arc &y) {
@@ -141,7 +141,7 @@ int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &
                 while (qh < qt) {
                     const int32_t w = queue[qh++];
                     for (int32_t r = g->row_ptr[w]; r < g->row_ptr[w + 1]; ++r)
-                        if (!g->fwd[r] && dist[g->other[r]] == n) { dist[g->other[r]] = dist[w] + 1; queue[qt++] = g->other[r]; }
+                        if (!g->fwd[r] && g->bw[r] > 0 && dist[g->other[r]] == n) { dist[g->other[r]] = dist[w] + 1; queue[qt++] = g->other[r]; }
                 }
                 int32_t hm = 0, L = 0;
                 for (int32_t v = 0; v < n; ++v) {
@@ -182,7 +182,7 @@ int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &
                     const int32_t v = order[i];
                     double best = 0; int32_t best_r = -1;
                     for (int32_t r = g->row_ptr[v]; r < g->row_ptr[v + 1]; ++r) {
-                        if (!g->fwd[r]) continue;
+                        if (!g->fwd[r] || g->bw[r] <= 0) continue;         // (a link of bandwidth zero carries nothing)
                         const int32_t q = g->other[r];
                         if (dist[q] + 1 != dist[v]) continue;
                         double cost = double(wt[v]) / double(g->bw[r]);
@@ -212,6 +212,56 @@ int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &
     } catch (const std::bad_alloc &) {
         return FC_ENOMEM;
     } catch (const std::system_error &) {
+        return FC_ENOMEM;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// In-place bandwidth updates (the edge-splitting loop of Appendix E.2 lowers c(u, w) and c(w, t) and raises c(u, t)
+// with every split).  The CSR keeps its shape: a link lowered to zero stays as a pair of records that carry nothing.
+int fc_host_update_arcs(fc_graph *g, int64_t n_updates, const int32_t *tail, const int32_t *head,
+                        const int32_t *bandwidth, std::vector<int32_t> &edits) {
+    if (!g || n_updates < 0 || (n_updates > 0 && (!tail || !head || !bandwidth))) return FC_EINVAL;
+    try {
+        edits.clear();
+        const int32_t n = g->n;
+        // where every update lands: the forward record in the tail's row, the reverse record in the head's row
+        std::vector<int32_t> rf(size_t(n_updates), -1), rr(size_t(n_updates), -1);
+        for (int64_t i = 0; i < n_updates; ++i) {
+            if (tail[i] < 0 || tail[i] >= n || head[i] < 0 || head[i] >= n || bandwidth[i] < 0) return FC_EINVAL;
+            for (int32_t r = g->row_ptr[size_t(tail[i])]; r < g->row_ptr[size_t(tail[i]) + 1]; ++r)
+                if (g->fwd[size_t(r)] && g->other[size_t(r)] == head[i]) { rf[size_t(i)] = r; break; }
+            if (rf[size_t(i)] < 0) return FC_EINVAL;              // no such link: the CSR has no room for it
+            const int32_t pr = g->pair[size_t(rf[size_t(i)])];
+            for (int32_t r = g->row_ptr[size_t(head[i])]; r < g->row_ptr[size_t(head[i]) + 1]; ++r)
+                if (!g->fwd[size_t(r)] && g->pair[size_t(r)] == pr) { rr[size_t(i)] = r; break; }
+            if (rr[size_t(i)] < 0) return FC_EINVAL;              // (cannot happen: every link has both records)
+        }
+        // the graph facts after the updates, checked before anything is changed (a later update of a link wins)
+        std::vector<int32_t> bw_new(g->bw);
+        for (int64_t i = 0; i < n_updates; ++i) { bw_new[size_t(rf[size_t(i)])] = bandwidth[i]; bw_new[size_t(rr[size_t(i)])] = bandwidth[i]; }
+        std::vector<int64_t> in_bw(size_t(n), 0), out_bw(size_t(n), 0);
+        int64_t gc = 0, mx = 0, sum = 0;
+        for (int32_t v = 0; v < n; ++v)
+            for (int32_t r = g->row_ptr[size_t(v)]; r < g->row_ptr[size_t(v) + 1]; ++r) {
+                if (!g->fwd[size_t(r)]) continue;
+                const int64_t b = bw_new[size_t(r)];
+                out_bw[size_t(v)] += b; in_bw[size_t(g->other[size_t(r)])] += b; sum += b;
+                gc = gcd64(gc, b); mx = std::max(mx, b);
+            }
+        int64_t min_in = -1; int32_t eul = 1;
+        for (int32_t v = 0; v < n; ++v) {
+            if (in_bw[size_t(v)] >= (int64_t(1) << 31)) return FC_EOVERFLOW;
+            if (in_bw[size_t(v)] != out_bw[size_t(v)]) eul = 0;
+            if (g->is_compute[size_t(v)] && (min_in < 0 || in_bw[size_t(v)] < min_in)) min_in = in_bw[size_t(v)];
+        }
+        for (size_t r = 0; r < bw_new.size(); ++r)
+            if (bw_new[r] != g->bw[r]) { edits.push_back(int32_t(r)); edits.push_back(bw_new[r]); }
+        g->bw.swap(bw_new);
+        for (int32_t v = 0; v < n; ++v) g->in_bw[size_t(v)] = int32_t(in_bw[size_t(v)]);
+        g->sum_bw = sum; g->min_in_bw = min_in; g->max_bw = int32_t(mx); g->gcd_bw = int32_t(gc); g->eulerian = eul;
+        return FC_OK;
+    } catch (const std::bad_alloc &) {
         return FC_ENOMEM;
     }
 }

@@ -43,11 +43,24 @@ struct fc_graph {
     int32_t *d_tree_ratio = nullptr;   // [n*2] per sink: worst load/bandwidth ratio of its first-arc tree (with d_p1)
     int32_t lds_limit = 0;             // bytes of LDS one workgroup may use
     int32_t n_cu = 0;
+    // The per-sink tables describe the bandwidths they were built from.  fc_graph_update_arcs either rebuilds them or
+    // marks them unusable; launches then start every problem with a search for heights in the kernel instead.
+    bool labels_valid = false;         // d_labels / d_label_hmax may be used
+    bool p1_valid = false;             // d_p1 / d_level_off / d_tree_ratio may be used
+    void *d_edits = nullptr;           // int2 [edits_cap] {record, bandwidth}: staging for fc_graph_update_arcs
+    size_t edits_cap = 0;
 };
 
 // host-only helpers implemented in fc_host.cpp
 int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &labels,
                         std::vector<uint16_t> &label_hmax, std::vector<uint32_t> &p1,
                         std::vector<uint16_t> &level_off, std::vector<int32_t> &tree_ratio, bool *too_deep);
+// keep_zero_links: an arc of bandwidth zero becomes a link that carries nothing (it has records and can be given
+// bandwidth later) instead of being dropped
 int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,
-                  const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out);
+                  const int32_t *bandwidth, const uint8_t *is_compute, fc_graph **out, bool keep_zero_links = false);
+// Set the bandwidth of existing links on the host side of g (records, in-bandwidths, the facts fc_graph_info reports).
+// Either every update is applied or none; `edits` receives {record, new bandwidth} for both records of every link
+// whose bandwidth changed.
+int fc_host_update_arcs(fc_graph *g, int64_t n_updates, const int32_t *tail, const int32_t *head,
+                        const int32_t *bandwidth, std::vector<int32_t> &edits);

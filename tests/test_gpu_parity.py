@@ -722,6 +722,201 @@ def test_remove_switches_on_config3_in_one_and_in_two_launches_per_batch():
     assert res[0]["table"] == want_table
 
 
+# ------------------------------------------------------------------ in-place bandwidth updates of an uploaded graph
+
+def _topology_of(base, cap):
+    live = sorted(key for key, b in cap.items() if b > 0)
+    return w.Topology(base.name + "_updated", base.n_vertices, np.array([a for a, _ in live], dtype=np.int32),
+                      np.array([b for _, b in live], dtype=np.int32), np.array([cap[x] for x in live], dtype=np.int32), base.is_compute)
+
+
+def _upload_with_spares(topo, spares):
+    tail = np.concatenate([topo.tail, np.array([a for a, _ in spares], dtype=np.int32)]).astype(np.int32)
+    head = np.concatenate([topo.head, np.array([b for _, b in spares], dtype=np.int32)]).astype(np.int32)
+    bw = np.concatenate([topo.bandwidth, np.zeros(len(spares), dtype=np.int32)]).astype(np.int32)
+    return fc.fc_graph_upload_with_spares(topo.n_vertices, tail, head, bw, topo.is_compute)
+
+
+def test_update_arcs_matches_oracle_on_random_graphs():
+    # links lowered (also to zero), raised, spare links brought to life; tables rebuilt or dropped: always the oracle's
+    # values on the updated arc list, and after a rebuild also its optimum
+    searched = 0
+    for seed in range(40):
+        rng = np.random.default_rng(33000 + seed)
+        topo = w.random_tiny(33000 + seed, max_cap=7, strongly_connected=(seed % 5 != 4))
+        n = topo.n_vertices
+        cap = o.link_capacities(topo)
+        spares = [(a, b) for a in range(n) for b in range(n) if a != b and (a, b) not in cap and rng.random() < 0.3]
+        for key in spares:
+            cap[key] = 0
+        for a, b, c in zip(topo.tail.tolist(), topo.head.tolist(), topo.bandwidth.tolist()):
+            if c == 0 and a != b:                       # the generator's own zero-bandwidth arc becomes a spare link too
+                cap.setdefault((a, b), 0)
+        with _upload_with_spares(topo, spares) as g:
+            assert fc.fc_graph_info(g).n_arcs_merged == len(cap)
+            for rnd in range(4):
+                keys = sorted(cap)
+                pick = [keys[int(i)] for i in rng.permutation(len(keys))[: max(1, int(len(keys) * rng.random()))]]
+                new = [int(rng.integers(0, 9)) if rng.random() < 0.8 else 0 for _ in pick]
+                refresh = bool((seed + rnd) % 2)
+                fc.fc_graph_update_arcs(g, [a for a, _ in pick], [b for _, b in pick], new, refresh_tables=refresh)
+                for key, b in zip(pick, new):
+                    cap[key] = b
+                now = _topology_of(topo, cap)
+                if now.n_arcs == 0:
+                    continue
+                info = fc.fc_graph_info(g)
+                assert info.min_in_bw_compute == o.min_compute_in_bandwidth(now) and info.is_eulerian == o.is_eulerian(now)
+                comp = now.compute_nodes
+                sink = np.tile(np.arange(n, dtype=np.int32), 3)
+                U = np.repeat(np.array([1, 2, 5], np.int32), n); k = np.repeat(np.array([1, 3, 4], np.int32), n)
+                want = o.aux_maxflow_batch(now, sink, U, k)
+                got, stats = _gpu_flows(g, sink, U, k, want_stats=True)
+                assert (got == want).all(), (seed, rnd, refresh)
+                assert stats["not_converged"] == 0
+                wide, _ = _gpu_flows(g, sink, U, k, options={"force_wide": 1})
+                assert (wide == want).all(), (seed, rnd, refresh)
+                if refresh:
+                    try:
+                        x = o.optimality_binary_search(now)
+                    except o.Disconnected:
+                        with pytest.raises(fc.FcError) as ei:
+                            fc.fc_opt_throughput_search(g, 4)
+                        assert ei.value.code == fc.FC_EDISCONNECTED
+                        continue
+                    assert fc.fc_opt_throughput_search(g, 1 + seed % 5)["inv_xstar"] == x, (seed, rnd)
+                    searched += 1
+    assert searched >= 30
+
+
+@pytest.mark.parametrize("cfg", [3, 5])
+def test_update_arcs_on_configs_matches_oracle(cfg):
+    # a degraded fabric: one link in ten at a fraction of its bandwidth, a few links down, a few upgraded; the full
+    # problem list against the oracle with the tables rebuilt (first pass along new first-arc trees) and without them
+    topo = w.config_topology(cfg)
+    rng = np.random.default_rng(34000 + cfg)
+    cap = o.link_capacities(topo)
+    keys = sorted(cap)
+    pick = [keys[int(i)] for i in rng.permutation(len(keys))[: len(keys) // 8]]
+    new = []
+    for j, key in enumerate(pick):
+        new.append(0 if j % 9 == 0 else (cap[key] * 3 if j % 9 == 1 else max(1, cap[key] // int(rng.integers(2, 5)))))
+    inv = _optimum(cfg, topo) if cfg == 5 else None
+    pl = w.config_problems(cfg, topo, inv)
+    with _upload(topo) as g:
+        for refresh in (False, True):
+            fc.fc_graph_update_arcs(g, [a for a, _ in pick], [b for _, b in pick], new, refresh_tables=refresh)
+            now = dict(cap)
+            for key, b in zip(pick, new):
+                now[key] = b
+            changed = _topology_of(topo, now)
+            want = o.aux_maxflow_batch(changed, pl.sink, pl.edge_mult, pl.src_cap, threads=16)
+            got, stats = _gpu_flows(g, pl.sink, pl.edge_mult, pl.src_cap, want_stats=True)
+            assert (got == want).all(), (cfg, refresh)
+            assert stats["not_converged"] == 0
+            # without tables every problem starts with a search for heights; with them none of these needs one up front
+            if not refresh:
+                assert stats["global_relabels"] >= len(pl.sink)
+            cert, _ = _gpu_flows(g, pl.sink, pl.edge_mult, pl.src_cap, options={"tree_certificate": 1})
+            assert (cert == want).all(), (cfg, refresh)
+            # and back: the original bandwidths give the original values again
+            fc.fc_graph_update_arcs(g, [a for a, _ in pick], [b for _, b in pick], [cap[key] for key in pick], refresh_tables=refresh)
+            want0 = o.aux_maxflow_batch(topo, pl.sink[:256], pl.edge_mult[:256], pl.src_cap[:256], threads=16)
+            got0, _ = _gpu_flows(g, pl.sink[:256], pl.edge_mult[:256], pl.src_cap[:256])
+            assert (got0 == want0).all(), (cfg, refresh)
+        assert fc.fc_opt_throughput_search(g, 16)["inv_xstar"] == Fraction(*_optimum(cfg, topo))
+
+
+def _remove_switches_in_place(D, k):
+    """Algorithm "Remove Switch Nodes" (Appendix E.2) driven from here: one uploaded graph, every gamma from
+    fc_split_gamma_batch on it, every split applied to it with fc_graph_update_arcs -- no second upload."""
+    cap = dict(o.link_capacities(D))
+    n = D.n_vertices
+    switches = [v for v in range(n) if not D.is_compute[v]]
+    # links a split can create: (u, t) over the ingress tails and egress heads of a switch, whatever was created before
+    ins = {v: set() for v in range(n)}; outs = {v: set() for v in range(n)}
+    for (a, b) in cap:
+        outs[a].add(b); ins[b].add(a)
+    spares = set()
+    for sw in switches:
+        for u in sorted(ins[sw]):
+            for t in sorted(outs[sw]):
+                if u != t and (u, t) not in cap:
+                    spares.add((u, t)); outs[u].add(t); ins[t].add(u)
+    spares = sorted(spares)
+    table = {}
+    with _upload_with_spares(D, spares) as g:
+        for sw in switches:
+            for t in sorted(h for (a, h), c in cap.items() if a == sw and c > 0):
+                for u in sorted(a for (a, h), c in cap.items() if h == sw and c > 0):
+                    if cap.get((sw, t), 0) == 0:
+                        break
+                    if cap.get((u, sw), 0) == 0:
+                        continue
+                    res = fc.fc_split_gamma_batch(g, 1, k, _dev([u]), _dev([sw]), _dev([t]))
+                    gam = int(res["gamma"].cpu()[0])
+                    assert gam >= 0
+                    if gam > 0:
+                        cap[(u, sw)] -= gam; cap[(sw, t)] -= gam
+                        upd = [(u, sw), (sw, t)]
+                        if u != t:
+                            cap[(u, t)] = cap.get((u, t), 0) + gam
+                            upd.append((u, t))
+                            table.setdefault((u, t), {})
+                            table[(u, t)][sw] = table[(u, t)].get(sw, 0) + gam
+                        fc.fc_graph_update_arcs(g, [a for a, _ in upd], [b for _, b in upd], [cap[x] for x in upd], refresh_tables=False)
+                assert cap.get((sw, t), 0) == 0
+    return {key: c for key, c in cap.items() if c > 0}, table
+
+
+def test_switch_removal_by_in_place_updates_matches_oracle():
+    # the paper's worked example, config 1 and random Eulerian switch topologies: D* and the path recovery table
+    cases = []
+    for b, U, k in ((1, 1, 1), (2, 3, 6)):
+        cases.append((_scaled(w.paper_example_switch(b), U), k))
+    topo = w.config_topology(1)
+    Uq, k = o.smallest_U_k(Fraction(*_optimum(1, topo)), topo.bandwidth)
+    cases.append((_scaled(topo, Uq.numerator), k * Uq.denominator))
+    for seed in range(12):
+        rng = np.random.default_rng(8000 + seed)
+        base = w.random_tiny(8000 + seed, n_vertices=int(rng.integers(4, 9)), max_cap=4, density=0.4)
+        if base.is_compute.all():
+            continue
+        cap = {}
+        for t, h, b in zip(base.tail.tolist(), base.head.tolist(), base.bandwidth.tolist()):
+            if t != h and b > 0:
+                key = (min(t, h), max(t, h)); cap[key] = cap.get(key, 0) + int(b)
+        tail = [a for a, b in cap] + [b for a, b in cap]; head = [b for a, b in cap] + [a for a, b in cap]
+        sym = w.Topology(f"euler{seed}", base.n_vertices, np.array(tail, dtype=np.int32), np.array(head, dtype=np.int32),
+                         np.array(list(cap.values()) * 2, dtype=np.int32), base.is_compute.copy())
+        try:
+            inv = o.optimality_binary_search(sym)
+        except o.Disconnected:
+            continue
+        Uq, k = o.smallest_U_k(inv, sym.bandwidth)
+        cases.append((_scaled(sym, Uq.numerator), k * Uq.denominator))
+    assert len(cases) >= 9
+    for D, k in cases:
+        want, want_table = o.remove_switches(D, k)
+        links, table = _remove_switches_in_place(D, k)
+        assert links == o.link_capacities(want), D.name
+        assert table == want_table, D.name
+
+
+def test_update_arcs_errors_on_the_device():
+    topo = w.config_topology(1)
+    with _upload(topo) as g:
+        sink = np.arange(16, dtype=np.int32); U = np.full(16, 1, np.int32); k = np.full(16, 4, np.int32)
+        before, _ = _gpu_flows(g, sink, U, k)
+        with pytest.raises(fc.FcError) as ei:
+            fc.fc_graph_update_arcs(g, [0, 0], [16, 5], [3, 3])             # (0, 5) is no link of config 1: nothing is applied
+        assert ei.value.code == fc.FC_EINVAL
+        after, _ = _gpu_flows(g, sink, U, k)
+        assert (before == after).all()
+        fc.fc_graph_update_arcs(g, [], [], [])                             # nothing to do
+        assert (_gpu_flows(g, sink, U, k)[0] == before).all()
+
+
 # ------------------------------------------------------------------ launch shapes the other tests do not reach
 
 def test_remove_switches_on_config4_keeps_the_optimum():

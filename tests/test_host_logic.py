@@ -262,3 +262,77 @@ def test_fixed_k_driver_synthetic_optima_and_errors():
     with pytest.raises(fc.FcError) as ei:
         fc.fc_fixed_k_search_with_verdicts(N, B, bmax, 0, 8, lambda c: [True] * len(c))
     assert ei.value.code == fc.FC_EINVAL
+
+
+# ------------------------------------------------------------------ in-place bandwidth updates (host side)
+
+def _links_of(g):
+    row_ptr, other, pair, bw, fwd = fc.fc_graph_csr(g)
+    out = {}
+    for u in range(len(row_ptr) - 1):
+        for r in range(row_ptr[u], row_ptr[u + 1]):
+            key = (u, int(other[r])) if fwd[r] else (int(other[r]), u)
+            out.setdefault(key, set()).add(int(bw[r]))
+    assert all(len(v) == 1 for v in out.values())          # both records of a link agree
+    return {key: next(iter(v)) for key, v in out.items()}
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_update_arcs_on_the_host_side_matches_a_fresh_build(seed):
+    rng = np.random.default_rng(31000 + seed)
+    topo = w.random_tiny(31000 + seed, max_cap=9)
+    g = fc.fc_graph_build(topo.n_vertices, topo.tail, topo.head, topo.bandwidth, topo.is_compute)
+    shape = [a.copy() for a in fc.fc_graph_csr(g)]
+    cap = _links_of(g)
+    assert cap == o.link_capacities(topo)
+    for _ in range(3):
+        keys = sorted(cap)
+        pick = [keys[int(i)] for i in rng.permutation(len(keys))[: max(1, len(keys) // 2)]]
+        new = [int(rng.integers(0, 12)) for _ in pick]
+        pick.append(pick[0]); new.append(int(rng.integers(0, 12)))      # listed twice: the later entry wins
+        fc.fc_graph_update_arcs(g, [a for a, _ in pick], [b for _, b in pick], new)
+        for key, b in zip(pick, new):
+            cap[key] = b
+        assert _links_of(g) == cap
+        now = fc.fc_graph_csr(g)
+        for i in (0, 1, 2, 4):                                           # everything but the bandwidths is where it was
+            assert (now[i] == shape[i]).all()
+        # the facts fc_graph_info reports are those of a graph built from the updated arc list
+        live = sorted(key for key, b in cap.items() if b > 0)
+        info = fc.fc_graph_info(g)
+        if live:
+            fresh = fc.fc_graph_build(topo.n_vertices, [a for a, _ in live], [b for _, b in live], [cap[x] for x in live], topo.is_compute)
+            want = fc.fc_graph_info(fresh)
+            assert (info.min_in_bw_compute, info.max_bw, info.gcd_bw, info.is_eulerian) == \
+                   (want.min_in_bw_compute, want.max_bw, want.gcd_bw, want.is_eulerian)
+        assert info.n_arcs_merged == len(cap)                            # links lowered to zero keep their records
+    g.close()
+
+
+def test_update_arcs_rejects_bad_input_and_changes_nothing_then():
+    g = fc.fc_graph_build(4, [0, 1, 2, 3], [1, 2, 3, 0], [5, 6, 7, 8], [1, 1, 0, 1])
+    before = _links_of(g)
+    for args, code in [
+        (([0], [2], [3]), fc.FC_EINVAL),                       # no such link
+        (([0, 1], [1, 0], [3, 3]), fc.FC_EINVAL),              # the second one is no link (the first must not be applied)
+        (([0], [1], [-1]), fc.FC_EINVAL),
+        (([4], [1], [1]), fc.FC_EINVAL),
+        (([0, 3], [1, 0], [2 ** 31 - 1, 1]), fc.FC_OK),        # large but representable
+    ]:
+        if code == fc.FC_OK:
+            fc.fc_graph_update_arcs(g, *args)
+            continue
+        with pytest.raises(fc.FcError) as ei:
+            fc.fc_graph_update_arcs(g, *args)
+        assert ei.value.code == code
+        assert _links_of(g) == before
+    # two links into one vertex whose bandwidths add up to 2^31
+    g2 = fc.fc_graph_build(3, [0, 1, 2], [2, 2, 0], [1, 1, 1], [1, 1, 1])
+    with pytest.raises(fc.FcError) as ei:
+        fc.fc_graph_update_arcs(g2, [0, 1], [2, 2], [2 ** 30, 2 ** 30])
+    assert ei.value.code == fc.FC_EOVERFLOW and _links_of(g2) == {(0, 2): 1, (1, 2): 1, (2, 0): 1}
+    lib = fc.load_library()
+    assert lib.fc_graph_update_arcs(g2.handle, 0, None, None, None, 2, None) == fc.FC_EINVAL      # refresh_tables is 0 or 1
+    assert lib.fc_graph_update_arcs(None, 0, None, None, None, 1, None) == fc.FC_EINVAL
+    assert lib.fc_graph_update_arcs(g2.handle, 0, None, None, None, 1, None) == fc.FC_OK          # nothing to do
+    g.close(); g2.close()
