@@ -240,7 +240,7 @@ def main():
         "roofline": main_leg["roofline"],
         "fc_feasible": head.get("fc_feasible") if entry_point != "fc_feasible" else None,
         "graph_upload_ms": head["graph_upload_ms"],
-        "graph_upload_is": "fc_graph_upload: validation, merging, residual CSR, per-sink label / first-arc tables on host threads, copies",
+        "graph_upload_is": "fc_graph_upload: validation, merging, residual CSR on the host, copies, per-sink label / first-arc tables by a kernel on the device",
         "search": head["search"],
     }
 

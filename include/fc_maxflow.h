@@ -138,7 +138,8 @@ typedef struct {
  * non-zero = compute node.
  *
  * fc_graph_build   : host-side part only (validation, merging, residual CSR); needs no GPU.
- * fc_graph_upload  : fc_graph_build + copy to the current HIP device (+ per-sink label table).
+ * fc_graph_upload  : fc_graph_build + copy to the current HIP device + the per-sink tables (initial heights and
+ *                    first-arc trees per sink, built by a kernel on the device; see fc_graph_sink_table).
  * Errors: FC_EINVAL (null pointers, ids out of range, negative bandwidth, fewer than two
  * compute nodes, n_vertices < 2), FC_EOVERFLOW (a merged bandwidth or an in-bandwidth sum
  * reaches 2^31), FC_ENOMEM, FC_EDEVICE, FC_EUNSUPPORTED (per-problem state exceeds on-chip memory).
@@ -167,8 +168,8 @@ int fc_graph_free(fc_graph *g);
  *
  * The facts fc_graph_info reports (min B^-, max b_e, gcd, Eulerian flag) follow the update.  The per-sink tables of
  * the uploaded graph (initial heights, first-arc trees: functions of the bandwidths) are
- *   refresh_tables = 1: rebuilt on host threads and copied again, as in fc_graph_upload; every later call then
- *                       behaves exactly as on a fresh upload of the updated arc list;
+ *   refresh_tables = 1: rebuilt by the same kernel as in fc_graph_upload; every later call then behaves exactly as
+ *                       on a fresh upload of the updated arc list;
  *   refresh_tables = 0: marked unusable until a later call with refresh_tables = 1: the solver kernels then start
  *                       each problem with a search for exact heights on the device instead.  Same values, slower
  *                       batches, a much cheaper update: the choice for loops that change the graph between launches.
@@ -214,6 +215,30 @@ int fc_graph_set_source_weights(fc_graph *g, const int32_t *weight_per_vertex);
  * [2 * n_arcs_merged]. */
 int fc_graph_csr(const fc_graph *g, int32_t *row_ptr, int32_t *other, int32_t *pair,
                  int32_t *bw, uint8_t *forward);
+
+/* The per-sink tables of an uploaded graph as the device holds them, for inspection and tests (synchronous copies
+ * from the current device).  For the vertex `sink` taken as the sink of a max-flow (Section 5.2: every compute node
+ * is one in turn), before any flow has been pushed:
+ *   label[v]        [n_vertices]  breadth-first distance from v to sink over links of positive bandwidth (n_vertices:
+ *                                 cannot reach it) -- the exact initial heights of push-relabel;
+ *   *label_hmax                   the largest finite label of a compute node;
+ *   level_table     [64]          [0] = deepest level L, [1 + j] = where level L - j starts in the order below,
+ *                                 [1 + L] = where the order ends;
+ *   order_vertex[i], first_head[i], first_pair[i], first_bw[i]   [n_vertices]  the i-th vertex by decreasing label (ties
+ *                                 by id) and the link along which its excess is sent first: head, merged-arc number
+ *                                 (as in fc_graph_csr) and bandwidth; entries past the order's end are 0.  The first
+ *                                 links form a spanning in-tree of the vertices that reach the sink, every link
+ *                                 going exactly one level down;
+ *   ratio           [2]           {num, den}: the largest (compute nodes in the subtree of v) / (bandwidth of v's first
+ *                                 link) over that tree, den = 0 if some compute node cannot reach the sink -- the
+ *                                 first-arc tree certificate: if k * num <= U * den, the tree alone carries N * k.
+ * *have: bit 0 = labels exist (label, label_hmax are filled), bit 1 = the level order exists (the rest is filled):
+ * large graphs (more than 8192 / 4096 vertices), sinks deeper than 62 levels, and graphs whose tables were switched
+ * off by fc_graph_update_arcs have fewer.  Any output pointer but `have` may be null.
+ * Errors: FC_EINVAL, FC_EDEVICE (graph not uploaded, copy failed), FC_ENOMEM. */
+int fc_graph_sink_table(const fc_graph *g, int32_t sink, int32_t *have, int32_t *label, int32_t *label_hmax,
+                        int32_t *level_table, int32_t *order_vertex, int32_t *first_head, int32_t *first_pair,
+                        int32_t *first_bw, int32_t *ratio);
 
 /* ------------------------------------------------------------------------------------------
  * fc_maxflow_batch -- many independent max-flows on the auxiliary network (Section 5.2,

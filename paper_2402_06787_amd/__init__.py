@@ -5,7 +5,7 @@ The product is the C-ABI library `libfcmaxflow.so` (HIP kernels for gfx950 + hos
 this package is its thin Python binding.  Build it with `python -m paper_2402_06787_amd.build`.
 """
 from .binding import (FcError, Graph, GraphInfo, fc_options, fc_stats, fc_rational, load_library, strerror,
-                      fc_graph_build, fc_graph_upload, fc_graph_upload_with_spares, fc_graph_update_arcs, fc_graph_info, fc_graph_csr, fc_graph_set_source_weights,
+                      fc_graph_build, fc_graph_upload, fc_graph_upload_with_spares, fc_graph_update_arcs, fc_graph_sink_table, fc_graph_info, fc_graph_csr, fc_graph_set_source_weights,
                       fc_maxflow_batch_workspace_bytes, fc_maxflow_batch, fc_maxflow_batch_static,
                       FC_MAXFLOW_BATCH_STATIC_MAX_PROBLEMS,
                       fc_feasible_workspace_bytes, fc_feasible, fc_opt_throughput_search,

@@ -22,7 +22,7 @@ FC_EWORKSPACE, FC_EDEVICE, FC_ENOCONVERGE, FC_EUNSUPPORTED = -5, -6, -7, -8
 FC_FLOW_INVALID, FC_FLOW_NOCONVERGE, FC_FLOW_UNSUPPORTED = -1, -2, -3
 FC_GAMMA_INVALID = -2147483648
 
-EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_upload_with_spares", "fc_graph_update_arcs", "fc_graph_free", "fc_graph_info", "fc_graph_csr", "fc_graph_set_source_weights",
+EXPORTED = ["fc_graph_build", "fc_graph_upload", "fc_graph_upload_with_spares", "fc_graph_update_arcs", "fc_graph_sink_table", "fc_graph_free", "fc_graph_info", "fc_graph_csr", "fc_graph_set_source_weights",
             "fc_maxflow_batch_workspace_bytes", "fc_maxflow_batch", "fc_maxflow_batch_static", "fc_maxflow_batch_floor", "fc_feasible_workspace_bytes",
             "fc_feasible_floor", "fc_fixed_k_search", "fc_fixed_k_search_with_verdicts",
             "fc_split_gamma_workspace_bytes", "fc_split_gamma_batch", "fc_remove_switches", "fc_tree_mu_batch", "fc_construct_trees",
@@ -84,6 +84,8 @@ def load_library():
     lib.fc_graph_upload_with_spares.argtypes = [i32, i64, vp, vp, vp, vp, c.POINTER(vp)]
     lib.fc_graph_update_arcs.restype = c.c_int
     lib.fc_graph_update_arcs.argtypes = [vp, i64, vp, vp, vp, i32, vp]
+    lib.fc_graph_sink_table.restype = c.c_int
+    lib.fc_graph_sink_table.argtypes = [vp, i32, c.POINTER(i32), vp, c.POINTER(i32), vp, vp, vp, vp, vp, vp]
     lib.fc_graph_free.restype = c.c_int
     lib.fc_graph_free.argtypes = [vp]
     lib.fc_graph_info.restype = c.c_int
@@ -236,6 +238,24 @@ def fc_graph_update_arcs(g: Graph, tail, head, bandwidth, refresh_tables: bool =
     _check(load_library().fc_graph_update_arcs(g.handle, int(tail.shape[0]), _host_ptr(tail), _host_ptr(head), _host_ptr(bandwidth),
                                                1 if refresh_tables else 0, _stream_ptr_for_host_call(stream)),
            "fc_graph_update_arcs")
+
+
+def fc_graph_sink_table(g: Graph, sink: int) -> dict:
+    """The per-sink tables the device holds for `sink` (see the header): dict with `have`, and when present `label`,
+    `label_hmax`, `level_table`, `order_vertex`, `first_head`, `first_pair`, `first_bw`, `ratio`."""
+    n = g.n_vertices
+    have, hmax = ctypes.c_int32(0), ctypes.c_int32(0)
+    label = np.zeros(n, np.int32); lt = np.zeros(64, np.int32); ratio = np.zeros(2, np.int32)
+    ov, fh, fp, fb = (np.zeros(n, np.int32) for _ in range(4))
+    _check(load_library().fc_graph_sink_table(g.handle, int(sink), ctypes.byref(have), _host_ptr(label), ctypes.byref(hmax), _host_ptr(lt),
+                                              _host_ptr(ov), _host_ptr(fh), _host_ptr(fp), _host_ptr(fb), _host_ptr(ratio)),
+           "fc_graph_sink_table")
+    out = {"have": have.value}
+    if have.value & 1:
+        out.update(label=label, label_hmax=hmax.value)
+    if have.value & 2:
+        out.update(level_table=lt, order_vertex=ov, first_head=fh, first_pair=fp, first_bw=fb, ratio=(int(ratio[0]), int(ratio[1])))
+    return out
 
 
 def fc_graph_info(g: Graph) -> GraphInfo:

@@ -6,8 +6,6 @@
 #include <cstring>
 #include <new>
 #include <numeric>
-#include <system_error>
-#include <thread>
 
 #include "fc_internal.h"
 
@@ -101,117 +99,6 @@ int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const
         *out = g;
         return FC_OK;
     } catch (const std::bad_alloc &) {
-        return FC_ENOMEM;
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Per-sink tables (topology only).  For every vertex t taken as the sink:
-//   labels[t][v]     breadth-first distance from v to t (n = cannot reach t), bit 15 = compute node:
-//                    the exact initial heights of push-relabel, when no flow has been pushed yet
-//   label_hmax[t]    largest finite label of a compute node (the first level to discharge)
-//   level_off[t][*]  [0] = deepest level L, [1 + j] = start of level L - j in p1[t], [1 + L] = end
-//   tree_ratio[t]    {num, den}: the largest ratio (compute nodes whose first-arc path runs through v) /
-//                    (bandwidth of v's first arc) over all v; den = 0 if a compute node cannot reach t
-//   p1[t][i]         4 words: the i-th vertex by decreasing label (ties by id) and the arc its excess is
-//                    sent along first -- {x, y} = that arc's 16-bit-layout record, z = vertex, w = 0
-// Any arc that leaves v and ends one level down is admissible for that first push.  Which one is
-// chosen does not change any max-flow value, only how much rerouting the solver has to do, so the
-// choice balances the tree: v goes to the parent q that keeps max(weight(v) / b(v,q),
-// load(q) / downhill bandwidth of q) smallest, where weight = compute nodes in the subtree.
-int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &labels,
-                        std::vector<uint16_t> &label_hmax, std::vector<uint32_t> &p1,
-                        std::vector<uint16_t> &level_off, std::vector<int32_t> &tree_ratio, bool *too_deep) {
-    const int32_t n = g->n;
-    const int32_t MAXL = 62;
-    try {
-        labels.assign(size_t(n) * n, 0); label_hmax.assign(size_t(n), 0);
-        if (want_p1) { p1.assign(size_t(n) * n * 4, 0u); level_off.assign(size_t(n) * 64, 0); tree_ratio.assign(size_t(n) * 2, 0); }
-        std::vector<int> deep(64, 0);
-        unsigned hw = std::thread::hardware_concurrency();
-        const int n_threads = int(std::max(1u, std::min(16u, hw ? hw : 1u)));
-        auto work = [&](int tid) {
-            const size_t nn = size_t(n);
-            std::vector<int32_t> dist(nn, 0), queue(nn, 0), parent_rec(nn, 0), order(nn, 0);
-            std::vector<int64_t> wt(nn, 0), load(nn, 0), cap_down(nn, 0);
-            std::vector<int32_t> lvl_start;
-            for (int32_t t = tid; t < n; t += n_threads) {
-                std::fill(dist.begin(), dist.end(), n);
-                int32_t qh = 0, qt = 0; dist[t] = 0; queue[qt++] = t;
-                while (qh < qt) {
-                    const int32_t w = queue[qh++];
-                    for (int32_t r = g->row_ptr[w]; r < g->row_ptr[w + 1]; ++r)
-                        if (!g->fwd[r] && g->bw[r] > 0 && dist[g->other[r]] == n) { dist[g->other[r]] = dist[w] + 1; queue[qt++] = g->other[r]; }
-                }
-                int32_t hm = 0, L = 0;
-                for (int32_t v = 0; v < n; ++v) {
-                    labels[size_t(t) * n + v] = uint16_t(dist[v] | (g->is_compute[v] ? 0x8000 : 0));
-                    if (v != t && dist[v] < n) { L = std::max(L, dist[v]); if (g->is_compute[v]) hm = std::max(hm, dist[v]); }
-                }
-                label_hmax[t] = uint16_t(hm);
-                if (!want_p1) continue;
-                if (L > MAXL) { deep[tid] = 1; continue; }
-                // the breadth-first queue already lists vertices by increasing distance; make ties go by id
-                lvl_start.assign(size_t(L) + 2, 0);
-                for (int32_t v = 0; v < n; ++v) if (v != t && dist[v] < n) lvl_start[dist[v]]++;
-                {   // positions by decreasing level
-                    int32_t pos = 0;
-                    for (int32_t d = L; d >= 1; --d) { int32_t c = lvl_start[d]; lvl_start[d] = pos; pos += c; }
-                    lvl_start[0] = pos;                                   // end
-                }
-                {
-                    std::vector<int32_t> fill(lvl_start.begin(), lvl_start.end());
-                    for (int32_t v = 0; v < n; ++v) if (v != t && dist[v] < n) order[fill[dist[v]]++] = v;
-                }
-                uint16_t *lo = &level_off[size_t(t) * 64];
-                lo[0] = uint16_t(L);
-                for (int32_t d = L; d >= 1; --d) lo[1 + (L - d)] = uint16_t(lvl_start[d]);
-                lo[1 + L] = uint16_t(lvl_start[0]);
-                // downhill bandwidth, then parents from the deepest level up
-                for (int32_t v = 0; v < n; ++v) {
-                    wt[v] = g->is_compute[v] ? 1 : 0; load[v] = 0; cap_down[v] = 0; parent_rec[v] = -1;
-                    if (dist[v] >= n || v == t) continue;
-                    for (int32_t r = g->row_ptr[v]; r < g->row_ptr[v + 1]; ++r)
-                        if (g->fwd[r] && dist[g->other[r]] + 1 == dist[v]) cap_down[v] += g->bw[r];
-                }
-                // largest (compute nodes below v) / (bandwidth of v's first arc) over the tree, as a fraction;
-                // 1/0 when some compute node cannot reach t at all
-                int64_t worst_num = 0, worst_den = 1;
-                for (int32_t v = 0; v < n; ++v) if (g->is_compute[v] && dist[v] >= n) { worst_num = 1; worst_den = 0; }
-                for (int32_t i = 0; i < lvl_start[0]; ++i) {             // order[] is by decreasing level
-                    const int32_t v = order[i];
-                    double best = 0; int32_t best_r = -1;
-                    for (int32_t r = g->row_ptr[v]; r < g->row_ptr[v + 1]; ++r) {
-                        if (!g->fwd[r] || g->bw[r] <= 0) continue;         // (a link of bandwidth zero carries nothing)
-                        const int32_t q = g->other[r];
-                        if (dist[q] + 1 != dist[v]) continue;
-                        double cost = double(wt[v]) / double(g->bw[r]);
-                        if (q != t && cap_down[q] > 0) cost = std::max(cost, double(load[q] + wt[v]) / double(cap_down[q]));
-                        if (best_r < 0 || cost < best) { best = cost; best_r = r; }
-                    }
-                    parent_rec[v] = best_r;                               // exists: v has a finite label >= 1
-                    const int32_t q = g->other[best_r];
-                    load[q] += wt[v]; wt[q] += wt[v];
-                    if (worst_den != 0 && wt[v] * worst_den > worst_num * int64_t(g->bw[best_r])) { worst_num = wt[v]; worst_den = g->bw[best_r]; }
-                    uint32_t *en = &p1[(size_t(t) * n + size_t(i)) * 4];
-                    en[0] = uint32_t(q) | (1u << 15) | (uint32_t(g->pair[best_r]) << 16);
-                    en[1] = uint32_t(g->bw[best_r]);
-                    en[2] = uint32_t(v);
-                    en[3] = 0u;
-                }
-                tree_ratio[size_t(t) * 2] = int32_t(worst_num); tree_ratio[size_t(t) * 2 + 1] = int32_t(worst_den);
-            }
-        };
-        std::vector<std::thread> pool;
-        for (int i = 1; i < n_threads; ++i) pool.emplace_back(work, i);
-        work(0);
-        for (auto &th : pool) th.join();
-        *too_deep = false;
-        for (int i = 0; i < n_threads; ++i) if (deep[i]) *too_deep = true;
-        return FC_OK;
-    } catch (const std::bad_alloc &) {
-        return FC_ENOMEM;
-    } catch (const std::system_error &) {
         return FC_ENOMEM;
     }
 }

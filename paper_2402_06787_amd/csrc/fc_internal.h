@@ -40,7 +40,7 @@ struct fc_graph {
     uint16_t *d_label_hmax = nullptr;  // [n] highest finite label of a compute node, per sink
     void *d_p1 = nullptr;              // uint4 [n*n] first-pass entries in level order, per sink (null: not built)
     uint16_t *d_level_off = nullptr;   // [n*64] level boundaries in d_p1, per sink
-    int32_t *d_tree_ratio = nullptr;   // [n*2] per sink: worst load/bandwidth ratio of its first-arc tree (with d_p1)
+    int32_t *d_tree_ratio = nullptr;   // [n*2] per sink: worst load/bandwidth ratio of its first-arc tree (with d_p1); then [n]: sink too deep for the level table
     int32_t lds_limit = 0;             // bytes of LDS one workgroup may use
     int32_t n_cu = 0;
     // The per-sink tables describe the bandwidths they were built from.  fc_graph_update_arcs either rebuilds them or
@@ -52,9 +52,6 @@ struct fc_graph {
 };
 
 // host-only helpers implemented in fc_host.cpp
-int fc_host_sink_tables(const fc_graph *g, bool want_p1, std::vector<uint16_t> &labels,
-                        std::vector<uint16_t> &label_hmax, std::vector<uint32_t> &p1,
-                        std::vector<uint16_t> &level_off, std::vector<int32_t> &tree_ratio, bool *too_deep);
 // keep_zero_links: an arc of bandwidth zero becomes a link that carries nothing (it has records and can be given
 // bandwidth later) instead of being dropped
 int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const int32_t *head,

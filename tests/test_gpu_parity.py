@@ -722,6 +722,87 @@ def test_remove_switches_on_config3_in_one_and_in_two_launches_per_batch():
     assert res[0]["table"] == want_table
 
 
+# ------------------------------------------------------------------ the per-sink tables the device builds at upload
+
+def _check_sink_table(topo, g, sink, tab, cap):
+    """What the tables promise, recomputed here from the link list alone."""
+    n = topo.n_vertices
+    into = {v: [] for v in range(n)}
+    for (a, b), c in cap.items():
+        if c > 0:
+            into[b].append(a)
+    dist = [n] * n; dist[sink] = 0; frontier = [sink]                     # breadth-first search against the links
+    while frontier:
+        nxt = []
+        for x in frontier:
+            for a in into[x]:
+                if dist[a] == n:
+                    dist[a] = dist[x] + 1; nxt.append(a)
+        frontier = nxt
+    assert tab["have"] & 1
+    assert tab["label"].tolist() == dist
+    reach = [v for v in range(n) if v != sink and dist[v] < n]
+    assert tab["label_hmax"] == max([dist[v] for v in reach if topo.is_compute[v]], default=0)
+    if not tab["have"] & 2:
+        return False
+    L = max([dist[v] for v in reach], default=0)
+    lt = tab["level_table"].tolist()
+    assert lt[0] == L
+    want_order = sorted(reach, key=lambda v: (-dist[v], v))
+    assert tab["order_vertex"][: len(reach)].tolist() == want_order
+    starts = [sum(1 for v in reach if dist[v] > d) for d in range(L, 0, -1)]   # level d starts after all deeper vertices
+    assert lt[1: 1 + L] == starts and lt[1 + L] == len(reach) and all(x == 0 for x in lt[2 + L:])
+    row_ptr, other, pair, bw, fwd = fc.fc_graph_csr(g)
+    pair_of = {}
+    for u in range(n):
+        for r in range(row_ptr[u], row_ptr[u + 1]):
+            if fwd[r]:
+                pair_of[(u, int(other[r]))] = int(pair[r])
+    weight = {v: int(topo.is_compute[v]) for v in range(n)}
+    num, den = (1, 0) if any(topo.is_compute[v] and dist[v] >= n for v in range(n)) else (0, 1)
+    for i, v in enumerate(want_order):                                       # children come before their parents
+        q, b = int(tab["first_head"][i]), int(tab["first_bw"][i])
+        assert cap.get((v, q), 0) == b > 0 and dist[q] == dist[v] - 1, (sink, v, q)
+        assert int(tab["first_pair"][i]) == pair_of[(v, q)]
+        weight[q] += weight[v]
+        if den != 0 and weight[v] * den > num * b:
+            num, den = weight[v], b
+    assert weight[sink] == sum(int(topo.is_compute[v]) for v in range(n) if dist[v] < n)   # a spanning in-tree: everything arrives
+    rn, rd = tab["ratio"]
+    assert (rd == 0) == (den == 0) and rn * den == num * rd, (sink, tab["ratio"], num, den)
+    for i in range(len(reach), n):
+        assert tab["first_bw"][i] == 0 and tab["order_vertex"][i] == 0
+    return True
+
+
+def test_sink_tables_on_random_graphs_and_configs():
+    full = 0
+    for seed in range(30):
+        topo = w.random_tiny(35000 + seed, max_cap=9, strongly_connected=(seed % 3 != 2))
+        cap = o.link_capacities(topo)
+        with _upload(topo) as g:
+            for sink in range(topo.n_vertices):
+                full += _check_sink_table(topo, g, sink, fc.fc_graph_sink_table(g, sink), cap)
+    assert full > 100
+    for cfg in (1, 2, 3, 4, 5):
+        topo = w.config_topology(cfg)
+        cap = o.link_capacities(topo)
+        rng = np.random.default_rng(35100 + cfg)
+        sinks = sorted(set([0, topo.n_vertices - 1] + [int(x) for x in rng.integers(0, topo.n_vertices, 6 if cfg < 4 else 3)]))
+        with _upload(topo) as g:
+            for sink in sinks:
+                assert _check_sink_table(topo, g, sink, fc.fc_graph_sink_table(g, sink), cap)
+    # a path of 70 vertices is deeper than the level table: labels only, and the solver still gets every value right
+    n = 70
+    tail = list(range(n - 1)) + list(range(1, n)); head = list(range(1, n)) + list(range(n - 1))
+    line = w.Topology("line70", n, np.array(tail, np.int32), np.array(head, np.int32), np.full(len(tail), 3, np.int32), np.ones(n, np.uint8))
+    with _upload(line) as g:
+        tab = fc.fc_graph_sink_table(g, 0)
+        assert tab["have"] == 1 and tab["label"].tolist() == list(range(n))
+        sink = np.arange(n, dtype=np.int32); U = np.full(n, 2, np.int32); k = np.full(n, 1, np.int32)
+        assert (_gpu_flows(g, sink, U, k)[0] == o.aux_maxflow_batch(line, sink, U, k)).all()
+
+
 # ------------------------------------------------------------------ in-place bandwidth updates of an uploaded graph
 
 def _topology_of(base, cap):
