@@ -676,18 +676,22 @@ def test_mu_by_max_flow_equals_its_definition(seed):
 @pytest.mark.parametrize("seed", range(16))
 def test_trees_after_switch_removal(seed):
     # the whole back end on a small random switch topology: optimum, scaling, switch removal, trees
-    base = w.random_tiny(7000 + seed, n_vertices=int(5 + seed % 3))
-    cap = {}
-    for t, h, b in zip(base.tail.tolist(), base.head.tolist(), base.bandwidth.tolist()):
-        if t != h and b > 0:
-            key = (min(t, h), max(t, h)); cap[key] = cap.get(key, 0) + int(b)
-    tail = [a for a, b in cap] + [b for a, b in cap]; head = [b for a, b in cap] + [a for a, b in cap]
-    sym = w.Topology(f"euler{seed}", base.n_vertices, np.array(tail, dtype=np.int32), np.array(head, dtype=np.int32),
-                     np.array(list(cap.values()) * 2, dtype=np.int32), base.is_compute.copy())
-    try:
-        inv = o.optimality_binary_search(sym)
-    except o.Disconnected:
-        pytest.skip("disconnected draw")
+    inv = None
+    for redraw in range(20):                               # a disconnected draw is drawn again, never skipped
+        base = w.random_tiny(7000 + seed + 100 * redraw, n_vertices=int(5 + seed % 3))
+        cap = {}
+        for t, h, b in zip(base.tail.tolist(), base.head.tolist(), base.bandwidth.tolist()):
+            if t != h and b > 0:
+                key = (min(t, h), max(t, h)); cap[key] = cap.get(key, 0) + int(b)
+        tail = [a for a, b in cap] + [b for a, b in cap]; head = [b for a, b in cap] + [a for a, b in cap]
+        sym = w.Topology(f"euler{seed}", base.n_vertices, np.array(tail, dtype=np.int32), np.array(head, dtype=np.int32),
+                         np.array(list(cap.values()) * 2, dtype=np.int32), base.is_compute.copy())
+        try:
+            inv = o.optimality_binary_search(sym)
+            break
+        except o.Disconnected:
+            continue
+    assert inv is not None
     Uq, k = o.smallest_U_k(inv, sym.bandwidth)
     U, kk = Uq.numerator, k * Uq.denominator
     D = w.Topology(sym.name, sym.n_vertices, sym.tail, sym.head, (sym.bandwidth.astype(np.int64) * U).astype(np.int32), sym.is_compute)
