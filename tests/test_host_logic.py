@@ -336,3 +336,15 @@ def test_update_arcs_rejects_bad_input_and_changes_nothing_then():
     assert lib.fc_graph_update_arcs(None, 0, None, None, None, 1, None) == fc.FC_EINVAL
     assert lib.fc_graph_update_arcs(g2.handle, 0, None, None, None, 1, None) == fc.FC_OK          # nothing to do
     g.close(); g2.close()
+
+
+def test_sink_table_needs_an_uploaded_graph():
+    g = fc.fc_graph_build(3, [0, 1], [1, 2], [1, 1], [1, 1, 0])   # host-only graph: the tables live on the device
+    with pytest.raises(fc.FcError) as ei:
+        fc.fc_graph_sink_table(g, 0)
+    assert ei.value.code == fc.FC_EDEVICE
+    for bad in (-1, 3):
+        with pytest.raises(fc.FcError) as ei:
+            fc.fc_graph_sink_table(g, bad)
+        assert ei.value.code == fc.FC_EINVAL
+    g.close()
