@@ -84,6 +84,18 @@ def roofline_block(stats, kernel_ms, n_problems, n_src, m_src, hw):
     }
 
 
+def _cpu_model():
+    """Model name of the host CPU the oracle is timed on (first entry of /proc/cpuinfo), or 'unknown'."""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -422,7 +434,8 @@ def main():
         out["cpu_baseline"] = {"value": len(idx) / t_all, "unit": "solves/s", "cores": cores, "kind": "oracle",
                                "sample": f"{len(idx)} of the step's {P} problems (Dinic, gcc -O2, problems split "
                                          f"statically over {cores} threads)",
-                               "single_thread_value": len(idx1) / t_one, "single_thread_sample": len(idx1)}
+                               "single_thread_value": len(idx1) / t_one, "single_thread_sample": len(idx1),
+                               "host": {"cpu_model": _cpu_model(), "logical_cpus": os.cpu_count()}}
         batch_flows = H["d_out"].cpu().numpy().astype(np.int64) if entry_point == "fc_maxflow_batch" else gpu_flows
         out["parity_vs_oracle"] = {"checked": int(len(idx)), "mismatches": int((gpu_flows[idx] != ref).sum()),
                                    "mismatches_fc_maxflow_batch": int((batch_flows[idx] != ref).sum())}
