@@ -75,11 +75,13 @@ typedef struct {
                                       than 8 problems fit a CU's LDS, else 128, 64 below 256 vertices)   */
     int32_t lanes_per_vertex;      /* power of two in [2, 64]: lanes that scan one vertex's arc list   */
     int32_t global_relabel_steps;  /* relabel from the sink when this many level steps passed since
-                                      the last one and some vertex was relabeled                       */
+                                      the last one and some vertex was relabeled (default 32; launches of
+                                      fc_construct_trees from kept flows: 4)                             */
     int32_t global_relabel_permille; /* ... or when relabels since then reach this fraction of |V|     */
     int32_t global_relabel_rises;  /* ... or when the working height level moved up this many times since
                                       then (-1: off; default: off, except fc_split_gamma_batch and
-                                      fc_remove_switches on graphs of 256 vertices or more: 2)          */
+                                      fc_remove_switches on graphs of 256 vertices or more: 2, and tree
+                                      launches from kept flows: 1)                                     */
     int32_t tight_sink_percent;    /* a problem whose sink cut U*B^-(t) (+k) is below this percentage of the
                                       demand N*k relabels from the sink the first time the working level
                                       moves up (default 200, -1: off)                                  */
