@@ -125,7 +125,8 @@ typedef struct {
                                       asked for).  On: a problem of the second launch gives the new sink v the units that
                                       still matter and pushes them backwards along the residual arcs to the excess the
                                       first launch left stranded, instead of moving all that excess towards v.  Same values. */
-    int32_t tree_chain_states;     /* fc_construct_trees: states one launch looks ahead, 1 to 64 (default 32, see there)   */
+    int32_t tree_chain_states;     /* fc_construct_trees: states one launch looks ahead, 1 to 64 (default 32; 64 on
+                                      digraphs of 1024 vertices or more; see there)                                       */
 } fc_options;
 
 /* ------------------------------------------------------------------------------------------
