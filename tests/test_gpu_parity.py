@@ -627,6 +627,33 @@ def test_split_gamma_on_configs(cfg):
     assert (early == got).all()
 
 
+def test_split_gamma_on_the_1024_compute_rail_fabric():
+    # Paper-scale Eulerian input (1 160 vertices): one pair over a box switch, one over a rail switch, at the optimum (127, 2);
+    # graphs of 1024 vertices or more run these launches with four wavefronts per problem.  The oracle takes about 8 s a pair.
+    topo = w.eulerian_fabric_1024()
+    U, k = 127, 2
+    D = _scaled(topo, U)
+    cap = o.link_capacities(topo)
+    pick = []
+    for sw, i_in, i_out in ((1024, 0, 1), (topo.n_vertices - 1, 3, 100)):
+        assert not topo.is_compute[sw]
+        ins = sorted(u for (u, x) in cap if x == sw); outs = sorted(t for (y, t) in cap if y == sw)
+        pick.append((ins[i_in], sw, outs[i_out]))
+    got, flows = _gamma_on_gpu(topo, U, k, pick)
+    for i, (u, sw, t) in enumerate(pick):
+        F1, F2 = o.split_flows(D, k, u, sw, t)
+        assert (flows[i, 0] == F1).all() and (flows[i, 1] == F2).all(), (u, sw, t)
+        # the oracle's gamma, from the flows it has just computed (o.split_gamma would compute them a second time)
+        capD = o.link_capacities(D)
+        Nk = int(np.count_nonzero(topo.is_compute)) * k
+        assert got[i] == min(capD[(u, sw)], capD[(sw, t)], int(F1.min()) - Nk, int(F2.min()) - Nk), (u, sw, t)
+    for opt in ({"split_two_launches": 1}, {"split_two_launches": 2}):
+        alt, alt_flows = _gamma_on_gpu(topo, U, k, pick, options=opt)
+        assert (alt == got).all() and (alt_flows == flows).all(), opt
+    early, _ = _gamma_on_gpu(topo, U, k, pick, want_flows=False)
+    assert (early == got).all()
+
+
 # ------------------------------------------------------------------ Algorithm 2: the switch-removal loop around the gamma batches
 
 def _remove_on_gpu(D, k, options=None):
