@@ -73,6 +73,7 @@ def load_library():
         return _lib
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2402_06787_amd.build`")
+    _ensure_gpu_ready()                                  # before the library (and the HIP runtime it links) is mapped: see there
     lib = ctypes.CDLL(LIB_PATH)
     c = ctypes
     vp, i32, i64, sz = c.c_void_p, c.c_int32, c.c_int64, c.c_size_t
@@ -298,6 +299,26 @@ def _dev_ptr(t, dtype, n, name):
     if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous() or t.numel() < n:
         raise ValueError(f"{name}: need a contiguous {dtype} device tensor with at least {n} elements")
     return ctypes.c_void_p(t.data_ptr())
+
+
+_gpu_ready = False
+
+
+def _ensure_gpu_ready():
+    """The library links the system HIP runtime, torch brings one of its own, and a process that uses both holds both.
+    When the library's runtime is mapped before torch has put anything on the device, its first hipMalloc has been seen
+    to report that there is no device (torch's runtime then comes up second and the two do not agree on the device).  So
+    torch's side is brought up -- one allocation -- before the library is loaded; torch is what provides device memory to
+    this binding anyway.  Without a GPU nothing is done and the library reports FC_EDEVICE by itself."""
+    global _gpu_ready
+    if not _gpu_ready:
+        import torch
+        if not torch.cuda.is_available():                 # (without a GPU the library reports FC_EDEVICE by itself)
+            return
+        torch.cuda.init()
+        torch.empty(1, device="cuda")
+        torch.cuda.synchronize()
+        _gpu_ready = True
 
 
 def _stream_ptr(stream):

@@ -50,6 +50,20 @@ def _optimum(cfg, topo):
 
 # ------------------------------------------------------------------ the paper's worked example
 
+def test_library_call_as_the_first_device_use_of_a_fresh_process():
+    # A process in which this package is the first thing to touch the GPU (torch imported, nothing allocated): the binding
+    # brings torch's side up before it maps the library, or the library's own HIP runtime finds no device.
+    import subprocess, sys, os
+    code = ("import workloads as w, paper_2402_06787_amd as fc\n"
+            "t = w.config_topology(1)\n"
+            "g = fc.fc_graph_upload(t.n_vertices, t.tail, t.head, t.bandwidth, t.is_compute)\n"
+            "print(fc.fc_opt_throughput_search(g, 16)['inv_xstar'])\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr[-2000:]
+    assert out.stdout.strip().splitlines()[-1] == "5/4"
+
+
 def test_paper_example_on_gpu():
     topo = w.paper_example_switch(1)
     with _upload(topo) as g:
