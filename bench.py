@@ -109,7 +109,7 @@ def main():
                     help="with --quick: time only this entry point (one kind of solver launch in a profile)")
     ap.add_argument("--back-end", type=str, default="3,4",
                     help="topologies for the switch-removal + tree-construction leg, comma-separated: config 3 and config 4 "
-                         "(default, about 4 s together), 6 = the 1024-compute Eulerian switch fabric (about 30 s), 0 = skip")
+                         "(default, about 3 s together), 6 = the 1024-compute Eulerian switch fabric (about 20 s), 0 = skip")
     ap.add_argument("--threads-per-problem", type=int, default=0)
     ap.add_argument("--lanes-per-vertex", type=int, default=0)
     ap.add_argument("--copy-probe", action="store_true",
