@@ -14,8 +14,10 @@ HEADERS = [os.path.join(CSRC, "fc_internal.h"), os.path.join(ROOT, "include", "f
           [os.path.join(CSRC, f) for f in ("fc_solver_kernels.inc", "fc_launch.inc", "fc_api.inc", "fc_surgery.inc")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-# packed-fp32 code generation is switched off for all device code of this project
-HIP_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
+# packed-fp32 code generation is switched off for all device code of this project.  The device code is built for size
+# (-Os): the solver kernels run out of scalar registers, and the smaller code keeps fewer values live (29 instead of 42
+# spilled scalar registers in the 1024-vertex build, 47 instead of 77 in the 7-wavefront one) -- 3 % faster on MI355X.
+HIP_FLAGS = ["-O3", "-Xarch_device", "-Os", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-Wall", "-Wno-unused-function"]
 
