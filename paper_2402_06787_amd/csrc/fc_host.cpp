@@ -84,7 +84,9 @@ int fc_host_build(int32_t n_vertices, int64_t n_arcs, const int32_t *tail, const
         for (int32_t v = 0; v < n_vertices; ++v) {
             g->row_ptr[v + 1] = g->row_ptr[v] + deg[v];
             g->max_row = std::max(g->max_row, deg[v]);
+            g->row_seen += double(deg[v]) * double(deg[v]);
         }
+        g->row_seen = g->row_ptr[size_t(n_vertices)] > 0 ? g->row_seen / double(g->row_ptr[size_t(n_vertices)]) : 0.0;
         size_t M = size_t(2 * g->m0);
         g->other.resize(M); g->pair.resize(M); g->bw.resize(M); g->fwd.resize(M);
         std::vector<int32_t> fill(g->row_ptr.begin(), g->row_ptr.end() - 1);

@@ -25,6 +25,7 @@ struct fc_graph {
     int64_t min_in_bw = 0;         // min over compute nodes of B^-(v)
     int32_t max_bw = 0, gcd_bw = 0, eulerian = 0;
     int32_t max_row = 0;           // longest residual row
+    double row_seen = 0;           // sum of squared row lengths / sum of row lengths: the length of the row a random record lies in
     // ---- device side (valid when on_device)
     bool on_device = false;
     int device = -1;
