@@ -74,8 +74,8 @@ typedef struct {
     int32_t threads_per_problem;   /* workgroup size, multiple of 64 in [64, 1024] (default: 256 when fewer
                                       than 8 problems fit a CU's LDS, else 128, 64 below 256 vertices)   */
     int32_t lanes_per_vertex;      /* power of two in [2, 64]: lanes that scan one vertex's arc list (default:
-                                      about 3/4 of a residual row's length -- of the row a random arc lies in
-                                      for the (sink, candidate) launches, of the average row elsewhere)   */
+                                      the power of two next to a residual row's length -- the row a random
+                                      arc lies in for the (sink, candidate) launches, the average row elsewhere) */
     int32_t global_relabel_steps;  /* relabel from the sink when this many level steps passed since
                                       the last one and some vertex was relabeled (default 32; launches of
                                       fc_construct_trees from kept flows: 4)                             */
