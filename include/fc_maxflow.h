@@ -102,7 +102,8 @@ typedef struct {
                                       answered from a per-sink ratio without running the solver (its
                                       counters stay 0).  Exact; it only skips work.                      */
     int32_t schedule;              /* 1 = on (default), 2 = off: start the problems that look hardest (least
-                                      slack in the sink's own cut) first, so the launch has no long tail */
+                                      slack in the sink's own cut) first, so the launch has no long tail (a
+                                      launch whose workgroups all fit the device at once is not ordered)  */
     int32_t tree_warm_start;       /* fc_construct_trees: 1 = on (default), 2 = off.  On: while a root-set grows, the
                                       flow that delivers the other root-sets' demands to a vertex y is kept on the
                                       device from launch to launch, repaired for the capacities that were used up
